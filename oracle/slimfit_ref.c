@@ -1,0 +1,506 @@
+/*
+ * SlimFit hot path -- CPU oracle (TEST INFRASTRUCTURE, not a product path).
+ *
+ * A plain, slow, obviously-correct implementation of what the GPU library
+ * computes, written from the paper's definitions.  It shares no code with the
+ * HIP path: only tests, the smoke check and the benchmark's cpu_baseline leg
+ * may load it.  Every pointer is a HOST pointer.  Each function runs its
+ * independent units (layers, quantisation blocks, score rows) sequentially or,
+ * when threads > 1, under "omp parallel for" over those units only, which
+ * cannot change any result.
+ *
+ * Precision: the distance score (Eq. 1) is evaluated in fp64.  The quantiser
+ * (Alg. 2) is evaluated in fp32 because the paper fixes that precision (all
+ * tensors are single precision and the rounding decides an integer code).
+ *
+ * dtype codes: 0 = fp32, 1 = bf16 (raw uint16 bit patterns).
+ * Return value: 0 on success, a negative number for an argument the
+ * definition does not cover.
+ *
+ * Pins (tests/, -m "not gpu"): Fig. 4 replay for the ILS pair; closed forms,
+ * scaling/sign/permutation invariants and a NumPy float64 one-liner for
+ * Eq. 1; exhaustive grid against Alg. 2 in double, half-step bound,
+ * idempotence and pack/unpack identity for the quantiser; brute-force
+ * repeat-argmax selector and a library stable argsort for the pruner.
+ * Parity unpinned by the paper (it prints no worked numbers for them): the
+ * per-block-scale mode, the 4-bit split of integer/fraction bits, the
+ * threshold pruning mode and bf16 I/O.  Those are pinned by brute force and
+ * invariants only.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define REF_OK 0
+#define REF_BAD (-1)
+
+/* ------------------------------------------------------------------ */
+/* bf16 <-> fp32                                                        */
+/* ------------------------------------------------------------------ */
+
+static float bf16_widen(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round-to-nearest-even on the 16 discarded bits; NaN stays NaN */
+static uint16_t bf16_narrow(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t keep = u >> 16;
+    uint32_t rest = u & 0xffffu;
+    if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u)))
+        keep += 1u;
+    return (uint16_t)keep;
+}
+
+static float load_elem(const void *p, int dt, int64_t j)
+{
+    if (dt == 0)
+        return ((const float *)p)[j];
+    return bf16_widen(((const uint16_t *)p)[j]);
+}
+
+static void store_elem(void *p, int dt, int64_t j, float v)
+{
+    if (dt == 0)
+        ((float *)p)[j] = v;
+    else
+        ((uint16_t *)p)[j] = bf16_narrow(v);
+}
+
+static int dtype_ok(int dt) { return dt == 0 || dt == 1; }
+
+/* ------------------------------------------------------------------ */
+/* Eq. 1 -- training-dynamics distance of one layer                     */
+/*   d_i = 1/(M*I) * sum_j | (W^t_ij - W^{t-1}_ij) / W^{t-1}_ij |       */
+/* Entry-wise l1 (the 1/(M*I) normaliser makes it a mean).  Readings    */
+/* where the paper is silent: an element whose weight did not change    */
+/* contributes 0 even if the old weight is 0; otherwise IEEE division   */
+/* (a zero old weight with a non-zero change gives +inf) unless the     */
+/* caller passes eps > 0, which floors the denominator's magnitude.     */
+/* An empty layer scores 0.                                             */
+/* ------------------------------------------------------------------ */
+
+static float layer_distance(const void *w_prev, int prev_dt, const void *w_cur,
+                            int cur_dt, int cur_is_delta, int64_t n, float eps)
+{
+    if (n <= 0)
+        return 0.0f;
+    double sum = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        double wp = (double)load_elem(w_prev, prev_dt, j);
+        double c = (double)load_elem(w_cur, cur_dt, j);
+        double delta = cur_is_delta ? c : c - wp;
+        if (delta == 0.0)
+            continue;
+        double den = fabs(wp);
+        if (den < (double)eps)
+            den = (double)eps;
+        sum += fabs(delta) / den;
+    }
+    return (float)(sum / (double)n);
+}
+
+int slimfit_ref_layer_delta(const void *const *w_prev, int prev_dt,
+                            const void *const *w_cur, int cur_dt,
+                            int cur_is_delta, const int64_t *numel, int L,
+                            float eps, float *d_out, int threads)
+{
+    if (L < 0 || !dtype_ok(prev_dt) || !dtype_ok(cur_dt) || !(eps >= 0.0f))
+        return REF_BAD;
+    if (L == 0)
+        return REF_OK;
+    if (!w_prev || !w_cur || !numel || !d_out)
+        return REF_BAD;
+    for (int i = 0; i < L; ++i)
+        if (numel[i] < 0 || (numel[i] > 0 && (!w_prev[i] || !w_cur[i])))
+            return REF_BAD;
+    if (threads < 1)
+        threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+    for (int i = 0; i < L; ++i)
+        d_out[i] = layer_distance(w_prev[i], prev_dt, w_cur[i], cur_dt,
+                                  cur_is_delta, numel[i], eps);
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Alg. 2 -- fixed-point conversion, plus the per-block-scale variant   */
+/*   quantise:   y = clamp(round(x * 2^fb), -2^(b-1), 2^(b-1)-1)        */
+/*   dequantise: x = y / 2^fb                                           */
+/* round = half-to-even (the paper's code is PyTorch, whose round is).  */
+/* mode 0 (FIXED): exactly the above, b = ib + fb total bits.           */
+/* mode 1 (BLOCK): 2^fb is replaced, per run of `block` consecutive     */
+/*   elements of the flattened tensor, by inv = qmax / absmax; the      */
+/*   stored scale = absmax / qmax replaces 1/2^fb on the way back.      */
+/*   Degenerate block (absmax == 0, or so small that qmax/absmax        */
+/*   overflows fp32): scale 0 and all codes 0.                          */
+/* Codes are signed two's-complement; 4-bit codes are stored two per    */
+/* byte by shifting, element 2m in the low nibble, 2m+1 in the high     */
+/* one; an odd tail pads the high nibble with 0.                        */
+/* ------------------------------------------------------------------ */
+
+static int quant_args_ok(int dt, int64_t n, int mode, int bits, int block,
+                         int frac_bits)
+{
+    if (!dtype_ok(dt) || n < 0)
+        return 0;
+    if (bits != 4 && bits != 8)
+        return 0;
+    if (mode == 0)
+        return frac_bits >= -32 && frac_bits <= 32;
+    if (mode == 1)
+        return block == 32 || block == 64 || block == 128 || block == 256;
+    return 0;
+}
+
+static int quantise_one(float x, float mult, int qmin, int qmax)
+{
+    float q = x * mult;              /* one fp32 multiply */
+    float r = nearbyintf(q);         /* half-to-even under the default mode */
+    if (r != r)
+        return 0;                    /* NaN is outside the contract */
+    if (r < (float)qmin)
+        r = (float)qmin;
+    if (r > (float)qmax)
+        r = (float)qmax;
+    return (int)r;
+}
+
+static void put_code(uint8_t *codes, int bits, int64_t j, int c)
+{
+    if (bits == 8) {
+        codes[j] = (uint8_t)(c & 0xff);
+    } else {
+        int64_t m = j >> 1;
+        uint8_t nib = (uint8_t)(c & 0xf);
+        if ((j & 1) == 0)
+            codes[m] = nib;                       /* also zeroes the pad */
+        else
+            codes[m] = (uint8_t)(codes[m] | (nib << 4));
+    }
+}
+
+static int get_code(const uint8_t *codes, int bits, int64_t j)
+{
+    if (bits == 8)
+        return (int)(int8_t)codes[j];
+    uint8_t byte = codes[j >> 1];
+    int nib = (j & 1) ? (byte >> 4) : (byte & 0xf);
+    return nib >= 8 ? nib - 16 : nib;             /* sign-extend */
+}
+
+int slimfit_ref_quant_pack(const void *x, int dt, int64_t n, int mode, int bits,
+                           int block, int frac_bits, uint8_t *codes,
+                           float *scales, int threads)
+{
+    if (!quant_args_ok(dt, n, mode, bits, block, frac_bits))
+        return REF_BAD;
+    if (n == 0)
+        return REF_OK;
+    if (!x || !codes || (mode == 1 && !scales))
+        return REF_BAD;
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int qmin = -(1 << (bits - 1));
+    if (threads < 1)
+        threads = 1;
+
+    if (mode == 0) {
+        const float mult = ldexpf(1.0f, frac_bits);
+        /* pairs of elements: neighbouring 4-bit codes share a byte */
+        const int64_t npair = (n + 1) / 2;
+#pragma omp parallel for num_threads(threads) schedule(static)
+        for (int64_t m = 0; m < npair; ++m)
+            for (int64_t j = 2 * m; j < 2 * m + 2 && j < n; ++j)
+                put_code(codes, bits, j,
+                         quantise_one(load_elem(x, dt, j), mult, qmin, qmax));
+        return REF_OK;
+    }
+
+    const int64_t nblk = (n + block - 1) / block;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t b = 0; b < nblk; ++b) {
+        int64_t lo = b * block;
+        int64_t hi = lo + block < n ? lo + block : n;
+        float a = 0.0f;
+        for (int64_t j = lo; j < hi; ++j) {
+            float m = fabsf(load_elem(x, dt, j));
+            if (m > a)
+                a = m;
+        }
+        float inv = 0.0f, scale = 0.0f;
+        if (a > 0.0f) {
+            inv = (float)qmax / a;               /* one fp32 division */
+            if (isinf(inv))
+                inv = 0.0f;
+            else
+                scale = a / (float)qmax;         /* one fp32 division */
+        }
+        scales[b] = scale;
+        /* block sizes are even, so a block never shares a byte with its
+         * neighbour and blocks may run in parallel */
+        for (int64_t j = lo; j < hi; ++j)
+            put_code(codes, bits, j,
+                     quantise_one(load_elem(x, dt, j), inv, qmin, qmax));
+    }
+    return REF_OK;
+}
+
+int slimfit_ref_dequant_unpack(const uint8_t *codes, const float *scales,
+                               int64_t n, int mode, int bits, int block,
+                               int frac_bits, void *y, int dt, int threads)
+{
+    if (!quant_args_ok(dt, n, mode, bits, block, frac_bits))
+        return REF_BAD;
+    if (n == 0)
+        return REF_OK;
+    if (!y || !codes || (mode == 1 && !scales))
+        return REF_BAD;
+    if (threads < 1)
+        threads = 1;
+    const float step = ldexpf(1.0f, frac_bits);
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t j = 0; j < n; ++j) {
+        float c = (float)get_code(codes, bits, j);
+        float v = (mode == 0) ? c / step           /* exact: power of two */
+                              : c * scales[j / block];
+        store_elem(y, dt, j, v);
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Alg. 5 -- pruning to (values, indices), applied to every row         */
+/*   sort the row from largest to smallest with indices, keep the       */
+/*   first k.  Readings: ties are broken by the lower column; the kept  */
+/*   pairs are emitted in ascending column order (the set is what       */
+/*   matters; restoring gives the same dense row either way).           */
+/* mode 0 (TOPK): exactly k pairs.                                      */
+/* mode 1 (THRESHOLD): the first min(k, #{p >= tau}) pairs of the same  */
+/*   order; unused slots hold value 0 and index 0xFFFF.                 */
+/* counts (optional) receives the number of pairs kept per row.         */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    float v;
+    int32_t col;
+} ref_pair;
+
+static int pair_before(const void *pa, const void *pb)
+{
+    const ref_pair *a = (const ref_pair *)pa, *b = (const ref_pair *)pb;
+    if (a->v > b->v)
+        return -1;
+    if (a->v < b->v)
+        return 1;
+    return (a->col > b->col) - (a->col < b->col);
+}
+
+int slimfit_ref_prune_scores(const void *p, int dt, int64_t rows, int cols,
+                             int k, int mode, float tau, void *vals,
+                             uint16_t *idx, int32_t *counts, int threads)
+{
+    if (!dtype_ok(dt) || rows < 0 || cols < 1 || cols > 65536 || k < 1 ||
+        k > cols || (mode != 0 && mode != 1))
+        return REF_BAD;
+    if (rows == 0)
+        return REF_OK;
+    if (!p || !vals || !idx)
+        return REF_BAD;
+    if (threads < 1)
+        threads = 1;
+    int failed = 0;
+#pragma omp parallel num_threads(threads)
+    {
+        ref_pair *buf = (ref_pair *)malloc(sizeof(ref_pair) * (size_t)cols);
+        uint8_t *kept = (uint8_t *)malloc((size_t)cols);
+        if (!buf || !kept) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (int64_t r = 0; r < rows; ++r) {
+            if (!buf || !kept)
+                continue;
+            const int64_t base = r * (int64_t)cols;
+            for (int c = 0; c < cols; ++c) {
+                buf[c].v = load_elem(p, dt, base + c);
+                buf[c].col = c;
+            }
+            qsort(buf, (size_t)cols, sizeof(ref_pair), pair_before);
+            int take = k;
+            if (mode == 1) {
+                int pass = 0;
+                while (pass < cols && buf[pass].v >= tau)
+                    ++pass;
+                if (pass < take)
+                    take = pass;
+            }
+            memset(kept, 0, (size_t)cols);
+            for (int s = 0; s < take; ++s)
+                kept[buf[s].col] = 1;
+            int out = 0;
+            const int64_t obase = r * (int64_t)k;
+            for (int c = 0; c < cols; ++c) {
+                if (!kept[c])
+                    continue;
+                /* the stored value is a bit copy of the input element */
+                if (dt == 0)
+                    ((float *)vals)[obase + out] =
+                        ((const float *)p)[base + c];
+                else
+                    ((uint16_t *)vals)[obase + out] =
+                        ((const uint16_t *)p)[base + c];
+                idx[obase + out] = (uint16_t)c;
+                ++out;
+            }
+            for (; out < k; ++out) {
+                if (dt == 0)
+                    ((float *)vals)[obase + out] = 0.0f;
+                else
+                    ((uint16_t *)vals)[obase + out] = 0;
+                idx[obase + out] = 0xFFFFu;
+            }
+            if (counts)
+                counts[r] = take;
+        }
+        free(buf);
+        free(kept);
+    }
+    return failed ? REF_BAD : REF_OK;
+}
+
+/* Alg. 5, restoring process: zeros(numel) then scatter the kept values.
+ * counts == NULL means every row holds k pairs. */
+int slimfit_ref_restore_scores(const void *vals, const uint16_t *idx,
+                               const int32_t *counts, int dt, int64_t rows,
+                               int cols, int k, void *out, int threads)
+{
+    if (!dtype_ok(dt) || rows < 0 || cols < 1 || cols > 65536 || k < 1 ||
+        k > cols)
+        return REF_BAD;
+    if (rows == 0)
+        return REF_OK;
+    if (!vals || !idx || !out)
+        return REF_BAD;
+    if (threads < 1)
+        threads = 1;
+    const size_t esz = dt == 0 ? 4 : 2;
+    int bad = 0;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        char *orow = (char *)out + (size_t)r * (size_t)cols * esz;
+        memset(orow, 0, (size_t)cols * esz);
+        int cnt = counts ? counts[r] : k;
+        if (cnt < 0 || cnt > k) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
+        for (int s = 0; s < cnt; ++s) {
+            uint16_t c = idx[r * (int64_t)k + s];
+            if ((int)c >= cols) {
+#pragma omp atomic write
+                bad = 1;
+                continue;
+            }
+            memcpy(orow + (size_t)c * esz,
+                   (const char *)vals + ((size_t)r * (size_t)k + (size_t)s) * esz,
+                   esz);
+        }
+    }
+    return bad ? REF_BAD : REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Alg. 1 -- inter-layer scheduling on the host                         */
+/*   idx = argsort(d)[:int(L*F)]  -> those layers are frozen            */
+/* Readings: equal distances freeze the lower layer index first; NaN    */
+/* orders as +inf.  Only active layers take a new distance afterwards;  */
+/* a frozen layer keeps its old one (Sec. 3.2, Fig. 4).                 */
+/* ------------------------------------------------------------------ */
+
+int slimfit_ref_freeze_count(int L, double F)
+{
+    if (L < 0 || !(F >= 0.0) || !(F <= 1.0))
+        return REF_BAD;
+    return (int)((double)L * F);                   /* Python's int(L*F) */
+}
+
+int slimfit_ref_keep_count(int cols, int keep_ppm)
+{
+    if (cols < 0 || keep_ppm < 0 || keep_ppm > 1000000)
+        return REF_BAD;
+    return (int)(((int64_t)cols * (int64_t)keep_ppm) / 1000000);
+}
+
+static int dist_before(float da, int ia, float db, int ib)
+{
+    /* NaN behaves like +inf */
+    int na = da != da, nb = db != db;
+    if (na || nb) {
+        if (na && nb)
+            return ia < ib;
+        return nb;                                 /* non-NaN first */
+    }
+    if (da < db)
+        return 1;
+    if (da > db)
+        return 0;
+    return ia < ib;
+}
+
+int slimfit_ref_ils_select(const float *d, int L, int n_freeze,
+                           int32_t *frozen_idx, uint8_t *mask)
+{
+    if (L < 0 || n_freeze < 0 || n_freeze > L)
+        return REF_BAD;
+    if (L > 0 && !d)
+        return REF_BAD;
+    if (n_freeze > 0 && !frozen_idx)
+        return REF_BAD;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)(L > 0 ? L : 1));
+    if (!order)
+        return REF_BAD;
+    /* insertion sort: stable, and L is about a hundred */
+    for (int i = 0; i < L; ++i) {
+        int pos = i;
+        while (pos > 0 && dist_before(d[i], i, d[order[pos - 1]], order[pos - 1])) {
+            order[pos] = order[pos - 1];
+            --pos;
+        }
+        order[pos] = i;
+    }
+    if (mask)
+        memset(mask, 0, (size_t)L);
+    for (int s = 0; s < n_freeze; ++s) {
+        frozen_idx[s] = order[s];
+        if (mask)
+            mask[order[s]] = 1;
+    }
+    free(order);
+    return REF_OK;
+}
+
+int slimfit_ref_ils_update(float *d, const float *new_scores,
+                           const uint8_t *frozen_mask, int L)
+{
+    if (L < 0)
+        return REF_BAD;
+    if (L == 0)
+        return REF_OK;
+    if (!d || !new_scores || !frozen_mask)
+        return REF_BAD;
+    for (int i = 0; i < L; ++i)
+        if (!frozen_mask[i])
+            d[i] = new_scores[i];
+    return REF_OK;
+}
