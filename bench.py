@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the SlimFit hot path on one MI355X.
+
+One "step" is one pass of the whole per-iteration path of a fine-tune step over
+one batch of synthetic input of the chosen workload configuration:
+
+  forward,  per encoder block : quant_pack(GELU input), quant_pack(LayerNorm
+                                input) x2, prune_scores(attention probabilities)
+  backward, per encoder block : dequant_unpack of the three cached tensors
+  after the optimizer step    : layer_delta over every weight tensor, copy of
+                                the L scores to the host, ils_update +
+                                ils_select on the host
+
+The metric is algorithmic bytes of the step / wall time of the step, inputs
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2305_18513_amd import binding as sf  # noqa: E402
+from paper_2305_18513_amd import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def esize(dt: torch.dtype) -> int:
+    return 2 if dt == torch.bfloat16 else 4
+
+
+class BlockSet:
+    """Device tensors of one encoder block: inputs and caller-owned outputs."""
+
+    def __init__(self, cfg: synth.WorkloadConfig, block: int, bits: int):
+        dev = "cuda"
+        self.gelu = synth.activation(cfg, "gelu_in", dev, block).reshape(-1)
+        self.ln = [synth.activation(cfg, "ln_in", dev, block * 2 + i).reshape(-1) for i in range(2)]
+        self.scores = synth.attention_scores(cfg, dev, block)
+        self.acts = [self.gelu] + self.ln
+        self.codes = [torch.empty(sf.packed_bytes(a.numel(), bits), dtype=torch.uint8, device=dev)
+                      for a in self.acts]
+        self.scales = [torch.empty(sf.num_blocks(a.numel(), cfg.quant_block), dtype=torch.float32, device=dev)
+                       for a in self.acts]
+        self.deq = [torch.empty_like(a) for a in self.acts]
+        rows, k = cfg.score_rows, cfg.keep_k
+        self.vals = torch.empty(rows, k, dtype=self.scores.dtype, device=dev)
+        self.idx = torch.empty(rows, k, dtype=torch.uint16, device=dev)
+        self.counts = torch.empty(rows, dtype=torch.int32, device=dev)
+
+
+class Timers:
+    """Per-kernel device time from events on the stream the kernels run on."""
+
+    def __init__(self):
+        self.pending = []
+        self.total_ms = {}
+        self.calls = {}
+        self.bytes = {}
+
+    def launch(self, name, nbytes, fn):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.pending.append((name, nbytes, a, b))
+
+    def collect(self):
+        for name, nbytes, a, b in self.pending:
+            self.total_ms[name] = self.total_ms.get(name, 0.0) + a.elapsed_time(b)
+            self.calls[name] = self.calls.get(name, 0) + 1
+            self.bytes[name] = nbytes
+        self.pending = []
+
+
+def quant_bytes(n, in_sz, bits, block):
+    return n * in_sz + (n * bits + 7) // 8 + ((n + block - 1) // block) * 4
+
+
+def prune_bytes(rows, cols, k, in_sz):
+    return rows * cols * in_sz + rows * k * (in_sz + 2)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (3 = BERT-large-shaped)")
+    ap.add_argument("--sets", type=int, default=3, help="distinct encoder-block buffer sets to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 1 GiB device copies (for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    if not sf.is_built():
+        from paper_2305_18513_amd import build
+        build.build_library()
+    sf.lib()
+
+    cfg = synth.CONFIGS[args.config]
+    bits = cfg.quant_bits[-1]
+    block = cfg.quant_block
+    mode = sf.PRUNE_THRESHOLD if cfg.threshold_variant else sf.PRUNE_TOPK
+    tau = cfg.threshold_tau if cfg.threshold_variant else 0.0
+    torch.cuda.set_device(0)
+    in_sz = esize(cfg.act_dtype)
+
+    n_sets = max(1, min(args.sets, cfg.n_blocks))
+    sets = [BlockSet(cfg, b, bits) for b in range(n_sets)]
+    prev, cur = synth.weight_units(cfg, "cuda")
+    numel = [t.numel() for t in prev]
+    L = len(numel)
+    ws = torch.empty(sf.layer_delta_workspace(numel), dtype=torch.uint8, device="cuda")
+    d_dev = torch.empty(L, dtype=torch.float32, device="cuda")
+    d_host_pinned = torch.empty(L, dtype=torch.float32, pin_memory=True)
+    d_vec = synth.initial_distance(cfg).numpy().copy()
+    n_freeze = sf.freeze_count(L, cfg.freeze_rate)
+    _, mask = sf.ils_select(d_vec, n_freeze)
+    pdt = sf.BF16 if cfg.w_dtype == torch.bfloat16 else sf.F32
+    sf.layer_delta_plan(prev, cur, ws)           # pointers are stable across steps: planned once
+    torch.cuda.synchronize()
+
+    w_bytes = sum(numel) * (esize(cfg.w_dtype) + 4) + 4 * L
+    b_quant = [quant_bytes(a.numel(), in_sz, bits, block) for a in sets[0].acts]
+    b_prune = prune_bytes(cfg.score_rows, cfg.score_cols, cfg.keep_k, in_sz)
+    step_bytes = cfg.n_blocks * (2 * sum(b_quant) + b_prune) + w_bytes
+    names_q = ["quant_pack[gelu_in]", "quant_pack[ln_in]", "quant_pack[ln_in]"]
+    names_d = ["dequant_unpack[gelu_in]", "dequant_unpack[ln_in]", "dequant_unpack[ln_in]"]
+
+    timers = Timers()
+
+    def step(record: bool):
+        nonlocal mask
+        run = timers.launch if record else (lambda name, nbytes, fn: fn())
+        for b in range(cfg.n_blocks):                     # forward
+            s = sets[b % n_sets]
+            for i, a in enumerate(s.acts):
+                run(names_q[i], b_quant[i],
+                    lambda a=a, i=i, s=s: sf.quant_pack(a, sf.Q_BLOCK, bits, block, 0, s.codes[i], s.scales[i]))
+            run("prune_scores", b_prune,
+                lambda s=s: sf.prune_scores(s.scores, cfg.keep_k, mode, tau, s.vals, s.idx, s.counts))
+        for b in reversed(range(cfg.n_blocks)):           # backward
+            s = sets[b % n_sets]
+            for i in reversed(range(3)):
+                run(names_d[i], b_quant[i],
+                    lambda i=i, s=s: sf.dequant_unpack(s.codes[i], s.scales[i], sf.Q_BLOCK, bits, block, 0, s.deq[i]))
+        run("layer_delta", w_bytes,
+            lambda: sf.layer_delta_run(numel, pdt, sf.F32, cfg.delta_given, 0.0, d_dev, ws))
+        d_host_pinned.copy_(d_dev, non_blocking=True)
+        torch.cuda.current_stream().synchronize()         # the host needs the L scores
+        sf.ils_update(d_vec, d_host_pinned.numpy(), mask)
+        _, mask = sf.ils_select(d_vec, n_freeze)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    timers.collect()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    ms_per_step = wall * 1e3 / args.steps
+    value = step_bytes / (wall / args.steps) / 1e9
+
+    kernels = {}
+    for name, tot in timers.total_ms.items():
+        calls = timers.calls[name]
+        avg_ms = tot / calls
+        gbs = timers.bytes[name] / (avg_ms * 1e-3) / 1e9
+        kernels[name] = {"calls": calls, "avg_ms": round(avg_ms, 5), "bytes_per_launch": timers.bytes[name],
+                         "GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                         "total_ms_per_step": round(tot / args.steps, 4)}
+    dom = max(kernels, key=lambda n: kernels[n]["total_ms_per_step"])
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"], "traffic": None}
+
+    out = {
+        "metric": "activation-compression + freeze-score GB/s per fine-tune step; % of HBM peak",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if cfg.act_dtype == torch.float32 else "bf16", "data": "synthetic",
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "config": {"workload": "config %d: %s-shaped (%d blocks, hidden %d, %d heads, tokens %d, batch %d)"
+                               % (cfg.index, cfg.name, cfg.n_blocks, cfg.hidden, cfg.heads, cfg.tokens, cfg.batch),
+                   "quant": "%d-bit block-%d" % (bits, block), "keep_k": cfg.keep_k, "score_cols": cfg.score_cols,
+                   "prune_mode": "threshold" if cfg.threshold_variant else "topk",
+                   "layers_scored": L, "n_freeze": n_freeze, "step_bytes": step_bytes,
+                   "buffer_sets": n_sets},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, bits, block, mode, tau)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(cfg, bits, block, mode, tau):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import ref
+    threads = min(ref.host_threads(), 16)
+    sample_batch = max(1, min(cfg.batch, 4))
+    in_sz = esize(cfg.act_dtype)
+
+    def host(t):
+        t = t.cpu().contiguous()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    gelu = host(synth.activation(cfg, "gelu_in", "cpu", 0, batch=sample_batch).reshape(-1))
+    lns = [host(synth.activation(cfg, "ln_in", "cpu", i, batch=sample_batch).reshape(-1)) for i in range(2)]
+    scores = host(synth.attention_scores(cfg, "cpu", 0, batch=sample_batch))
+    prev, cur = synth.weight_units(cfg, "cpu", n_blocks=1)
+    prev, cur = [host(t) for t in prev], [host(t) for t in cur]
+    ref.lib()
+    nbytes = 0
+    t0 = time.perf_counter()
+    packed = []
+    for a in [gelu] + lns:
+        packed.append(ref.quant_pack(a, mode=ref.Q_BLOCK, bits=bits, block=block, threads=threads))
+        nbytes += quant_bytes(a.size, in_sz, bits, block)
+    ref.prune_scores(scores, cfg.keep_k, mode=mode, tau=tau, threads=threads)
+    nbytes += prune_bytes(scores.shape[0], scores.shape[1], cfg.keep_k, in_sz)
+    for a, (c, s) in zip([gelu] + lns, packed):
+        ref.dequant_unpack(c, s, a.size, mode=ref.Q_BLOCK, bits=bits, block=block,
+                           out_dtype=a.dtype, threads=threads)
+        nbytes += quant_bytes(a.size, in_sz, bits, block)
+    d = ref.layer_delta(prev, cur, cur_is_delta=cfg.delta_given, threads=threads)
+    nbytes += sum(p.size for p in prev) * (esize(cfg.w_dtype) + 4)
+    ref.ils_select(d, ref.freeze_count(d.size, cfg.freeze_rate))
+    dt = time.perf_counter() - t0
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": "one encoder block of the same config at batch %d (quant x3, prune, dequant x3) plus "
+                      "layer_delta over that block's 8 weight tensors and one ils_select" % sample_batch}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,219 @@
+/*
+ * slimfit.h -- C ABI of the MI355X (gfx950) SlimFit hot-path library.
+ *
+ * SlimFit (arXiv 2305.18513) fine-tunes transformers under a memory budget by
+ * (1) scoring every layer by how much its weights moved in the last step
+ * (Eq. 1), (2) freezing the lowest-scoring layers each iteration (Alg. 1,
+ * inter-layer scheduling, ILS), (3) caching the activations that cannot be
+ * discarded in 8 or 4 bits (Alg. 2, Sec. 4 and 5) and (4) caching only the
+ * largest 10 % of some activations as values + indices (Alg. 5).  This
+ * library is that per-step path and nothing else.
+ *
+ * Conventions
+ *  - Every function returns a slimfit_status as int32_t.  Nothing throws,
+ *    nothing allocates device memory, nothing synchronises with the host.
+ *  - "device pointer" = memory the GPU can address (hipMalloc / a torch CUDA
+ *    tensor); "host pointer" = ordinary process memory.  Each argument says
+ *    which one it is.  The caller owns every buffer and keeps it alive until
+ *    the stream has passed the call.  Inputs are never written; outputs are
+ *    fully overwritten for the sizes given.
+ *  - Device pointers must be 16-byte aligned (SLIMFIT_ERR_ALIGNMENT), except
+ *    where a narrower alignment is stated.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    All device work of a call is enqueued on it, in order.
+ *  - Arguments are validated before anything is launched, so every error
+ *    return leaves the GPU untouched.  A size of zero is SLIMFIT_OK and a
+ *    no-op.  With pointer checks on (the default, see
+ *    slimfit_set_pointer_checks) each device pointer is also looked up in the
+ *    HIP runtime and rejected with SLIMFIT_ERR_POINTER when it is not device
+ *    memory or when the bytes the call would touch run past the end of its
+ *    allocation.
+ *  - Inputs must be finite.  NaN/Inf never fault but their results are
+ *    unspecified.
+ *  - dtype SLIMFIT_BF16 means raw bfloat16 bit patterns (uint16_t).
+ */
+#ifndef SLIMFIT_H
+#define SLIMFIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SLIMFIT_OK = 0,
+    SLIMFIT_ERR_INVALID_ARG = 1, /* NULL where data is required, negative size, k > cols ... */
+    SLIMFIT_ERR_UNSUPPORTED = 2, /* a value outside the supported set (bits, block, cols) */
+    SLIMFIT_ERR_ALIGNMENT = 3,   /* a device pointer is not aligned as required */
+    SLIMFIT_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than the size query says */
+    SLIMFIT_ERR_HIP = 5,         /* the HIP runtime refused a launch or a query */
+    SLIMFIT_ERR_POINTER = 6      /* pointer check failed: not device memory / too small */
+} slimfit_status;
+
+typedef enum { SLIMFIT_F32 = 0, SLIMFIT_BF16 = 1 } slimfit_dtype;
+typedef enum { SLIMFIT_Q_FIXED = 0, SLIMFIT_Q_BLOCK = 1 } slimfit_qmode;
+typedef enum { SLIMFIT_PRUNE_TOPK = 0, SLIMFIT_PRUNE_THRESHOLD = 1 } slimfit_prune_mode;
+
+/* Static text for a status code (never NULL). */
+const char *slimfit_status_string(int32_t status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t slimfit_version(void);
+
+/* Turn the run-time device-pointer checks on (non-zero, default) or off.
+ * Returns the previous setting.  Host-side only; costs a few microseconds per
+ * call when on. */
+int32_t slimfit_set_pointer_checks(int32_t on);
+
+/* ------------------------------------------------------------------------
+ * (a) Training-dynamics freeze score -- Eq. 1 (Sec. 3.1):
+ *        d_i = 1/(M*I) * || (W_i^t - W_i^{t-1}) / W_i^{t-1} ||_l1
+ *     entry-wise over the M x I weights of layer i, i.e. the mean of
+ *     |delta| / |w_prev|.  One call scores all L layers ("layer" = one weight
+ *     tensor, the granularity of the paper's layer list).
+ *
+ *  w_prev, w_cur : HOST arrays of L DEVICE pointers.  w_prev[i] holds
+ *                  W_i^{t-1} (numel[i] elements of prev_dt); w_cur[i] holds
+ *                  W_i^t, or, when cur_is_delta != 0, the update
+ *                  W_i^t - W_i^{t-1} itself (numel[i] elements of cur_dt).
+ *                  The arrays are read during the call only.
+ *  numel         : HOST array of L element counts, each >= 0 (0 scores 0).
+ *  eps           : >= 0.  Floor on |w_prev| in the denominator; 0 gives the
+ *                  literal equation (a changed weight whose old value is 0
+ *                  makes the score +inf).  An unchanged element contributes 0
+ *                  whatever its old value.
+ *  d_out         : DEVICE float[L], 4-byte aligned.
+ *  workspace     : DEVICE scratch of at least the bytes
+ *                  slimfit_layer_delta_workspace reports, 256-byte aligned.
+ *
+ *  Arithmetic: each term is formed in fp32 (difference, IEEE division), the
+ *  terms are accumulated in fp64 in a fixed order, so results are identical
+ *  from run to run.  A term above FLT_MAX saturates to +inf.
+ *
+ *  slimfit_layer_delta       = plan + run in one call.
+ *  slimfit_layer_delta_plan  writes the layer table into the workspace (the
+ *                            pointers of a model do not change between
+ *                            steps, so a trainer plans once).
+ *  slimfit_layer_delta_run   scores the planned layers; numel, L and the
+ *                            dtypes must be the ones given to the plan.  If
+ *                            the workspace does not hold a matching plan,
+ *                            d_out is filled with NaN and nothing else is
+ *                            touched.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_layer_delta_workspace(int32_t L, const int64_t *numel, size_t *bytes);
+
+int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t prev_dt,
+                                 const void *const *w_cur, int32_t cur_dt,
+                                 const int64_t *numel, int32_t L,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+int32_t slimfit_layer_delta_run(const int64_t *numel, int32_t L,
+                                int32_t prev_dt, int32_t cur_dt, int32_t cur_is_delta,
+                                float eps, float *d_out,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_dt,
+                            const void *const *w_cur, int32_t cur_dt, int32_t cur_is_delta,
+                            const int64_t *numel, int32_t L, float eps,
+                            float *d_out, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/* ------------------------------------------------------------------------
+ * (b) Low-bit caching of saved activations -- Alg. 2 (appendix on the
+ *     conversion between fixed point and fp32), Sec. 4 (8 bits = 4 integer +
+ *     4 fractional for the imbalanced layer) and Sec. 5 (4 bits for GELU, two
+ *     codes stored per byte "using shift operations").
+ *
+ *     FIXED (the paper's algorithm): b = bits, fb = frac_bits,
+ *         code = clamp(round(x * 2^fb), -2^(b-1), 2^(b-1)-1),   x^ = code / 2^fb
+ *       round = half-to-even.  block and scales are ignored (scales may be
+ *       NULL).  -32 <= frac_bits <= 32.
+ *     BLOCK (per-block scale in place of 2^fb): for each run of `block`
+ *       consecutive elements of the flat tensor (the last may be short),
+ *         a = max|x|, inv = qmax / a, scale = a / qmax   (qmax = 2^(b-1)-1)
+ *         code = clamp(round(x * inv), -2^(b-1), qmax),         x^ = code * scale
+ *       all in fp32.  A block with a == 0, or with a so small that qmax / a
+ *       overflows fp32, stores scale 0 and codes 0.  block in {32,64,128,256}.
+ *     bits in {4, 8}.  Codes are two's complement.  8-bit: byte j = code j.
+ *     4-bit: byte m = (code[2m] & 0xF) | (code[2m+1] & 0xF) << 4; an odd n
+ *     leaves the last high nibble 0.
+ *
+ *  x / y  : DEVICE, n elements of dtype dt (bf16 input is widened exactly;
+ *           bf16 output is x^ rounded to nearest-even).
+ *  codes  : DEVICE uint8[slimfit_packed_bytes(n, bits)].
+ *  scales : DEVICE float[slimfit_num_blocks(n, block)] (BLOCK mode).
+ * ---------------------------------------------------------------------- */
+size_t slimfit_packed_bytes(int64_t n, int32_t bits);  /* ceil(n*bits/8); 0 if n<0 or bad bits */
+int64_t slimfit_num_blocks(int64_t n, int32_t block);  /* ceil(n/block);  0 if n<0 or block<=0 */
+
+int32_t slimfit_quant_pack(const void *x, int32_t dt, int64_t n,
+                           int32_t mode, int32_t bits, int32_t block, int32_t frac_bits,
+                           uint8_t *codes, float *scales, void *stream);
+
+int32_t slimfit_dequant_unpack(const uint8_t *codes, const float *scales, int64_t n,
+                               int32_t mode, int32_t bits, int32_t block, int32_t frac_bits,
+                               void *y, int32_t dt, void *stream);
+
+/* ------------------------------------------------------------------------
+ * (c) Pruning to values + indices -- Alg. 5 and the appendix on pruning:
+ *     sort from largest to smallest with indices, keep the first k, store
+ *     them with their indices (the dense size is rows x cols, which the
+ *     caller keeps); restoring creates zeros and scatters the kept values.
+ *     Here the algorithm is applied to each row of a row-major rows x cols
+ *     matrix (attention probabilities: one row per query).
+ *
+ *     The kept set of a row is the first k entries of the order "value
+ *     descending, then column ascending" (signed comparison; -0 equals +0);
+ *     it is emitted in ascending column order.
+ *     TOPK      : exactly k pairs per row.
+ *     THRESHOLD : the first min(k, #{p >= tau}) pairs of the same order;
+ *                 unused slots hold value 0 and index 0xFFFF.
+ *
+ *  p      : DEVICE, rows*cols elements of dt; alignment = element size.
+ *  vals   : DEVICE, rows*k elements of dt, bit copies of the kept inputs.
+ *  idx    : DEVICE uint16[rows*k], column of each kept value.
+ *  counts : DEVICE int32[rows] or NULL; pairs kept per row (k in TOPK mode).
+ *  1 <= k <= cols <= 65536 (else INVALID_ARG / UNSUPPORTED).
+ *
+ *  slimfit_restore_scores is the backward half: out (rows x cols of dt) is
+ *  zero-filled and the first counts[r] (or k when counts is NULL) pairs of
+ *  each row are scattered into it.  An index >= cols is skipped.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_keep_count(int32_t cols, int32_t keep_ppm); /* cols*keep_ppm/1e6, integer; -1 on bad input */
+
+int32_t slimfit_prune_scores(const void *p, int32_t dt, int64_t rows, int32_t cols, int32_t k,
+                             int32_t mode, float tau,
+                             void *vals, uint16_t *idx, int32_t *counts, void *stream);
+
+int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int32_t *counts,
+                               int32_t dt, int64_t rows, int32_t cols, int32_t k,
+                               void *out, void *stream);
+
+/* ------------------------------------------------------------------------
+ * (d) Inter-layer scheduling on the host -- Alg. 1 and Sec. 3.2 / Fig. 4:
+ *        idx = argsort(d)[: int(L*F)]   -> these layers are frozen;
+ *     afterwards only the layers that were active take their new distance,
+ *     frozen layers keep the old one.  Every pointer is a HOST pointer.
+ *
+ *  slimfit_freeze_count : int(L*F) evaluated in double like the pseudo code;
+ *                         -1 if L < 0 or F outside [0, 1].
+ *  slimfit_ils_select   : frozen_idx[0..n_freeze) = the n_freeze layers with
+ *                         the smallest d, smallest first; equal values go by
+ *                         lower index; NaN orders after +inf.  mask (uint8[L]
+ *                         or NULL) gets 1 for frozen, 0 for active.
+ *  slimfit_ils_update   : d[i] = new_scores[i] where frozen_mask[i] == 0.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_freeze_count(int32_t L, double F);
+
+int32_t slimfit_ils_select(const float *d, int32_t L, int32_t n_freeze,
+                           int32_t *frozen_idx, uint8_t *mask);
+
+int32_t slimfit_ils_update(float *d, const float *new_scores,
+                           const uint8_t *frozen_mask, int32_t L);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIMFIT_H */

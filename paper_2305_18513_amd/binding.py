@@ -1,0 +1,263 @@
+"""Thin ctypes binding of ``libslimfit.so`` (see ``include/slimfit.h``).
+
+Argument marshalling only: every step of the hot path runs in the library's
+HIP kernels (or, for the ILS pair, in its host C++).  Functions carry the C
+names without the ``slimfit_`` prefix and take torch tensors for device
+buffers (inputs and caller-allocated outputs) and NumPy arrays / sequences for
+host buffers.  Device work is enqueued on torch's current stream unless a
+stream handle is given.  A non-zero status raises :class:`SlimfitError`.
+There is no fallback: if the library has not been built, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libslimfit.so")
+
+F32, BF16 = 0, 1
+Q_FIXED, Q_BLOCK = 0, 1
+PRUNE_TOPK, PRUNE_THRESHOLD = 0, 1
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_HIP, ERR_POINTER = range(7)
+
+EXPORTS = (
+    "slimfit_status_string", "slimfit_version", "slimfit_set_pointer_checks",
+    "slimfit_layer_delta_workspace", "slimfit_layer_delta_plan",
+    "slimfit_layer_delta_run", "slimfit_layer_delta",
+    "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
+    "slimfit_dequant_unpack", "slimfit_keep_count", "slimfit_prune_scores",
+    "slimfit_restore_scores", "slimfit_freeze_count", "slimfit_ils_select",
+    "slimfit_ils_update",
+)
+
+
+class SlimfitError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def is_built() -> bool:
+    return os.path.exists(LIB_PATH)
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not is_built():
+            raise RuntimeError(
+                "libslimfit.so is missing: build it with "
+                "`python -m paper_2305_18513_amd.build` (there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.slimfit_status_string.restype = C.c_char_p
+        L.slimfit_status_string.argtypes = [C.c_int32]
+        L.slimfit_packed_bytes.restype = C.c_size_t
+        L.slimfit_packed_bytes.argtypes = [C.c_int64, C.c_int32]
+        L.slimfit_num_blocks.restype = C.c_int64
+        L.slimfit_num_blocks.argtypes = [C.c_int64, C.c_int32]
+        L.slimfit_freeze_count.argtypes = [C.c_int32, C.c_double]
+        for name in EXPORTS:
+            fn = getattr(L, name)
+            if fn.restype is C.c_int:          # ctypes default
+                fn.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().slimfit_status_string(C.c_int32(status)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        raise SlimfitError(rc, where)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("expected float32 or bfloat16, got %s" % t.dtype)
+
+
+def _dev(t: Optional[torch.Tensor]):
+    """Raw device address of a contiguous tensor (None -> NULL)."""
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    return C.c_void_p(int(stream))
+
+
+def version() -> int:
+    return lib().slimfit_version()
+
+
+def set_pointer_checks(on: bool) -> bool:
+    return bool(lib().slimfit_set_pointer_checks(C.c_int32(int(bool(on)))))
+
+
+# ---------------------------------------------------------------- (a) Eq. 1
+
+def _numel_array(numel: Sequence[int]):
+    return np.ascontiguousarray(np.asarray(numel, dtype=np.int64))
+
+
+def layer_delta_workspace(numel: Sequence[int]) -> int:
+    n = _numel_array(numel)
+    out = C.c_size_t(0)
+    rc = lib().slimfit_layer_delta_workspace(C.c_int32(n.size), C.c_void_p(n.ctypes.data), C.byref(out))
+    _check(rc, "layer_delta_workspace")
+    return int(out.value)
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    for t in tensors:
+        if not t.is_contiguous():
+            raise ValueError("tensor must be contiguous")
+    return (C.c_void_p * max(1, len(tensors)))(*[t.data_ptr() for t in tensors])
+
+
+def layer_delta_plan(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor],
+                     workspace: torch.Tensor, stream=None) -> None:
+    L = len(w_prev)
+    assert len(w_cur) == L
+    numel = _numel_array([t.numel() for t in w_prev])
+    for a, b in zip(w_prev, w_cur):
+        assert a.numel() == b.numel()
+    pdt = _dt(w_prev[0]) if L else F32
+    cdt = _dt(w_cur[0]) if L else F32
+    rc = lib().slimfit_layer_delta_plan(
+        _ptr_array(w_prev), C.c_int32(pdt), _ptr_array(w_cur), C.c_int32(cdt),
+        C.c_void_p(numel.ctypes.data), C.c_int32(L), _dev(workspace),
+        C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(rc, "layer_delta_plan")
+
+
+def layer_delta_run(numel: Sequence[int], prev_dt: int, cur_dt: int, cur_is_delta: bool,
+                    eps: float, d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    n = _numel_array(numel)
+    assert d_out.dtype == torch.float32 and d_out.numel() >= n.size
+    rc = lib().slimfit_layer_delta_run(
+        C.c_void_p(n.ctypes.data), C.c_int32(n.size), C.c_int32(prev_dt), C.c_int32(cur_dt),
+        C.c_int32(int(bool(cur_is_delta))), C.c_float(eps), _dev(d_out), _dev(workspace),
+        C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(rc, "layer_delta_run")
+
+
+def layer_delta(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor], cur_is_delta: bool,
+                eps: float, d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    L = len(w_prev)
+    assert len(w_cur) == L
+    numel = _numel_array([t.numel() for t in w_prev])
+    pdt = _dt(w_prev[0]) if L else F32
+    cdt = _dt(w_cur[0]) if L else F32
+    assert d_out.dtype == torch.float32 and d_out.numel() >= L
+    rc = lib().slimfit_layer_delta(
+        _ptr_array(w_prev), C.c_int32(pdt), _ptr_array(w_cur), C.c_int32(cdt),
+        C.c_int32(int(bool(cur_is_delta))), C.c_void_p(numel.ctypes.data), C.c_int32(L),
+        C.c_float(eps), _dev(d_out), _dev(workspace),
+        C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(rc, "layer_delta")
+
+
+# ---------------------------------------------------------------- (b) Alg. 2
+
+def packed_bytes(n: int, bits: int) -> int:
+    return int(lib().slimfit_packed_bytes(C.c_int64(n), C.c_int32(bits)))
+
+
+def num_blocks(n: int, block: int) -> int:
+    return int(lib().slimfit_num_blocks(C.c_int64(n), C.c_int32(block)))
+
+
+def quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int,
+               codes: torch.Tensor, scales: Optional[torch.Tensor], stream=None) -> None:
+    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    rc = lib().slimfit_quant_pack(
+        _dev(x), C.c_int32(_dt(x)), C.c_int64(x.numel()), C.c_int32(mode), C.c_int32(bits),
+        C.c_int32(block), C.c_int32(frac_bits), _dev(codes), _dev(scales), _stream(stream))
+    _check(rc, "quant_pack")
+
+
+def dequant_unpack(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: int, bits: int,
+                   block: int, frac_bits: int, y: torch.Tensor, stream=None) -> None:
+    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    rc = lib().slimfit_dequant_unpack(
+        _dev(codes), _dev(scales), C.c_int64(y.numel()), C.c_int32(mode), C.c_int32(bits),
+        C.c_int32(block), C.c_int32(frac_bits), _dev(y), C.c_int32(_dt(y)), _stream(stream))
+    _check(rc, "dequant_unpack")
+
+
+# ---------------------------------------------------------------- (c) Alg. 5
+
+def keep_count(cols: int, keep_ppm: int) -> int:
+    return int(lib().slimfit_keep_count(C.c_int32(cols), C.c_int32(keep_ppm)))
+
+
+def prune_scores(p: torch.Tensor, k: int, mode: int, tau: float, vals: torch.Tensor,
+                 idx: torch.Tensor, counts: Optional[torch.Tensor], stream=None) -> None:
+    assert p.dim() == 2 and vals.dtype == p.dtype and idx.dtype == torch.uint16
+    assert counts is None or counts.dtype == torch.int32
+    rows, cols = p.shape
+    rc = lib().slimfit_prune_scores(
+        _dev(p), C.c_int32(_dt(p)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
+        C.c_int32(mode), C.c_float(tau), _dev(vals), _dev(idx), _dev(counts), _stream(stream))
+    _check(rc, "prune_scores")
+
+
+def restore_scores(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch.Tensor],
+                   out: torch.Tensor, stream=None) -> None:
+    assert out.dim() == 2 and vals.dtype == out.dtype and idx.dtype == torch.uint16
+    rows, cols = out.shape
+    k = vals.shape[1]
+    rc = lib().slimfit_restore_scores(
+        _dev(vals), _dev(idx), _dev(counts), C.c_int32(_dt(out)), C.c_int64(rows),
+        C.c_int32(cols), C.c_int32(k), _dev(out), _stream(stream))
+    _check(rc, "restore_scores")
+
+
+# ---------------------------------------------------------------- (d) Alg. 1 (host)
+
+def freeze_count(L: int, F: float) -> int:
+    return int(lib().slimfit_freeze_count(C.c_int32(L), C.c_double(F)))
+
+
+def ils_select(d: np.ndarray, n_freeze: int):
+    """Returns (frozen_idx int32[n_freeze], mask uint8[L])."""
+    d = np.ascontiguousarray(d, dtype=np.float32)
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(d.size, dtype=np.uint8)
+    rc = lib().slimfit_ils_select(C.c_void_p(d.ctypes.data), C.c_int32(d.size), C.c_int32(n_freeze),
+                                  C.c_void_p(frozen.ctypes.data), C.c_void_p(mask.ctypes.data))
+    _check(rc, "ils_select")
+    return frozen, mask
+
+
+def ils_update(d: np.ndarray, new_scores: np.ndarray, frozen_mask: np.ndarray) -> np.ndarray:
+    """In place on ``d`` (float32, contiguous); returns it."""
+    assert d.dtype == np.float32 and d.flags.c_contiguous
+    new_scores = np.ascontiguousarray(new_scores, dtype=np.float32)
+    frozen_mask = np.ascontiguousarray(frozen_mask, dtype=np.uint8)
+    assert d.size == new_scores.size == frozen_mask.size
+    rc = lib().slimfit_ils_update(C.c_void_p(d.ctypes.data), C.c_void_p(new_scores.ctypes.data),
+                                  C.c_void_p(frozen_mask.ctypes.data), C.c_int32(d.size))
+    _check(rc, "ils_update")
+    return d

@@ -1,0 +1,106 @@
+// Host side of the C ABI: status text, pointer checks and the inter-layer
+// scheduling routines (Alg. 1; Sec. 3.2), which run on the host because the
+// distance vector has one entry per layer (about a hundred).
+#include "common.hpp"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <numeric>
+#include <vector>
+
+namespace slimfit {
+
+static std::atomic<int32_t> g_pointer_checks{1};
+
+int32_t launch_status()
+{
+    return hipGetLastError() == hipSuccess ? SLIMFIT_OK : SLIMFIT_ERR_HIP;
+}
+
+int32_t check_device_range(const void *p, size_t bytes)
+{
+    if (!g_pointer_checks.load(std::memory_order_relaxed) || bytes == 0) return SLIMFIT_OK;
+    if (!p) return SLIMFIT_ERR_INVALID_ARG;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();                 // clear the sticky error of a failed lookup
+        return SLIMFIT_ERR_POINTER;
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) return SLIMFIT_ERR_POINTER;
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) != hipSuccess) {
+        (void)hipGetLastError();
+        return SLIMFIT_ERR_POINTER;
+    }
+    const char *lo = static_cast<const char *>(base);
+    const char *q = static_cast<const char *>(p);
+    if (q < lo || bytes > size || (size_t)(q - lo) > size - bytes) return SLIMFIT_ERR_POINTER;
+    return SLIMFIT_OK;
+}
+
+}  // namespace slimfit
+
+using namespace slimfit;
+
+extern "C" const char *slimfit_status_string(int32_t status)
+{
+    switch (status) {
+    case SLIMFIT_OK: return "ok";
+    case SLIMFIT_ERR_INVALID_ARG: return "invalid argument";
+    case SLIMFIT_ERR_UNSUPPORTED: return "unsupported value";
+    case SLIMFIT_ERR_ALIGNMENT: return "misaligned pointer";
+    case SLIMFIT_ERR_WORKSPACE: return "workspace missing or too small";
+    case SLIMFIT_ERR_HIP: return "HIP runtime error";
+    case SLIMFIT_ERR_POINTER: return "not device memory, or buffer too small for the call";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int32_t slimfit_version(void) { return 100; }   // 0.1.0
+
+extern "C" int32_t slimfit_set_pointer_checks(int32_t on)
+{
+    return g_pointer_checks.exchange(on ? 1 : 0);
+}
+
+extern "C" int32_t slimfit_freeze_count(int32_t L, double F)
+{
+    if (L < 0 || !(F >= 0.0) || !(F <= 1.0)) return -1;
+    const double prod = (double)L * F;            // the pseudo code's L*F in double
+    return (int32_t)prod;                         // int(): truncation
+}
+
+extern "C" int32_t slimfit_ils_select(const float *d, int32_t L, int32_t n_freeze, int32_t *frozen_idx, uint8_t *mask)
+{
+    if (L < 0 || n_freeze < 0 || n_freeze > L) return SLIMFIT_ERR_INVALID_ARG;
+    if ((L > 0 && !d) || (n_freeze > 0 && !frozen_idx)) return SLIMFIT_ERR_INVALID_ARG;
+    if (mask) std::fill(mask, mask + L, (uint8_t)0);
+    if (n_freeze == 0) return SLIMFIT_OK;
+    std::vector<int32_t> order((size_t)L);
+    std::iota(order.begin(), order.end(), 0);
+    // ascending distance, ties by layer index, NaN after everything else
+    auto before = [d](int32_t a, int32_t b) {
+        const bool na = std::isnan(d[a]), nb = std::isnan(d[b]);
+        if (na != nb) return nb;
+        if (!na && d[a] != d[b]) return d[a] < d[b];
+        return a < b;
+    };
+    std::partial_sort(order.begin(), order.begin() + n_freeze, order.end(), before);
+    for (int32_t s = 0; s < n_freeze; ++s) {
+        frozen_idx[s] = order[(size_t)s];
+        if (mask) mask[order[(size_t)s]] = 1;
+    }
+    return SLIMFIT_OK;
+}
+
+extern "C" int32_t slimfit_ils_update(float *d, const float *new_scores, const uint8_t *frozen_mask, int32_t L)
+{
+    if (L < 0) return SLIMFIT_ERR_INVALID_ARG;
+    if (L == 0) return SLIMFIT_OK;
+    if (!d || !new_scores || !frozen_mask) return SLIMFIT_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < L; ++i)
+        if (!frozen_mask[i]) d[i] = new_scores[i];
+    return SLIMFIT_OK;
+}

@@ -1,0 +1,109 @@
+// Shared host/device helpers of the gfx950 kernels (wave64, DPP cross-lane ops).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "slimfit.h"
+
+namespace slimfit {
+
+constexpr int kWave = 64;
+
+// ---- host-side helpers (api.cpp) --------------------------------------------
+int32_t check_device_range(const void *p, size_t bytes);   // pointer checks, see slimfit.h
+int32_t launch_status();                                    // hipGetLastError -> status
+
+inline bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline bool dtype_ok(int32_t dt) { return dt == SLIMFIT_F32 || dt == SLIMFIT_BF16; }
+inline size_t dtype_size(int32_t dt) { return dt == SLIMFIT_F32 ? 4 : 2; }
+
+#if defined(__HIPCC__)
+// ---- DPP lane exchange --------------------------------------------------------
+// A DPP "row" is 16 consecutive lanes.  The controls used here only permute
+// inside a row, so every source lane exists.
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
+}
+
+// max over groups of G consecutive lanes (G = 4..64, power of two); every lane
+// of a group receives the group's result.
+template <int G>
+__device__ __forceinline__ float group_max_f32(float v)
+{
+    static_assert(G == 4 || G == 8 || G == 16 || G == 32 || G == 64, "group size");
+    v = fmaxf(v, dpp_f32<kDppXor1>(v));
+    v = fmaxf(v, dpp_f32<kDppXor2>(v));
+    if (G >= 8) v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+    if (G >= 16) v = fmaxf(v, dpp_f32<kDppMirror>(v));
+    if (G >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    if (G >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+
+// Whole-wave reductions of unsigned keys; the result is wave-uniform (SGPR).
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    v = max(v, dpp_u32<kDppXor1>(v));
+    v = max(v, dpp_u32<kDppXor2>(v));
+    v = max(v, dpp_u32<kDppHalfMirror>(v));
+    v = max(v, dpp_u32<kDppMirror>(v));
+    uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return max(max(a, b), max(c, d));
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+    v = min(v, dpp_u32<kDppXor1>(v));
+    v = min(v, dpp_u32<kDppXor2>(v));
+    v = min(v, dpp_u32<kDppHalfMirror>(v));
+    v = min(v, dpp_u32<kDppMirror>(v));
+    uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return min(min(a, b), min(c, d));
+}
+
+// number of set bits of `mask` strictly below this lane
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// ---- bf16 -----------------------------------------------------------------------
+__device__ __forceinline__ float bf16_widen(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
+
+// fp32 -> bf16, round to nearest even (finite inputs; NaN keeps a NaN pattern)
+__device__ __forceinline__ uint32_t bf16_narrow(float f)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : r;
+}
+
+// Order-preserving map float -> uint32 (larger float <=> larger key) and back.
+__device__ __forceinline__ uint32_t float_to_key(float f)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k)
+{
+    uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+    return __builtin_bit_cast(float, u);
+}
+#endif  // __HIPCC__
+
+}  // namespace slimfit

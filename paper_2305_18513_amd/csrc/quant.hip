@@ -1,0 +1,290 @@
+// Low-bit caching of saved activations (Alg. 2; Sec. 4 and 5): fused
+// quantise + pack and unpack + dequantise for gfx950.
+//
+// Layout: every lane owns one 16-byte vector of the flat tensor (4 fp32 or
+// 8 bf16 elements) per step; consecutive lanes own consecutive vectors, so a
+// wave's load is one contiguous 1 KiB run.  A quantisation block of `block`
+// elements is therefore G = block / V consecutive lanes, and the block's
+// absolute maximum is a DPP butterfly over those lanes -- no LDS, no second
+// pass over the data.  A workgroup covers kUnroll such steps so that each lane
+// has kUnroll independent 128-bit loads in flight.
+#include "common.hpp"
+
+namespace slimfit {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+    static constexpr int V = 4;
+    using raw = float4;
+    __device__ static void unpack(const raw &r, float (&f)[4]) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
+    __device__ static raw pack(const float (&f)[4]) { return make_float4(f[0], f[1], f[2], f[3]); }
+    __device__ static float load1(const float *p) { return *p; }
+    __device__ static void store1(float *p, float v) { *p = v; }
+};
+template <> struct Vec<uint16_t> {   // bf16 bit patterns
+    static constexpr int V = 8;
+    using raw = uint4;
+    __device__ static void unpack(const raw &r, float (&f)[8])
+    {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+            f[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static raw pack(const float (&f)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = bf16_narrow(f[2 * i]) | (bf16_narrow(f[2 * i + 1]) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    __device__ static float load1(const uint16_t *p) { return bf16_widen(*p); }
+    __device__ static void store1(uint16_t *p, float v) { *p = (uint16_t)bf16_narrow(v); }
+};
+
+// code = clamp(round_half_even(x * mult), qmin, qmax) -- one fp32 multiply
+template <int BITS>
+__device__ __forceinline__ int quantise_one(float x, float mult)
+{
+    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+    constexpr float qmin = -(float)(1 << (BITS - 1));
+    float r = __builtin_rintf(x * mult);
+    r = fminf(fmaxf(r, qmin), qmax);
+    return (int)r;
+}
+
+// T: element type, BITS: 4|8, BLOCKED: per-block scale, G: lanes per block
+template <typename T, int BITS, bool BLOCKED, int G>
+__global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restrict__ x, int64_t n, float fixed_mult,
+                                                              uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    constexpr int V = Vec<T>::V;
+    constexpr int OUT_BYTES = V * BITS / 8;            // packed bytes per lane-vector: 2, 4 or 8
+    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+    const int64_t first_vec = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+
+    float f[kUnroll][V];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+        if (e0 + V <= n) {
+            typename Vec<T>::raw r = *reinterpret_cast<const typename Vec<T>::raw *>(x + e0);
+            Vec<T>::unpack(r, f[u]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) f[u][i] = (e0 + i < n) ? Vec<T>::load1(x + e0 + i) : 0.0f;
+        }
+    }
+
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+        float mult = fixed_mult;
+        if (BLOCKED) {
+            float a = 0.0f;
+#pragma unroll
+            for (int i = 0; i < V; ++i) a = fmaxf(a, fabsf(f[u][i]));
+            a = group_max_f32<G>(a);                   // all lanes take part (no divergence above)
+            float inv = 0.0f, scale = 0.0f;
+            if (a > 0.0f) {
+                inv = qmax / a;                        // IEEE fp32 division
+                if (__builtin_isinf(inv)) inv = 0.0f;
+                else scale = a / qmax;                 // IEEE fp32 division
+            }
+            mult = inv;
+            if ((threadIdx.x & (G - 1)) == 0 && e0 < n) scales[e0 / (V * G)] = scale;
+        }
+        if (e0 >= n) continue;
+
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const uint32_t c = (uint32_t)quantise_one<BITS>(f[u][i], mult) & ((1u << BITS) - 1u);
+            w[(i * BITS) / 32] |= c << ((i * BITS) % 32);
+        }
+        uint8_t *dst = codes + (e0 * BITS) / 8;
+        if (e0 + V <= n) {
+            if (OUT_BYTES == 2) *reinterpret_cast<uint16_t *>(dst) = (uint16_t)w[0];
+            else if (OUT_BYTES == 4) *reinterpret_cast<uint32_t *>(dst) = w[0];
+            else *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
+        } else {
+            const int nbytes = (int)(((n - e0) * BITS + 7) / 8);   // elements past n quantised 0
+            for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+        }
+    }
+}
+
+template <typename T, int BITS, bool BLOCKED>
+__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
+                                                                  const float *__restrict__ scales, int64_t n,
+                                                                  int block, float fixed_step, T *__restrict__ y)
+{
+    constexpr int V = Vec<T>::V;
+    constexpr int IN_BYTES = V * BITS / 8;
+    const int64_t first_vec = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+
+    uint32_t w[kUnroll][2];
+    float s[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+        w[u][0] = w[u][1] = 0u;
+        s[u] = fixed_step;
+        if (e0 >= n) continue;
+        const uint8_t *src = codes + (e0 * BITS) / 8;
+        if (e0 + V <= n) {
+            if (IN_BYTES == 2) w[u][0] = *reinterpret_cast<const uint16_t *>(src);
+            else if (IN_BYTES == 4) w[u][0] = *reinterpret_cast<const uint32_t *>(src);
+            else { uint2 t = *reinterpret_cast<const uint2 *>(src); w[u][0] = t.x; w[u][1] = t.y; }
+        } else {
+            const int nbytes = (int)(((n - e0) * BITS + 7) / 8);
+            for (int b = 0; b < nbytes; ++b) w[u][b / 4] |= (uint32_t)src[b] << (8 * (b % 4));
+        }
+        if (BLOCKED) s[u] = scales[e0 / block];
+    }
+
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+        if (e0 >= n) continue;
+        float f[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const uint32_t word = w[u][(i * BITS) / 32];
+            const int sh = (i * BITS) % 32;
+            const int c = (int)(word << (32 - BITS - sh)) >> (32 - BITS);   // sign-extending field extract
+            f[i] = (float)c * s[u];                                        // one fp32 multiply
+        }
+        if (e0 + V <= n) {
+            *reinterpret_cast<typename Vec<T>::raw *>(y + e0) = Vec<T>::pack(f);
+        } else {
+            for (int i = 0; i < V && e0 + i < n; ++i) Vec<T>::store1(y + e0 + i, f[i]);
+        }
+    }
+}
+
+inline unsigned grid_for(int64_t n, int V)
+{
+    const int64_t per_block = (int64_t)kThreads * kUnroll * V;
+    return (unsigned)((n + per_block - 1) / per_block);
+}
+
+template <typename T, int BITS>
+void launch_quant(const void *x, int64_t n, int mode, int block, int frac_bits, uint8_t *codes, float *scales,
+                  hipStream_t st)
+{
+    constexpr int V = Vec<T>::V;
+    const dim3 grid(grid_for(n, V)), tb(kThreads);
+    const T *xp = static_cast<const T *>(x);
+    if (mode == SLIMFIT_Q_FIXED) {
+        quant_pack_kernel<T, BITS, false, 4><<<grid, tb, 0, st>>>(xp, n, __builtin_ldexpf(1.0f, frac_bits), codes, nullptr);
+        return;
+    }
+    switch (block / V) {
+    case 4: quant_pack_kernel<T, BITS, true, 4><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
+    case 8: quant_pack_kernel<T, BITS, true, 8><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
+    case 16: quant_pack_kernel<T, BITS, true, 16><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
+    case 32: quant_pack_kernel<T, BITS, true, 32><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
+    default: quant_pack_kernel<T, BITS, true, 64><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
+    }
+}
+
+template <typename T, int BITS>
+void launch_dequant(const uint8_t *codes, const float *scales, int64_t n, int mode, int block, int frac_bits, void *y,
+                    hipStream_t st)
+{
+    constexpr int V = Vec<T>::V;
+    const dim3 grid(grid_for(n, V)), tb(kThreads);
+    T *yp = static_cast<T *>(y);
+    if (mode == SLIMFIT_Q_FIXED)
+        dequant_unpack_kernel<T, BITS, false><<<grid, tb, 0, st>>>(codes, nullptr, n, 1, __builtin_ldexpf(1.0f, -frac_bits), yp);
+    else
+        dequant_unpack_kernel<T, BITS, true><<<grid, tb, 0, st>>>(codes, scales, n, block, 0.0f, yp);
+}
+
+int32_t validate(int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block, int32_t frac_bits)
+{
+    if (!dtype_ok(dt) || n < 0) return SLIMFIT_ERR_INVALID_ARG;
+    if (mode != SLIMFIT_Q_FIXED && mode != SLIMFIT_Q_BLOCK) return SLIMFIT_ERR_INVALID_ARG;
+    if (bits != 4 && bits != 8) return SLIMFIT_ERR_UNSUPPORTED;
+    if (mode == SLIMFIT_Q_FIXED && (frac_bits < -32 || frac_bits > 32)) return SLIMFIT_ERR_UNSUPPORTED;
+    if (mode == SLIMFIT_Q_BLOCK && block != 32 && block != 64 && block != 128 && block != 256)
+        return SLIMFIT_ERR_UNSUPPORTED;
+    // grid = ceil(n / 4096 or 8192) must fit an unsigned 31-bit launch dimension
+    if (n > ((int64_t)1 << 42)) return SLIMFIT_ERR_UNSUPPORTED;
+    return SLIMFIT_OK;
+}
+
+}  // namespace
+}  // namespace slimfit
+
+using namespace slimfit;
+
+extern "C" size_t slimfit_packed_bytes(int64_t n, int32_t bits)
+{
+    if (n < 0 || (bits != 4 && bits != 8)) return 0;
+    return (size_t)((n * bits + 7) / 8);
+}
+
+extern "C" int64_t slimfit_num_blocks(int64_t n, int32_t block)
+{
+    if (n < 0 || block <= 0) return 0;
+    return (n + block - 1) / block;
+}
+
+extern "C" int32_t slimfit_quant_pack(const void *x, int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block,
+                                      int32_t frac_bits, uint8_t *codes, float *scales, void *stream)
+{
+    int32_t rc = validate(dt, n, mode, bits, block, frac_bits);
+    if (rc != SLIMFIT_OK) return rc;
+    if (n == 0) return SLIMFIT_OK;
+    if (!x || !codes || (mode == SLIMFIT_Q_BLOCK && !scales)) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(x, 16) || !aligned_to(codes, 16) || (mode == SLIMFIT_Q_BLOCK && !aligned_to(scales, 16)))
+        return SLIMFIT_ERR_ALIGNMENT;
+    if ((rc = check_device_range(x, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(codes, slimfit_packed_bytes(n, bits))) != SLIMFIT_OK) return rc;
+    if (mode == SLIMFIT_Q_BLOCK &&
+        (rc = check_device_range(scales, (size_t)slimfit_num_blocks(n, block) * 4)) != SLIMFIT_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == SLIMFIT_F32) {
+        if (bits == 4) launch_quant<float, 4>(x, n, mode, block, frac_bits, codes, scales, st);
+        else launch_quant<float, 8>(x, n, mode, block, frac_bits, codes, scales, st);
+    } else {
+        if (bits == 4) launch_quant<uint16_t, 4>(x, n, mode, block, frac_bits, codes, scales, st);
+        else launch_quant<uint16_t, 8>(x, n, mode, block, frac_bits, codes, scales, st);
+    }
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_dequant_unpack(const uint8_t *codes, const float *scales, int64_t n, int32_t mode,
+                                          int32_t bits, int32_t block, int32_t frac_bits, void *y, int32_t dt,
+                                          void *stream)
+{
+    int32_t rc = validate(dt, n, mode, bits, block, frac_bits);
+    if (rc != SLIMFIT_OK) return rc;
+    if (n == 0) return SLIMFIT_OK;
+    if (!y || !codes || (mode == SLIMFIT_Q_BLOCK && !scales)) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(y, 16) || !aligned_to(codes, 16) || (mode == SLIMFIT_Q_BLOCK && !aligned_to(scales, 16)))
+        return SLIMFIT_ERR_ALIGNMENT;
+    if ((rc = check_device_range(y, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(codes, slimfit_packed_bytes(n, bits))) != SLIMFIT_OK) return rc;
+    if (mode == SLIMFIT_Q_BLOCK &&
+        (rc = check_device_range(scales, (size_t)slimfit_num_blocks(n, block) * 4)) != SLIMFIT_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == SLIMFIT_F32) {
+        if (bits == 4) launch_dequant<float, 4>(codes, scales, n, mode, block, frac_bits, y, st);
+        else launch_dequant<float, 8>(codes, scales, n, mode, block, frac_bits, y, st);
+    } else {
+        if (bits == 4) launch_dequant<uint16_t, 4>(codes, scales, n, mode, block, frac_bits, y, st);
+        else launch_dequant<uint16_t, 8>(codes, scales, n, mode, block, frac_bits, y, st);
+    }
+    return launch_status();
+}

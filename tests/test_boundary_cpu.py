@@ -1,0 +1,190 @@
+"""Host-only tests of the C-ABI library: it loads, exports what the header
+declares, rejects bad arguments before touching a GPU, and its host-side ILS
+routines agree with the oracle and with the paper's Fig. 4."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2305_18513_amd import binding as sf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not sf.is_built():
+        from paper_2305_18513_amd import build
+        build.build_library(verbose=False)
+    return sf.lib()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "slimfit.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slimfit_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = _declared()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(sf.EXPORTS) == names
+
+
+def test_status_strings_and_version(lib):
+    assert sf.version() >= 100
+    texts = {sf.status_string(s) for s in range(7)}
+    assert len(texts) == 7 and "ok" in texts
+    assert sf.status_string(99) == "unknown status"
+
+
+def test_size_helpers(lib):
+    assert sf.packed_bytes(0, 4) == 0 and sf.packed_bytes(5, 4) == 3 and sf.packed_bytes(5, 8) == 5
+    assert sf.packed_bytes(5, 3) == 0 and sf.packed_bytes(-1, 4) == 0
+    assert sf.num_blocks(0, 64) == 0 and sf.num_blocks(65, 64) == 2 and sf.num_blocks(64, 64) == 1
+    for cols, ppm in ((64, 100000), (128, 100000), (197, 50000), (384, 100000), (577, 100000)):
+        assert sf.keep_count(cols, ppm) == ref.keep_count(cols, ppm) == int(cols * ppm / 1e6)
+    assert sf.keep_count(10, 2000000) == -1
+    for L in (0, 8, 16, 96, 100, 192):
+        for F in (0.0, 0.5, 0.8, 0.9, 0.95, 1.0):
+            assert sf.freeze_count(L, F) == int(L * F) == ref.freeze_count(L, F)
+    assert sf.freeze_count(8, 1.5) == -1 and sf.freeze_count(-1, 0.5) == -1
+
+
+def _quant(lib, x=16, dt=0, n=64, mode=1, bits=4, block=64, fb=0, codes=16, scales=16):
+    return lib.slimfit_quant_pack(C.c_void_p(x), C.c_int32(dt), C.c_int64(n), C.c_int32(mode),
+                                  C.c_int32(bits), C.c_int32(block), C.c_int32(fb),
+                                  C.c_void_p(codes), C.c_void_p(scales), C.c_void_p(0))
+
+
+def test_quant_argument_errors_return_before_any_launch(lib):
+    assert _quant(lib, n=0) == sf.OK                          # empty is a no-op
+    assert _quant(lib, n=-1) == sf.ERR_INVALID_ARG
+    assert _quant(lib, dt=7) == sf.ERR_INVALID_ARG
+    assert _quant(lib, mode=2) == sf.ERR_INVALID_ARG
+    assert _quant(lib, bits=5) == sf.ERR_UNSUPPORTED
+    assert _quant(lib, block=48) == sf.ERR_UNSUPPORTED
+    assert _quant(lib, mode=0, fb=40) == sf.ERR_UNSUPPORTED
+    assert _quant(lib, x=0) == sf.ERR_INVALID_ARG
+    assert _quant(lib, scales=0) == sf.ERR_INVALID_ARG
+    assert _quant(lib, x=20) == sf.ERR_ALIGNMENT
+    assert _quant(lib, codes=8) == sf.ERR_ALIGNMENT
+    rc = lib.slimfit_dequant_unpack(C.c_void_p(16), C.c_void_p(16), C.c_int64(64), C.c_int32(1),
+                                    C.c_int32(8), C.c_int32(100), C.c_int32(0), C.c_void_p(16),
+                                    C.c_int32(0), C.c_void_p(0))
+    assert rc == sf.ERR_UNSUPPORTED
+    rc = lib.slimfit_dequant_unpack(C.c_void_p(16), C.c_void_p(16), C.c_int64(64), C.c_int32(1),
+                                    C.c_int32(8), C.c_int32(64), C.c_int32(0), C.c_void_p(0),
+                                    C.c_int32(0), C.c_void_p(0))
+    assert rc == sf.ERR_INVALID_ARG
+
+
+def _prune(lib, p=16, dt=0, rows=4, cols=64, k=6, mode=0, vals=16, idx=16, counts=0):
+    return lib.slimfit_prune_scores(C.c_void_p(p), C.c_int32(dt), C.c_int64(rows), C.c_int32(cols),
+                                    C.c_int32(k), C.c_int32(mode), C.c_float(0.0), C.c_void_p(vals),
+                                    C.c_void_p(idx), C.c_void_p(counts), C.c_void_p(0))
+
+
+def test_prune_argument_errors(lib):
+    assert _prune(lib, rows=0) == sf.OK
+    assert _prune(lib, k=0) == sf.ERR_INVALID_ARG
+    assert _prune(lib, k=65) == sf.ERR_INVALID_ARG
+    assert _prune(lib, cols=0) == sf.ERR_INVALID_ARG
+    assert _prune(lib, cols=65537, k=5) == sf.ERR_UNSUPPORTED
+    assert _prune(lib, mode=4) == sf.ERR_INVALID_ARG
+    assert _prune(lib, rows=-2) == sf.ERR_INVALID_ARG
+    assert _prune(lib, p=0) == sf.ERR_INVALID_ARG
+    assert _prune(lib, p=18) == sf.ERR_ALIGNMENT                # fp32 needs 4-byte alignment
+    assert _prune(lib, idx=17) == sf.ERR_ALIGNMENT
+    rc = lib.slimfit_restore_scores(C.c_void_p(16), C.c_void_p(16), C.c_void_p(0), C.c_int32(0),
+                                    C.c_int64(4), C.c_int32(64), C.c_int32(6), C.c_void_p(8),
+                                    C.c_void_p(0))
+    assert rc == sf.ERR_ALIGNMENT
+
+
+def test_layer_delta_argument_errors(lib):
+    numel = np.array([100, 0, 5000], dtype=np.int64)
+    assert sf.layer_delta_workspace(numel) >= 64 + 3 * 32 + 8 * 2
+    assert sf.layer_delta_workspace([]) >= 64
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.layer_delta_workspace([5, -1])
+    assert e.value.status == sf.ERR_INVALID_ARG
+    ptrs = (C.c_void_p * 3)(256, 0, 512)
+    n = C.c_void_p(numel.ctypes.data)
+
+    def plan(ws=256, ws_bytes=1 << 20, prev=ptrs, dt=0, L=3):
+        return lib.slimfit_layer_delta_plan(prev, C.c_int32(dt), ptrs, C.c_int32(0), n, C.c_int32(L),
+                                            C.c_void_p(ws), C.c_size_t(ws_bytes), C.c_void_p(0))
+
+    assert plan(L=0) == sf.OK
+    assert plan(L=-1) == sf.ERR_INVALID_ARG
+    assert plan(dt=3) == sf.ERR_INVALID_ARG
+    assert plan(ws=0) == sf.ERR_WORKSPACE
+    assert plan(ws_bytes=64) == sf.ERR_WORKSPACE
+    assert plan(ws=264) == sf.ERR_ALIGNMENT
+    assert plan(prev=(C.c_void_p * 3)(0, 0, 512)) == sf.ERR_INVALID_ARG     # non-empty layer, NULL
+    assert plan(prev=(C.c_void_p * 3)(260, 0, 512)) == sf.ERR_ALIGNMENT
+    rc = lib.slimfit_layer_delta_run(n, C.c_int32(3), C.c_int32(0), C.c_int32(0), C.c_int32(0),
+                                     C.c_float(-1.0), C.c_void_p(256), C.c_void_p(256),
+                                     C.c_size_t(1 << 20), C.c_void_p(0))
+    assert rc == sf.ERR_INVALID_ARG                                         # negative eps
+    rc = lib.slimfit_layer_delta_run(n, C.c_int32(3), C.c_int32(0), C.c_int32(0), C.c_int32(0),
+                                     C.c_float(0.0), C.c_void_p(0), C.c_void_p(256),
+                                     C.c_size_t(1 << 20), C.c_void_p(0))
+    assert rc == sf.ERR_INVALID_ARG                                         # d_out NULL
+
+
+def test_ils_fig4_replay_through_the_library(lib, golden_dir):
+    rows = []
+    with open(os.path.join(golden_dir, "fig4_ils.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                _, d, frozen = [s.strip() for s in line.split("|")]
+                rows.append((np.array(d.split(), dtype=np.float32),
+                             sorted(int(s) - 1 for s in frozen.split())))
+    d = rows[0][0].copy()
+    n_freeze = sf.freeze_count(8, 0.5)
+    assert n_freeze == 4
+    for step in range(3):
+        idx, mask = sf.ils_select(d, n_freeze)
+        assert sorted(idx.tolist()) == rows[step][1]
+        if step < 2:
+            new = np.where(mask == 1, np.float32(1e9), rows[step + 1][0]).astype(np.float32)
+            sf.ils_update(d, new, mask)
+            np.testing.assert_array_equal(d, rows[step + 1][0])
+
+
+def test_ils_matches_oracle_bit_exact(lib):
+    rng = np.random.default_rng(0)
+    for L in (1, 2, 16, 96, 192, 198):
+        for trial in range(4):
+            d = (rng.integers(0, 20, L) / 8).astype(np.float32)        # many ties
+            if trial == 3 and L > 4:
+                d[rng.integers(0, L, 3)] = np.nan
+                d[rng.integers(0, L)] = np.inf
+            for n in {0, 1, L // 2, int(L * 0.95), L}:
+                gi, gm = sf.ils_select(d, n)
+                oi, om = ref.ils_select(d, n)
+                np.testing.assert_array_equal(gi, oi)
+                np.testing.assert_array_equal(gm, om)
+            mask = (rng.random(L) < 0.5).astype(np.uint8)
+            new = rng.random(L).astype(np.float32)
+            got = sf.ils_update(d.copy(), new, mask)
+            np.testing.assert_array_equal(got, ref.ils_update(d, new, mask))
+
+
+def test_ils_argument_errors(lib):
+    d = np.zeros(4, dtype=np.float32)
+    for n in (-1, 5):
+        with pytest.raises(sf.SlimfitError) as e:
+            sf.ils_select(d, n)
+        assert e.value.status == sf.ERR_INVALID_ARG
+    rc = lib.slimfit_ils_select(C.c_void_p(0), C.c_int32(4), C.c_int32(2), C.c_void_p(0), C.c_void_p(0))
+    assert rc == sf.ERR_INVALID_ARG
+    assert lib.slimfit_ils_update(C.c_void_p(0), C.c_void_p(0), C.c_void_p(0), C.c_int32(0)) == sf.OK
+    assert lib.slimfit_ils_update(C.c_void_p(0), C.c_void_p(0), C.c_void_p(0), C.c_int32(3)) == sf.ERR_INVALID_ARG

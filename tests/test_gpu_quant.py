@@ -1,0 +1,129 @@
+"""GPU parity: slimfit_quant_pack / slimfit_dequant_unpack vs the CPU oracle.
+Codes, scales and dequantised values must be bit-identical."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2305_18513_amd import binding as sf
+from paper_2305_18513_amd import synth
+from tests.gpu_util import Guarded, require_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_both(x: torch.Tensor, mode, bits, block, fb):
+    """x: flat device tensor.  Runs GPU and oracle, asserts bit equality, returns codes."""
+    n = x.numel()
+    codes = Guarded(sf.packed_bytes(n, bits), torch.uint8)
+    scales = Guarded(sf.num_blocks(n, block) if mode == sf.Q_BLOCK else 0, torch.float32)
+    sf.quant_pack(x, mode, bits, block, fb, codes.t, scales.t if mode == sf.Q_BLOCK else None)
+    y = Guarded(n, x.dtype)
+    sf.dequant_unpack(codes.t, scales.t if mode == sf.Q_BLOCK else None, mode, bits, block, fb, y.t)
+    torch.cuda.synchronize()
+    codes.check(); scales.check(); y.check()
+
+    xh = to_np(x)
+    oc, osc = ref.quant_pack(xh, mode=mode, bits=bits, block=block, frac_bits=fb, threads=4)
+    np.testing.assert_array_equal(to_np(codes.t), oc)
+    if mode == sf.Q_BLOCK:
+        np.testing.assert_array_equal(to_np(scales.t).view(np.uint32), osc.view(np.uint32))
+    oy = ref.dequant_unpack(oc, osc, n, mode=mode, bits=bits, block=block, frac_bits=fb,
+                            out_dtype=xh.dtype, threads=4)
+    gy = to_np(y.t)
+    if xh.dtype == np.float32:
+        np.testing.assert_array_equal(gy.view(np.uint32), oy.view(np.uint32))
+    else:
+        np.testing.assert_array_equal(gy, oy)
+    return oc
+
+
+SIZES = [1, 2, 3, 7, 31, 32, 33, 63, 64, 65, 255, 256, 257, 1023, 4096, 4097, 8191,
+         3 * 8192 + 37, 100003]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+def test_block_mode_sizes(dtype, bits, block):
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(bits * 1000 + block)
+    for n in SIZES:
+        x = torch.randn(n, generator=g, device="cuda")
+        x = torch.where(torch.rand(n, generator=g, device="cuda") < 0.01, x * 20, x).to(dtype)
+        _run_both(x, sf.Q_BLOCK, bits, block, 0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bits,fb", [(8, 4), (4, 2), (4, 0), (8, 7), (8, 0), (8, -3)])
+def test_fixed_mode_incl_halfway_points(dtype, bits, fb):
+    require_gpu()
+    step = 2.0 ** -fb
+    kk = torch.arange(-300, 301, dtype=torch.float64)
+    pts = torch.cat([kk * step, kk * step + step / 2, kk * step + step / 2 * (1 + 2 ** -20),
+                     kk * step + step / 2 * (1 - 2 ** -20), kk * step - step / 4,
+                     torch.tensor([0.0, -0.0, 1e-45, -1e-45, 1e-39, 3e38, -3e38])])
+    x = pts.to(torch.float32).to(dtype).cuda()
+    _run_both(x, sf.Q_FIXED, bits, 64, fb)
+    g = torch.Generator(device="cuda").manual_seed(fb + 100)
+    for n in (5, 4099, 65537):
+        _run_both((torch.randn(n, generator=g, device="cuda") * 3).to(dtype), sf.Q_FIXED, bits, 64, fb)
+
+
+def test_degenerate_blocks_and_denormals():
+    require_gpu()
+    x = torch.zeros(64 * 6 + 10, dtype=torch.float32)
+    x[64:128] = 1e-39                                # 8-bit: 127/1e-39 overflows -> zero block
+    x[128:192] = torch.linspace(-1e-37, 1e-37, 64)   # tiny but representable
+    x[192:256] = torch.linspace(-3e-39, 3e-39, 64)   # denormal block
+    x[256:320] = 3.0e38
+    x[320:384] = -0.0
+    x[384:] = 1e-30
+    for bits in (4, 8):
+        oc = _run_both(x.cuda(), sf.Q_BLOCK, bits, 64, 0)
+        assert oc.any()
+    _run_both(x.cuda(), sf.Q_FIXED, 8, 64, 4)
+
+
+@pytest.mark.parametrize("ci", [0])
+def test_config0_tensors(ci):
+    require_gpu()
+    cfg = synth.CONFIGS[ci]
+    for kind in ("gelu_in", "ln_in"):
+        for blk in range(cfg.n_blocks):
+            x = synth.activation(cfg, kind, device="cuda", block=blk).reshape(-1)
+            _run_both(x, sf.Q_BLOCK, 4, 64, 0)
+    x = synth.activation(cfg, "gelu_in", device="cuda").reshape(-1)
+    _run_both(x, sf.Q_FIXED, 8, 64, 4)               # the paper's 4.4 format saturates the x20 outliers
+
+
+def test_heavy_tailed_channels_8bit_and_bf16_block32():
+    require_gpu()
+    v = synth.CONFIGS[2]
+    x = synth.activation(v, "gelu_in", device="cuda", batch=2).reshape(-1)       # 197 tokens
+    for bits in v.quant_bits:
+        _run_both(x, sf.Q_BLOCK, bits, 64, 0)
+    w = synth.CONFIGS[4]
+    xb = synth.activation(w, "ln_in", device="cuda", batch=3).reshape(-1)
+    assert xb.dtype == torch.bfloat16
+    _run_both(xb, sf.Q_BLOCK, 4, 32, 0)
+
+
+def test_pointer_checks_reject_host_memory_and_short_buffers():
+    require_gpu()
+    x = torch.randn(4096, device="cuda")
+    codes = torch.empty(2048, dtype=torch.uint8, device="cuda")
+    scales = torch.empty(64, dtype=torch.float32, device="cuda")
+    host = torch.randn(4096)
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.quant_pack(host, sf.Q_BLOCK, 4, 64, 0, codes, scales)
+    assert e.value.status == sf.ERR_POINTER
+    # claim far more elements than the allocation holds
+    import ctypes as C
+    rc = sf.lib().slimfit_quant_pack(C.c_void_p(x.data_ptr()), C.c_int32(0), C.c_int64(1 << 34),
+                                     C.c_int32(1), C.c_int32(4), C.c_int32(64), C.c_int32(0),
+                                     C.c_void_p(codes.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                     C.c_void_p(0))
+    assert rc == sf.ERR_POINTER
+    sf.quant_pack(x, sf.Q_BLOCK, 4, 64, 0, codes, scales)      # still usable afterwards
+    torch.cuda.synchronize()
