@@ -39,9 +39,9 @@ def hipcc() -> str:
     return exe
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, extra_flags=(), obj_dir: str = OBJ_DIR) -> str:
+    obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops' is not a recognized feature"
     err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
@@ -52,18 +52,23 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile every source and link the shared library.  Always rebuilds."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build_library(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
+    """Compile every source and link the shared library.  Always rebuilds.
+
+    ``extra_flags`` (e.g. ``-DSLIMFIT_QUANT_UNROLL=2``) and ``out`` exist for
+    tuning sweeps; the defaults build the library the binding loads.
+    """
+    obj_dir = OBJ_DIR if out == LIB else out + ".obj"
+    os.makedirs(obj_dir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    tmp = LIB + ".tmp.%d" % os.getpid()
+        objs = list(pool.map(lambda s: _compile(s, tuple(extra_flags), obj_dir), SOURCES))
+    tmp = out + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
+    os.replace(tmp, out)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":

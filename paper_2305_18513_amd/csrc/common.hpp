@@ -19,6 +19,23 @@ inline bool dtype_ok(int32_t dt) { return dt == SLIMFIT_F32 || dt == SLIMFIT_BF1
 inline size_t dtype_size(int32_t dt) { return dt == SLIMFIT_F32 ? 4 : 2; }
 
 #if defined(__HIPCC__)
+// ---- 128/64-bit global access, optionally non-temporal (streamed once) ----------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <bool NT, typename V>
+__device__ __forceinline__ V load_global(const V *p)
+{
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void store_global(V *p, V v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 // ---- DPP lane exchange --------------------------------------------------------
 // A DPP "row" is 16 consecutive lanes.  The controls used here only permute
 // inside a row, so every source lane exists.

@@ -24,6 +24,10 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
 constexpr int kMaxRegSlots = 16;             // register path: cols <= 64 * 16
+#ifndef SLIMFIT_PRUNE_BLOCKS
+#define SLIMFIT_PRUNE_BLOCKS 8192
+#endif
+constexpr int64_t kMaxPruneBlocks = SLIMFIT_PRUNE_BLOCKS;
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -42,117 +46,323 @@ __device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(
 // ---------------------------------------------------------------------------
 // register path: one wave per row, M slots per lane
 // ---------------------------------------------------------------------------
-template <typename T, int M>
+//
+// Finding the cut value T (the k-th largest entry of the row):
+//   1. lane-local, then wave-wide minimum and maximum (DPP butterflies);
+//   2. a 256-bin histogram of the row in the wave's private LDS region, bins
+//      of equal width in the order-preserving integer image of the floats,
+//      bin 0 holding the largest values (ds_add, one per element);
+//   3. a wave prefix sum over the bins locates the bin that holds the k-th
+//      largest entry; if the entries above that bin plus the bin's own are
+//      exactly k, its lower edge separates the kept set and the search is over
+//      (about half of all softmax rows);
+//   4. otherwise a bisection inside that bin (1/256 of the row's range; one or
+//      two probes on average), each probe one v_cmp per held element whose
+//      lane mask is popcounted on the scalar unit, ending as soon as a probe is
+//      passed by exactly k entries or the bracket is a single value (ties).
+// Survivors are compacted in ascending column order with mask-prefix counts
+// (mbcnt), staged through LDS when k <= 64 so that a row's output leaves as
+// two coalesced stores.
+constexpr int kBins = 256;
+constexpr int kStage = 64;           // largest k whose output is staged in LDS
+constexpr int kRowsPerUnit = 8;      // consecutive rows a wave stages before it stores them
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_keep_f32(float v)      // lanes outside ROW_MASK keep their value
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF,
+                                           false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_zero_i32(int v)          // absent sources contribute 0
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false);
+}
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;
+
+// wave-wide maximum of unsigned keys, result uniform.  Sources that a DPP
+// control does not reach contribute 0, the identity of an unsigned max.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_zero_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ uint32_t wave_umax(uint32_t v)
+{
+    v = max(v, dpp_zero_u32<kDppXor1, 0xF>(v));
+    v = max(v, dpp_zero_u32<kDppXor2, 0xF>(v));
+    v = max(v, dpp_zero_u32<kDppHalfMirror, 0xF>(v));
+    v = max(v, dpp_zero_u32<kDppMirror, 0xF>(v));
+    v = max(v, dpp_zero_u32<kDppBcast15, 0xA>(v));
+    v = max(v, dpp_zero_u32<kDppBcast31, 0xC>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int wave_scan_i32(int v)
+{
+    v += dpp_zero_i32<kDppRowShr1, 0xF>(v);
+    v += dpp_zero_i32<kDppRowShr2, 0xF>(v);
+    v += dpp_zero_i32<kDppRowShr4, 0xF>(v);
+    v += dpp_zero_i32<kDppRowShr8, 0xF>(v);
+    v += dpp_zero_i32<kDppBcast15, 0xA>(v);
+    v += dpp_zero_i32<kDppBcast31, 0xC>(v);
+    return v;
+}
+
+#ifndef SLIMFIT_PRUNE_NT
+#define SLIMFIT_PRUNE_NT 1             // row loads are streamed once
+#endif
+#ifndef SLIMFIT_PRUNE_NT_STORE
+#define SLIMFIT_PRUNE_NT_STORE 1       // so are the staged output stores
+#endif
+
+template <typename T> __device__ __forceinline__ float load_elem_stream(const T *p);
+template <> __device__ __forceinline__ float load_elem_stream<float>(const float *p)
+{
+    return SLIMFIT_PRUNE_NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <> __device__ __forceinline__ float load_elem_stream<uint16_t>(const uint16_t *p)
+{
+    return bf16_widen(SLIMFIT_PRUNE_NT ? __builtin_nontemporal_load(p) : *p);
+}
+
+// LDS staging of one wave: the (value bits, column) records of the kept entries
+// of kRowsPerUnit consecutive rows, in output order (row stride k).
+struct StageRec {
+    uint32_t v, c;
+};
+struct alignas(16) WaveStage {
+    StageRec rec[kRowsPerUnit * kStage];
+};
+
+// Places the kept entries of one row in ascending column order, either as
+// records in the staging area (STAGED; at most k <= kStage per row) or directly
+// in global memory.  pred(j) is this lane's "entry j is kept" flag.  Every caller
+// derives the flags from the same comparisons that counted kk <= k entries, so a
+// position never reaches k.  first: index of the row's first output slot (in the
+// staging area, or 0).
+template <typename T, int M, bool STAGED, typename Pred>
+__device__ __forceinline__ void emit_row(Pred pred, const float (&f)[M], int lane, int k, int kk, T *ov, uint16_t *oi,
+                                         StageRec *rec, uint32_t first)
+{
+    uint32_t base = first;
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+        const bool s = pred(j);
+        const uint64_t m = __builtin_amdgcn_ballot_w64(s);
+        const uint32_t pos =
+            __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, base));
+        if (s) {
+            if (STAGED) {
+                rec[pos].v = __builtin_bit_cast(uint32_t, f[j]);
+                rec[pos].c = (uint32_t)(j * kWave + lane);
+            } else {
+                ov[pos] = Elem<T>::raw(f[j]);
+                oi[pos] = (uint16_t)(j * kWave + lane);
+            }
+        }
+        base += (uint32_t)popc64(m);
+    }
+    for (int s = kk + lane; s < k; s += kWave) {             // THRESHOLD: unused slots
+        if (STAGED) {
+            rec[first + s].v = 0u;
+            rec[first + s].c = 0xFFFFu;
+        } else {
+            ov[s] = Elem<T>::zero();
+            oi[s] = 0xFFFFu;
+        }
+    }
+}
+
+// T: element type; M: slots per lane; FULL: cols == 64*M (no absent columns);
+// STAGED: k <= kStage, outputs of kRowsPerUnit rows leave as contiguous runs.
+template <typename T, int M, bool FULL, bool STAGED>
 __global__ __launch_bounds__(kThreads) void prune_rows_kernel(const T *__restrict__ p, int64_t rows, int cols, int k,
                                                               int mode, float tau, T *__restrict__ vals,
                                                               uint16_t *__restrict__ idx, int32_t *__restrict__ counts)
 {
+    // keys of bf16 inputs have 16 zero low bits: work in units of 2^16 there
+    constexpr int KEY_SHIFT = sizeof(T) == 2 ? 16 : 0;
+    constexpr uint32_t UNIT = 1u << KEY_SHIFT;
+    __shared__ uint32_t s_hist[kWavesPerBlock][kBins];
+    __shared__ WaveStage s_stage[STAGED ? kWavesPerBlock : 1];
+
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // uniform: rows and pointers stay scalar
+    uint32_t *hist = s_hist[wave];
+    StageRec *rec = s_stage[STAGED ? wave : 0].rec;
     const float ninf = -__builtin_inff(), pinf = __builtin_inff();
 
-    for (int64_t row = wave0; row < rows; row += n_waves) {      // wave-uniform trip count
-        const T *src = p + row * (int64_t)cols;
-        float f[M];
-        bool valid[M];
-        // every load is issued (absent columns re-read the last one) so that
-        // all of a row's loads are in flight together
-#pragma unroll
-        for (int j = 0; j < M; ++j) {
-            const int col = j * kWave + lane;
-            valid[j] = col < cols;
-            f[j] = Elem<T>::load(src + (valid[j] ? col : cols - 1));
-        }
-        float lmax = ninf, lmin = pinf;
-#pragma unroll
-        for (int j = 0; j < M; ++j) {
-            f[j] = valid[j] ? f[j] : ninf;
-            lmax = fmaxf(lmax, f[j]);
-            lmin = fminf(lmin, valid[j] ? f[j] : pinf);
-        }
+    // a unit is kRowsPerUnit consecutive rows owned by one wave; a workgroup owns
+    // kWavesPerBlock consecutive units, so its output is one contiguous run
+    const int64_t n_units = (rows + kRowsPerUnit - 1) / kRowsPerUnit;
+    const int64_t unit0 = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t unit_stride = (int64_t)gridDim.x * kWavesPerBlock;
 
-        auto count_ge = [&](float t) {
-            int c = 0;
+    bool valid[M];
+    uint32_t ccol[M];
 #pragma unroll
-            for (int j = 0; j < M; ++j) c += popc64(__builtin_amdgcn_ballot_w64(f[j] >= t));
-            return c;
-        };
+    for (int j = 0; j < M; ++j) {
+        const int col = j * kWave + lane;
+        valid[j] = FULL || col < cols;
+        ccol[j] = (uint32_t)(valid[j] ? col : cols - 1);   // absent columns re-read the last one
+    }
 
-        int kk = k;                  // pairs to keep for this row
-        float T_cut = 0.0f;
-        int c_ge = 0;
-        bool have_cut = false;
-        if (mode == SLIMFIT_PRUNE_THRESHOLD) {
-            const int c_tau = count_ge(tau);
-            if (c_tau <= k) { kk = c_tau; T_cut = tau; c_ge = c_tau; have_cut = true; }
-        }
-        if (!have_cut) {
-            uint32_t lo = wave_min_u32(float_to_key(lmin));
-            uint32_t hi = wave_max_u32(float_to_key(lmax));
-            const int c_hi = count_ge(key_to_float(hi));
-            if (c_hi >= kk) {
-                lo = hi;
-                c_ge = c_hi;
-            } else {
-                c_ge = cols;                                     // every entry is >= the minimum
-                while (hi - lo > 1u) {                           // at most 32 probes
-                    const uint32_t mid = lo + ((hi - lo) >> 1);
-                    const int c = count_ge(key_to_float(mid));
-                    if (c >= kk) {
-                        lo = mid;
-                        c_ge = c;
-                        if (c == kk) break;                      // the probe separates exactly kk entries
-                    } else {
-                        hi = mid;
-                    }
+    float nxt[M];
+    if (unit0 < n_units) {
+        const T *src = p + unit0 * kRowsPerUnit * (int64_t)cols;
+#pragma unroll
+        for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(src + ccol[j]);
+    }
+
+    for (int64_t unit = unit0; unit < n_units; unit += unit_stride) {        // wave-uniform trip counts
+        const int64_t row0 = unit * kRowsPerUnit;
+        const int n_here = (int)min((int64_t)kRowsPerUnit, rows - row0);
+        int my_count = 0;                                                    // lane i keeps row i's count
+        for (int i = 0; i < n_here; ++i) {
+            const int64_t row = row0 + i;
+            float f[M];
+#pragma unroll
+            for (int j = 0; j < M; ++j) f[j] = nxt[j];
+            {   // the next row's loads fly during this row's work
+                const int64_t next = (i + 1 < n_here) ? row + 1 : (unit + unit_stride) * kRowsPerUnit;
+                if (next < rows) {
+                    const T *src = p + next * (int64_t)cols;
+#pragma unroll
+                    for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(src + ccol[j]);
                 }
             }
-            T_cut = key_to_float(lo);
-        }
 
-        // which entries survive
-        bool sel[M];
-        if (c_ge == kk) {
+            auto count_ge = [&](float t) {
+                int c = 0;
 #pragma unroll
-            for (int j = 0; j < M; ++j) sel[j] = valid[j] && f[j] >= T_cut;
-        } else {
-            // more than kk entries reach the cut value: all above it, then the
-            // equal ones by ascending column until kk are taken
-            int c_gt = 0;
-#pragma unroll
-            for (int j = 0; j < M; ++j) c_gt += popc64(__builtin_amdgcn_ballot_w64(f[j] > T_cut));
-            const int need = kk - c_gt;
-            int seen = 0;
-#pragma unroll
-            for (int j = 0; j < M; ++j) {
-                const bool eq = valid[j] && f[j] == T_cut;
-                const uint64_t eqm = __builtin_amdgcn_ballot_w64(eq);
-                const int rank = seen + (int)lanes_below(eqm);
-                sel[j] = valid[j] && (f[j] > T_cut || (eq && rank < need));
-                seen += popc64(eqm);
-            }
-        }
+                for (int j = 0; j < M; ++j) c += popc64(__builtin_amdgcn_ballot_w64(valid[j] && f[j] >= t));
+                return c;
+            };
 
-        // compaction in ascending column order
-        T *ov = vals + row * (int64_t)k;
-        uint16_t *oi = idx + row * (int64_t)k;
-        int base = 0;
-#pragma unroll
-        for (int j = 0; j < M; ++j) {
-            const uint64_t m = __builtin_amdgcn_ballot_w64(sel[j]);
-            const int pos = base + (int)lanes_below(m);
-            if (sel[j] && pos < k) {
-                ov[pos] = Elem<T>::raw(f[j]);
-                oi[pos] = (uint16_t)(j * kWave + lane);
+            int kk = k;                  // pairs to keep for this row
+            float T_cut = 0.0f;
+            int c_ge = 0;
+            bool have_cut = false;
+            if (mode == SLIMFIT_PRUNE_THRESHOLD) {
+                const int c_tau = count_ge(tau);
+                if (c_tau <= k) { kk = c_tau; T_cut = tau; c_ge = c_tau; have_cut = true; }
             }
-            base += popc64(m);
+            if (!have_cut) {
+                // 1. extrema as order-preserving keys (the minimum as a maximum of complements)
+                float lmax = ninf, lmin = pinf;
+#pragma unroll
+                for (int j = 0; j < M; ++j) {
+                    lmax = fmaxf(lmax, valid[j] ? f[j] : ninf);
+                    lmin = fminf(lmin, valid[j] ? f[j] : pinf);
+                }
+                uint32_t hi = wave_umax(float_to_key(lmax));
+                uint32_t lo = ~wave_umax(~float_to_key(lmin));
+                // a key below that of +0 means a set sign bit somewhere in the row
+                const bool any_neg = lo < 0x80000000u;
+                // -0 is folded onto +0 so that integer order agrees with float comparison
+                if (hi == 0x7FFFFFFFu) hi = 0x80000000u;
+                if (lo == 0x7FFFFFFFu) lo = 0x80000000u;
+                const uint32_t range = (hi - lo) >> KEY_SHIFT;
+                const int width_bits = 32 - __builtin_clz(range | 1u);
+                const int sh = KEY_SHIFT + (width_bits > 8 ? width_bits - 8 : 0);   // bin = (hi - key) >> sh < 256
+
+                // 2. histogram
+                reinterpret_cast<uint4 *>(hist)[lane] = make_uint4(0u, 0u, 0u, 0u);
+                __builtin_amdgcn_wave_barrier();
+                if (!any_neg) {
+                    const uint32_t hi_bits = hi ^ 0x80000000u;   // keys of non-negative floats are their bits
+#pragma unroll
+                    for (int j = 0; j < M; ++j) {
+                        const uint32_t b = ((hi_bits - __builtin_bit_cast(uint32_t, f[j])) >> sh) & (kBins - 1);
+                        if (FULL || valid[j]) atomicAdd(&hist[b], 1u);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < M; ++j) {
+                        const uint32_t b = ((hi - float_to_key(f[j] + 0.0f)) >> sh) & (kBins - 1);
+                        if (FULL || valid[j]) atomicAdd(&hist[b], 1u);
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                const uint4 h4 = reinterpret_cast<const uint4 *>(hist)[lane];    // bins 4*lane .. 4*lane+3
+
+                // 3. the bin holding the kk-th largest entry
+                const int s4 = (int)(h4.x + h4.y + h4.z + h4.w);
+                const int incl = wave_scan_i32(s4);
+                const uint64_t reached = __builtin_amdgcn_ballot_w64(incl >= kk);
+                const int L = reached ? __builtin_ctzll(reached) : 63;          // always reached for finite input
+                // the crossing lane's four bins are resolved on the scalar unit
+                const int e_L = __builtin_amdgcn_readlane(incl - s4, L);         // entries in bins before lane L's
+                const int h0 = __builtin_amdgcn_readlane((int)h4.x, L), h1 = __builtin_amdgcn_readlane((int)h4.y, L);
+                const int h2 = __builtin_amdgcn_readlane((int)h4.z, L), h3 = __builtin_amdgcn_readlane((int)h4.w, L);
+                const int c0 = e_L + h0, c1 = c0 + h1, c2 = c1 + h2, c3 = c2 + h3;
+                const int sub = c0 >= kk ? 0 : (c1 >= kk ? 1 : (c2 >= kk ? 2 : 3));
+                const int c_bin = sub == 0 ? c0 : (sub == 1 ? c1 : (sub == 2 ? c2 : c3));   // entries >= the bin's lower edge
+                const int B = 4 * L + sub;
+                // keys of bin B: (hi - (B+1)<<sh, hi - B<<sh]
+                const uint64_t span = (uint64_t)(B + 1) << sh;
+                uint32_t blo = span > (uint64_t)(hi - lo) ? lo : (uint32_t)(hi - (uint32_t)span + UNIT);
+                uint32_t bhi = hi - ((uint32_t)B << sh) + UNIT;  // exclusive
+                c_ge = c_bin;
+                // 4. bisection inside the bin
+                if (c_ge != kk) {
+                    while (bhi - blo > UNIT) {                    // at most 32 probes
+                        const uint32_t mid = blo + (((bhi - blo) >> (KEY_SHIFT + 1)) << KEY_SHIFT);
+                        const int c = count_ge(key_to_float(mid));
+                        if (c >= kk) {
+                            blo = mid;
+                            c_ge = c;
+                            if (c == kk) break;                  // the probe separates exactly kk entries
+                        } else {
+                            bhi = mid;
+                        }
+                    }
+                }
+                T_cut = key_to_float(blo);
+            }
+
+            T *ov = vals + row * (int64_t)k;
+            uint16_t *oi = idx + row * (int64_t)k;
+            const uint32_t first = STAGED ? (uint32_t)(i * k) : 0u;
+            if (c_ge == kk) {
+                emit_row<T, M, STAGED>([&](int j) { return valid[j] && f[j] >= T_cut; }, f, lane, k, kk, ov, oi, rec, first);
+            } else {
+                // more than kk entries reach the cut value: all above it, then the
+                // equal ones by ascending column until kk are taken
+                int c_gt = 0;
+#pragma unroll
+                for (int j = 0; j < M; ++j) c_gt += popc64(__builtin_amdgcn_ballot_w64(valid[j] && f[j] > T_cut));
+                const int need = kk - c_gt;
+                bool sel[M];
+                int seen = 0;
+#pragma unroll
+                for (int j = 0; j < M; ++j) {
+                    const bool eq = valid[j] && f[j] == T_cut;
+                    const uint64_t eqm = __builtin_amdgcn_ballot_w64(eq);
+                    const int rank = seen + (int)lanes_below(eqm);
+                    sel[j] = valid[j] && (f[j] > T_cut || (eq && rank < need));
+                    seen += popc64(eqm);
+                }
+                emit_row<T, M, STAGED>([&](int j) { return sel[j]; }, f, lane, k, kk, ov, oi, rec, first);
+            }
+            my_count = lane == i ? kk : my_count;
         }
-        for (int s = kk + lane; s < k; s += kWave) {             // THRESHOLD: unused slots
-            ov[s] = Elem<T>::zero();
-            oi[s] = 0xFFFFu;
+        if (STAGED) {                            // the unit's records leave as two contiguous runs
+            __builtin_amdgcn_wave_barrier();
+            T *ov = vals + row0 * (int64_t)k;
+            uint16_t *oi = idx + row0 * (int64_t)k;
+            const int n_out = n_here * k;
+            for (int t = lane; t < n_out; t += kWave) {
+                const StageRec r = rec[t];
+                store_global<SLIMFIT_PRUNE_NT_STORE != 0>(ov + t, Elem<T>::raw(__builtin_bit_cast(float, r.v)));
+                store_global<SLIMFIT_PRUNE_NT_STORE != 0>(oi + t, (uint16_t)r.c);
+            }
+            __builtin_amdgcn_wave_barrier();
         }
-        if (counts && lane == 0) counts[row] = kk;
+        if (counts && lane < n_here) counts[row0 + lane] = my_count;
     }
 }
 
@@ -343,10 +553,21 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
         prune_rows_wide_kernel<T><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
         return;
     }
-    const int64_t blocks_needed = (rows + kWavesPerBlock - 1) / kWavesPerBlock;
-    const unsigned grid = (unsigned)(blocks_needed < 16384 ? blocks_needed : 16384);
-#define SLIMFIT_PRUNE_CASE(MM) \
-    prune_rows_kernel<T, MM><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts)
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock * kRowsPerUnit;
+    const int64_t blocks_needed = (rows + rows_per_block - 1) / rows_per_block;
+    const unsigned grid = (unsigned)(blocks_needed < kMaxPruneBlocks ? blocks_needed : kMaxPruneBlocks);
+#define SLIMFIT_PRUNE_CASE(MM)                                                                                  \
+    do {                                                                                                        \
+        const bool full = cols == MM * kWave, staged = k <= kStage;                                             \
+        if (full && staged)                                                                                     \
+            prune_rows_kernel<T, MM, true, true><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);   \
+        else if (full)                                                                                          \
+            prune_rows_kernel<T, MM, true, false><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
+        else if (staged)                                                                                        \
+            prune_rows_kernel<T, MM, false, true><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
+        else                                                                                                    \
+            prune_rows_kernel<T, MM, false, false><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts); \
+    } while (0)
     if (slots <= 1) SLIMFIT_PRUNE_CASE(1);
     else if (slots <= 2) SLIMFIT_PRUNE_CASE(2);
     else if (slots <= 3) SLIMFIT_PRUNE_CASE(3);

@@ -13,21 +13,35 @@
 namespace slimfit {
 namespace {
 
+// Tunables (compile-time): vectors per lane in the two kernels, and whether
+// the bulk streams bypass the caches' retention (each byte is touched once).
+#ifndef SLIMFIT_QUANT_UNROLL
+#define SLIMFIT_QUANT_UNROLL 4
+#endif
+#ifndef SLIMFIT_DEQUANT_UNROLL
+#define SLIMFIT_DEQUANT_UNROLL 4
+#endif
+#ifndef SLIMFIT_QUANT_NT
+#define SLIMFIT_QUANT_NT 0
+#endif
+
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;
+constexpr int kUnrollQ = SLIMFIT_QUANT_UNROLL;
+constexpr int kUnrollD = SLIMFIT_DEQUANT_UNROLL;
+constexpr bool kNT = SLIMFIT_QUANT_NT != 0;
 
 template <typename T> struct Vec;
 template <> struct Vec<float> {
     static constexpr int V = 4;
-    using raw = float4;
+    using raw = f32x4;
     __device__ static void unpack(const raw &r, float (&f)[4]) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
-    __device__ static raw pack(const float (&f)[4]) { return make_float4(f[0], f[1], f[2], f[3]); }
+    __device__ static raw pack(const float (&f)[4]) { return raw{f[0], f[1], f[2], f[3]}; }
     __device__ static float load1(const float *p) { return *p; }
     __device__ static void store1(float *p, float v) { *p = v; }
 };
 template <> struct Vec<uint16_t> {   // bf16 bit patterns
     static constexpr int V = 8;
-    using raw = uint4;
+    using raw = u32x4;
     __device__ static void unpack(const raw &r, float (&f)[8])
     {
         const uint32_t w[4] = {r.x, r.y, r.z, r.w};
@@ -42,7 +56,7 @@ template <> struct Vec<uint16_t> {   // bf16 bit patterns
         uint32_t w[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) w[i] = bf16_narrow(f[2 * i]) | (bf16_narrow(f[2 * i + 1]) << 16);
-        return make_uint4(w[0], w[1], w[2], w[3]);
+        return raw{w[0], w[1], w[2], w[3]};
     }
     __device__ static float load1(const uint16_t *p) { return bf16_widen(*p); }
     __device__ static void store1(uint16_t *p, float v) { *p = (uint16_t)bf16_narrow(v); }
@@ -67,6 +81,7 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
     constexpr int V = Vec<T>::V;
     constexpr int OUT_BYTES = V * BITS / 8;            // packed bytes per lane-vector: 2, 4 or 8
     constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+    constexpr int kUnroll = kUnrollQ;
     const int64_t first_vec = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
 
     float f[kUnroll][V];
@@ -74,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
         if (e0 + V <= n) {
-            typename Vec<T>::raw r = *reinterpret_cast<const typename Vec<T>::raw *>(x + e0);
+            typename Vec<T>::raw r = load_global<kNT>(reinterpret_cast<const typename Vec<T>::raw *>(x + e0));
             Vec<T>::unpack(r, f[u]);
         } else {
 #pragma unroll
@@ -110,9 +125,9 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
         }
         uint8_t *dst = codes + (e0 * BITS) / 8;
         if (e0 + V <= n) {
-            if (OUT_BYTES == 2) *reinterpret_cast<uint16_t *>(dst) = (uint16_t)w[0];
-            else if (OUT_BYTES == 4) *reinterpret_cast<uint32_t *>(dst) = w[0];
-            else *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
+            if (OUT_BYTES == 2) store_global<kNT>(reinterpret_cast<uint16_t *>(dst), (uint16_t)w[0]);
+            else if (OUT_BYTES == 4) store_global<kNT>(reinterpret_cast<uint32_t *>(dst), w[0]);
+            else store_global<kNT>(reinterpret_cast<u32x2 *>(dst), u32x2{w[0], w[1]});
         } else {
             const int nbytes = (int)(((n - e0) * BITS + 7) / 8);   // elements past n quantised 0
             for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
@@ -123,10 +138,12 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
 template <typename T, int BITS, bool BLOCKED>
 __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
                                                                   const float *__restrict__ scales, int64_t n,
-                                                                  int block, float fixed_step, T *__restrict__ y)
+                                                                  int block_shift, float fixed_step,
+                                                                  T *__restrict__ y)
 {
     constexpr int V = Vec<T>::V;
     constexpr int IN_BYTES = V * BITS / 8;
+    constexpr int kUnroll = kUnrollD;
     const int64_t first_vec = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
 
     uint32_t w[kUnroll][2];
@@ -139,14 +156,14 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t 
         if (e0 >= n) continue;
         const uint8_t *src = codes + (e0 * BITS) / 8;
         if (e0 + V <= n) {
-            if (IN_BYTES == 2) w[u][0] = *reinterpret_cast<const uint16_t *>(src);
-            else if (IN_BYTES == 4) w[u][0] = *reinterpret_cast<const uint32_t *>(src);
-            else { uint2 t = *reinterpret_cast<const uint2 *>(src); w[u][0] = t.x; w[u][1] = t.y; }
+            if (IN_BYTES == 2) w[u][0] = load_global<kNT>(reinterpret_cast<const uint16_t *>(src));
+            else if (IN_BYTES == 4) w[u][0] = load_global<kNT>(reinterpret_cast<const uint32_t *>(src));
+            else { u32x2 t = load_global<kNT>(reinterpret_cast<const u32x2 *>(src)); w[u][0] = t.x; w[u][1] = t.y; }
         } else {
             const int nbytes = (int)(((n - e0) * BITS + 7) / 8);
             for (int b = 0; b < nbytes; ++b) w[u][b / 4] |= (uint32_t)src[b] << (8 * (b % 4));
         }
-        if (BLOCKED) s[u] = scales[e0 / block];
+        if (BLOCKED) s[u] = scales[e0 >> block_shift];      // block is a power of two
     }
 
 #pragma unroll
@@ -162,16 +179,16 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t 
             f[i] = (float)c * s[u];                                        // one fp32 multiply
         }
         if (e0 + V <= n) {
-            *reinterpret_cast<typename Vec<T>::raw *>(y + e0) = Vec<T>::pack(f);
+            store_global<kNT>(reinterpret_cast<typename Vec<T>::raw *>(y + e0), Vec<T>::pack(f));
         } else {
             for (int i = 0; i < V && e0 + i < n; ++i) Vec<T>::store1(y + e0 + i, f[i]);
         }
     }
 }
 
-inline unsigned grid_for(int64_t n, int V)
+inline unsigned grid_for(int64_t n, int V, int unroll)
 {
-    const int64_t per_block = (int64_t)kThreads * kUnroll * V;
+    const int64_t per_block = (int64_t)kThreads * unroll * V;
     return (unsigned)((n + per_block - 1) / per_block);
 }
 
@@ -180,7 +197,7 @@ void launch_quant(const void *x, int64_t n, int mode, int block, int frac_bits, 
                   hipStream_t st)
 {
     constexpr int V = Vec<T>::V;
-    const dim3 grid(grid_for(n, V)), tb(kThreads);
+    const dim3 grid(grid_for(n, V, kUnrollQ)), tb(kThreads);
     const T *xp = static_cast<const T *>(x);
     if (mode == SLIMFIT_Q_FIXED) {
         quant_pack_kernel<T, BITS, false, 4><<<grid, tb, 0, st>>>(xp, n, __builtin_ldexpf(1.0f, frac_bits), codes, nullptr);
@@ -200,12 +217,12 @@ void launch_dequant(const uint8_t *codes, const float *scales, int64_t n, int mo
                     hipStream_t st)
 {
     constexpr int V = Vec<T>::V;
-    const dim3 grid(grid_for(n, V)), tb(kThreads);
+    const dim3 grid(grid_for(n, V, kUnrollD)), tb(kThreads);
     T *yp = static_cast<T *>(y);
     if (mode == SLIMFIT_Q_FIXED)
-        dequant_unpack_kernel<T, BITS, false><<<grid, tb, 0, st>>>(codes, nullptr, n, 1, __builtin_ldexpf(1.0f, -frac_bits), yp);
+        dequant_unpack_kernel<T, BITS, false><<<grid, tb, 0, st>>>(codes, nullptr, n, 0, __builtin_ldexpf(1.0f, -frac_bits), yp);
     else
-        dequant_unpack_kernel<T, BITS, true><<<grid, tb, 0, st>>>(codes, scales, n, block, 0.0f, yp);
+        dequant_unpack_kernel<T, BITS, true><<<grid, tb, 0, st>>>(codes, scales, n, __builtin_ctz((unsigned)block), 0.0f, yp);
 }
 
 int32_t validate(int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block, int32_t frac_bits)
@@ -216,8 +233,8 @@ int32_t validate(int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t bloc
     if (mode == SLIMFIT_Q_FIXED && (frac_bits < -32 || frac_bits > 32)) return SLIMFIT_ERR_UNSUPPORTED;
     if (mode == SLIMFIT_Q_BLOCK && block != 32 && block != 64 && block != 128 && block != 256)
         return SLIMFIT_ERR_UNSUPPORTED;
-    // grid = ceil(n / 4096 or 8192) must fit an unsigned 31-bit launch dimension
-    if (n > ((int64_t)1 << 42)) return SLIMFIT_ERR_UNSUPPORTED;
+    // one workgroup per >= 1024 elements: the grid must fit a 31-bit launch dimension
+    if (n > ((int64_t)1 << 40)) return SLIMFIT_ERR_UNSUPPORTED;
     return SLIMFIT_OK;
 }
 
