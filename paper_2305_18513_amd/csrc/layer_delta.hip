@@ -19,8 +19,15 @@
 namespace slimfit {
 namespace {
 
+#ifndef SLIMFIT_DELTA_CHUNK
+#define SLIMFIT_DELTA_CHUNK 16384
+#endif
+#ifndef SLIMFIT_DELTA_NT
+#define SLIMFIT_DELTA_NT 1                   // both tensors are streamed once
+#endif
 constexpr int kThreads = 256;
-constexpr int kChunk = 8192;                 // elements per workgroup
+constexpr int kChunk = SLIMFIT_DELTA_CHUNK;  // elements per workgroup
+constexpr bool kNT = SLIMFIT_DELTA_NT != 0;
 constexpr int kVecPerThread = kChunk / 4 / kThreads;
 constexpr uint32_t kMagic = 0x534C4644u;     // "SLFD"
 constexpr int kPlanBatch = 32;
@@ -59,7 +66,7 @@ template <typename T> struct Load4;
 template <> struct Load4<float> {
     __device__ static void vec(const float *p, float (&f)[4])
     {
-        float4 r = *reinterpret_cast<const float4 *>(p);
+        f32x4 r = load_global<kNT>(reinterpret_cast<const f32x4 *>(p));
         f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
     }
     __device__ static float one(const float *p) { return *p; }
@@ -67,7 +74,7 @@ template <> struct Load4<float> {
 template <> struct Load4<uint16_t> {
     __device__ static void vec(const uint16_t *p, float (&f)[4])
     {
-        uint2 r = *reinterpret_cast<const uint2 *>(p);
+        u32x2 r = load_global<kNT>(reinterpret_cast<const u32x2 *>(p));
         f[0] = __builtin_bit_cast(float, r.x << 16); f[1] = __builtin_bit_cast(float, r.x & 0xFFFF0000u);
         f[2] = __builtin_bit_cast(float, r.y << 16); f[3] = __builtin_bit_cast(float, r.y & 0xFFFF0000u);
     }

@@ -19,10 +19,10 @@ namespace {
 #define SLIMFIT_QUANT_UNROLL 4
 #endif
 #ifndef SLIMFIT_DEQUANT_UNROLL
-#define SLIMFIT_DEQUANT_UNROLL 4
+#define SLIMFIT_DEQUANT_UNROLL 2
 #endif
 #ifndef SLIMFIT_QUANT_NT
-#define SLIMFIT_QUANT_NT 0
+#define SLIMFIT_QUANT_NT 1
 #endif
 
 constexpr int kThreads = 256;
@@ -73,10 +73,13 @@ __device__ __forceinline__ int quantise_one(float x, float mult)
     return (int)r;
 }
 
+// One workgroup tile of quantise + pack.  INSIDE: the whole tile lies below n, so
+// the code is straight-line (all loads issue back to back, no per-lane bounds);
+// otherwise every access is guarded and elements past n count as 0.
 // T: element type, BITS: 4|8, BLOCKED: per-block scale, G: lanes per block
-template <typename T, int BITS, bool BLOCKED, int G>
-__global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restrict__ x, int64_t n, float fixed_mult,
-                                                              uint8_t *__restrict__ codes, float *__restrict__ scales)
+template <typename T, int BITS, bool BLOCKED, int G, bool INSIDE>
+__device__ __forceinline__ void quant_tile(const T *__restrict__ x, int64_t n, float fixed_mult,
+                                           uint8_t *__restrict__ codes, float *__restrict__ scales)
 {
     constexpr int V = Vec<T>::V;
     constexpr int OUT_BYTES = V * BITS / 8;            // packed bytes per lane-vector: 2, 4 or 8
@@ -88,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
-        if (e0 + V <= n) {
+        if (INSIDE || e0 + V <= n) {
             typename Vec<T>::raw r = load_global<kNT>(reinterpret_cast<const typename Vec<T>::raw *>(x + e0));
             Vec<T>::unpack(r, f[u]);
         } else {
@@ -113,9 +116,9 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
                 else scale = a / qmax;                 // IEEE fp32 division
             }
             mult = inv;
-            if ((threadIdx.x & (G - 1)) == 0 && e0 < n) scales[e0 / (V * G)] = scale;
+            if ((threadIdx.x & (G - 1)) == 0 && (INSIDE || e0 < n)) scales[e0 / (V * G)] = scale;
         }
-        if (e0 >= n) continue;
+        if (!INSIDE && e0 >= n) continue;
 
         uint32_t w[2] = {0u, 0u};
 #pragma unroll
@@ -124,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
             w[(i * BITS) / 32] |= c << ((i * BITS) % 32);
         }
         uint8_t *dst = codes + (e0 * BITS) / 8;
-        if (e0 + V <= n) {
+        if (INSIDE || e0 + V <= n) {
             if (OUT_BYTES == 2) store_global<kNT>(reinterpret_cast<uint16_t *>(dst), (uint16_t)w[0]);
             else if (OUT_BYTES == 4) store_global<kNT>(reinterpret_cast<uint32_t *>(dst), w[0]);
             else store_global<kNT>(reinterpret_cast<u32x2 *>(dst), u32x2{w[0], w[1]});
@@ -135,11 +138,20 @@ __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restric
     }
 }
 
-template <typename T, int BITS, bool BLOCKED>
-__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
-                                                                  const float *__restrict__ scales, int64_t n,
-                                                                  int block_shift, float fixed_step,
-                                                                  T *__restrict__ y)
+template <typename T, int BITS, bool BLOCKED, int G>
+__global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restrict__ x, int64_t n, float fixed_mult,
+                                                              uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    constexpr int64_t TILE = (int64_t)kThreads * kUnrollQ * Vec<T>::V;
+    if (((int64_t)blockIdx.x + 1) * TILE <= n)         // workgroup-uniform
+        quant_tile<T, BITS, BLOCKED, G, true>(x, n, fixed_mult, codes, scales);
+    else
+        quant_tile<T, BITS, BLOCKED, G, false>(x, n, fixed_mult, codes, scales);
+}
+
+template <typename T, int BITS, bool BLOCKED, bool INSIDE>
+__device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, const float *__restrict__ scales,
+                                             int64_t n, int block_shift, float fixed_step, T *__restrict__ y)
 {
     constexpr int V = Vec<T>::V;
     constexpr int IN_BYTES = V * BITS / 8;
@@ -153,9 +165,9 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t 
         const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
         w[u][0] = w[u][1] = 0u;
         s[u] = fixed_step;
-        if (e0 >= n) continue;
+        if (!INSIDE && e0 >= n) continue;
         const uint8_t *src = codes + (e0 * BITS) / 8;
-        if (e0 + V <= n) {
+        if (INSIDE || e0 + V <= n) {
             if (IN_BYTES == 2) w[u][0] = load_global<kNT>(reinterpret_cast<const uint16_t *>(src));
             else if (IN_BYTES == 4) w[u][0] = load_global<kNT>(reinterpret_cast<const uint32_t *>(src));
             else { u32x2 t = load_global<kNT>(reinterpret_cast<const u32x2 *>(src)); w[u][0] = t.x; w[u][1] = t.y; }
@@ -169,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t 
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
-        if (e0 >= n) continue;
+        if (!INSIDE && e0 >= n) continue;
         float f[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) {
@@ -178,12 +190,25 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t 
             const int c = (int)(word << (32 - BITS - sh)) >> (32 - BITS);   // sign-extending field extract
             f[i] = (float)c * s[u];                                        // one fp32 multiply
         }
-        if (e0 + V <= n) {
+        if (INSIDE || e0 + V <= n) {
             store_global<kNT>(reinterpret_cast<typename Vec<T>::raw *>(y + e0), Vec<T>::pack(f));
         } else {
             for (int i = 0; i < V && e0 + i < n; ++i) Vec<T>::store1(y + e0 + i, f[i]);
         }
     }
+}
+
+template <typename T, int BITS, bool BLOCKED>
+__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
+                                                                  const float *__restrict__ scales, int64_t n,
+                                                                  int block_shift, float fixed_step,
+                                                                  T *__restrict__ y)
+{
+    constexpr int64_t TILE = (int64_t)kThreads * kUnrollD * Vec<T>::V;
+    if (((int64_t)blockIdx.x + 1) * TILE <= n)         // workgroup-uniform
+        dequant_tile<T, BITS, BLOCKED, true>(codes, scales, n, block_shift, fixed_step, y);
+    else
+        dequant_tile<T, BITS, BLOCKED, false>(codes, scales, n, block_shift, fixed_step, y);
 }
 
 inline unsigned grid_for(int64_t n, int V, int unroll)
