@@ -36,6 +36,13 @@ from paper_2305_18513_amd import synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same counters' reading of
+# a 1 GiB device copy; see profiles/bench_config3_bert_large.txt), for the default workload only.
+MEASURED_TRAFFIC_BYTES = {
+    3: {"quant_pack[gelu_in]": 918.6e6, "dequant_unpack[gelu_in]": 918.7e6,
+        "prune_scores": 1400.1e6, "layer_delta": 2417.0e6},
+}
+
 
 def esize(dt: torch.dtype) -> int:
     return 2 if dt == torch.bfloat16 else 4
@@ -202,7 +209,9 @@ def main() -> int:
                          "total_ms_per_step": round(tot / args.steps, 4)}
     dom = max(kernels, key=lambda n: kernels[n]["total_ms_per_step"])
     roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"], "traffic": None}
+                "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index, {}).get(dom),
+                "algorithmic_bytes": kernels[dom]["bytes_per_launch"], "avg_ms": kernels[dom]["avg_ms"]}
 
     out = {
         "metric": "activation-compression + freeze-score GB/s per fine-tune step; % of HBM peak",
@@ -220,48 +229,50 @@ def main() -> int:
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, bits, block, mode, tau)
+        out["cpu_baseline"] = cpu_baseline(cfg, bits, block, mode, tau, sets, prev, cur)
     print(json.dumps(out))
     return 0
 
 
-def cpu_baseline(cfg, bits, block, mode, tau):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+def cpu_baseline(cfg, bits, block, mode, tau, sets, prev, cur):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload:
+    the first resident encoder-block sets (full batch, copied back from HBM) and
+    every weight tensor."""
     from oracle import ref
     threads = min(ref.host_threads(), 16)
-    sample_batch = max(1, min(cfg.batch, 4))
     in_sz = esize(cfg.act_dtype)
+    n_blocks = min(2, len(sets))
 
     def host(t):
-        t = t.cpu().contiguous()
+        t = t.detach().cpu().contiguous()
         return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
 
-    gelu = host(synth.activation(cfg, "gelu_in", "cpu", 0, batch=sample_batch).reshape(-1))
-    lns = [host(synth.activation(cfg, "ln_in", "cpu", i, batch=sample_batch).reshape(-1)) for i in range(2)]
-    scores = host(synth.attention_scores(cfg, "cpu", 0, batch=sample_batch))
-    prev, cur = synth.weight_units(cfg, "cpu", n_blocks=1)
-    prev, cur = [host(t) for t in prev], [host(t) for t in cur]
+    acts = [[host(a) for a in s.acts] for s in sets[:n_blocks]]
+    scores = [host(s.scores) for s in sets[:n_blocks]]
+    hp, hc = [host(t) for t in prev], [host(t) for t in cur]
     ref.lib()
     nbytes = 0
     t0 = time.perf_counter()
-    packed = []
-    for a in [gelu] + lns:
-        packed.append(ref.quant_pack(a, mode=ref.Q_BLOCK, bits=bits, block=block, threads=threads))
-        nbytes += quant_bytes(a.size, in_sz, bits, block)
-    ref.prune_scores(scores, cfg.keep_k, mode=mode, tau=tau, threads=threads)
-    nbytes += prune_bytes(scores.shape[0], scores.shape[1], cfg.keep_k, in_sz)
-    for a, (c, s) in zip([gelu] + lns, packed):
-        ref.dequant_unpack(c, s, a.size, mode=ref.Q_BLOCK, bits=bits, block=block,
-                           out_dtype=a.dtype, threads=threads)
-        nbytes += quant_bytes(a.size, in_sz, bits, block)
-    d = ref.layer_delta(prev, cur, cur_is_delta=cfg.delta_given, threads=threads)
-    nbytes += sum(p.size for p in prev) * (esize(cfg.w_dtype) + 4)
+    for b in range(n_blocks):
+        packed = []
+        for a in acts[b]:
+            packed.append(ref.quant_pack(a, mode=ref.Q_BLOCK, bits=bits, block=block, threads=threads))
+            nbytes += quant_bytes(a.size, in_sz, bits, block)
+        ref.prune_scores(scores[b], cfg.keep_k, mode=mode, tau=tau, threads=threads)
+        nbytes += prune_bytes(scores[b].shape[0], scores[b].shape[1], cfg.keep_k, in_sz)
+        for a, (c, sc) in zip(acts[b], packed):
+            ref.dequant_unpack(c, sc, a.size, mode=ref.Q_BLOCK, bits=bits, block=block,
+                               out_dtype=a.dtype, threads=threads)
+            nbytes += quant_bytes(a.size, in_sz, bits, block)
+    d = ref.layer_delta(hp, hc, cur_is_delta=cfg.delta_given, threads=threads)
+    nbytes += sum(p.size for p in hp) * (esize(cfg.w_dtype) + 4)
     ref.ils_select(d, ref.freeze_count(d.size, cfg.freeze_rate))
     dt = time.perf_counter() - t0
     return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "seconds": round(dt, 2),
-            "sample": "one encoder block of the same config at batch %d (quant x3, prune, dequant x3) plus "
-                      "layer_delta over that block's 8 weight tensors and one ils_select" % sample_batch}
+            "seconds": round(dt, 2), "bytes": nbytes,
+            "sample": "%d of the %d encoder blocks at full batch (quant x3, prune, dequant x3 each) plus "
+                      "layer_delta over all %d weight tensors and one ils_select; OpenMP over independent "
+                      "blocks/rows/layers" % (n_blocks, cfg.n_blocks, len(hp))}
 
 
 if __name__ == "__main__":
