@@ -127,6 +127,9 @@ def weight_units(cfg: WorkloadConfig, device="cpu", n_blocks=None):
         gp = _gen(cfg, "w_prev", i, device)
         gd = _gen(cfg, "delta", i, device)
         wp = torch.randn(n, generator=gp, device=device, dtype=torch.float32) * 0.02
+        # the 32-bit uniform source behind randn yields an exact 0.0 about once in 10^7 draws; a
+        # continuous N(0, 0.02) never does, and Eq. 1 divides by this tensor
+        wp = torch.where(wp == 0, torch.full_like(wp, 0.02), wp)
         dl = torch.randn(n, generator=gd, device=device, dtype=torch.float32) * float(lrs[i])
         if cfg.w_dtype == torch.bfloat16:
             wp = wp.to(torch.bfloat16)
