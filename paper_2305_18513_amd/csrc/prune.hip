@@ -23,9 +23,14 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
+#ifndef SLIMFIT_PRUNE_WAVES
+#define SLIMFIT_PRUNE_WAVES 4
+#endif
+constexpr int kRowWaves = SLIMFIT_PRUNE_WAVES;          // waves per workgroup of the register-path kernel
+constexpr int kRowThreads = kRowWaves * kWave;
 constexpr int kMaxRegSlots = 16;             // register path: cols <= 64 * 16
 #ifndef SLIMFIT_PRUNE_BLOCKS
-#define SLIMFIT_PRUNE_BLOCKS 8192
+#define SLIMFIT_PRUNE_BLOCKS (1 << 30)
 #endif
 constexpr int64_t kMaxPruneBlocks = SLIMFIT_PRUNE_BLOCKS;
 
@@ -65,7 +70,10 @@ __device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(
 // two coalesced stores.
 constexpr int kBins = 256;
 constexpr int kStage = 64;           // largest k whose output is staged in LDS
-constexpr int kRowsPerUnit = 8;      // consecutive rows a wave stages before it stores them
+#ifndef SLIMFIT_PRUNE_ROWS_PER_UNIT
+#define SLIMFIT_PRUNE_ROWS_PER_UNIT 8
+#endif
+constexpr int kRowsPerUnit = SLIMFIT_PRUNE_ROWS_PER_UNIT;   // consecutive rows a wave stages before it stores them
 
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_keep_f32(float v)      // lanes outside ROW_MASK keep their value
@@ -114,6 +122,9 @@ __device__ __forceinline__ int wave_scan_i32(int v)
 #ifndef SLIMFIT_PRUNE_NT
 #define SLIMFIT_PRUNE_NT 1             // row loads are streamed once
 #endif
+#ifndef SLIMFIT_PRUNE_EMIT_DUMP
+#define SLIMFIT_PRUNE_EMIT_DUMP 0      // 1: unconditional LDS record writes (rejects to a dump area) instead of exec masks
+#endif
 #ifndef SLIMFIT_PRUNE_NT_STORE
 #define SLIMFIT_PRUNE_NT_STORE 1       // so are the staged output stores
 #endif
@@ -134,7 +145,7 @@ struct StageRec {
     uint32_t v, c;
 };
 struct alignas(16) WaveStage {
-    StageRec rec[kRowsPerUnit * kStage];
+    StageRec rec[kRowsPerUnit * kStage + (SLIMFIT_PRUNE_EMIT_DUMP ? kWave : 0)];
 };
 
 // Places the kept entries of one row in ascending column order, either as
@@ -154,6 +165,13 @@ __device__ __forceinline__ void emit_row(Pred pred, const float (&f)[M], int lan
         const uint64_t m = __builtin_amdgcn_ballot_w64(s);
         const uint32_t pos =
             __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, base));
+#if SLIMFIT_PRUNE_EMIT_DUMP
+        if (STAGED) {                      // every lane writes; rejected entries land in a per-lane dump record
+            const uint32_t at = s ? pos : (uint32_t)(kRowsPerUnit * kStage + lane);
+            rec[at].v = __builtin_bit_cast(uint32_t, f[j]);
+            rec[at].c = (uint32_t)(j * kWave + lane);
+        } else
+#endif
         if (s) {
             if (STAGED) {
                 rec[pos].v = __builtin_bit_cast(uint32_t, f[j]);
@@ -179,15 +197,15 @@ __device__ __forceinline__ void emit_row(Pred pred, const float (&f)[M], int lan
 // T: element type; M: slots per lane; FULL: cols == 64*M (no absent columns);
 // STAGED: k <= kStage, outputs of kRowsPerUnit rows leave as contiguous runs.
 template <typename T, int M, bool FULL, bool STAGED>
-__global__ __launch_bounds__(kThreads) void prune_rows_kernel(const T *__restrict__ p, int64_t rows, int cols, int k,
+__global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__restrict__ p, int64_t rows, int cols, int k,
                                                               int mode, float tau, T *__restrict__ vals,
                                                               uint16_t *__restrict__ idx, int32_t *__restrict__ counts)
 {
     // keys of bf16 inputs have 16 zero low bits: work in units of 2^16 there
     constexpr int KEY_SHIFT = sizeof(T) == 2 ? 16 : 0;
     constexpr uint32_t UNIT = 1u << KEY_SHIFT;
-    __shared__ uint32_t s_hist[kWavesPerBlock][kBins];
-    __shared__ WaveStage s_stage[STAGED ? kWavesPerBlock : 1];
+    __shared__ uint32_t s_hist[kRowWaves][kBins];
+    __shared__ WaveStage s_stage[STAGED ? kRowWaves : 1];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // uniform: rows and pointers stay scalar
@@ -196,10 +214,10 @@ __global__ __launch_bounds__(kThreads) void prune_rows_kernel(const T *__restric
     const float ninf = -__builtin_inff(), pinf = __builtin_inff();
 
     // a unit is kRowsPerUnit consecutive rows owned by one wave; a workgroup owns
-    // kWavesPerBlock consecutive units, so its output is one contiguous run
+    // kRowWaves consecutive units, so its output is one contiguous run
     const int64_t n_units = (rows + kRowsPerUnit - 1) / kRowsPerUnit;
-    const int64_t unit0 = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-    const int64_t unit_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t unit0 = (int64_t)blockIdx.x * kRowWaves + wave;
+    const int64_t unit_stride = (int64_t)gridDim.x * kRowWaves;
 
     bool valid[M];
     uint32_t ccol[M];
@@ -211,10 +229,10 @@ __global__ __launch_bounds__(kThreads) void prune_rows_kernel(const T *__restric
     }
 
     float nxt[M];
+    const T *next_src = p + unit0 * kRowsPerUnit * (int64_t)cols;     // row whose loads are in flight
     if (unit0 < n_units) {
-        const T *src = p + unit0 * kRowsPerUnit * (int64_t)cols;
 #pragma unroll
-        for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(src + ccol[j]);
+        for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(next_src + ccol[j]);
     }
 
     for (int64_t unit = unit0; unit < n_units; unit += unit_stride) {        // wave-uniform trip counts
@@ -227,11 +245,12 @@ __global__ __launch_bounds__(kThreads) void prune_rows_kernel(const T *__restric
 #pragma unroll
             for (int j = 0; j < M; ++j) f[j] = nxt[j];
             {   // the next row's loads fly during this row's work
-                const int64_t next = (i + 1 < n_here) ? row + 1 : (unit + unit_stride) * kRowsPerUnit;
+                const bool last = i + 1 >= n_here;
+                const int64_t next = last ? (unit + unit_stride) * kRowsPerUnit : row + 1;
+                next_src = last ? p + next * (int64_t)cols : next_src + cols;
                 if (next < rows) {
-                    const T *src = p + next * (int64_t)cols;
 #pragma unroll
-                    for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(src + ccol[j]);
+                    for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(next_src + ccol[j]);
                 }
             }
 
@@ -553,20 +572,20 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
         prune_rows_wide_kernel<T><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
         return;
     }
-    const int64_t rows_per_block = (int64_t)kWavesPerBlock * kRowsPerUnit;
+    const int64_t rows_per_block = (int64_t)kRowWaves * kRowsPerUnit;
     const int64_t blocks_needed = (rows + rows_per_block - 1) / rows_per_block;
     const unsigned grid = (unsigned)(blocks_needed < kMaxPruneBlocks ? blocks_needed : kMaxPruneBlocks);
 #define SLIMFIT_PRUNE_CASE(MM)                                                                                  \
     do {                                                                                                        \
         const bool full = cols == MM * kWave, staged = k <= kStage;                                             \
         if (full && staged)                                                                                     \
-            prune_rows_kernel<T, MM, true, true><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);   \
+            prune_rows_kernel<T, MM, true, true><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);   \
         else if (full)                                                                                          \
-            prune_rows_kernel<T, MM, true, false><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
+            prune_rows_kernel<T, MM, true, false><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
         else if (staged)                                                                                        \
-            prune_rows_kernel<T, MM, false, true><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
+            prune_rows_kernel<T, MM, false, true><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
         else                                                                                                    \
-            prune_rows_kernel<T, MM, false, false><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts); \
+            prune_rows_kernel<T, MM, false, false><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts); \
     } while (0)
     if (slots <= 1) SLIMFIT_PRUNE_CASE(1);
     else if (slots <= 2) SLIMFIT_PRUNE_CASE(2);
