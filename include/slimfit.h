@@ -124,7 +124,7 @@ int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_dt,
  * (b) Low-bit caching of saved activations -- Alg. 2 (appendix on the
  *     conversion between fixed point and fp32), Sec. 4 (8 bits = 4 integer +
  *     4 fractional for the imbalanced layer) and Sec. 5 (4 bits for GELU, two
- *     codes stored per byte "using shift operations").
+ *     codes stored per byte by shifting).
  *
  *     FIXED (the paper's algorithm): b = bits, fb = frac_bits,
  *         code = clamp(round(x * 2^fb), -2^(b-1), 2^(b-1)-1),   x^ = code / 2^fb
@@ -177,9 +177,11 @@ int32_t slimfit_dequant_unpack(const uint8_t *codes, const float *scales, int64_
  *  counts : DEVICE int32[rows] or NULL; pairs kept per row (k in TOPK mode).
  *  1 <= k <= cols <= 65536 (else INVALID_ARG / UNSUPPORTED).
  *
- *  slimfit_restore_scores is the backward half: out (rows x cols of dt) is
- *  zero-filled and the first counts[r] (or k when counts is NULL) pairs of
- *  each row are scattered into it.  An index >= cols is skipped.
+ *  slimfit_restore_scores is the backward half: out (rows x cols of dt,
+ *  16-byte aligned) is zero-filled and the first counts[r] (or k when counts is
+ *  NULL) pairs of each row are scattered into it, in one pass that writes every
+ *  output byte once.  An index >= cols is skipped; columns must be distinct
+ *  within a row.
  * ---------------------------------------------------------------------- */
 int32_t slimfit_keep_count(int32_t cols, int32_t keep_ppm); /* cols*keep_ppm/1e6, integer; -1 on bad input */
 

@@ -533,31 +533,85 @@ __global__ __launch_bounds__(kThreads) void prune_rows_wide_kernel(const T *__re
 }
 
 // ---------------------------------------------------------------------------
-// restore: zeros, then scatter (two launches in stream order)
+// restore (Alg. 5, restoring process): zeros, then scatter -- fused
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void zero_fill_kernel(uint4 *__restrict__ out16, int64_t n16,
-                                                             uint8_t *__restrict__ tail, int n_tail)
-{
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t j = i; j < n16; j += stride) out16[j] = make_uint4(0u, 0u, 0u, 0u);
-    if (i < n_tail) tail[i] = 0;
-}
+// The dense output is produced in flat tiles of kTile elements.  A workgroup
+// zero-fills its tile in LDS, scatters into it the records of the rows that
+// intersect the tile (their (value, column) pairs are one contiguous run of the
+// record arrays), and streams the tile out with 16-byte stores.  Every output
+// byte is written exactly once; no zero-fill pass over HBM.
+#ifndef SLIMFIT_RESTORE_TILE
+#define SLIMFIT_RESTORE_TILE 4096
+#endif
+constexpr int kTile = SLIMFIT_RESTORE_TILE;
 
 template <typename T>
-__global__ __launch_bounds__(kThreads) void scatter_kernel(const T *__restrict__ vals, const uint16_t *__restrict__ idx,
-                                                           const int32_t *__restrict__ counts, int64_t rows, int cols,
-                                                           int k, T *__restrict__ out)
+__global__ __launch_bounds__(kThreads) void restore_tile_kernel(const T *__restrict__ vals,
+                                                                const uint16_t *__restrict__ idx,
+                                                                const int32_t *__restrict__ counts, int64_t rows,
+                                                                int cols, int k, T *__restrict__ out)
 {
-    const int64_t total = rows * (int64_t)k;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
-        const int64_t row = i / k;
-        const int s = (int)(i - row * k);
-        const int cnt = counts ? counts[row] : k;
-        const int col = idx[i];
-        if (s < cnt && col < cols) out[row * (int64_t)cols + col] = vals[i];
+    __shared__ alignas(16) T tile[kTile];
+    constexpr int PER16 = 16 / (int)sizeof(T);                  // elements per 16-byte vector
+    constexpr int kVecs = kTile / PER16;
+    const int tid = threadIdx.x;
+    const int64_t total = rows * (int64_t)cols;
+    const int64_t t0 = (int64_t)blockIdx.x * kTile;
+    const int n = (int)min((int64_t)kTile, total - t0);         // >= 1 by the launch size
+
+    const int64_t r_lo = t0 / cols, r_hi = (t0 + n - 1) / cols; // rows touching this tile
+    const int n_rec = (int)(r_hi - r_lo + 1) * k;
+    const int64_t rec0 = r_lo * (int64_t)k;
+
+    // a record's place in the tile, or -1 if it is unused / lies outside
+    auto place = [&](int j, int col, int cnt_or_neg) {
+        const int rl = j / k;
+        const int s = j - rl * k;
+        const int cnt = cnt_or_neg < 0 ? k : cnt_or_neg;
+        const int64_t at = (r_lo + rl) * (int64_t)cols + col - t0;
+        return (s < cnt && col < cols && at >= 0 && at < n) ? (int)at : -1;
+    };
+
+    // the first records of every thread are fetched before the tile is cleared,
+    // so their latency overlaps the zero-fill and the barrier
+    constexpr int PRE = 2;
+    int pre_col[PRE], pre_cnt[PRE];
+    T pre_val[PRE];
+#pragma unroll
+    for (int u = 0; u < PRE; ++u) {
+        const int j = tid + u * kThreads;
+        pre_col[u] = 0;
+        pre_cnt[u] = -1;
+        pre_val[u] = T(0);
+        if (j < n_rec) {
+            pre_col[u] = idx[rec0 + j];
+            pre_val[u] = vals[rec0 + j];
+            if (counts) pre_cnt[u] = counts[r_lo + j / k];
+        }
     }
+
+    for (int v = tid; v < kVecs; v += kThreads) reinterpret_cast<uint4 *>(tile)[v] = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+
+#pragma unroll
+    for (int u = 0; u < PRE; ++u) {
+        const int j = tid + u * kThreads;
+        if (j < n_rec) {
+            const int at = place(j, pre_col[u], pre_cnt[u]);
+            if (at >= 0) tile[at] = pre_val[u];
+        }
+    }
+    for (int j = tid + PRE * kThreads; j < n_rec; j += kThreads) {
+        const int at = place(j, idx[rec0 + j], counts ? counts[r_lo + j / k] : -1);
+        if (at >= 0) tile[at] = vals[rec0 + j];
+    }
+    __syncthreads();
+
+    T *dst = out + t0;                                          // 16-byte aligned: kTile * sizeof(T) is
+    const int n_vec = n / PER16;
+    for (int v = tid; v < n_vec; v += kThreads)
+        store_global<true>(reinterpret_cast<u32x4 *>(dst) + v, reinterpret_cast<const u32x4 *>(tile)[v]);
+    for (int e = n_vec * PER16 + tid; e < n; e += kThreads) dst[e] = tile[e];
 }
 
 template <typename T>
@@ -657,21 +711,15 @@ extern "C" int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx,
     if ((rc = check_device_range(idx, (size_t)rows * (size_t)k * 2)) != SLIMFIT_OK) return rc;
     if (counts && (rc = check_device_range(counts, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int64_t n16 = (int64_t)(out_bytes / 16);
-    const int n_tail = (int)(out_bytes % 16);
-    int64_t zb = (n16 + kThreads - 1) / kThreads;
-    if (zb < 1) zb = 1;
-    if (zb > 65536) zb = 65536;
-    zero_fill_kernel<<<(unsigned)zb, kThreads, 0, st>>>(static_cast<uint4 *>(out), n16,
-                                                         static_cast<uint8_t *>(out) + n16 * 16, n_tail);
-    const int64_t total = rows * (int64_t)k;
-    int64_t sb = (total + kThreads - 1) / kThreads;
-    if (sb > 65536) sb = 65536;
+    const int64_t total = rows * (int64_t)cols;
+    const int64_t tiles = (total + kTile - 1) / kTile;
+    if (tiles > 0x7FFFFFFF) return SLIMFIT_ERR_UNSUPPORTED;
     if (dt == SLIMFIT_F32)
-        scatter_kernel<float><<<(unsigned)sb, kThreads, 0, st>>>(static_cast<const float *>(vals), idx, counts, rows,
-                                                                 cols, k, static_cast<float *>(out));
+        restore_tile_kernel<float><<<(unsigned)tiles, kThreads, 0, st>>>(static_cast<const float *>(vals), idx, counts,
+                                                                         rows, cols, k, static_cast<float *>(out));
     else
-        scatter_kernel<uint16_t><<<(unsigned)sb, kThreads, 0, st>>>(static_cast<const uint16_t *>(vals), idx, counts,
-                                                                    rows, cols, k, static_cast<uint16_t *>(out));
+        restore_tile_kernel<uint16_t><<<(unsigned)tiles, kThreads, 0, st>>>(static_cast<const uint16_t *>(vals), idx,
+                                                                            counts, rows, cols, k,
+                                                                            static_cast<uint16_t *>(out));
     return launch_status();
 }

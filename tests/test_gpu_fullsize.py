@@ -98,7 +98,12 @@ def test_prune_full_tensor(ci):
         _eq(to_np(counts), oc)
         if mode == sf.PRUNE_THRESHOLD:
             assert (oc < k).any() and (oc == k).any()
-        del vals, idx, counts
+        # backward half: zeros + scatter of the kept pairs
+        dense = torch.empty_like(p)
+        sf.restore_scores(vals, idx, counts, dense)
+        torch.cuda.synchronize()
+        _eq(to_np(dense), ref.restore_scores(ov, oi, oc, cols, threads=THREADS))
+        del vals, idx, counts, dense
 
 
 @pytest.mark.parametrize("ci", [1, 2, 3, 4])
