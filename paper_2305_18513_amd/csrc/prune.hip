@@ -3,16 +3,12 @@
 //
 // The paper sorts the whole input to find the largest 10 %.  A sort is not
 // needed for that: the kept set is {p > T} plus the first few {p == T} in
-// column order, where T is the k-th largest value of the row.  One wavefront
-// owns one row at a time and keeps it in registers (lane l holds columns
-// l, l+64, ...).  T is found by bisection over the order-preserving integer
-// image of the floats between the row's minimum and maximum; every probe is
-// one v_cmp per held element whose lane mask is popcounted on the scalar
-// unit, and the search stops as soon as a probe is passed by exactly k
-// entries.  Survivors are compacted in ascending column order with
-// mask-prefix counts (mbcnt), so no LDS and no atomics are involved.
-// Rows wider than the register path are handled by a workgroup-per-row
-// kernel with the same logic that re-reads the row from cache for each probe.
+// column order, where T is the k-th largest value of the row.  Three kernels:
+//   prune_rows_kernel       rows of up to 1024 columns, one wavefront per row,
+//                           the row held in registers (lane l: columns l, l+64, ...)
+//   prune_rows_wide_kernel  wider rows, one workgroup per row, the row re-read
+//                           from cache for every probe
+//   restore_tile_kernel     the restoring process: zeros + scatter in one pass
 #include "common.hpp"
 
 #include <cfloat>
@@ -66,8 +62,11 @@ __device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(
 //      lane mask is popcounted on the scalar unit, ending as soon as a probe is
 //      passed by exactly k entries or the bracket is a single value (ties).
 // Survivors are compacted in ascending column order with mask-prefix counts
-// (mbcnt), staged through LDS when k <= 64 so that a row's output leaves as
-// two coalesced stores.
+// (mbcnt) into (value, column) records in LDS when k <= 64; a wave owns 8
+// consecutive rows and stores their records as two contiguous runs, so the
+// output leaves in full cache lines instead of a dozen masked stores per row.
+// Launch shape: one 8-row unit per wave (no persistent loop; the chip streams
+// best with many short workgroups).
 constexpr int kBins = 256;
 constexpr int kStage = 64;           // largest k whose output is staged in LDS
 #ifndef SLIMFIT_PRUNE_ROWS_PER_UNIT
@@ -75,13 +74,6 @@ constexpr int kStage = 64;           // largest k whose output is staged in LDS
 #endif
 constexpr int kRowsPerUnit = SLIMFIT_PRUNE_ROWS_PER_UNIT;   // consecutive rows a wave stages before it stores them
 
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_keep_f32(float v)      // lanes outside ROW_MASK keep their value
-{
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF,
-                                           false));
-}
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ int dpp_zero_i32(int v)          // absent sources contribute 0
 {
@@ -122,9 +114,6 @@ __device__ __forceinline__ int wave_scan_i32(int v)
 #ifndef SLIMFIT_PRUNE_NT
 #define SLIMFIT_PRUNE_NT 1             // row loads are streamed once
 #endif
-#ifndef SLIMFIT_PRUNE_EMIT_DUMP
-#define SLIMFIT_PRUNE_EMIT_DUMP 0      // 1: unconditional LDS record writes (rejects to a dump area) instead of exec masks
-#endif
 #ifndef SLIMFIT_PRUNE_NT_STORE
 #define SLIMFIT_PRUNE_NT_STORE 1       // so are the staged output stores
 #endif
@@ -145,7 +134,7 @@ struct StageRec {
     uint32_t v, c;
 };
 struct alignas(16) WaveStage {
-    StageRec rec[kRowsPerUnit * kStage + (SLIMFIT_PRUNE_EMIT_DUMP ? kWave : 0)];
+    StageRec rec[kRowsPerUnit * kStage];
 };
 
 // Places the kept entries of one row in ascending column order, either as
@@ -165,13 +154,6 @@ __device__ __forceinline__ void emit_row(Pred pred, const float (&f)[M], int lan
         const uint64_t m = __builtin_amdgcn_ballot_w64(s);
         const uint32_t pos =
             __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, base));
-#if SLIMFIT_PRUNE_EMIT_DUMP
-        if (STAGED) {                      // every lane writes; rejected entries land in a per-lane dump record
-            const uint32_t at = s ? pos : (uint32_t)(kRowsPerUnit * kStage + lane);
-            rec[at].v = __builtin_bit_cast(uint32_t, f[j]);
-            rec[at].c = (uint32_t)(j * kWave + lane);
-        } else
-#endif
         if (s) {
             if (STAGED) {
                 rec[pos].v = __builtin_bit_cast(uint32_t, f[j]);
@@ -204,6 +186,7 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
     // keys of bf16 inputs have 16 zero low bits: work in units of 2^16 there
     constexpr int KEY_SHIFT = sizeof(T) == 2 ? 16 : 0;
     constexpr uint32_t UNIT = 1u << KEY_SHIFT;
+    constexpr uint32_t KEY_MASK = ~(UNIT - 1u);
     __shared__ uint32_t s_hist[kRowWaves][kBins];
     __shared__ WaveStage s_stage[STAGED ? kRowWaves : 1];
 
@@ -262,12 +245,12 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
             };
 
             int kk = k;                  // pairs to keep for this row
-            float T_cut = 0.0f;
+            float T_cut = 0.0f, T_exact = 0.0f;
             int c_ge = 0;
             bool have_cut = false;
             if (mode == SLIMFIT_PRUNE_THRESHOLD) {
                 const int c_tau = count_ge(tau);
-                if (c_tau <= k) { kk = c_tau; T_cut = tau; c_ge = c_tau; have_cut = true; }
+                if (c_tau <= k) { kk = c_tau; T_cut = T_exact = tau; c_ge = c_tau; have_cut = true; }
             }
             if (!have_cut) {
                 // 1. extrema as order-preserving keys (the minimum as a maximum of complements)
@@ -284,6 +267,10 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                 // -0 is folded onto +0 so that integer order agrees with float comparison
                 if (hi == 0x7FFFFFFFu) hi = 0x80000000u;
                 if (lo == 0x7FFFFFFFu) lo = 0x80000000u;
+                // bf16: the keys of negative values end in 0xFFFF, those of the others in 0x0000;
+                // dropping the low bits keeps the order and puts every key on a multiple of UNIT
+                hi &= KEY_MASK;
+                lo &= KEY_MASK;
                 const uint32_t range = (hi - lo) >> KEY_SHIFT;
                 const int width_bits = 32 - __builtin_clz(range | 1u);
                 const int sh = KEY_SHIFT + (width_bits > 8 ? width_bits - 8 : 0);   // bin = (hi - key) >> sh < 256
@@ -301,7 +288,7 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                 } else {
 #pragma unroll
                     for (int j = 0; j < M; ++j) {
-                        const uint32_t b = ((hi - float_to_key(f[j] + 0.0f)) >> sh) & (kBins - 1);
+                        const uint32_t b = ((hi - (float_to_key(f[j] + 0.0f) & KEY_MASK)) >> sh) & (kBins - 1);
                         if (FULL || valid[j]) atomicAdd(&hist[b], 1u);
                     }
                 }
@@ -341,6 +328,9 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                     }
                 }
                 T_cut = key_to_float(blo);
+                // the value itself when blo is the key of a row entry (negative bf16 values
+                // have the dropped low bits set); only the tie path below compares for equality
+                T_exact = key_to_float((blo & 0x80000000u) ? blo : (blo | (UNIT - 1u)));
             }
 
             T *ov = vals + row * (int64_t)k;
@@ -353,16 +343,16 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                 // equal ones by ascending column until kk are taken
                 int c_gt = 0;
 #pragma unroll
-                for (int j = 0; j < M; ++j) c_gt += popc64(__builtin_amdgcn_ballot_w64(valid[j] && f[j] > T_cut));
+                for (int j = 0; j < M; ++j) c_gt += popc64(__builtin_amdgcn_ballot_w64(valid[j] && f[j] > T_exact));
                 const int need = kk - c_gt;
                 bool sel[M];
                 int seen = 0;
 #pragma unroll
                 for (int j = 0; j < M; ++j) {
-                    const bool eq = valid[j] && f[j] == T_cut;
+                    const bool eq = valid[j] && f[j] == T_exact;
                     const uint64_t eqm = __builtin_amdgcn_ballot_w64(eq);
                     const int rank = seen + (int)lanes_below(eqm);
-                    sel[j] = valid[j] && (f[j] > T_cut || (eq && rank < need));
+                    sel[j] = valid[j] && (f[j] > T_exact || (eq && rank < need));
                     seen += popc64(eqm);
                 }
                 emit_row<T, M, STAGED>([&](int j) { return sel[j]; }, f, lane, k, kk, ov, oi, rec, first);

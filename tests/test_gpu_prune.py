@@ -58,6 +58,25 @@ def test_topk_random_and_ties(rows, cols, k):
     _run_both(p, k)
 
 
+@pytest.mark.parametrize("cols,k", [(64, 6), (197, 9), (384, 38), (300, 64), (1024, 33), (2000, 70)])
+def test_bf16_signed_rows_with_ties_at_the_cut(cols, k):
+    # bf16 keys of negative values are not multiples of 2^16 in the integer image of
+    # the floats; coarse values force ties at the cut on both sides of zero
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(cols + k)
+    base = torch.randn(96, cols, generator=g, device="cuda")
+    p = (base * 4).round() / 4                                   # few distinct values: ties everywhere
+    p[:32] = -p[:32].abs() - 0.25                                # all negative
+    p[32:48] = (base[32:48] * 64).round() / 64                   # finer grid, mixed signs
+    p[48] = -1.0                                                 # all equal, negative
+    p[49:80] = -p[49:80].abs() - 0.25                            # negative rows with two positive entries:
+    p[49:80, 0] = 3.0                                            # the cut falls among tied negative values
+    p[49:80, cols // 2] = 0.5                                    # while the row maximum is positive
+    _run_both(p.to(torch.bfloat16), k)
+    _run_both(p.to(torch.bfloat16), k, mode=sf.PRUNE_THRESHOLD, tau=-0.5)
+    _run_both(p, k)                                              # the same rows in fp32
+
+
 def test_signed_zero_and_without_counts():
     require_gpu()
     p = torch.tensor([[-0.0, 0.0, -1.0, 0.0, -0.0, 0.0, -2.0]], device="cuda").repeat(5, 1)
