@@ -111,7 +111,11 @@ __global__ __launch_bounds__(kThreads) void layer_delta_partials_kernel(const ch
 {
     __shared__ double lds[kThreads / kWave];
     const Header *h = reinterpret_cast<const Header *>(ws);
-    if (h->magic != kMagic || h->n_layers != L || h->total_chunks != total_chunks) return;   // stale plan
+    constexpr int32_t kPrevDt = sizeof(TP) == 2 ? SLIMFIT_BF16 : SLIMFIT_F32;
+    constexpr int32_t kCurDt = sizeof(TC) == 2 ? SLIMFIT_BF16 : SLIMFIT_F32;
+    if (h->magic != kMagic || h->n_layers != L || h->total_chunks != total_chunks || h->prev_dt != kPrevDt ||
+        h->cur_dt != kCurDt)
+        return;                                                          // no matching plan: touch nothing
     const LayerEntry *table = reinterpret_cast<const LayerEntry *>(ws + sizeof(Header));
     const int64_t chunk = blockIdx.x;
 
@@ -149,13 +153,15 @@ __global__ __launch_bounds__(kThreads) void layer_delta_partials_kernel(const ch
 }
 
 __global__ __launch_bounds__(kWave) void layer_delta_finish_kernel(const char *__restrict__ ws, int32_t L,
-                                                                   int64_t total_chunks,
+                                                                   int64_t total_chunks, int32_t prev_dt,
+                                                                   int32_t cur_dt,
                                                                    const double *__restrict__ partials,
                                                                    float *__restrict__ d_out)
 {
     const int layer = blockIdx.x;
     const Header *h = reinterpret_cast<const Header *>(ws);
-    if (h->magic != kMagic || h->n_layers != L || h->total_chunks != total_chunks) {
+    if (h->magic != kMagic || h->n_layers != L || h->total_chunks != total_chunks || h->prev_dt != prev_dt ||
+        h->cur_dt != cur_dt) {
         if (threadIdx.x == 0) d_out[layer] = __builtin_nanf("");
         return;
     }
@@ -296,7 +302,7 @@ extern "C" int32_t slimfit_layer_delta_run(const int64_t *numel, int32_t L, int3
         else
             launch_partials<uint16_t, uint16_t>(is_delta, grid, st, ws, L, lay.total_chunks, eps, partials);
     }
-    layer_delta_finish_kernel<<<(unsigned)L, kWave, 0, st>>>(ws, L, lay.total_chunks, partials, d_out);
+    layer_delta_finish_kernel<<<(unsigned)L, kWave, 0, st>>>(ws, L, lay.total_chunks, prev_dt, cur_dt, partials, d_out);
     return launch_status();
 }
 
@@ -308,6 +314,7 @@ extern "C" int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_d
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;
+    if (L > 0 && check_device_range(d_out, sizeof(float) * (size_t)L) != SLIMFIT_OK) return SLIMFIT_ERR_POINTER;
     int32_t rc = slimfit_layer_delta_plan(w_prev, prev_dt, w_cur, cur_dt, numel, L, workspace, workspace_bytes, stream);
     if (rc != SLIMFIT_OK) return rc;
     return slimfit_layer_delta_run(numel, L, prev_dt, cur_dt, cur_is_delta, eps, d_out, workspace, workspace_bytes,

@@ -125,6 +125,11 @@ def test_stale_plan_yields_nan_not_a_wild_read():
     sf.layer_delta_run([9000, 9000], sf.F32, sf.F32, False, 0.0, d2, ws)   # plan was for 3 layers
     torch.cuda.synchronize()
     assert torch.isnan(d2).all()
+    d3 = torch.zeros(3, device="cuda")
+    sf.layer_delta_run(numel, sf.F32, sf.BF16, False, 0.0, d3, ws)         # plan was for fp32 tensors
+    sf.layer_delta_run(numel, sf.BF16, sf.F32, False, 0.0, d3, ws)
+    torch.cuda.synchronize()
+    assert torch.isnan(d3).all()
 
 
 def test_scores_feed_ils_like_the_oracle_chain():
