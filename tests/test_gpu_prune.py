@@ -42,7 +42,9 @@ def _run_both(p: torch.Tensor, k, mode=sf.PRUNE_TOPK, tau=0.0, with_counts=True,
 
 SHAPES = [(1, 1, 1), (7, 5, 1), (7, 5, 5), (33, 64, 6), (65, 70, 69), (130, 128, 12),
           (257, 197, 9), (101, 384, 38), (40, 577, 57), (19, 1024, 102),
-          (9, 1025, 100), (5, 4097, 409), (3, 65536, 6553), (2, 65536, 65536), (3, 300, 300)]
+          (9, 1025, 100), (5, 4097, 409), (3, 65536, 6553), (2, 65536, 65536), (3, 300, 300),
+          # short rows (four per wave): ragged row counts, every slot template, k up to its limit
+          (1001, 256, 32), (37, 208, 20), (130, 16, 3), (9, 17, 17), (6, 200, 1), (43, 255, 31), (5, 209, 33)]
 
 
 @pytest.mark.parametrize("rows,cols,k", SHAPES)
