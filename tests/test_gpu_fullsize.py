@@ -74,6 +74,26 @@ def test_paper_fixed_point_4p4_full_tensor(ci):
     _eq(to_np(y), ref.dequant_unpack(oc, None, n, mode=ref.Q_FIXED, bits=8, frac_bits=4, threads=THREADS))
 
 
+@pytest.mark.parametrize("ci", [1, 3])
+def test_paper_placement_8bit_fixed_point_on_attention_probabilities(ci):
+    # the paper caches the Softmax/MatMul operand in 8 bits (Sec. 5); its format is Alg. 2's 4.4
+    require_gpu()
+    cfg = synth.CONFIGS[ci]
+    p = synth.attention_scores(cfg, "cuda", 0).reshape(-1)
+    n = p.numel()
+    codes = torch.empty(n, dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(p)
+    sf.quant_pack(p, sf.Q_FIXED, 8, 64, 4, codes, None)
+    sf.dequant_unpack(codes, None, sf.Q_FIXED, 8, 64, 4, y)
+    torch.cuda.synchronize()
+    ph = to_np(p)
+    oc, _ = ref.quant_pack(ph, mode=ref.Q_FIXED, bits=8, frac_bits=4, threads=THREADS)
+    _eq(to_np(codes), oc)
+    oy = ref.dequant_unpack(oc, None, n, mode=ref.Q_FIXED, bits=8, frac_bits=4, threads=THREADS)
+    _eq(to_np(y), oy)
+    assert np.abs(ph.astype(np.float64) - oy).max() <= 1.0 / 32      # in range: half a step of 1/16
+
+
 @pytest.mark.parametrize("ci", [1, 2, 3, 4])
 def test_prune_full_tensor(ci):
     require_gpu()
