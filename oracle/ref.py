@@ -47,7 +47,8 @@ def lib():
             _lib = C.CDLL(build())
             for name in ("layer_delta", "quant_pack", "dequant_unpack",
                          "prune_scores", "restore_scores", "ils_select",
-                         "ils_update", "freeze_count", "keep_count"):
+                         "ils_update", "freeze_count", "keep_count",
+                         "prune_global", "restore_global"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
         return _lib
 
@@ -161,6 +162,28 @@ def restore_scores(vals, idx, counts, cols, threads=1):
         _ptr(vals), _ptr(idx), _ptr(counts), C.c_int(_dt(vals)),
         C.c_int64(rows), C.c_int(cols), C.c_int(k), _ptr(out), C.c_int(threads))
     _check(rc, "restore_scores")
+    return out
+
+
+def prune_global(x, k, by_magnitude=True):
+    """Alg. 5 on the flattened tensor.  Returns (vals[k], idx int32[k]) in ascending index order."""
+    x = np.ascontiguousarray(x).reshape(-1)
+    vals = np.zeros(k, dtype=x.dtype)
+    idx = np.zeros(k, dtype=np.int32)
+    rc = lib().slimfit_ref_prune_global(_ptr(x), C.c_int(_dt(x)), C.c_int64(x.size), C.c_int64(k),
+                                        C.c_int(int(bool(by_magnitude))), _ptr(vals), _ptr(idx))
+    _check(rc, "prune_global")
+    return vals, idx
+
+
+def restore_global(vals, idx, n):
+    """zeros(n) + scatter.  Returns the dense flat array."""
+    vals = np.ascontiguousarray(vals)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    out = np.empty(n, dtype=vals.dtype)
+    rc = lib().slimfit_ref_restore_global(_ptr(vals), _ptr(idx), C.c_int64(vals.size), C.c_int(_dt(vals)),
+                                          C.c_int64(n), _ptr(out))
+    _check(rc, "restore_global")
     return out
 
 

@@ -21,7 +21,8 @@
  * scaling/sign/permutation invariants and a NumPy float64 one-liner for
  * Eq. 1; exhaustive grid against Alg. 2 in double, half-step bound,
  * idempotence and pack/unpack identity for the quantiser; brute-force
- * repeat-argmax selector and a library stable argsort for the pruner.
+ * repeat-argmax selector and a library stable argsort for the pruner (row-wise
+ * and whole-tensor forms).
  * Parity unpinned by the paper (it prints no worked numbers for them): the
  * per-block-scale mode, the 4-bit split of integer/fraction bits, the
  * threshold pruning mode and bf16 I/O.  Those are pinned by brute force and
@@ -418,6 +419,89 @@ int slimfit_ref_restore_scores(const void *vals, const uint16_t *idx,
         }
     }
     return bad ? REF_BAD : REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Alg. 5 as the paper states it: the whole flattened tensor is one     */
+/* input vector (the paper applies it to LayerNorm's standardised input */
+/* and keeps int(numel * 0.1) entries).                                 */
+/*   sort all n entries from largest to smallest with their indices,    */
+/*   keep the first k.  by_magnitude != 0 orders by |x| (Sec. 5 speaks  */
+/*   of discarding the small values of a signed tensor), otherwise by   */
+/*   the signed value (Alg. 5's plain sort).  Ties: lower index first.  */
+/*   The kept pairs are emitted in ascending index order; values are    */
+/*   bit copies of the (signed) inputs.                                 */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    float key;
+    int64_t pos;
+} ref_gpair;
+
+static int gpair_before(const void *pa, const void *pb)
+{
+    const ref_gpair *a = (const ref_gpair *)pa, *b = (const ref_gpair *)pb;
+    if (a->key > b->key)
+        return -1;
+    if (a->key < b->key)
+        return 1;
+    return (a->pos > b->pos) - (a->pos < b->pos);
+}
+
+int slimfit_ref_prune_global(const void *x, int dt, int64_t n, int64_t k,
+                             int by_magnitude, void *vals, int32_t *idx)
+{
+    if (!dtype_ok(dt) || n < 1 || n > 2147483647LL || k < 1 || k > n)
+        return REF_BAD;
+    if (!x || !vals || !idx)
+        return REF_BAD;
+    ref_gpair *buf = (ref_gpair *)malloc(sizeof(ref_gpair) * (size_t)n);
+    uint8_t *kept = (uint8_t *)calloc((size_t)n, 1);
+    if (!buf || !kept) {
+        free(buf);
+        free(kept);
+        return REF_BAD;
+    }
+    for (int64_t j = 0; j < n; ++j) {
+        float v = load_elem(x, dt, j);
+        buf[j].key = by_magnitude ? fabsf(v) : v;
+        buf[j].pos = j;
+    }
+    qsort(buf, (size_t)n, sizeof(ref_gpair), gpair_before);
+    for (int64_t s = 0; s < k; ++s)
+        kept[buf[s].pos] = 1;
+    int64_t out = 0;
+    for (int64_t j = 0; j < n; ++j) {
+        if (!kept[j])
+            continue;
+        if (dt == 0)
+            ((float *)vals)[out] = ((const float *)x)[j];
+        else
+            ((uint16_t *)vals)[out] = ((const uint16_t *)x)[j];
+        idx[out] = (int32_t)j;
+        ++out;
+    }
+    free(buf);
+    free(kept);
+    return out == k ? REF_OK : REF_BAD;
+}
+
+/* restoring process for the flattened form: zeros(n), then scatter */
+int slimfit_ref_restore_global(const void *vals, const int32_t *idx, int64_t k,
+                               int dt, int64_t n, void *out)
+{
+    if (!dtype_ok(dt) || n < 1 || k < 0 || k > n)
+        return REF_BAD;
+    if (!out || (k > 0 && (!vals || !idx)))
+        return REF_BAD;
+    const size_t esz = dt == 0 ? 4 : 2;
+    memset(out, 0, (size_t)n * esz);
+    for (int64_t s = 0; s < k; ++s) {
+        if (idx[s] < 0 || idx[s] >= n)
+            return REF_BAD;
+        memcpy((char *)out + (size_t)idx[s] * esz, (const char *)vals + (size_t)s * esz, esz);
+    }
+    return REF_OK;
 }
 
 /* ------------------------------------------------------------------ */
