@@ -194,6 +194,40 @@ int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int3
                                void *out, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (c') Alg. 5 on a whole flattened tensor -- the form the paper applies to the
+ *     standardised input of LayerNorm: sort all n entries from largest to
+ *     smallest with their indices, keep the first k = int(n * 0.1), store the
+ *     values with int32 indices; restoring creates zeros(n) and scatters.
+ *
+ *     by_magnitude != 0 orders by |x| (discarding the small values of a signed
+ *     tensor), by_magnitude == 0 by the signed value (-0 equals +0).  Equal
+ *     keys go by lower index.  The k survivors are emitted in ascending index
+ *     order; vals are bit copies of the (signed) inputs.  NaN inputs are
+ *     outside the contract.
+ *
+ *  x         : DEVICE, n elements of dt, 16-byte aligned.  0 <= k <= n < 2^31
+ *              (k == 0 or n == 0: nothing is written).
+ *  vals, idx : DEVICE, k elements of dt / int32[k].
+ *  workspace : DEVICE, 16-byte aligned, at least the byte count that
+ *              slimfit_prune_global_workspace(n) reports; owned by the caller,
+ *              contents need not be initialised and are overwritten.  Calls
+ *              that share a workspace must not overlap.
+ *  slimfit_restore_global : out (n elements of dt, 16-byte aligned) = zeros,
+ *              then out[idx[s]] = vals[s] for s < k; an index outside [0, n) is
+ *              skipped; indices must be distinct.
+ *  Errors: INVALID_ARG (dtype, sizes, null pointers), UNSUPPORTED (n >= 2^31),
+ *  ALIGNMENT, WORKSPACE (too small), POINTER, HIP.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_prune_global_workspace(int64_t n, size_t *bytes);
+
+int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, int64_t k, int32_t by_magnitude,
+                             void *vals, int32_t *idx, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+int32_t slimfit_restore_global(const void *vals, const int32_t *idx, int64_t k, int32_t dt, int64_t n,
+                               void *out, void *stream);
+
+/* ------------------------------------------------------------------------
  * (d) Inter-layer scheduling on the host -- Alg. 1 and Sec. 3.2 / Fig. 4:
  *        idx = argsort(d)[: int(L*F)]   -> these layers are frozen;
  *     afterwards only the layers that were active take their new distance,

@@ -32,7 +32,8 @@ EXPORTS = (
     "slimfit_layer_delta_run", "slimfit_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_keep_count", "slimfit_prune_scores",
-    "slimfit_restore_scores", "slimfit_freeze_count", "slimfit_ils_select",
+    "slimfit_restore_scores", "slimfit_prune_global_workspace", "slimfit_prune_global",
+    "slimfit_restore_global", "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update",
 )
 
@@ -232,6 +233,35 @@ def restore_scores(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch
         _dev(vals), _dev(idx), _dev(counts), C.c_int32(_dt(out)), C.c_int64(rows),
         C.c_int32(cols), C.c_int32(k), _dev(out), _stream(stream))
     _check(rc, "restore_scores")
+
+
+# ---------------------------------------------------------------- (c') Alg. 5, whole tensor
+
+def prune_global_workspace(n: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().slimfit_prune_global_workspace(C.c_int64(n), C.byref(out)), "prune_global_workspace")
+    return int(out.value)
+
+
+def prune_global(x: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor, by_magnitude: bool = True,
+                 workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Keeps the k largest entries of the flattened ``x``; ``workspace`` is a uint8 device tensor."""
+    assert x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32
+    assert vals.numel() >= k and idx.numel() >= k
+    n = x.numel()
+    if workspace is None:
+        workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
+    rc = lib().slimfit_prune_global(
+        _dev(x), C.c_int32(_dt(x)), C.c_int64(n), C.c_int64(k), C.c_int32(int(bool(by_magnitude))),
+        _dev(vals), _dev(idx), _dev(workspace), C.c_size_t(workspace.numel()), _stream(stream))
+    _check(rc, "prune_global")
+
+
+def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Tensor, stream=None) -> None:
+    assert out.is_contiguous() and vals.dtype == out.dtype and idx.dtype == torch.int32
+    rc = lib().slimfit_restore_global(
+        _dev(vals), _dev(idx), C.c_int64(k), C.c_int32(_dt(out)), C.c_int64(out.numel()), _dev(out), _stream(stream))
+    _check(rc, "restore_global")
 
 
 # ---------------------------------------------------------------- (d) Alg. 1 (host)
