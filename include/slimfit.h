@@ -208,24 +208,37 @@ int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int3
  *  x         : DEVICE, n elements of dt, 16-byte aligned.  0 <= k <= n < 2^31
  *              (k == 0 or n == 0: nothing is written).
  *  vals, idx : DEVICE, k elements of dt / int32[k].
+ *  tile_ptr  : DEVICE int32[slimfit_global_tile_ptr_len(n)] or NULL.  Optional
+ *              companion of the index list, not part of the paper's format:
+ *              tile_ptr[t] = number of survivors whose index is below
+ *              t * SLIMFIT_GLOBAL_TILE, the last entry = k.  With it the
+ *              restoring process builds every output tile once instead of
+ *              filling zeros and scattering into them.
  *  workspace : DEVICE, 16-byte aligned, at least the byte count that
- *              slimfit_prune_global_workspace(n) reports; owned by the caller,
- *              contents need not be initialised and are overwritten.  Calls
- *              that share a workspace must not overlap.
+ *              slimfit_prune_global_workspace(n) reports (about n/2 bytes);
+ *              owned by the caller, contents need not be initialised and are
+ *              overwritten.  Calls that share a workspace must not overlap.
  *  slimfit_restore_global : out (n elements of dt, 16-byte aligned) = zeros,
  *              then out[idx[s]] = vals[s] for s < k; an index outside [0, n) is
- *              skipped; indices must be distinct.
+ *              skipped; indices must be distinct.  tile_ptr == NULL accepts the
+ *              pairs in any order.  With tile_ptr the pairs must be in ascending
+ *              index order with pointers as described above (what
+ *              slimfit_prune_global emits); a pair filed under the wrong tile
+ *              is skipped, never written out of bounds.
  *  Errors: INVALID_ARG (dtype, sizes, null pointers), UNSUPPORTED (n >= 2^31),
  *  ALIGNMENT, WORKSPACE (too small), POINTER, HIP.
  * ---------------------------------------------------------------------- */
+#define SLIMFIT_GLOBAL_TILE 4096
+
 int32_t slimfit_prune_global_workspace(int64_t n, size_t *bytes);
+int64_t slimfit_global_tile_ptr_len(int64_t n);   /* ceil(n / SLIMFIT_GLOBAL_TILE) + 1; -1 if n < 0 or n >= 2^31 */
 
 int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, int64_t k, int32_t by_magnitude,
-                             void *vals, int32_t *idx, void *workspace, size_t workspace_bytes,
-                             void *stream);
+                             void *vals, int32_t *idx, int32_t *tile_ptr,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
-int32_t slimfit_restore_global(const void *vals, const int32_t *idx, int64_t k, int32_t dt, int64_t n,
-                               void *out, void *stream);
+int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32_t *tile_ptr, int64_t k,
+                               int32_t dt, int64_t n, void *out, void *stream);
 
 /* ------------------------------------------------------------------------
  * (d) Inter-layer scheduling on the host -- Alg. 1 and Sec. 3.2 / Fig. 4:

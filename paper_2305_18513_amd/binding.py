@@ -23,6 +23,7 @@ LIB_PATH = os.path.join(_PKG, "libslimfit.so")
 F32, BF16 = 0, 1
 Q_FIXED, Q_BLOCK = 0, 1
 PRUNE_TOPK, PRUNE_THRESHOLD = 0, 1
+GLOBAL_TILE = 4096                 # SLIMFIT_GLOBAL_TILE: granularity of prune_global's tile pointers
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_HIP, ERR_POINTER = range(7)
 
@@ -32,7 +33,7 @@ EXPORTS = (
     "slimfit_layer_delta_run", "slimfit_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_keep_count", "slimfit_prune_scores",
-    "slimfit_restore_scores", "slimfit_prune_global_workspace", "slimfit_prune_global",
+    "slimfit_restore_scores", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update",
 )
@@ -243,24 +244,35 @@ def prune_global_workspace(n: int) -> int:
     return int(out.value)
 
 
+def global_tile_ptr_len(n: int) -> int:
+    fn = lib().slimfit_global_tile_ptr_len
+    fn.restype = C.c_int64
+    return int(fn(C.c_int64(n)))
+
+
 def prune_global(x: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor, by_magnitude: bool = True,
-                 workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+                 tile_ptr: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 stream=None) -> None:
     """Keeps the k largest entries of the flattened ``x``; ``workspace`` is a uint8 device tensor."""
     assert x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32
     assert vals.numel() >= k and idx.numel() >= k
     n = x.numel()
+    assert tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n))
     if workspace is None:
         workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
     rc = lib().slimfit_prune_global(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(n), C.c_int64(k), C.c_int32(int(bool(by_magnitude))),
-        _dev(vals), _dev(idx), _dev(workspace), C.c_size_t(workspace.numel()), _stream(stream))
+        _dev(vals), _dev(idx), _dev(tile_ptr), _dev(workspace), C.c_size_t(workspace.numel()), _stream(stream))
     _check(rc, "prune_global")
 
 
-def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Tensor, stream=None) -> None:
+def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Tensor,
+                   tile_ptr: Optional[torch.Tensor] = None, stream=None) -> None:
     assert out.is_contiguous() and vals.dtype == out.dtype and idx.dtype == torch.int32
+    assert tile_ptr is None or tile_ptr.dtype == torch.int32
     rc = lib().slimfit_restore_global(
-        _dev(vals), _dev(idx), C.c_int64(k), C.c_int32(_dt(out)), C.c_int64(out.numel()), _dev(out), _stream(stream))
+        _dev(vals), _dev(idx), _dev(tile_ptr), C.c_int64(k), C.c_int32(_dt(out)), C.c_int64(out.numel()),
+        _dev(out), _stream(stream))
     _check(rc, "restore_global")
 
 

@@ -11,37 +11,46 @@
 //             bit pattern without its sign (by magnitude) or the usual signed
 //             fold with -0 mapped onto +0 (by value); 32 bits for fp32, 16 for
 //             bf16.
-//   select    most significant digit first, 12 bits a digit (4096 bins): every
-//             workgroup histograms its share of the tensor in LDS (ds_add),
-//             adds the non-empty bins to one global histogram, and a single
-//             workgroup walks the bins from the top to fix the digit and the
-//             count still to take below it.  fp32 takes 12+12+8 bits, bf16
-//             12+4.  Later digits only count the keys that match the prefix, so
-//             their LDS traffic is a few percent of the first sweep's.
-//   count     per tile (4096 fp32 / 8192 bf16 elements): keys above T, keys
-//             equal to T.
-//   scan      one workgroup turns those into each tile's first output slot and
-//             the number of ties it may still keep.
+//   digit 1   every workgroup histograms the top 12 key bits of its share of
+//             the tensor in LDS (ds_add) and adds the non-empty bins to one
+//             global histogram; a single workgroup walks the 4096 bins from the
+//             top and fixes the bin that holds T and the count still to take
+//             from it.
+//   bracket   if that bin is small enough (the usual case: a bin is 1/16 of a
+//             binade, 1-2 % of a bell-shaped tensor), one sweep counts, per
+//             tile, the keys above the bin and files the bin's own keys in the
+//             tile's slot of a key list (1/16 of the tile's size; slots are
+//             granted from an LDS counter, no global atomics).  The remaining
+//             digits (8+12 bits for fp32, 4 for bf16) and the per-tile counts
+//             of keys above / equal to T then read the lists only, a wave per
+//             tile.  A bin too large for the lists (heavy ties, constant
+//             tensors), or a tile whose slot overflows because the bin's keys
+//             are bunched, takes the plain route instead: every further digit
+//             and the count sweep read the tensor again.
+//   scan      one workgroup turns the tile counts into each tile's first output
+//             slot and the number of ties it may still keep.
 //   write     every tile ranks its survivors with a packed wave prefix sum and
-//             stores (value, index) pairs at their final places.
+//             stores (value, index) pairs at their final places, plus the
+//             optional tile pointers (survivors ahead of every 4096 elements)
+//             that let the restoring process run as one pass.
 //
-// The tensors this path is meant for (some 10^6..10^8 elements) stay resident
-// in the 256 MB memory-side cache between sweeps, so HBM sees the input about
-// once; the cost is the chain of short dependent launches.  No kernel waits on
-// another workgroup.
+// Both routes run the same launches; a kernel looks at the route flag in the
+// state block and either returns or picks its source.  No kernel waits on
+// another workgroup.  The tensor is read three times on the list route (digit
+// 1, bracket, write) and 2 + number of digits times on the plain one.
 #include "common.hpp"
 
 namespace slimfit {
 namespace {
 
-constexpr int kTileThreads = 256;          // count / write kernels: 4 waves
+constexpr int kTileThreads = 256;          // tile kernels: 4 waves
 constexpr int kVecPerThread = 4;           // 16-byte vectors a thread holds
 constexpr int kDigitBits = 12;
 constexpr int kMaxBins = 1 << kDigitBits;
 constexpr int kHistThreads = 1024;
 constexpr int kSelectThreads = 1024;
 constexpr int kScanThreads = 1024;
-constexpr int64_t kMinTile = 4096;         // smallest tile (fp32); sizes the workspace
+constexpr int64_t kPtrTile = SLIMFIT_GLOBAL_TILE;   // granularity of the tile pointers; smallest kernel tile
 
 struct State {                             // first 64 bytes of the workspace
     uint32_t prefix;                       // key bits fixed so far
@@ -49,9 +58,18 @@ struct State {                             // first 64 bytes of the workspace
     uint32_t k_rem;                        // entries still to take among the keys matching prefix
     uint32_t T;                            // k-th largest key (after the last digit)
     uint32_t take_eq;                      // how many keys equal to T are kept
-    uint32_t pad[11];
+    uint32_t route;                        // 1: digits after the first and the counts read the candidate list
+    uint32_t overflow;                     // 1: a tile's list ran out of slots; the lists are not used after all
+    uint32_t pad[9];
 };
-static_assert(sizeof(State) == 64, "state block");
+#ifndef SLIMFIT_PG_HIST_GRID
+#define SLIMFIT_PG_HIST_GRID 256          // workgroups of a histogram sweep: each adds its non-empty bins with global atomics
+#endif
+#ifndef SLIMFIT_PG_NT
+#define SLIMFIT_PG_NT 0
+#endif
+constexpr int kListShare = 16;             // a tile's key list holds 1/16 of the tile's element count
+__device__ __forceinline__ bool use_list(const State *st) { return st->route != 0u && st->overflow == 0u; }
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -83,13 +101,13 @@ __device__ __forceinline__ uint32_t raw_bits(const uint16_t *p) { return *p; }
 
 // The EPV raw elements of vector `v` (element offset v*EPV); returns how many of
 // them lie inside [0, n).  A vector that straddles n is read element by element.
-template <typename T>
+template <typename T, bool NT = false>
 __device__ __forceinline__ int load_vec(const T *x, int64_t n, int64_t v, uint32_t (&bits)[Elem<T>::EPV])
 {
     constexpr int EPV = Elem<T>::EPV;
     const int64_t e0 = v * EPV;
     if (e0 + EPV <= n) {
-        const u32x4 w = *reinterpret_cast<const u32x4 *>(x + e0);
+        const u32x4 w = load_global<NT>(reinterpret_cast<const u32x4 *>(x + e0));
         if constexpr (EPV == 4) {
             bits[0] = w.x; bits[1] = w.y; bits[2] = w.z; bits[3] = w.w;
         } else {
@@ -143,40 +161,60 @@ __global__ void __launch_bounds__(kSelectThreads) init_kernel(State *st, uint32_
         st->k_rem = k;
         st->T = 0u;
         st->take_eq = 0u;
+        st->route = 0u;
+        st->overflow = 0u;
     }
 }
 
 // ---- one digit of the select: histogram of the keys that match the prefix ------------
+// Source: the tensor (first digit, and every digit on the plain route) or the
+// candidate list.
 template <typename T, bool MAG>
 __global__ void __launch_bounds__(kHistThreads)
-hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, uint32_t *__restrict__ hist, int shift,
-            int nbins)
+hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, uint32_t *__restrict__ hist,
+            const u32x2 *__restrict__ tile_cnt, const uint32_t *__restrict__ lists, int64_t ntiles, int shift, int nbins)
 {
     constexpr int EPV = Elem<T>::EPV;
     __shared__ uint32_t bins[kMaxBins];
     for (int i = threadIdx.x; i < nbins; i += kHistThreads) bins[i] = 0u;
     const uint32_t prefix = st->prefix, mask = st->mask;
     const uint32_t digit_mask = (uint32_t)nbins - 1u;
+    const bool listed = use_list(st);
     __syncthreads();
 
-    const int64_t nvec = (n + EPV - 1) / EPV;
-    const int64_t chunk = (int64_t)kHistThreads * kVecPerThread;
-    for (int64_t base = (int64_t)blockIdx.x * chunk; base < nvec; base += (int64_t)gridDim.x * chunk) {
-        uint32_t bits[kVecPerThread][EPV];
-        int valid[kVecPerThread];
-#pragma unroll
-        for (int j = 0; j < kVecPerThread; ++j) {
-            const int64_t v = base + (int64_t)j * kHistThreads + threadIdx.x;
-            valid[j] = 0;
-            if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+    if (listed) {
+        // a wave per tile list; the tile's count sits in the second word of its counters
+        constexpr int64_t kSlot = (int64_t)kTileThreads * kVecPerThread * EPV / kListShare;
+        const int lane = threadIdx.x & (kWave - 1);
+        const int64_t waves = (int64_t)gridDim.x * (kHistThreads / kWave);
+        for (int64_t t = (int64_t)blockIdx.x * (kHistThreads / kWave) + (threadIdx.x >> 6); t < ntiles; t += waves) {
+            const uint32_t cnt = min(tile_cnt[t].y, (uint32_t)kSlot);
+            const uint32_t *keys = lists + t * kSlot;
+            for (uint32_t i = lane; i < cnt; i += kWave) {
+                const uint32_t key = keys[i];
+                if ((key & mask) == prefix) atomicAdd(&bins[(key >> shift) & digit_mask], 1u);
+            }
         }
+    } else {
+        const int64_t nvec = (n + EPV - 1) / EPV;
+        const int64_t chunk = (int64_t)kHistThreads * kVecPerThread;
+        for (int64_t base = (int64_t)blockIdx.x * chunk; base < nvec; base += (int64_t)gridDim.x * chunk) {
+            uint32_t bits[kVecPerThread][EPV];
+            int valid[kVecPerThread];
 #pragma unroll
-        for (int j = 0; j < kVecPerThread; ++j) {
+            for (int j = 0; j < kVecPerThread; ++j) {
+                const int64_t v = base + (int64_t)j * kHistThreads + threadIdx.x;
+                valid[j] = 0;
+                if (v < nvec) valid[j] = load_vec<T, SLIMFIT_PG_NT != 0>(x, n, v, bits[j]);
+            }
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                if (e < valid[j]) {
-                    const uint32_t key = make_key<T, MAG>(bits[j][e]);
-                    if ((key & mask) == prefix) atomicAdd(&bins[(key >> shift) & digit_mask], 1u);
+            for (int j = 0; j < kVecPerThread; ++j) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    if (e < valid[j]) {
+                        const uint32_t key = make_key<T, MAG>(bits[j][e]);
+                        if ((key & mask) == prefix) atomicAdd(&bins[(key >> shift) & digit_mask], 1u);
+                    }
                 }
             }
         }
@@ -212,8 +250,10 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
 
 // Walk the bins from the highest digit down: the digit of the k-th largest key
 // is the first one whose running count reaches k_rem.  Clears the histogram.
+// After the first digit it also picks the route: the candidate list is used
+// when the chosen bin fits into it.
 __global__ void __launch_bounds__(kSelectThreads)
-select_kernel(State *st, uint32_t *hist, int shift, int nbins, int last)
+select_kernel(State *st, uint32_t *hist, int shift, int nbins, int first, int last, uint32_t cap)
 {
     __shared__ uint32_t wave_sums[kSelectThreads / kWave];
     constexpr int PER = kMaxBins / kSelectThreads;         // 4 bins a thread, highest first
@@ -243,6 +283,7 @@ select_kernel(State *st, uint32_t *hist, int shift, int nbins, int last)
             st->prefix = new_prefix;
             st->mask = mask | (((uint32_t)nbins - 1u) << shift);
             st->k_rem = left;
+            if (first) st->route = (!last && h[j] <= cap) ? 1u : 0u;
             if (last) {
                 st->T = new_prefix;
                 st->take_eq = left;
@@ -258,14 +299,112 @@ __device__ __forceinline__ int64_t tile_vec(int64_t tile, int wave, int j, int l
     return tile * (int64_t)(kTileThreads * kVecPerThread) + (int64_t)((wave * kVecPerThread + j) * kWave + lane);
 }
 
-// ---- per tile: keys above T, keys equal to T -------------------------------------------
+// ---- list route: per tile, keys above the chosen bin; the bin's own keys go to the tile's list ----
+// Leaves tile_cnt[tile] = (keys above the bin, keys filed).
 template <typename T, bool MAG>
 __global__ void __launch_bounds__(kTileThreads)
-count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u32x2 *__restrict__ tile_cnt)
+bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict__ tile_cnt, uint32_t *__restrict__ lists)
 {
     constexpr int EPV = Elem<T>::EPV;
+    constexpr uint32_t kSlot = kTileThreads * kVecPerThread * EPV / kListShare;
+    __shared__ uint32_t wave_gt[kTileThreads / kWave];
+    __shared__ uint32_t filed;
+    if (st->route == 0u) return;
+    const uint32_t prefix = st->prefix, mask = st->mask;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t nvec = (n + EPV - 1) / EPV;
+    if (threadIdx.x == 0) filed = 0u;
+    uint32_t bits[kVecPerThread][EPV];
+    int valid[kVecPerThread];
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) {
+        const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
+        valid[j] = 0;
+        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+    }
+    uint32_t gt = 0u, in_bin = 0u;
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            if (e < valid[j]) {
+                const uint32_t top = make_key<T, MAG>(bits[j][e]) & mask;
+                gt += top > prefix ? 1u : 0u;
+                in_bin += top == prefix ? 1u : 0u;
+            }
+        }
+    }
+    const uint32_t packed = gt | (in_bin << 16);            // a wave holds at most 2048 elements
+    const uint32_t incl = wave_scan_u32(packed);
+    const uint32_t wave_total = wave_total_u32(incl);
+    if (lane == 0) wave_gt[wave] = wave_total & 0xFFFFu;
+    const uint32_t wave_filed = wave_total >> 16;
+    __syncthreads();                                        // `filed` is zero
+    if (wave_filed) {                                       // wave-uniform
+        uint32_t base = 0u;
+        if (lane == 0) base = atomicAdd(&filed, wave_filed);
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        uint32_t slot = base + ((incl - packed) >> 16);
+        uint32_t *keys = lists + (int64_t)blockIdx.x * kSlot;
+#pragma unroll
+        for (int j = 0; j < kVecPerThread; ++j) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                if (e < valid[j]) {
+                    const uint32_t key = make_key<T, MAG>(bits[j][e]);
+                    if ((key & mask) == prefix) {
+                        if (slot < kSlot) keys[slot] = key;
+                        ++slot;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32x2 c = {0u, min(filed, kSlot)};
+#pragma unroll
+        for (int w = 0; w < kTileThreads / kWave; ++w) c.x += wave_gt[w];
+        tile_cnt[blockIdx.x] = c;
+        if (filed > kSlot) st->overflow = 1u;
+    }
+}
+
+// ---- per tile: keys above T, keys equal to T -------------------------------------------
+// plain route: from the tensor; list route: the list's keys are added to the
+// counts that bracket_kernel left.
+template <typename T, bool MAG>
+__global__ void __launch_bounds__(kTileThreads)
+count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u32x2 *__restrict__ tile_cnt,
+             const uint32_t *__restrict__ lists, int64_t ntiles)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    constexpr uint32_t kTileElems = kTileThreads * kVecPerThread * EPV;
     __shared__ uint32_t wave_gt[kTileThreads / kWave], wave_eq[kTileThreads / kWave];
     const uint32_t Tk = st->T;
+    if (use_list(st)) {                                     // a wave per tile list
+        constexpr int64_t kSlot = (int64_t)kTileElems / kListShare;
+        const int64_t t = (int64_t)blockIdx.x * (kTileThreads / kWave) + (threadIdx.x >> 6);
+        if (t >= ntiles) return;
+        const int lane_ = threadIdx.x & (kWave - 1);
+        const u32x2 c = tile_cnt[t];
+        const uint32_t cnt = min(c.y, (uint32_t)kSlot);
+        const uint32_t *keys = lists + t * kSlot;
+        uint32_t gt_ = 0u, eq_ = 0u;
+        for (uint32_t i = lane_; i < cnt; i += kWave) {
+            const uint32_t key = keys[i];
+            gt_ += key > Tk ? 1u : 0u;
+            eq_ += key == Tk ? 1u : 0u;
+        }
+        const uint32_t sums = wave_total_u32(wave_scan_u32(gt_ | (eq_ << 16)));
+        if (lane_ == 0) {
+            u32x2 r;
+            r.x = c.x + (sums & 0xFFFFu);
+            r.y = sums >> 16;
+            tile_cnt[t] = r;
+        }
+        return;
+    }
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int64_t nvec = (n + EPV - 1) / EPV;
     uint32_t bits[kVecPerThread][EPV];
@@ -306,28 +445,63 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
 }
 
 // ---- tile counts -> first output slot and tie budget of every tile ----------------------
+// Thread t owns the run of `run` consecutive tiles starting at t * run.  Runs of
+// up to kScanKeep tiles are fetched with all loads in flight and kept in
+// registers between the two sweeps.
+constexpr int kScanKeep = 16;
 __global__ void __launch_bounds__(kScanThreads)
 scan_kernel(const State *__restrict__ st, const u32x2 *__restrict__ tile_cnt, u32x2 *__restrict__ tile_base,
-            int64_t ntiles)
+            int64_t ntiles, int64_t run)
 {
     __shared__ uint32_t wave_sums[kScanThreads / kWave];
     const uint32_t take_eq = st->take_eq;
-    uint32_t gt_carry = 0u, eq_carry = 0u;
-    for (int64_t base = 0; base < ntiles; base += kScanThreads) {
-        const int64_t t = base + threadIdx.x;
-        u32x2 c = {0u, 0u};
-        if (t < ntiles) c = tile_cnt[t];
-        uint32_t gt_total, eq_total;
-        const uint32_t gt_before = gt_carry + block_exclusive_scan<kScanThreads>(c.x, wave_sums, gt_total);
-        const uint32_t eq_before = eq_carry + block_exclusive_scan<kScanThreads>(c.y, wave_sums, eq_total);
-        if (t < ntiles) {
-            u32x2 b;
-            b.x = gt_before + min(eq_before, take_eq);
-            b.y = take_eq > eq_before ? take_eq - eq_before : 0u;
-            tile_base[t] = b;
+    const int64_t lo = (int64_t)threadIdx.x * run;
+    const int64_t hi = min(lo + run, ntiles);
+    const bool kept = run <= kScanKeep;                       // uniform
+    u32x2 c[kScanKeep];
+    uint32_t gt_sum = 0u, eq_sum = 0u;
+    if (kept) {
+#pragma unroll
+        for (int i = 0; i < kScanKeep; ++i) {
+            c[i] = u32x2{0u, 0u};
+            if (lo + i < hi) c[i] = tile_cnt[lo + i];
         }
-        gt_carry += gt_total;
-        eq_carry += eq_total;
+#pragma unroll
+        for (int i = 0; i < kScanKeep; ++i) {
+            gt_sum += c[i].x;
+            eq_sum += c[i].y;
+        }
+    } else {
+        for (int64_t t = lo; t < hi; ++t) {
+            const u32x2 v = tile_cnt[t];
+            gt_sum += v.x;
+            eq_sum += v.y;
+        }
+    }
+    uint32_t total;
+    uint32_t gt_before = block_exclusive_scan<kScanThreads>(gt_sum, wave_sums, total);
+    uint32_t eq_before = block_exclusive_scan<kScanThreads>(eq_sum, wave_sums, total);
+    (void)total;
+    auto base_of = [&](uint32_t gt_b, uint32_t eq_b) {
+        u32x2 b;
+        b.x = gt_b + min(eq_b, take_eq);
+        b.y = take_eq > eq_b ? take_eq - eq_b : 0u;
+        return b;
+    };
+    if (kept) {
+#pragma unroll
+        for (int i = 0; i < kScanKeep; ++i) {
+            if (lo + i < hi) tile_base[lo + i] = base_of(gt_before, eq_before);
+            gt_before += c[i].x;
+            eq_before += c[i].y;
+        }
+    } else {
+        for (int64_t t = lo; t < hi; ++t) {
+            const u32x2 v = tile_cnt[t];
+            tile_base[t] = base_of(gt_before, eq_before);
+            gt_before += v.x;
+            eq_before += v.y;
+        }
     }
 }
 
@@ -339,10 +513,11 @@ template <> __device__ __forceinline__ void store_raw<uint16_t>(uint16_t *p, uin
 template <typename T, bool MAG>
 __global__ void __launch_bounds__(kTileThreads)
 write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
-             T *__restrict__ vals, int32_t *__restrict__ idx, uint32_t k)
+             T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int NW = kTileThreads / kWave;
+    constexpr int64_t kWaveElems = (int64_t)kWave * kVecPerThread * EPV;       // 1024 (fp32) / 2048 (bf16)
     __shared__ uint32_t wave_gt[NW], wave_eq[NW];
     const uint32_t Tk = st->T;
     const u32x2 tb = tile_base[blockIdx.x];
@@ -387,6 +562,12 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
         run_gt += (w < wave) ? wave_gt[w] : 0u;
         run_eq += (w < wave) ? wave_eq[w] : 0u;
     }
+    if (tile_ptr) {
+        const int64_t wave_start = (int64_t)blockIdx.x * (kWaveElems * NW) + wave * kWaveElems;
+        if (lane == 0 && wave_start % kPtrTile == 0 && wave_start < n)
+            tile_ptr[wave_start / kPtrTile] = (int32_t)(out_base + run_gt + min(run_eq, budget));
+        if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) tile_ptr[(n + kPtrTile - 1) / kPtrTile] = (int32_t)k;
+    }
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
         const uint32_t excl = incl[j] - packed[j];
@@ -416,7 +597,7 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
     }
 }
 
-// ---- restore: zeros, then scatter ---------------------------------------------------------
+// ---- restore without tile pointers: zeros, then scatter -----------------------------------
 __global__ void __launch_bounds__(kTileThreads) zero_kernel(u32x4 *__restrict__ out, int64_t nvec16, uint8_t *tail, int tail_bytes)
 {
     const int64_t v = (int64_t)blockIdx.x * (kTileThreads * kVecPerThread) + threadIdx.x;
@@ -439,37 +620,138 @@ scatter_kernel(const T *__restrict__ vals, const int32_t *__restrict__ idx, int6
     if (at >= 0 && (int64_t)at < n) out[at] = vals[i];
 }
 
+// ---- restore with tile pointers: each 4096-element tile of the output is built in LDS
+// (zeros + its own records) and written once ------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(kTileThreads)
+restore_tiles_kernel(const T *__restrict__ vals, const int32_t *__restrict__ idx, const int32_t *__restrict__ tile_ptr,
+                     int64_t k, int64_t n, T *__restrict__ out)
+{
+    constexpr int PER16 = 16 / (int)sizeof(T);
+    constexpr int kVecs = (int)kPtrTile / PER16;
+    __shared__ alignas(16) T tile[kPtrTile];
+    const int tid = threadIdx.x;
+    const int64_t t0 = (int64_t)blockIdx.x * kPtrTile;
+    const int m = (int)min(kPtrTile, n - t0);                  // >= 1 by the launch size
+
+    int64_t p0 = tile_ptr[blockIdx.x], p1 = tile_ptr[blockIdx.x + 1];
+    p0 = min(max(p0, (int64_t)0), k);                          // pointers that do not fit the record arrays are cut
+    p1 = min(max(p1, p0), min(k, p0 + kPtrTile));
+    const int n_rec = (int)(p1 - p0);
+
+    // the first records of every thread are fetched before the tile is cleared,
+    // so their latency overlaps the zero-fill and the barrier
+    constexpr int PRE = 2;
+    int pre_at[PRE];
+    T pre_val[PRE];
+#pragma unroll
+    for (int u = 0; u < PRE; ++u) {
+        const int j = tid + u * kTileThreads;
+        pre_at[u] = -1;
+        pre_val[u] = T(0);
+        if (j < n_rec) {
+            const int64_t at = (int64_t)idx[p0 + j] - t0;
+            pre_at[u] = (at >= 0 && at < m) ? (int)at : -1;
+            pre_val[u] = vals[p0 + j];
+        }
+    }
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int v = tid; v < kVecs; v += kTileThreads) reinterpret_cast<u32x4 *>(tile)[v] = z;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PRE; ++u)
+        if (pre_at[u] >= 0) tile[pre_at[u]] = pre_val[u];
+    for (int j = tid + PRE * kTileThreads; j < n_rec; j += kTileThreads) {
+        const int64_t at = (int64_t)idx[p0 + j] - t0;
+        if (at >= 0 && at < m) tile[at] = vals[p0 + j];
+    }
+    __syncthreads();
+    const int full = m / PER16;                                // whole 16-byte vectors inside the tensor
+    u32x4 *dst = reinterpret_cast<u32x4 *>(out + t0);
+    for (int v = tid; v < full; v += kTileThreads)
+        __builtin_nontemporal_store(reinterpret_cast<const u32x4 *>(tile)[v], dst + v);
+    for (int e = full * PER16 + tid; e < m; e += kTileThreads) out[t0 + e] = tile[e];
+}
+
+// Workspace: state | histogram | tile counts | tile bases | tile key lists.
+struct Workspace {
+    State *st;
+    uint32_t *hist;
+    u32x2 *tile_cnt, *tile_base;
+    uint32_t *lists;
+    uint32_t route_cap;                    // largest bin that is sent to the lists: half of their slots
+    size_t bytes;
+};
+Workspace carve(void *base, int64_t n)
+{
+    Workspace w;
+    const size_t slots = (size_t)((n + kPtrTile - 1) / kPtrTile);        // >= kernel tiles of either dtype
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = static_cast<char *>(base) + off;
+        off += (bytes + 127) / 128 * 128;
+        return p;
+    };
+    w.st = reinterpret_cast<State *>(take(sizeof(State)));
+    w.hist = reinterpret_cast<uint32_t *>(take((size_t)kMaxBins * 4));
+    w.tile_cnt = reinterpret_cast<u32x2 *>(take(slots * 8));
+    w.tile_base = reinterpret_cast<u32x2 *>(take(slots * 8));
+    // a bf16 tile spans two pointer tiles and owns both their list slots
+    w.lists = reinterpret_cast<uint32_t *>(take((slots + 1) * (size_t)(kPtrTile / kListShare) * 4));
+    w.route_cap = (uint32_t)(n / (2 * kListShare));
+    w.bytes = off;
+    return w;
+}
+size_t workspace_bytes_for(int64_t n)
+{
+    static char origin[1];                 // only offsets are taken
+    return carve(origin, n).bytes;
+}
+
+// digits from the top: fp32 12 | 8 | 12, bf16 12 | 4.  The middle digit is kept
+// narrow because every workgroup adds its non-empty bins to the global
+// histogram with atomics, and on the list route the second digit still sees
+// every filed key.
+template <typename T> struct Digits;
+template <> struct Digits<float> {
+    static constexpr int N = 3;
+    static constexpr int bits[3] = {12, 8, 12};
+};
+template <> struct Digits<uint16_t> {
+    static constexpr int N = 2;
+    static constexpr int bits[3] = {12, 4, 0};
+};
+
 template <typename T, bool MAG>
-void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, State *st, uint32_t *hist, u32x2 *tile_cnt,
-                   u32x2 *tile_base, hipStream_t s)
+void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int32_t *tile_ptr, const Workspace &w,
+                   hipStream_t s)
 {
     constexpr int EPV = Elem<T>::EPV;
-    constexpr int KEYBITS = Elem<T>::KEYBITS;
     const int64_t nvec = (n + EPV - 1) / EPV;
     const int64_t chunk = (int64_t)kHistThreads * kVecPerThread;
     const int64_t nchunks = (nvec + chunk - 1) / chunk;
-    const unsigned hist_grid = (unsigned)(nchunks < 1024 ? nchunks : 1024);
+    const unsigned hist_grid = (unsigned)(nchunks < SLIMFIT_PG_HIST_GRID ? nchunks : SLIMFIT_PG_HIST_GRID);
     const int64_t tile_vecs = (int64_t)kTileThreads * kVecPerThread;
     const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+    const int64_t run = (ntiles + kScanThreads - 1) / kScanThreads;
 
-    init_kernel<<<1, kSelectThreads, 0, s>>>(st, hist, k);
-    int hi = KEYBITS;
-    while (hi > 0) {
-        const int bits = hi >= kDigitBits ? kDigitBits : hi;
+    init_kernel<<<1, kSelectThreads, 0, s>>>(w.st, w.hist, k);
+    int hi = Elem<T>::KEYBITS;
+    for (int d = 0; d < Digits<T>::N; ++d) {
+        const int bits = Digits<T>::bits[d];
         const int shift = hi - bits;
-        hist_kernel<T, MAG><<<hist_grid, kHistThreads, 0, s>>>(x, n, st, hist, shift, 1 << bits);
-        select_kernel<<<1, kSelectThreads, 0, s>>>(st, hist, shift, 1 << bits, shift == 0 ? 1 : 0);
+        const bool first = d == 0, last = d == Digits<T>::N - 1;
+        hist_kernel<T, MAG><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists, ntiles, shift,
+                                                              1 << bits);
+        select_kernel<<<1, kSelectThreads, 0, s>>>(w.st, w.hist, shift, 1 << bits, first ? 1 : 0, last ? 1 : 0,
+                                                   w.route_cap);
+        if (first && !last)
+            bracket_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists);
         hi = shift;
     }
-    count_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, st, tile_cnt);
-    scan_kernel<<<1, kScanThreads, 0, s>>>(st, tile_cnt, tile_base, ntiles);
-    write_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, st, tile_base, vals, idx, k);
-}
-
-size_t workspace_bytes_for(int64_t n)
-{
-    const int64_t ntiles = (n + kMinTile - 1) / kMinTile;
-    return sizeof(State) + (size_t)kMaxBins * 4 + (size_t)ntiles * 16;
+    count_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists, ntiles);
+    scan_kernel<<<1, kScanThreads, 0, s>>>(w.st, w.tile_cnt, w.tile_base, ntiles, run);
+    write_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_base, vals, idx, tile_ptr, k);
 }
 
 }  // namespace
@@ -484,56 +766,61 @@ extern "C" int32_t slimfit_prune_global_workspace(int64_t n, size_t *bytes)
     return SLIMFIT_OK;
 }
 
+extern "C" int64_t slimfit_global_tile_ptr_len(int64_t n)
+{
+    if (n < 0 || n > 0x7FFFFFFFLL) return -1;
+    return (n + kPtrTile - 1) / kPtrTile + 1;
+}
+
 extern "C" int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, int64_t k, int32_t by_magnitude,
-                                        void *vals, int32_t *idx, void *workspace, size_t workspace_bytes,
-                                        void *stream)
+                                        void *vals, int32_t *idx, int32_t *tile_ptr, void *workspace,
+                                        size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dt) || n < 0 || k < 0 || k > n) return SLIMFIT_ERR_INVALID_ARG;
     if (n > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;                 // indices are int32
     if (k == 0) return SLIMFIT_OK;
     if (!x || !vals || !idx || !workspace) return SLIMFIT_ERR_INVALID_ARG;
     const size_t esz = dtype_size(dt);
-    if (!aligned_to(x, 16) || !aligned_to(vals, esz) || !aligned_to(idx, 4) || !aligned_to(workspace, 16))
+    if (!aligned_to(x, 16) || !aligned_to(vals, esz) || !aligned_to(idx, 4) || !aligned_to(workspace, 16) ||
+        (tile_ptr && !aligned_to(tile_ptr, 4)))
         return SLIMFIT_ERR_ALIGNMENT;
-    const size_t need = workspace_bytes_for(n);
-    if (workspace_bytes < need) return SLIMFIT_ERR_WORKSPACE;
+    const Workspace w = carve(workspace, n);
+    if (workspace_bytes < w.bytes) return SLIMFIT_ERR_WORKSPACE;
     int32_t rc;
     if ((rc = check_device_range(x, (size_t)n * esz)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(vals, (size_t)k * esz)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(idx, (size_t)k * 4)) != SLIMFIT_OK) return rc;
-    if ((rc = check_device_range(workspace, need)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(workspace, w.bytes)) != SLIMFIT_OK) return rc;
+    if (tile_ptr && (rc = check_device_range(tile_ptr, (size_t)slimfit_global_tile_ptr_len(n) * 4)) != SLIMFIT_OK)
+        return rc;
 
-    char *ws = static_cast<char *>(workspace);
-    State *st = reinterpret_cast<State *>(ws);
-    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + sizeof(State));
-    const int64_t slots = (n + kMinTile - 1) / kMinTile;
-    u32x2 *tile_cnt = reinterpret_cast<u32x2 *>(ws + sizeof(State) + (size_t)kMaxBins * 4);
-    u32x2 *tile_base = tile_cnt + slots;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t kk = (uint32_t)k;
     if (dt == SLIMFIT_F32) {
         const float *xf = static_cast<const float *>(x);
         float *vf = static_cast<float *>(vals);
-        if (by_magnitude) launch_select<float, true>(xf, n, kk, vf, idx, st, hist, tile_cnt, tile_base, s);
-        else launch_select<float, false>(xf, n, kk, vf, idx, st, hist, tile_cnt, tile_base, s);
+        if (by_magnitude) launch_select<float, true>(xf, n, kk, vf, idx, tile_ptr, w, s);
+        else launch_select<float, false>(xf, n, kk, vf, idx, tile_ptr, w, s);
     } else {
         const uint16_t *xh = static_cast<const uint16_t *>(x);
         uint16_t *vh = static_cast<uint16_t *>(vals);
-        if (by_magnitude) launch_select<uint16_t, true>(xh, n, kk, vh, idx, st, hist, tile_cnt, tile_base, s);
-        else launch_select<uint16_t, false>(xh, n, kk, vh, idx, st, hist, tile_cnt, tile_base, s);
+        if (by_magnitude) launch_select<uint16_t, true>(xh, n, kk, vh, idx, tile_ptr, w, s);
+        else launch_select<uint16_t, false>(xh, n, kk, vh, idx, tile_ptr, w, s);
     }
     return launch_status();
 }
 
-extern "C" int32_t slimfit_restore_global(const void *vals, const int32_t *idx, int64_t k, int32_t dt, int64_t n,
-                                          void *out, void *stream)
+extern "C" int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32_t *tile_ptr, int64_t k,
+                                          int32_t dt, int64_t n, void *out, void *stream)
 {
     if (!dtype_ok(dt) || n < 0 || k < 0 || k > n) return SLIMFIT_ERR_INVALID_ARG;
     if (n > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;
     if (n == 0) return SLIMFIT_OK;
     if (!out || (k > 0 && (!vals || !idx))) return SLIMFIT_ERR_INVALID_ARG;
     const size_t esz = dtype_size(dt);
-    if (!aligned_to(out, 16) || (k > 0 && (!aligned_to(vals, esz) || !aligned_to(idx, 4)))) return SLIMFIT_ERR_ALIGNMENT;
+    if (!aligned_to(out, 16) || (k > 0 && (!aligned_to(vals, esz) || !aligned_to(idx, 4))) ||
+        (tile_ptr && !aligned_to(tile_ptr, 4)))
+        return SLIMFIT_ERR_ALIGNMENT;
     int32_t rc;
     if ((rc = check_device_range(out, (size_t)n * esz)) != SLIMFIT_OK) return rc;
     if (k > 0) {
@@ -541,6 +828,17 @@ extern "C" int32_t slimfit_restore_global(const void *vals, const int32_t *idx, 
         if ((rc = check_device_range(idx, (size_t)k * 4)) != SLIMFIT_OK) return rc;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (tile_ptr && k > 0) {
+        const int64_t tiles = (n + kPtrTile - 1) / kPtrTile;
+        if ((rc = check_device_range(tile_ptr, (size_t)(tiles + 1) * 4)) != SLIMFIT_OK) return rc;
+        if (dt == SLIMFIT_F32)
+            restore_tiles_kernel<float><<<(unsigned)tiles, kTileThreads, 0, s>>>(
+                static_cast<const float *>(vals), idx, tile_ptr, k, n, static_cast<float *>(out));
+        else
+            restore_tiles_kernel<uint16_t><<<(unsigned)tiles, kTileThreads, 0, s>>>(
+                static_cast<const uint16_t *>(vals), idx, tile_ptr, k, n, static_cast<uint16_t *>(out));
+        return launch_status();
+    }
     const size_t bytes = (size_t)n * esz;
     const int64_t nvec16 = (int64_t)(bytes / 16);
     const int tail_bytes = (int)(bytes % 16);

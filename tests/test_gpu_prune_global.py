@@ -21,18 +21,32 @@ def _run_both(x: torch.Tensor, k: int, by_magnitude: bool, restore=True, workspa
     vals = Guarded(k, x.dtype)
     idx = Guarded(k, torch.int32)
     ws = Guarded(sf.prune_global_workspace(n), torch.uint8) if workspace is None else workspace
-    sf.prune_global(x, k, vals.t, idx.t, by_magnitude=by_magnitude, workspace=ws.t)
+    ptr = Guarded(sf.global_tile_ptr_len(n), torch.int32)
+    sf.prune_global(x, k, vals.t, idx.t, by_magnitude=by_magnitude, tile_ptr=ptr.t, workspace=ws.t)
     torch.cuda.synchronize()
-    vals.check(); idx.check(); ws.check()
+    vals.check(); idx.check(); ws.check(); ptr.check()
     ov, oi = ref.prune_global(to_np(x), k, by_magnitude=by_magnitude)
     np.testing.assert_array_equal(to_np(idx.t), oi)
     np.testing.assert_array_equal(_bits(to_np(vals.t)), _bits(ov))
+    # tile pointers: survivors ahead of every 4096 elements, counted on the oracle's index list
+    edges = np.arange(ptr.t.numel(), dtype=np.int64) * sf.GLOBAL_TILE
+    np.testing.assert_array_equal(to_np(ptr.t), np.searchsorted(oi, edges, side="left").astype(np.int32))
+    assert int(ptr.t[-1]) == k
     if restore:
-        out = Guarded(n, x.dtype)
-        sf.restore_global(vals.t, idx.t, k, out.t)
-        torch.cuda.synchronize()
-        out.check()
-        np.testing.assert_array_equal(_bits(to_np(out.t)), _bits(ref.restore_global(ov, oi, n)))
+        want = _bits(ref.restore_global(ov, oi, n))
+        for tp in (None, ptr.t):                                   # zeros + scatter, and the one-pass form
+            out = Guarded(n, x.dtype)
+            sf.restore_global(vals.t, idx.t, k, out.t, tile_ptr=tp)
+            torch.cuda.synchronize()
+            out.check()
+            np.testing.assert_array_equal(_bits(to_np(out.t)), want)
+    # the pointer list is optional
+    vals2 = Guarded(k, x.dtype)
+    idx2 = Guarded(k, torch.int32)
+    sf.prune_global(x, k, vals2.t, idx2.t, by_magnitude=by_magnitude, workspace=ws.t)
+    torch.cuda.synchronize()
+    vals2.check(); idx2.check()
+    assert torch.equal(idx2.t, idx.t) and torch.equal(vals2.t.view(torch.uint8), vals.t.view(torch.uint8))
     return oi
 
 
@@ -80,6 +94,24 @@ def test_wide_dynamic_range_and_infinities():
         _run_both(x, k, False, restore=False)
 
 
+def test_bunched_candidates_overflow_a_sub_list():
+    """The keys that share the cut's leading digit sit in one tile: the candidate list gives up and the
+    digits are counted from the tensor instead."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(21)
+    n = 1 << 21
+    for dtype in (torch.float32, torch.bfloat16):
+        x = torch.rand(n, generator=g, device="cuda") * 0.5
+        x[1000:4000] = 1.0 + torch.rand(3000, generator=g, device="cuda") * 0.06      # one 1/16-binade bin
+        hot = torch.randperm(n, generator=g, device="cuda")[:100]
+        hot = hot[(hot < 1000) | (hot >= 4000)]
+        x[hot] = 2.0 + torch.rand(hot.numel(), generator=g, device="cuda")
+        x = (x * torch.where(torch.rand(n, generator=g, device="cuda") < 0.5, -1.0, 1.0)).to(dtype)
+        _run_both(x, int(hot.numel()) + 1500, True)
+        # the same keys spread over the tensor take the list
+        _run_both(x[torch.randperm(n, generator=g, device="cuda")].contiguous(), int(hot.numel()) + 1500, True)
+
+
 def test_workspace_is_reusable_and_need_not_be_clean():
     require_gpu()
     g = torch.Generator(device="cuda").manual_seed(5)
@@ -115,6 +147,27 @@ def test_restore_skips_bad_indices_and_accepts_any_order():
     torch.cuda.synchronize()
     out.check()
     assert out.t.tolist() == [3.0, 0, 0, 0, 0, 0, 0, 1.0, 0]
+
+
+def test_restore_with_inconsistent_tile_pointers_stays_in_bounds():
+    require_gpu()
+    n, k = 10000, 6
+    vals = torch.arange(1, k + 1, device="cuda").float()
+    idx = torch.tensor([5, 4095, 4096, 9000, 9999, 123456], dtype=torch.int32, device="cuda")
+    out = Guarded(n, torch.float32)
+    good = torch.tensor([0, 2, 3, 6], dtype=torch.int32, device="cuda")
+    sf.restore_global(vals, idx, k, out.t, tile_ptr=good)
+    torch.cuda.synchronize()
+    out.check()
+    want = torch.zeros(n)
+    want[[5, 4095, 4096, 9000, 9999]] = torch.tensor([1.0, 2.0, 3.0, 4.0, 5.0])
+    assert torch.equal(out.t.cpu(), want)
+    for bad in ([0, 6, 6, 6], [-5, 100, 3, 99], [6, 0, 0, 0], [0, 0, 0, 0]):
+        sf.restore_global(vals, idx, k, out.t, tile_ptr=torch.tensor(bad, dtype=torch.int32, device="cuda"))
+        torch.cuda.synchronize()
+        out.check()
+        got = out.t.cpu()
+        assert bool(((got == 0) | (got == want)).all())            # misplaced pairs are dropped, nothing else appears
 
 
 def test_argument_errors():
