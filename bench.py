@@ -109,7 +109,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (3 = BERT-large-shaped)")
     ap.add_argument("--sets", type=int, default=3, help="distinct encoder-block buffer sets to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip kernels outside the timed step (restore_scores)")
+    ap.add_argument("--no-extras", action="store_true", help="skip kernels outside the timed step (restore_scores, 8-bit scores, whole-tensor pruning)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device copies (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -229,6 +229,36 @@ def main() -> int:
                                                    "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                                                    "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del c8, sc
+        # Alg. 5 as printed: the flattened LayerNorm input, int(numel * 0.1) survivors by magnitude, and its restore
+        lns = [s.ln[0] for s in sets]
+        n_ln = lns[0].numel()
+        k_ln = sf.keep_count(n_ln, 100000)
+        gv = [torch.empty(k_ln, dtype=lns[0].dtype, device="cuda") for _ in sets]
+        gi = [torch.empty(k_ln, dtype=torch.int32, device="cuda") for _ in sets]
+        gp = [torch.empty(sf.global_tile_ptr_len(n_ln), dtype=torch.int32, device="cuda") for _ in sets]
+        gws = torch.empty(sf.prune_global_workspace(n_ln), dtype=torch.uint8, device="cuda")
+        gout = [torch.empty_like(x) for x in lns]
+        nb = n_ln * in_sz + k_ln * (in_sz + 4)
+        runs = {
+            "prune_global[ln_in, 10%]": lambda i: sf.prune_global(lns[i], k_ln, gv[i], gi[i], True, gp[i], gws),
+            "restore_global[ln_in, tile pointers]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i], gp[i]),
+            "restore_global[ln_in, zeros+scatter]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i]),
+        }
+        for name, fn in runs.items():
+            for i in range(len(sets)):
+                fn(i)
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for i, (a, b) in enumerate(ev):
+                a.record()
+                fn(i % n_sets)
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+            extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb, "numel": n_ln, "k": k_ln,
+                            "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del gv, gi, gp, gws, gout
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

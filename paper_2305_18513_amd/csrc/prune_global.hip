@@ -36,7 +36,10 @@
 //
 // Both routes run the same launches; a kernel looks at the route flag in the
 // state block and either returns or picks its source.  No kernel waits on
-// another workgroup.  The tensor is read three times on the list route (digit
+// another workgroup, and the single-workgroup steps (digit selection, scan) are
+// launches of their own: letting the last workgroup of a sweep do them needs an
+// agent-scope release in every workgroup, which on this part writes back the
+// XCD's whole L2 and made the sweeps 2-25x slower when it was tried.  The tensor is read three times on the list route (digit
 // 1, bracket, write) and 2 + number of digits times on the plain one.
 #include "common.hpp"
 
@@ -445,63 +448,48 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
 }
 
 // ---- tile counts -> first output slot and tie budget of every tile ----------------------
-// Thread t owns the run of `run` consecutive tiles starting at t * run.  Runs of
-// up to kScanKeep tiles are fetched with all loads in flight and kept in
-// registers between the two sweeps.
+// One workgroup.  A round covers kScanThreads * kScanKeep tiles: thread t owns
+// kScanKeep consecutive ones, fetched with all loads in flight and kept in
+// registers between the sum and the write-out; totals carry over to the next
+// round.
 constexpr int kScanKeep = 16;
 __global__ void __launch_bounds__(kScanThreads)
 scan_kernel(const State *__restrict__ st, const u32x2 *__restrict__ tile_cnt, u32x2 *__restrict__ tile_base,
-            int64_t ntiles, int64_t run)
+            int64_t ntiles)
 {
     __shared__ uint32_t wave_sums[kScanThreads / kWave];
     const uint32_t take_eq = st->take_eq;
-    const int64_t lo = (int64_t)threadIdx.x * run;
-    const int64_t hi = min(lo + run, ntiles);
-    const bool kept = run <= kScanKeep;                       // uniform
-    u32x2 c[kScanKeep];
-    uint32_t gt_sum = 0u, eq_sum = 0u;
-    if (kept) {
+    uint32_t gt_carry = 0u, eq_carry = 0u;
+    for (int64_t base = 0; base < ntiles; base += (int64_t)kScanThreads * kScanKeep) {
+        const int64_t lo = base + (int64_t)threadIdx.x * kScanKeep;
+        u32x2 c[kScanKeep];
+        uint32_t gt_sum = 0u, eq_sum = 0u;
 #pragma unroll
         for (int i = 0; i < kScanKeep; ++i) {
             c[i] = u32x2{0u, 0u};
-            if (lo + i < hi) c[i] = tile_cnt[lo + i];
+            if (lo + i < ntiles) c[i] = tile_cnt[lo + i];
         }
 #pragma unroll
         for (int i = 0; i < kScanKeep; ++i) {
             gt_sum += c[i].x;
             eq_sum += c[i].y;
         }
-    } else {
-        for (int64_t t = lo; t < hi; ++t) {
-            const u32x2 v = tile_cnt[t];
-            gt_sum += v.x;
-            eq_sum += v.y;
-        }
-    }
-    uint32_t total;
-    uint32_t gt_before = block_exclusive_scan<kScanThreads>(gt_sum, wave_sums, total);
-    uint32_t eq_before = block_exclusive_scan<kScanThreads>(eq_sum, wave_sums, total);
-    (void)total;
-    auto base_of = [&](uint32_t gt_b, uint32_t eq_b) {
-        u32x2 b;
-        b.x = gt_b + min(eq_b, take_eq);
-        b.y = take_eq > eq_b ? take_eq - eq_b : 0u;
-        return b;
-    };
-    if (kept) {
+        uint32_t gt_total, eq_total;
+        uint32_t gt_before = gt_carry + block_exclusive_scan<kScanThreads>(gt_sum, wave_sums, gt_total);
+        uint32_t eq_before = eq_carry + block_exclusive_scan<kScanThreads>(eq_sum, wave_sums, eq_total);
 #pragma unroll
         for (int i = 0; i < kScanKeep; ++i) {
-            if (lo + i < hi) tile_base[lo + i] = base_of(gt_before, eq_before);
+            if (lo + i < ntiles) {
+                u32x2 b;
+                b.x = gt_before + min(eq_before, take_eq);
+                b.y = take_eq > eq_before ? take_eq - eq_before : 0u;
+                tile_base[lo + i] = b;
+            }
             gt_before += c[i].x;
             eq_before += c[i].y;
         }
-    } else {
-        for (int64_t t = lo; t < hi; ++t) {
-            const u32x2 v = tile_cnt[t];
-            tile_base[t] = base_of(gt_before, eq_before);
-            gt_before += v.x;
-            eq_before += v.y;
-        }
+        gt_carry += gt_total;
+        eq_carry += eq_total;
     }
 }
 
@@ -733,7 +721,6 @@ void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int
     const unsigned hist_grid = (unsigned)(nchunks < SLIMFIT_PG_HIST_GRID ? nchunks : SLIMFIT_PG_HIST_GRID);
     const int64_t tile_vecs = (int64_t)kTileThreads * kVecPerThread;
     const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
-    const int64_t run = (ntiles + kScanThreads - 1) / kScanThreads;
 
     init_kernel<<<1, kSelectThreads, 0, s>>>(w.st, w.hist, k);
     int hi = Elem<T>::KEYBITS;
@@ -750,7 +737,7 @@ void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int
         hi = shift;
     }
     count_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists, ntiles);
-    scan_kernel<<<1, kScanThreads, 0, s>>>(w.st, w.tile_cnt, w.tile_base, ntiles, run);
+    scan_kernel<<<1, kScanThreads, 0, s>>>(w.st, w.tile_cnt, w.tile_base, ntiles);
     write_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_base, vals, idx, tile_ptr, k);
 }
 
