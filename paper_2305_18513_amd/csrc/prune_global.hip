@@ -448,48 +448,87 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
 }
 
 // ---- tile counts -> first output slot and tie budget of every tile ----------------------
-// One workgroup.  A round covers kScanThreads * kScanKeep tiles: thread t owns
-// kScanKeep consecutive ones, fetched with all loads in flight and kept in
-// registers between the sum and the write-out; totals carry over to the next
-// round.
-constexpr int kScanKeep = 16;
+// One workgroup.  Loads and stores are 16 bytes a lane, lanes side by side (a
+// lane that fetched 16 consecutive tiles of its own made the kernel's one CU
+// request every cache line 16 times over and took twice as long).  A pass covers
+// 2 * kScanThreads tiles, thread t owning tiles 2t and 2t+1 of it; a round
+// issues the loads of kScanPasses passes at once and then scans them in turn,
+// carrying the totals.
+constexpr int kScanPasses = 8;
+__device__ __forceinline__ void block_exclusive_scan2(uint32_t a, uint32_t b, uint32_t *sums_a, uint32_t *sums_b,
+                                                      uint32_t &before_a, uint32_t &before_b, uint32_t &total_a,
+                                                      uint32_t &total_b)
+{
+    constexpr int NW = kScanThreads / kWave;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const uint32_t ia = wave_scan_u32(a), ib = wave_scan_u32(b);
+    __syncthreads();                                       // the sums of the previous pass have been read
+    if (lane == kWave - 1) {
+        sums_a[wave] = ia;
+        sums_b[wave] = ib;
+    }
+    __syncthreads();
+    uint32_t ba = 0u, bb = 0u, ta = 0u, tb = 0u;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const uint32_t sa = sums_a[w], sb = sums_b[w];
+        ba += (w < wave) ? sa : 0u;
+        bb += (w < wave) ? sb : 0u;
+        ta += sa;
+        tb += sb;
+    }
+    before_a = ba + ia - a;
+    before_b = bb + ib - b;
+    total_a = ta;
+    total_b = tb;
+}
 __global__ void __launch_bounds__(kScanThreads)
 scan_kernel(const State *__restrict__ st, const u32x2 *__restrict__ tile_cnt, u32x2 *__restrict__ tile_base,
             int64_t ntiles)
 {
-    __shared__ uint32_t wave_sums[kScanThreads / kWave];
+    __shared__ uint32_t sums_gt[kScanThreads / kWave], sums_eq[kScanThreads / kWave];
     const uint32_t take_eq = st->take_eq;
+    auto base_of = [&](uint32_t gt_b, uint32_t eq_b) {
+        u32x2 r;
+        r.x = gt_b + min(eq_b, take_eq);
+        r.y = take_eq > eq_b ? take_eq - eq_b : 0u;
+        return r;
+    };
     uint32_t gt_carry = 0u, eq_carry = 0u;
-    for (int64_t base = 0; base < ntiles; base += (int64_t)kScanThreads * kScanKeep) {
-        const int64_t lo = base + (int64_t)threadIdx.x * kScanKeep;
-        u32x2 c[kScanKeep];
-        uint32_t gt_sum = 0u, eq_sum = 0u;
+    for (int64_t base = 0; base < ntiles; base += (int64_t)kScanPasses * 2 * kScanThreads) {
+        u32x2 c0[kScanPasses], c1[kScanPasses];
 #pragma unroll
-        for (int i = 0; i < kScanKeep; ++i) {
-            c[i] = u32x2{0u, 0u};
-            if (lo + i < ntiles) c[i] = tile_cnt[lo + i];
-        }
-#pragma unroll
-        for (int i = 0; i < kScanKeep; ++i) {
-            gt_sum += c[i].x;
-            eq_sum += c[i].y;
-        }
-        uint32_t gt_total, eq_total;
-        uint32_t gt_before = gt_carry + block_exclusive_scan<kScanThreads>(gt_sum, wave_sums, gt_total);
-        uint32_t eq_before = eq_carry + block_exclusive_scan<kScanThreads>(eq_sum, wave_sums, eq_total);
-#pragma unroll
-        for (int i = 0; i < kScanKeep; ++i) {
-            if (lo + i < ntiles) {
-                u32x2 b;
-                b.x = gt_before + min(eq_before, take_eq);
-                b.y = take_eq > eq_before ? take_eq - eq_before : 0u;
-                tile_base[lo + i] = b;
+        for (int p = 0; p < kScanPasses; ++p) {
+            const int64_t t = base + (int64_t)p * 2 * kScanThreads + 2 * threadIdx.x;
+            c0[p] = u32x2{0u, 0u};
+            c1[p] = u32x2{0u, 0u};
+            if (t + 1 < ntiles) {                           // tile_cnt is 128-byte aligned and t is even
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(tile_cnt + t);
+                c0[p] = u32x2{v.x, v.y};
+                c1[p] = u32x2{v.z, v.w};
+            } else if (t < ntiles) {
+                c0[p] = tile_cnt[t];
             }
-            gt_before += c[i].x;
-            eq_before += c[i].y;
         }
-        gt_carry += gt_total;
-        eq_carry += eq_total;
+#pragma unroll
+        for (int p = 0; p < kScanPasses; ++p) {
+            const int64_t t = base + (int64_t)p * 2 * kScanThreads + 2 * threadIdx.x;
+            if (base + (int64_t)p * 2 * kScanThreads >= ntiles) break;          // uniform
+            uint32_t gt_before, eq_before, gt_total, eq_total;
+            block_exclusive_scan2(c0[p].x + c1[p].x, c0[p].y + c1[p].y, sums_gt, sums_eq, gt_before, eq_before, gt_total,
+                                  eq_total);
+            gt_before += gt_carry;
+            eq_before += eq_carry;
+            const u32x2 b0 = base_of(gt_before, eq_before);
+            const u32x2 b1 = base_of(gt_before + c0[p].x, eq_before + c0[p].y);
+            if (t + 1 < ntiles) {
+                *reinterpret_cast<u32x4 *>(tile_base + t) = u32x4{b0.x, b0.y, b1.x, b1.y};
+            } else if (t < ntiles) {
+                tile_base[t] = b0;
+            }
+            gt_carry += gt_total;
+            eq_carry += eq_total;
+        }
     }
 }
 
