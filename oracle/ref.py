@@ -48,7 +48,7 @@ def lib():
             for name in ("layer_delta", "quant_pack", "dequant_unpack",
                          "prune_scores", "restore_scores", "ils_select",
                          "ils_update", "freeze_count", "keep_count",
-                         "prune_global", "restore_global"):
+                         "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
         return _lib
 
@@ -185,6 +185,40 @@ def restore_global(vals, idx, n):
                                           C.c_int64(n), _ptr(out))
     _check(rc, "restore_global")
     return out
+
+
+def softmax_prune(logits, k, want_probs=True, threads=1):
+    """Row softmax (fp64, rounded to the logits' dtype) + Alg. 5 per row, the kept set decided on the
+    logits.  Returns (probs | None, vals, idx)."""
+    logits = np.ascontiguousarray(logits)
+    assert logits.ndim == 2
+    rows, cols = logits.shape
+    probs = np.empty_like(logits) if want_probs else None
+    vals = np.zeros((rows, k), dtype=logits.dtype)
+    idx = np.zeros((rows, k), dtype=np.uint16)
+    rc = lib().slimfit_ref_softmax_prune(_ptr(logits), C.c_int(_dt(logits)), C.c_int64(rows), C.c_int(cols),
+                                         C.c_int(k), _ptr(probs), _ptr(vals), _ptr(idx), C.c_int(threads))
+    _check(rc, "softmax_prune")
+    return probs, vals, idx
+
+
+def gelu(x):
+    """Exact (erf) GELU in fp64, rounded to x's dtype."""
+    x = np.ascontiguousarray(x).reshape(-1)
+    y = np.empty_like(x)
+    _check(lib().slimfit_ref_gelu(_ptr(x), C.c_int(_dt(x)), C.c_int64(x.size), _ptr(y)), "gelu")
+    return y
+
+
+def gelu_backward(xhat, dy):
+    """dy * GELU'(xhat) in fp64; xhat float32 (dequantised cache), dy / result share a dtype."""
+    xhat = np.ascontiguousarray(xhat, dtype=np.float32).reshape(-1)
+    dy = np.ascontiguousarray(dy).reshape(-1)
+    assert xhat.size == dy.size
+    dx = np.empty_like(dy)
+    rc = lib().slimfit_ref_gelu_backward(_ptr(xhat), _ptr(dy), C.c_int(_dt(dy)), C.c_int64(dy.size), _ptr(dx))
+    _check(rc, "gelu_backward")
+    return dx
 
 
 def freeze_count(L, F):

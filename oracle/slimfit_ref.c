@@ -22,7 +22,8 @@
  * Eq. 1; exhaustive grid against Alg. 2 in double, half-step bound,
  * idempotence and pack/unpack identity for the quantiser; brute-force
  * repeat-argmax selector and a library stable argsort for the pruner (row-wise
- * and whole-tensor forms).
+ * and whole-tensor forms); textbook values, the reflection identity, a library
+ * normal CDF and numerical differentiation for GELU and its derivative.
  * Parity unpinned by the paper (it prints no worked numbers for them): the
  * per-block-scale mode, the 4-bit split of integer/fraction bits, the
  * threshold pruning mode and bf16 I/O.  Those are pinned by brute force and
@@ -417,6 +418,113 @@ int slimfit_ref_restore_scores(const void *vals, const uint16_t *idx,
                    (const char *)vals + ((size_t)r * (size_t)k + (size_t)s) * esz,
                    esz);
         }
+    }
+    return bad ? REF_BAD : REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* GELU, whose input is the activation that Sec. 4 caches in 4 bits.    */
+/* The paper names the function without printing it; this is the exact  */
+/* (erf) form,  GELU(x) = x * Phi(x),  Phi(x) = (1 + erf(x / sqrt 2))/2, */
+/* and its derivative  Phi(x) + x * phi(x),  phi(x) = exp(-x^2/2)/sqrt(2 pi). */
+/* Evaluated in fp64 on the widened inputs, rounded once to the output  */
+/* dtype.  The fused GPU entry points are this composed with the        */
+/* quantiser above: forward caches quant(x) and returns GELU(x);        */
+/* backward returns dy * GELU'(x^) with x^ = code * scale in fp32.      */
+/* ------------------------------------------------------------------ */
+
+/* (1 + erf(t)) / 2 written as erfc(-t) / 2, which keeps its accuracy in the left tail */
+static double gelu_value(double x) { return 0.5 * x * erfc(-x * 0.70710678118654752440); }
+
+static double gelu_slope(double x)
+{
+    const double cdf = 0.5 * erfc(-x * 0.70710678118654752440);
+    const double pdf = exp(-0.5 * x * x) * 0.39894228040143267794;
+    return cdf + x * pdf;
+}
+
+int slimfit_ref_gelu(const void *x, int dt, int64_t n, void *y)
+{
+    if (!dtype_ok(dt) || n < 0 || (n > 0 && (!x || !y)))
+        return REF_BAD;
+    for (int64_t j = 0; j < n; ++j)
+        store_elem(y, dt, j, (float)gelu_value((double)load_elem(x, dt, j)));
+    return REF_OK;
+}
+
+/* xhat is always fp32 (the dequantised cache); dy and dx have dtype dt */
+int slimfit_ref_gelu_backward(const float *xhat, const void *dy, int dt, int64_t n, void *dx)
+{
+    if (!dtype_ok(dt) || n < 0 || (n > 0 && (!xhat || !dy || !dx)))
+        return REF_BAD;
+    for (int64_t j = 0; j < n; ++j)
+        store_elem(dx, dt, j, (float)((double)load_elem(dy, dt, j) * gelu_slope((double)xhat[j])));
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Softmax whose output Alg. 5 prunes (the attention probabilities that */
+/* Softmax and the following MatMul share as their cached activation).  */
+/* Per row:  p_j = exp(l_j - max_i l_i) / sum_i exp(l_i - max_i l_i),   */
+/* evaluated in fp64 on the widened logits and rounded once to dt.      */
+/* The kept set is decided on the logits, which order the row exactly   */
+/* as the probabilities do (exp is increasing) but are not subject to   */
+/* rounding: first k of "logit descending, column ascending", emitted   */
+/* in ascending column order; the kept values are the row's p_j.        */
+/* probs may be NULL (only the pruned form is wanted).                  */
+/* ------------------------------------------------------------------ */
+
+int slimfit_ref_softmax_prune(const void *logits, int dt, int64_t rows, int cols,
+                              int k, void *probs, void *vals, uint16_t *idx,
+                              int threads)
+{
+    if (!dtype_ok(dt) || rows < 0 || cols < 1 || cols > 65536 || k < 1 || k > cols)
+        return REF_BAD;
+    if (rows > 0 && (!logits || !vals || !idx))
+        return REF_BAD;
+    int bad = 0;
+    (void)threads;
+#pragma omp parallel for num_threads(threads > 1 ? threads : 1) schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const int64_t base = r * (int64_t)cols;
+        double *e = (double *)malloc(sizeof(double) * (size_t)cols);
+        ref_pair *buf = (ref_pair *)malloc(sizeof(ref_pair) * (size_t)cols);
+        uint8_t *kept = (uint8_t *)calloc((size_t)cols, 1);
+        if (!e || !buf || !kept) {
+            bad = 1;
+            free(e);
+            free(buf);
+            free(kept);
+            continue;
+        }
+        double top = -INFINITY, sum = 0.0;
+        for (int c = 0; c < cols; ++c) {
+            buf[c].v = load_elem(logits, dt, base + c);
+            buf[c].col = c;
+            if ((double)buf[c].v > top)
+                top = (double)buf[c].v;
+        }
+        for (int c = 0; c < cols; ++c) {
+            e[c] = exp((double)buf[c].v - top);
+            sum += e[c];
+        }
+        if (probs)
+            for (int c = 0; c < cols; ++c)
+                store_elem(probs, dt, base + c, (float)(e[c] / sum));
+        qsort(buf, (size_t)cols, sizeof(ref_pair), pair_before);
+        for (int s = 0; s < k; ++s)
+            kept[buf[s].col] = 1;
+        int out = 0;
+        for (int c = 0; c < cols; ++c) {
+            if (!kept[c])
+                continue;
+            store_elem(vals, dt, r * (int64_t)k + out, (float)(e[c] / sum));
+            idx[r * (int64_t)k + out] = (uint16_t)c;
+            ++out;
+        }
+        free(e);
+        free(buf);
+        free(kept);
     }
     return bad ? REF_BAD : REF_OK;
 }
