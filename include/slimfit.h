@@ -157,6 +157,35 @@ int32_t slimfit_dequant_unpack(const uint8_t *codes, const float *scales, int64_
                                void *y, int32_t dt, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (b') The same cache fused into its producer and consumer -- Sec. 4: the
+ *     input of GELU is a static activation kept for the backward pass in 4
+ *     bits; compression does not change the forward result.
+ *
+ *  slimfit_gelu_quant_pack       : y = GELU(x) from the exact x, and
+ *                                  (codes, scales) = slimfit_quant_pack(x), with
+ *                                  x read once.
+ *  slimfit_gelu_backward_dequant : dx = dy * GELU'(x^),  x^ = code * scale (the
+ *                                  fp32 product slimfit_dequant_unpack forms),
+ *                                  never written to memory.
+ *  GELU is the exact form  x * (1 + erf(x / sqrt 2)) / 2,  its derivative
+ *  (1 + erf(x / sqrt 2)) / 2 + x * exp(-x^2 / 2) / sqrt(2 pi); both in fp32
+ *  (codes and scales are bit-identical to the unfused call; y within
+ *  4e-7 * |x| + 1e-6 * |y| and dx within 1e-6 * |dy| of the fp64 value, bf16
+ *  results within one bf16 rounding of that).
+ *
+ *  x, y, dy, dx : DEVICE, n elements of dt, 16-byte aligned; y must not be x
+ *                 and dx must not be dy (INVALID_ARG), nor overlap them.
+ *  other arguments, layouts and errors as in (b).
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_gelu_quant_pack(const void *x, int32_t dt, int64_t n,
+                                int32_t mode, int32_t bits, int32_t block, int32_t frac_bits,
+                                void *y, uint8_t *codes, float *scales, void *stream);
+
+int32_t slimfit_gelu_backward_dequant(const uint8_t *codes, const float *scales, int64_t n,
+                                      int32_t mode, int32_t bits, int32_t block, int32_t frac_bits,
+                                      const void *dy, void *dx, int32_t dt, void *stream);
+
+/* ------------------------------------------------------------------------
  * (c) Pruning to values + indices -- Alg. 5 and the appendix on pruning:
  *     sort from largest to smallest with indices, keep the first k, store
  *     them with their indices (the dense size is rows x cols, which the

@@ -32,7 +32,7 @@ EXPORTS = (
     "slimfit_layer_delta_workspace", "slimfit_layer_delta_plan",
     "slimfit_layer_delta_run", "slimfit_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
-    "slimfit_dequant_unpack", "slimfit_keep_count", "slimfit_prune_scores",
+    "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update",
@@ -206,6 +206,30 @@ def dequant_unpack(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: in
         _dev(codes), _dev(scales), C.c_int64(y.numel()), C.c_int32(mode), C.c_int32(bits),
         C.c_int32(block), C.c_int32(frac_bits), _dev(y), C.c_int32(_dt(y)), _stream(stream))
     _check(rc, "dequant_unpack")
+
+
+# ---------------------------------------------------------------- (b') the cache fused into GELU
+
+def gelu_quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int, y: torch.Tensor,
+                    codes: torch.Tensor, scales: Optional[torch.Tensor], stream=None) -> None:
+    """y = GELU(x) and (codes, scales) = quant_pack(x) in one pass over x."""
+    assert x.is_contiguous() and y.is_contiguous() and y.dtype == x.dtype and y.numel() == x.numel()
+    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    rc = lib().slimfit_gelu_quant_pack(
+        _dev(x), C.c_int32(_dt(x)), C.c_int64(x.numel()), C.c_int32(mode), C.c_int32(bits), C.c_int32(block),
+        C.c_int32(frac_bits), _dev(y), _dev(codes), _dev(scales), _stream(stream))
+    _check(rc, "gelu_quant_pack")
+
+
+def gelu_backward_dequant(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: int, bits: int, block: int,
+                          frac_bits: int, dy: torch.Tensor, dx: torch.Tensor, stream=None) -> None:
+    """dx = dy * GELU'(dequantised cache); the dequantised values stay in registers."""
+    assert dy.is_contiguous() and dx.is_contiguous() and dx.dtype == dy.dtype and dx.numel() == dy.numel()
+    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    rc = lib().slimfit_gelu_backward_dequant(
+        _dev(codes), _dev(scales), C.c_int64(dx.numel()), C.c_int32(mode), C.c_int32(bits), C.c_int32(block),
+        C.c_int32(frac_bits), _dev(dy), _dev(dx), C.c_int32(_dt(dx)), _stream(stream))
+    _check(rc, "gelu_backward_dequant")
 
 
 # ---------------------------------------------------------------- (c) Alg. 5

@@ -8,6 +8,12 @@
 // absolute maximum is a DPP butterfly over those lanes -- no LDS, no second
 // pass over the data.  A workgroup covers kUnroll such steps so that each lane
 // has kUnroll independent 128-bit loads in flight.
+//
+// Producer fusion: the same tiles can also carry the GELU whose input is being
+// cached.  Forward, the lane that holds x for the quantiser also writes
+// GELU(x), so the activation is read once for both; backward, the dequantised
+// x^ never reaches memory: the lane multiplies the incoming gradient by
+// GELU'(x^) and writes the input gradient.
 #include "common.hpp"
 
 namespace slimfit {
@@ -73,13 +79,51 @@ __device__ __forceinline__ int quantise_one(float x, float mult)
     return (int)r;
 }
 
+// Exact (erf) GELU and its derivative in fp32.
+// 1 + erf(x / sqrt 2) is built from erfc(t), t = |x| / sqrt 2:  2 - erfc(t) for
+// x >= 0 and erfc(t) itself for x < 0, which also keeps the left tail free of
+// cancellation.  erfc(t) = exp(-t * Q(t)) with Q(t) = -ln(erfc t) / t, a smooth
+// function (Q(0) = 2 / sqrt pi) replaced by a degree-8 polynomial fitted to it
+// on [0, 4.2] (weighted least squares at Chebyshev nodes, weight erfc(t) * t);
+// beyond 4.2 erfc is below 3e-9 and t is clamped.  In fp32 with fused
+// multiply-adds and the hardware exp2 the absolute error of erfc stays under
+// 1.5e-7 (checked against fp64 on 3 M points), one branch-free path of about 16
+// instructions where the library erff takes two divergent ones of about 40.
+__device__ __forceinline__ float erfc_nonneg(float t)
+{
+    t = fminf(t, 4.2f);
+    float q = -8.094536919e-06f;
+    q = fmaf(q, t, 1.064909658e-04f);
+    q = fmaf(q, t, -5.896771888e-04f);
+    q = fmaf(q, t, 1.580125120e-03f);
+    q = fmaf(q, t, -6.248015670e-05f);
+    q = fmaf(q, t, -1.921485045e-02f);
+    q = fmaf(q, t, 1.027984564e-01f);
+    q = fmaf(q, t, 6.366162197e-01f);
+    q = fmaf(q, t, 1.128379327e+00f);
+    return __builtin_amdgcn_exp2f(-(q * t) * 1.44269504088896340736f);
+}
+__device__ __forceinline__ float twice_normal_cdf(float x)        // 1 + erf(x / sqrt 2)
+{
+    const float e = erfc_nonneg(fabsf(x) * 0.70710678118654752440f);
+    return x >= 0.0f ? 2.0f - e : e;
+}
+__device__ __forceinline__ float gelu_f32(float x) { return (0.5f * x) * twice_normal_cdf(x); }
+__device__ __forceinline__ float gelu_slope_f32(float x)
+{
+    const float pdf = __builtin_amdgcn_exp2f(((-0.5f * x) * x) * 1.44269504088896340736f) * 0.39894228040143267794f;
+    return 0.5f * twice_normal_cdf(x) + x * pdf;
+}
+
 // One workgroup tile of quantise + pack.  INSIDE: the whole tile lies below n, so
 // the code is straight-line (all loads issue back to back, no per-lane bounds);
 // otherwise every access is guarded and elements past n count as 0.
-// T: element type, BITS: 4|8, BLOCKED: per-block scale, G: lanes per block
-template <typename T, int BITS, bool BLOCKED, int G, bool INSIDE>
+// T: element type, BITS: 4|8, BLOCKED: per-block scale, G: lanes per block,
+// GELU: also write GELU(x) to y
+template <typename T, int BITS, bool BLOCKED, int G, bool INSIDE, bool GELU>
 __device__ __forceinline__ void quant_tile(const T *__restrict__ x, int64_t n, float fixed_mult,
-                                           uint8_t *__restrict__ codes, float *__restrict__ scales)
+                                           uint8_t *__restrict__ codes, float *__restrict__ scales,
+                                           T *__restrict__ y)
 {
     constexpr int V = Vec<T>::V;
     constexpr int OUT_BYTES = V * BITS / 8;            // packed bytes per lane-vector: 2, 4 or 8
@@ -97,6 +141,21 @@ __device__ __forceinline__ void quant_tile(const T *__restrict__ x, int64_t n, f
         } else {
 #pragma unroll
             for (int i = 0; i < V; ++i) f[u][i] = (e0 + i < n) ? Vec<T>::load1(x + e0 + i) : 0.0f;
+        }
+    }
+
+    if (GELU) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+            float g[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) g[i] = gelu_f32(f[u][i]);
+            if (INSIDE || e0 + V <= n) {
+                store_global<kNT>(reinterpret_cast<typename Vec<T>::raw *>(y + e0), Vec<T>::pack(g));
+            } else {
+                for (int i = 0; i < V && e0 + i < n; ++i) Vec<T>::store1(y + e0 + i, g[i]);
+            }
         }
     }
 
@@ -138,20 +197,23 @@ __device__ __forceinline__ void quant_tile(const T *__restrict__ x, int64_t n, f
     }
 }
 
-template <typename T, int BITS, bool BLOCKED, int G>
+template <typename T, int BITS, bool BLOCKED, int G, bool GELU>
 __global__ __launch_bounds__(kThreads) void quant_pack_kernel(const T *__restrict__ x, int64_t n, float fixed_mult,
-                                                              uint8_t *__restrict__ codes, float *__restrict__ scales)
+                                                              uint8_t *__restrict__ codes, float *__restrict__ scales,
+                                                              T *__restrict__ y)
 {
     constexpr int64_t TILE = (int64_t)kThreads * kUnrollQ * Vec<T>::V;
     if (((int64_t)blockIdx.x + 1) * TILE <= n)         // workgroup-uniform
-        quant_tile<T, BITS, BLOCKED, G, true>(x, n, fixed_mult, codes, scales);
+        quant_tile<T, BITS, BLOCKED, G, true, GELU>(x, n, fixed_mult, codes, scales, y);
     else
-        quant_tile<T, BITS, BLOCKED, G, false>(x, n, fixed_mult, codes, scales);
+        quant_tile<T, BITS, BLOCKED, G, false, GELU>(x, n, fixed_mult, codes, scales, y);
 }
 
-template <typename T, int BITS, bool BLOCKED, bool INSIDE>
+// GELU: y receives dy * GELU'(x^) instead of x^
+template <typename T, int BITS, bool BLOCKED, bool INSIDE, bool GELU>
 __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, const float *__restrict__ scales,
-                                             int64_t n, int block_shift, float fixed_step, T *__restrict__ y)
+                                             int64_t n, int block_shift, float fixed_step, T *__restrict__ y,
+                                             const T *__restrict__ dy)
 {
     constexpr int V = Vec<T>::V;
     constexpr int IN_BYTES = V * BITS / 8;
@@ -160,12 +222,22 @@ __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, 
 
     uint32_t w[kUnroll][2];
     float s[kUnroll];
+    float grad[GELU ? kUnroll : 1][V];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
         w[u][0] = w[u][1] = 0u;
         s[u] = fixed_step;
         if (!INSIDE && e0 >= n) continue;
+        if (GELU) {
+            if (INSIDE || e0 + V <= n) {
+                typename Vec<T>::raw r = load_global<kNT>(reinterpret_cast<const typename Vec<T>::raw *>(dy + e0));
+                Vec<T>::unpack(r, grad[u]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) grad[u][i] = (e0 + i < n) ? Vec<T>::load1(dy + e0 + i) : 0.0f;
+            }
+        }
         const uint8_t *src = codes + (e0 * BITS) / 8;
         if (INSIDE || e0 + V <= n) {
             if (IN_BYTES == 2) w[u][0] = load_global<kNT>(reinterpret_cast<const uint16_t *>(src));
@@ -189,6 +261,7 @@ __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, 
             const int sh = (i * BITS) % 32;
             const int c = (int)(word << (32 - BITS - sh)) >> (32 - BITS);   // sign-extending field extract
             f[i] = (float)c * s[u];                                        // one fp32 multiply
+            if (GELU) f[i] = grad[u][i] * gelu_slope_f32(f[i]);
         }
         if (INSIDE || e0 + V <= n) {
             store_global<kNT>(reinterpret_cast<typename Vec<T>::raw *>(y + e0), Vec<T>::pack(f));
@@ -198,17 +271,17 @@ __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, 
     }
 }
 
-template <typename T, int BITS, bool BLOCKED>
+template <typename T, int BITS, bool BLOCKED, bool GELU>
 __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
                                                                   const float *__restrict__ scales, int64_t n,
                                                                   int block_shift, float fixed_step,
-                                                                  T *__restrict__ y)
+                                                                  T *__restrict__ y, const T *__restrict__ dy)
 {
     constexpr int64_t TILE = (int64_t)kThreads * kUnrollD * Vec<T>::V;
     if (((int64_t)blockIdx.x + 1) * TILE <= n)         // workgroup-uniform
-        dequant_tile<T, BITS, BLOCKED, true>(codes, scales, n, block_shift, fixed_step, y);
+        dequant_tile<T, BITS, BLOCKED, true, GELU>(codes, scales, n, block_shift, fixed_step, y, dy);
     else
-        dequant_tile<T, BITS, BLOCKED, false>(codes, scales, n, block_shift, fixed_step, y);
+        dequant_tile<T, BITS, BLOCKED, false, GELU>(codes, scales, n, block_shift, fixed_step, y, dy);
 }
 
 inline unsigned grid_for(int64_t n, int V, int unroll)
@@ -217,37 +290,42 @@ inline unsigned grid_for(int64_t n, int V, int unroll)
     return (unsigned)((n + per_block - 1) / per_block);
 }
 
-template <typename T, int BITS>
-void launch_quant(const void *x, int64_t n, int mode, int block, int frac_bits, uint8_t *codes, float *scales,
+template <typename T, int BITS, bool GELU>
+void launch_quant(const void *x, int64_t n, int mode, int block, int frac_bits, uint8_t *codes, float *scales, void *y,
                   hipStream_t st)
 {
     constexpr int V = Vec<T>::V;
     const dim3 grid(grid_for(n, V, kUnrollQ)), tb(kThreads);
     const T *xp = static_cast<const T *>(x);
+    T *yp = static_cast<T *>(y);
     if (mode == SLIMFIT_Q_FIXED) {
-        quant_pack_kernel<T, BITS, false, 4><<<grid, tb, 0, st>>>(xp, n, __builtin_ldexpf(1.0f, frac_bits), codes, nullptr);
+        quant_pack_kernel<T, BITS, false, 4, GELU><<<grid, tb, 0, st>>>(xp, n, __builtin_ldexpf(1.0f, frac_bits), codes,
+                                                                        nullptr, yp);
         return;
     }
     switch (block / V) {
-    case 4: quant_pack_kernel<T, BITS, true, 4><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
-    case 8: quant_pack_kernel<T, BITS, true, 8><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
-    case 16: quant_pack_kernel<T, BITS, true, 16><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
-    case 32: quant_pack_kernel<T, BITS, true, 32><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
-    default: quant_pack_kernel<T, BITS, true, 64><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales); break;
+    case 4: quant_pack_kernel<T, BITS, true, 4, GELU><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales, yp); break;
+    case 8: quant_pack_kernel<T, BITS, true, 8, GELU><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales, yp); break;
+    case 16: quant_pack_kernel<T, BITS, true, 16, GELU><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales, yp); break;
+    case 32: quant_pack_kernel<T, BITS, true, 32, GELU><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales, yp); break;
+    default: quant_pack_kernel<T, BITS, true, 64, GELU><<<grid, tb, 0, st>>>(xp, n, 0.0f, codes, scales, yp); break;
     }
 }
 
-template <typename T, int BITS>
+template <typename T, int BITS, bool GELU>
 void launch_dequant(const uint8_t *codes, const float *scales, int64_t n, int mode, int block, int frac_bits, void *y,
-                    hipStream_t st)
+                    const void *dy, hipStream_t st)
 {
     constexpr int V = Vec<T>::V;
     const dim3 grid(grid_for(n, V, kUnrollD)), tb(kThreads);
     T *yp = static_cast<T *>(y);
+    const T *gp = static_cast<const T *>(dy);
     if (mode == SLIMFIT_Q_FIXED)
-        dequant_unpack_kernel<T, BITS, false><<<grid, tb, 0, st>>>(codes, nullptr, n, 0, __builtin_ldexpf(1.0f, -frac_bits), yp);
+        dequant_unpack_kernel<T, BITS, false, GELU><<<grid, tb, 0, st>>>(codes, nullptr, n, 0,
+                                                                         __builtin_ldexpf(1.0f, -frac_bits), yp, gp);
     else
-        dequant_unpack_kernel<T, BITS, true><<<grid, tb, 0, st>>>(codes, scales, n, __builtin_ctz((unsigned)block), 0.0f, yp);
+        dequant_unpack_kernel<T, BITS, true, GELU><<<grid, tb, 0, st>>>(codes, scales, n, __builtin_ctz((unsigned)block),
+                                                                        0.0f, yp, gp);
 }
 
 int32_t validate(int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block, int32_t frac_bits)
@@ -280,53 +358,91 @@ extern "C" int64_t slimfit_num_blocks(int64_t n, int32_t block)
     return (n + block - 1) / block;
 }
 
-extern "C" int32_t slimfit_quant_pack(const void *x, int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block,
-                                      int32_t frac_bits, uint8_t *codes, float *scales, void *stream)
+namespace {
+
+template <bool GELU>
+int32_t quant_entry(const void *x, int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block, int32_t frac_bits,
+                    void *y, uint8_t *codes, float *scales, void *stream)
 {
     int32_t rc = validate(dt, n, mode, bits, block, frac_bits);
     if (rc != SLIMFIT_OK) return rc;
     if (n == 0) return SLIMFIT_OK;
-    if (!x || !codes || (mode == SLIMFIT_Q_BLOCK && !scales)) return SLIMFIT_ERR_INVALID_ARG;
-    if (!aligned_to(x, 16) || !aligned_to(codes, 16) || (mode == SLIMFIT_Q_BLOCK && !aligned_to(scales, 16)))
+    if (!x || !codes || (mode == SLIMFIT_Q_BLOCK && !scales) || (GELU && !y)) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(x, 16) || !aligned_to(codes, 16) || (mode == SLIMFIT_Q_BLOCK && !aligned_to(scales, 16)) ||
+        (GELU && !aligned_to(y, 16)))
         return SLIMFIT_ERR_ALIGNMENT;
     if ((rc = check_device_range(x, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
+    if (GELU && (rc = check_device_range(y, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(codes, slimfit_packed_bytes(n, bits))) != SLIMFIT_OK) return rc;
     if (mode == SLIMFIT_Q_BLOCK &&
         (rc = check_device_range(scales, (size_t)slimfit_num_blocks(n, block) * 4)) != SLIMFIT_OK)
         return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dt == SLIMFIT_F32) {
-        if (bits == 4) launch_quant<float, 4>(x, n, mode, block, frac_bits, codes, scales, st);
-        else launch_quant<float, 8>(x, n, mode, block, frac_bits, codes, scales, st);
+        if (bits == 4) launch_quant<float, 4, GELU>(x, n, mode, block, frac_bits, codes, scales, y, st);
+        else launch_quant<float, 8, GELU>(x, n, mode, block, frac_bits, codes, scales, y, st);
     } else {
-        if (bits == 4) launch_quant<uint16_t, 4>(x, n, mode, block, frac_bits, codes, scales, st);
-        else launch_quant<uint16_t, 8>(x, n, mode, block, frac_bits, codes, scales, st);
+        if (bits == 4) launch_quant<uint16_t, 4, GELU>(x, n, mode, block, frac_bits, codes, scales, y, st);
+        else launch_quant<uint16_t, 8, GELU>(x, n, mode, block, frac_bits, codes, scales, y, st);
     }
     return launch_status();
+}
+
+template <bool GELU>
+int32_t dequant_entry(const uint8_t *codes, const float *scales, int64_t n, int32_t mode, int32_t bits, int32_t block,
+                      int32_t frac_bits, const void *dy, void *y, int32_t dt, void *stream)
+{
+    int32_t rc = validate(dt, n, mode, bits, block, frac_bits);
+    if (rc != SLIMFIT_OK) return rc;
+    if (n == 0) return SLIMFIT_OK;
+    if (!y || !codes || (mode == SLIMFIT_Q_BLOCK && !scales) || (GELU && !dy)) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(y, 16) || !aligned_to(codes, 16) || (mode == SLIMFIT_Q_BLOCK && !aligned_to(scales, 16)) ||
+        (GELU && !aligned_to(dy, 16)))
+        return SLIMFIT_ERR_ALIGNMENT;
+    if ((rc = check_device_range(y, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
+    if (GELU && (rc = check_device_range(dy, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(codes, slimfit_packed_bytes(n, bits))) != SLIMFIT_OK) return rc;
+    if (mode == SLIMFIT_Q_BLOCK &&
+        (rc = check_device_range(scales, (size_t)slimfit_num_blocks(n, block) * 4)) != SLIMFIT_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == SLIMFIT_F32) {
+        if (bits == 4) launch_dequant<float, 4, GELU>(codes, scales, n, mode, block, frac_bits, y, dy, st);
+        else launch_dequant<float, 8, GELU>(codes, scales, n, mode, block, frac_bits, y, dy, st);
+    } else {
+        if (bits == 4) launch_dequant<uint16_t, 4, GELU>(codes, scales, n, mode, block, frac_bits, y, dy, st);
+        else launch_dequant<uint16_t, 8, GELU>(codes, scales, n, mode, block, frac_bits, y, dy, st);
+    }
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" int32_t slimfit_quant_pack(const void *x, int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block,
+                                      int32_t frac_bits, uint8_t *codes, float *scales, void *stream)
+{
+    return quant_entry<false>(x, dt, n, mode, bits, block, frac_bits, nullptr, codes, scales, stream);
 }
 
 extern "C" int32_t slimfit_dequant_unpack(const uint8_t *codes, const float *scales, int64_t n, int32_t mode,
                                           int32_t bits, int32_t block, int32_t frac_bits, void *y, int32_t dt,
                                           void *stream)
 {
-    int32_t rc = validate(dt, n, mode, bits, block, frac_bits);
-    if (rc != SLIMFIT_OK) return rc;
-    if (n == 0) return SLIMFIT_OK;
-    if (!y || !codes || (mode == SLIMFIT_Q_BLOCK && !scales)) return SLIMFIT_ERR_INVALID_ARG;
-    if (!aligned_to(y, 16) || !aligned_to(codes, 16) || (mode == SLIMFIT_Q_BLOCK && !aligned_to(scales, 16)))
-        return SLIMFIT_ERR_ALIGNMENT;
-    if ((rc = check_device_range(y, (size_t)n * dtype_size(dt))) != SLIMFIT_OK) return rc;
-    if ((rc = check_device_range(codes, slimfit_packed_bytes(n, bits))) != SLIMFIT_OK) return rc;
-    if (mode == SLIMFIT_Q_BLOCK &&
-        (rc = check_device_range(scales, (size_t)slimfit_num_blocks(n, block) * 4)) != SLIMFIT_OK)
-        return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == SLIMFIT_F32) {
-        if (bits == 4) launch_dequant<float, 4>(codes, scales, n, mode, block, frac_bits, y, st);
-        else launch_dequant<float, 8>(codes, scales, n, mode, block, frac_bits, y, st);
-    } else {
-        if (bits == 4) launch_dequant<uint16_t, 4>(codes, scales, n, mode, block, frac_bits, y, st);
-        else launch_dequant<uint16_t, 8>(codes, scales, n, mode, block, frac_bits, y, st);
-    }
-    return launch_status();
+    return dequant_entry<false>(codes, scales, n, mode, bits, block, frac_bits, nullptr, y, dt, stream);
+}
+
+extern "C" int32_t slimfit_gelu_quant_pack(const void *x, int32_t dt, int64_t n, int32_t mode, int32_t bits,
+                                           int32_t block, int32_t frac_bits, void *y, uint8_t *codes, float *scales,
+                                           void *stream)
+{
+    if (x && x == y) return SLIMFIT_ERR_INVALID_ARG;                    // the kernels are compiled for distinct buffers
+    return quant_entry<true>(x, dt, n, mode, bits, block, frac_bits, y, codes, scales, stream);
+}
+
+extern "C" int32_t slimfit_gelu_backward_dequant(const uint8_t *codes, const float *scales, int64_t n, int32_t mode,
+                                                 int32_t bits, int32_t block, int32_t frac_bits, const void *dy,
+                                                 void *dx, int32_t dt, void *stream)
+{
+    if (dy && dy == dx) return SLIMFIT_ERR_INVALID_ARG;
+    return dequant_entry<true>(codes, scales, n, mode, bits, block, frac_bits, dy, dx, dt, stream);
 }
