@@ -259,6 +259,36 @@ def main() -> int:
                             "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                             "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del gv, gi, gp, gws, gout
+        # the caches fused into their producer / consumer (x read once; the dequantised values never stored;
+        # softmax and pruning in one pass over the logits)
+        n_g = sets[0].gelu.numel()
+        nb_g = 2 * n_g * in_sz + sf.packed_bytes(n_g, bits) + 4 * sf.num_blocks(n_g, block)
+        rows_s, cols_s = sets[0].scores.shape
+        nb_s = 2 * rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (in_sz + 2)
+        probs = [torch.empty_like(s.scores) for s in sets]
+        fused = {
+            "gelu_quant_pack[gelu_in]": (nb_g, lambda i: sf.gelu_quant_pack(
+                sets[i].gelu, sf.Q_BLOCK, bits, block, 0, sets[i].deq[0], sets[i].codes[0], sets[i].scales[0])),
+            "gelu_backward_dequant[gelu_in]": (nb_g, lambda i: sf.gelu_backward_dequant(
+                sets[i].codes[0], sets[i].scales[0], sf.Q_BLOCK, bits, block, 0, sets[i].gelu, sets[i].deq[0])),
+            "softmax_prune[scores as logits]": (nb_s, lambda i: sf.softmax_prune(
+                sets[i].scores, cfg.keep_k, probs[i], sets[i].vals, sets[i].idx)),
+        }
+        for name, (nb, fn) in fused.items():
+            for i in range(len(sets)):
+                fn(i)
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for i, (a, b) in enumerate(ev):
+                a.record()
+                fn(i % n_sets)
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+            extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                            "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del probs
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

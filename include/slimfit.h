@@ -223,6 +223,29 @@ int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int3
                                void *out, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (c'') Pruning fused into the Softmax that produces the probabilities -- the
+ *     output of Softmax is the activation that Softmax and the following MatMul
+ *     share (Sec. 4); Alg. 5 prunes it for the backward pass while the forward
+ *     pass goes on with the dense row.
+ *
+ *     Per row of logits:  p_j = exp(l_j - max l) / sum_i exp(l_i - max l)  is
+ *     written to probs (dense, for the forward MatMul), and the k pairs that
+ *     slimfit_prune_scores would keep are written to vals / idx.  The kept set
+ *     is decided on the logits: they order the row exactly as the probabilities
+ *     do and are not subject to rounding (equal logits: lower column first);
+ *     vals are the row's p_j, emitted in ascending column order.  Arithmetic is
+ *     fp32 (hardware exp2, fixed-order wave sum, one IEEE division per row):
+ *     p_j within p_j * (2e-6 + 2e-7 * (max l - l_j)) of the exact value (a
+ *     subnormal p_j may be flushed to zero), bf16 results within one further
+ *     bf16 rounding.
+ *
+ *  logits, probs : DEVICE, rows*cols elements of dt, distinct buffers.
+ *  vals, idx     : as in (c).   1 <= k <= cols <= 1024 (wider rows: UNSUPPORTED).
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_softmax_prune(const void *logits, int32_t dt, int64_t rows, int32_t cols, int32_t k,
+                              void *probs, void *vals, uint16_t *idx, void *stream);
+
+/* ------------------------------------------------------------------------
  * (c') Alg. 5 on a whole flattened tensor -- the form the paper applies to the
  *     standardised input of LayerNorm: sort all n entries from largest to
  *     smallest with their indices, keep the first k = int(n * 0.1), store the

@@ -33,7 +33,7 @@ EXPORTS = (
     "slimfit_layer_delta_run", "slimfit_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
-    "slimfit_restore_scores", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
+    "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update",
 )
@@ -258,6 +258,19 @@ def restore_scores(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch
         _dev(vals), _dev(idx), _dev(counts), C.c_int32(_dt(out)), C.c_int64(rows),
         C.c_int32(cols), C.c_int32(k), _dev(out), _stream(stream))
     _check(rc, "restore_scores")
+
+
+def softmax_prune(logits: torch.Tensor, k: int, probs: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor,
+                  stream=None) -> None:
+    """probs = softmax(logits) per row; (vals, idx) = the k largest of every row (decided on the logits)."""
+    assert logits.dim() == 2 and logits.is_contiguous() and probs.is_contiguous()
+    assert probs.shape == logits.shape and probs.dtype == logits.dtype
+    assert vals.dtype == logits.dtype and idx.dtype == torch.uint16
+    rows, cols = logits.shape
+    rc = lib().slimfit_softmax_prune(
+        _dev(logits), C.c_int32(_dt(logits)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
+        _dev(probs), _dev(vals), _dev(idx), _stream(stream))
+    _check(rc, "softmax_prune")
 
 
 # ---------------------------------------------------------------- (c') Alg. 5, whole tensor

@@ -111,6 +111,23 @@ __device__ __forceinline__ int wave_scan_i32(int v)
     return v;
 }
 
+// sum of one float per lane, in a fixed order; result uniform
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add_f32(float v)      // absent sources contribute +0
+{
+    return v + __builtin_bit_cast(float, dpp_zero_i32<CTRL, ROW_MASK>(__builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+    v = dpp_add_f32<kDppRowShr1, 0xF>(v);
+    v = dpp_add_f32<kDppRowShr2, 0xF>(v);
+    v = dpp_add_f32<kDppRowShr4, 0xF>(v);
+    v = dpp_add_f32<kDppRowShr8, 0xF>(v);
+    v = dpp_add_f32<kDppBcast15, 0xA>(v);
+    v = dpp_add_f32<kDppBcast31, 0xC>(v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
 #ifndef SLIMFIT_PRUNE_NT
 #define SLIMFIT_PRUNE_NT 1             // row loads are streamed once
 #endif
@@ -177,11 +194,15 @@ __device__ __forceinline__ void emit_row(Pred pred, const float (&f)[M], int lan
 }
 
 // T: element type; M: slots per lane; FULL: cols == 64*M (no absent columns);
-// STAGED: k <= kStage, outputs of kRowsPerUnit rows leave as contiguous runs.
-template <typename T, int M, bool FULL, bool STAGED>
+// STAGED: k <= kStage, outputs of kRowsPerUnit rows leave as contiguous runs;
+// SOFTMAX: the rows are logits: the row's softmax is written to `probs`, the
+// kept set is decided on the logits (which order the row as the probabilities
+// do, without their rounding) and the kept values are the probabilities.
+template <typename T, int M, bool FULL, bool STAGED, bool SOFTMAX>
 __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__restrict__ p, int64_t rows, int cols, int k,
                                                               int mode, float tau, T *__restrict__ vals,
-                                                              uint16_t *__restrict__ idx, int32_t *__restrict__ counts)
+                                                              uint16_t *__restrict__ idx, int32_t *__restrict__ counts,
+                                                              T *__restrict__ probs)
 {
     // keys of bf16 inputs have 16 zero low bits: work in units of 2^16 there
     constexpr int KEY_SHIFT = sizeof(T) == 2 ? 16 : 0;
@@ -236,6 +257,32 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                     for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(next_src + ccol[j]);
                 }
             }
+
+            float pv[M];                 // SOFTMAX: the row's probabilities, in the output dtype's values
+            if constexpr (SOFTMAX) {
+                float lm = ninf;
+#pragma unroll
+                for (int j = 0; j < M; ++j) lm = fmaxf(lm, (FULL || valid[j]) ? f[j] : ninf);
+                const float row_max = key_to_float(wave_umax(float_to_key(lm)));
+                float part = 0.0f;
+#pragma unroll
+                for (int j = 0; j < M; ++j) {
+                    const float e = __builtin_amdgcn_exp2f((f[j] - row_max) * 1.44269504088896340736f);
+                    pv[j] = (FULL || valid[j]) ? e : 0.0f;
+                    part += pv[j];
+                }
+                const float inv = 1.0f / wave_sum_f32(part);      // IEEE division
+                T *prow = probs + row * (int64_t)cols;
+#pragma unroll
+                for (int j = 0; j < M; ++j) {
+                    float pj = pv[j] * inv;
+                    if (sizeof(T) == 2) pj = bf16_widen(bf16_narrow(pj));
+                    pv[j] = pj;
+                    if (FULL || valid[j])
+                        store_global<SLIMFIT_PRUNE_NT_STORE != 0>(prow + j * kWave + lane, Elem<T>::raw(pj));
+                }
+            }
+            const float(&kept_value)[M] = SOFTMAX ? pv : f;
 
             auto count_ge = [&](float t) {
                 int c = 0;
@@ -337,7 +384,8 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
             uint16_t *oi = idx + row * (int64_t)k;
             const uint32_t first = STAGED ? (uint32_t)(i * k) : 0u;
             if (c_ge == kk) {
-                emit_row<T, M, STAGED>([&](int j) { return valid[j] && f[j] >= T_cut; }, f, lane, k, kk, ov, oi, rec, first);
+                emit_row<T, M, STAGED>([&](int j) { return valid[j] && f[j] >= T_cut; }, kept_value, lane, k, kk, ov, oi, rec,
+                                       first);
             } else {
                 // more than kk entries reach the cut value: all above it, then the
                 // equal ones by ascending column until kk are taken
@@ -355,7 +403,7 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                     sel[j] = valid[j] && (f[j] > T_exact || (eq && rank < need));
                     seen += popc64(eqm);
                 }
-                emit_row<T, M, STAGED>([&](int j) { return sel[j]; }, f, lane, k, kk, ov, oi, rec, first);
+                emit_row<T, M, STAGED>([&](int j) { return sel[j]; }, kept_value, lane, k, kk, ov, oi, rec, first);
             }
             my_count = lane == i ? kk : my_count;
         }
@@ -604,14 +652,15 @@ __global__ __launch_bounds__(kThreads) void restore_tile_kernel(const T *__restr
     for (int e = n_vec * PER16 + tid; e < n; e += kThreads) dst[e] = tile[e];
 }
 
-template <typename T>
+template <typename T, bool SOFTMAX>
 void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float tau, void *vals, uint16_t *idx,
-                  int32_t *counts, hipStream_t st)
+                  int32_t *counts, void *probs, hipStream_t st)
 {
     const T *pp = static_cast<const T *>(p);
     T *vv = static_cast<T *>(vals);
+    T *pr = static_cast<T *>(probs);
     const int slots = (cols + kWave - 1) / kWave;
-    if (slots > kMaxRegSlots) {
+    if (slots > kMaxRegSlots) {                       // never with SOFTMAX: the entry point rejects such rows
         const unsigned grid = (unsigned)(rows < 16384 ? rows : 16384);
         prune_rows_wide_kernel<T><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
         return;
@@ -619,17 +668,15 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
     const int64_t rows_per_block = (int64_t)kRowWaves * kRowsPerUnit;
     const int64_t blocks_needed = (rows + rows_per_block - 1) / rows_per_block;
     const unsigned grid = (unsigned)(blocks_needed < kMaxPruneBlocks ? blocks_needed : kMaxPruneBlocks);
+#define SLIMFIT_PRUNE_LAUNCH(MM, FF, SS)                                                                       \
+    prune_rows_kernel<T, MM, FF, SS, SOFTMAX><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts, pr)
 #define SLIMFIT_PRUNE_CASE(MM)                                                                                  \
     do {                                                                                                        \
         const bool full = cols == MM * kWave, staged = k <= kStage;                                             \
-        if (full && staged)                                                                                     \
-            prune_rows_kernel<T, MM, true, true><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);   \
-        else if (full)                                                                                          \
-            prune_rows_kernel<T, MM, true, false><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
-        else if (staged)                                                                                        \
-            prune_rows_kernel<T, MM, false, true><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);  \
-        else                                                                                                    \
-            prune_rows_kernel<T, MM, false, false><<<grid, kRowThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts); \
+        if (full && staged) SLIMFIT_PRUNE_LAUNCH(MM, true, true);                                               \
+        else if (full) SLIMFIT_PRUNE_LAUNCH(MM, true, false);                                                   \
+        else if (staged) SLIMFIT_PRUNE_LAUNCH(MM, false, true);                                                 \
+        else SLIMFIT_PRUNE_LAUNCH(MM, false, false);                                                            \
     } while (0)
     if (slots <= 1) SLIMFIT_PRUNE_CASE(1);
     else if (slots <= 2) SLIMFIT_PRUNE_CASE(2);
@@ -640,6 +687,7 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
     else if (slots <= 12) SLIMFIT_PRUNE_CASE(12);
     else SLIMFIT_PRUNE_CASE(16);
 #undef SLIMFIT_PRUNE_CASE
+#undef SLIMFIT_PRUNE_LAUNCH
 }
 
 int32_t validate(int32_t dt, int64_t rows, int32_t cols, int32_t k)
@@ -680,8 +728,31 @@ extern "C" int32_t slimfit_prune_scores(const void *p, int32_t dt, int64_t rows,
     // columns with -inf, so use the lowest finite value instead
     if (mode == SLIMFIT_PRUNE_THRESHOLD && tau == -INFINITY) tau = -FLT_MAX;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == SLIMFIT_F32) launch_prune<float>(p, rows, cols, k, mode, tau, vals, idx, counts, st);
-    else launch_prune<uint16_t>(p, rows, cols, k, mode, tau, vals, idx, counts, st);
+    if (dt == SLIMFIT_F32) launch_prune<float, false>(p, rows, cols, k, mode, tau, vals, idx, counts, nullptr, st);
+    else launch_prune<uint16_t, false>(p, rows, cols, k, mode, tau, vals, idx, counts, nullptr, st);
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_softmax_prune(const void *logits, int32_t dt, int64_t rows, int32_t cols, int32_t k,
+                                         void *probs, void *vals, uint16_t *idx, void *stream)
+{
+    int32_t rc = validate(dt, rows, cols, k);
+    if (rc != SLIMFIT_OK) return rc;
+    if (cols > kMaxRegSlots * kWave) return SLIMFIT_ERR_UNSUPPORTED;      // the row has to fit one wave's registers
+    if (rows == 0) return SLIMFIT_OK;
+    if (!logits || !probs || !vals || !idx || logits == probs) return SLIMFIT_ERR_INVALID_ARG;
+    const size_t esz = dtype_size(dt);
+    if (!aligned_to(logits, esz) || !aligned_to(probs, esz) || !aligned_to(vals, esz) || !aligned_to(idx, 2))
+        return SLIMFIT_ERR_ALIGNMENT;
+    if ((rc = check_device_range(logits, (size_t)rows * (size_t)cols * esz)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(probs, (size_t)rows * (size_t)cols * esz)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(vals, (size_t)rows * (size_t)k * esz)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(idx, (size_t)rows * (size_t)k * 2)) != SLIMFIT_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == SLIMFIT_F32)
+        launch_prune<float, true>(logits, rows, cols, k, SLIMFIT_PRUNE_TOPK, 0.0f, vals, idx, nullptr, probs, st);
+    else
+        launch_prune<uint16_t, true>(logits, rows, cols, k, SLIMFIT_PRUNE_TOPK, 0.0f, vals, idx, nullptr, probs, st);
     return launch_status();
 }
 
