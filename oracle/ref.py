@@ -48,7 +48,8 @@ def lib():
             for name in ("layer_delta", "quant_pack", "dequant_unpack",
                          "prune_scores", "restore_scores", "ils_select",
                          "ils_update", "freeze_count", "keep_count",
-                         "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune"):
+                         "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune",
+                         "layernorm_forward", "standardize", "layernorm_backward_pruned"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
         return _lib
 
@@ -200,6 +201,51 @@ def softmax_prune(logits, k, want_probs=True, threads=1):
                                          C.c_int(k), _ptr(probs), _ptr(vals), _ptr(idx), C.c_int(threads))
     _check(rc, "softmax_prune")
     return probs, vals, idx
+
+
+def layernorm_forward(x, gamma, beta, eps=1e-5, threads=1):
+    """Row LayerNorm in fp64 -> (y, mean, rstd) as float32; x is (rows, H) float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, H = x.shape
+    gamma = np.ascontiguousarray(gamma, dtype=np.float32)
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    assert gamma.size == H and beta.size == H
+    y = np.empty_like(x)
+    mean = np.empty(rows, dtype=np.float32)
+    rstd = np.empty(rows, dtype=np.float32)
+    rc = lib().slimfit_ref_layernorm_forward(_ptr(x), _ptr(gamma), _ptr(beta), C.c_int64(rows), C.c_int(H),
+                                             C.c_float(eps), _ptr(y), _ptr(mean), _ptr(rstd), C.c_int(threads))
+    _check(rc, "layernorm_forward")
+    return y, mean, rstd
+
+
+def standardize(x, mean, rstd):
+    """x~ = fl(fl(x - mean_r) * rstd_r) in fp32 (the values the fused pruner orders)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, H = x.shape
+    mean = np.ascontiguousarray(mean, dtype=np.float32)
+    rstd = np.ascontiguousarray(rstd, dtype=np.float32)
+    assert mean.size == rows and rstd.size == rows
+    xs = np.empty_like(x)
+    _check(lib().slimfit_ref_standardize(_ptr(x), _ptr(mean), _ptr(rstd), C.c_int64(rows), C.c_int(H), _ptr(xs)),
+           "standardize")
+    return xs
+
+
+def layernorm_backward_pruned(vals, idx, rstd, gamma, dy):
+    """Input gradient of a frozen LayerNorm from the kept (value, flat index) pairs of x~; dy is (rows, H)."""
+    dy = np.ascontiguousarray(dy, dtype=np.float32)
+    rows, H = dy.shape
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    rstd = np.ascontiguousarray(rstd, dtype=np.float32)
+    gamma = np.ascontiguousarray(gamma, dtype=np.float32)
+    assert vals.size == idx.size and rstd.size == rows and gamma.size == H
+    dx = np.empty_like(dy)
+    rc = lib().slimfit_ref_layernorm_backward_pruned(_ptr(vals), _ptr(idx), C.c_int64(vals.size), _ptr(rstd),
+                                                     _ptr(gamma), _ptr(dy), C.c_int64(rows), C.c_int(H), _ptr(dx))
+    _check(rc, "layernorm_backward_pruned")
+    return dx
 
 
 def gelu(x):

@@ -23,7 +23,9 @@
  * idempotence and pack/unpack identity for the quantiser; brute-force
  * repeat-argmax selector and a library stable argsort for the pruner (row-wise
  * and whole-tensor forms); textbook values, the reflection identity, a library
- * normal CDF and numerical differentiation for GELU and its derivative.
+ * normal CDF and numerical differentiation for GELU and its derivative; a
+ * library layer norm and its automatic derivative (fp64) for LayerNorm and the
+ * paper's input-gradient formula.
  * Parity unpinned by the paper (it prints no worked numbers for them): the
  * per-block-scale mode, the 4-bit split of integer/fraction bits, the
  * threshold pruning mode and bf16 I/O.  Those are pinned by brute force and
@@ -609,6 +611,102 @@ int slimfit_ref_restore_global(const void *vals, const int32_t *idx, int64_t k,
             return REF_BAD;
         memcpy((char *)out + (size_t)idx[s] * esz, (const char *)vals + (size_t)s * esz, esz);
     }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* LayerNorm as Sec. 4 writes it, per row of H elements:                */
+/*   x~ = (x - E x) / sqrt(Var x + eps),   y = x~ * gamma + beta,       */
+/* and, for a frozen LayerNorm, the input gradient                      */
+/*   g = gamma * y^ / (H * sqrt(Var x + eps)),                          */
+/*   x^ = H * g - sum_H g - x~ * sum_H (g * x~),                        */
+/* where x~ is what the layer keeps for the backward pass: all of it,   */
+/* or the pairs Alg. 5 kept of it (every other x~ counts as 0).         */
+/* Var is the mean of squared deviations (divisor H).  All in fp64 on   */
+/* the fp32 inputs, rounded once to fp32.                               */
+/* ------------------------------------------------------------------ */
+
+int slimfit_ref_layernorm_forward(const float *x, const float *gamma, const float *beta,
+                                  int64_t rows, int H, float eps, float *y,
+                                  float *mean, float *rstd, int threads)
+{
+    if (rows < 0 || H < 1 || !(eps >= 0.0f))
+        return REF_BAD;
+    if (rows > 0 && (!x || !gamma || !beta || !y || !mean || !rstd))
+        return REF_BAD;
+    (void)threads;
+#pragma omp parallel for num_threads(threads > 1 ? threads : 1) schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *xr = x + r * (int64_t)H;
+        double mu = 0.0, var = 0.0;
+        for (int j = 0; j < H; ++j)
+            mu += (double)xr[j];
+        mu /= (double)H;
+        for (int j = 0; j < H; ++j) {
+            const double d = (double)xr[j] - mu;
+            var += d * d;
+        }
+        var /= (double)H;
+        const double rs = 1.0 / sqrt(var + (double)eps);
+        for (int j = 0; j < H; ++j)
+            y[r * (int64_t)H + j] = (float)(((double)xr[j] - mu) * rs * (double)gamma[j] + (double)beta[j]);
+        mean[r] = (float)mu;
+        rstd[r] = (float)rs;
+    }
+    return REF_OK;
+}
+
+/* The standardised tensor as the fused pruner forms it: two fp32 operations  */
+/* per element on given fp32 statistics, x~_j = fl(fl(x_j - mean_r) * rstd_r), */
+/* so that the k-th largest |x~| is decided on the same bits on both sides.    */
+int slimfit_ref_standardize(const float *x, const float *mean, const float *rstd,
+                            int64_t rows, int H, float *xs)
+{
+    if (rows < 0 || H < 1 || (rows > 0 && (!x || !mean || !rstd || !xs)))
+        return REF_BAD;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int j = 0; j < H; ++j) {
+            const float d = x[r * (int64_t)H + j] - mean[r];
+            xs[r * (int64_t)H + j] = d * rstd[r];
+        }
+    }
+    return REF_OK;
+}
+
+/* vals/idx: k kept entries of the flattened x~ (flat int32 indices, any order, distinct) */
+int slimfit_ref_layernorm_backward_pruned(const float *vals, const int32_t *idx, int64_t k,
+                                          const float *rstd, const float *gamma,
+                                          const float *dy, int64_t rows, int H, float *dx)
+{
+    if (rows < 0 || H < 1 || k < 0 || k > rows * (int64_t)H)
+        return REF_BAD;
+    if (rows > 0 && (!rstd || !gamma || !dy || !dx || (k > 0 && (!vals || !idx))))
+        return REF_BAD;
+    const int64_t n = rows * (int64_t)H;
+    double *xt = (double *)calloc((size_t)(n > 0 ? n : 1), sizeof(double));
+    if (!xt)
+        return REF_BAD;
+    for (int64_t s = 0; s < k; ++s) {
+        if (idx[s] < 0 || idx[s] >= n) {
+            free(xt);
+            return REF_BAD;
+        }
+        xt[idx[s]] = (double)vals[s];
+    }
+    for (int64_t r = 0; r < rows; ++r) {
+        const int64_t base = r * (int64_t)H;
+        double sum_g = 0.0, sum_gx = 0.0;
+        for (int j = 0; j < H; ++j) {
+            const double g = (double)gamma[j] * (double)dy[base + j] * (double)rstd[r] / (double)H;
+            sum_g += g;
+            sum_gx += g * xt[base + j];
+        }
+        for (int j = 0; j < H; ++j) {
+            const double g = (double)gamma[j] * (double)dy[base + j] * (double)rstd[r] / (double)H;
+            dx[base + j] = (float)((double)H * g - sum_g - xt[base + j] * sum_gx);
+        }
+    }
+    free(xt);
     return REF_OK;
 }
 
