@@ -293,6 +293,46 @@ int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32
                                int32_t dt, int64_t n, void *out, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (c-ln) LayerNorm around the pruned cache of its standardised input -- Sec. 4:
+ *        x~ = (x - E x) / sqrt(Var x + eps),   y = x~ * gamma + beta   per row of
+ *     H elements (Var with divisor H).  A frozen LayerNorm keeps only the
+ *     largest 10 % of x~ (Alg. 5) and computes its input gradient as
+ *        g = gamma * y^ / (H * sqrt(Var x + eps)),
+ *        x^ = H * g - sum_H g - x~ * sum_H (g * x~),
+ *     every pruned x~ counting as 0.  All tensors fp32, fp32 arithmetic with
+ *     fixed-order sums.
+ *
+ *  slimfit_layernorm_forward : y, and per row mean = E x and
+ *        rstd = 1 / sqrt(Var x + eps).  Against the fp64 values: mean within
+ *        1e-6 * max|x_row|, rstd within 2e-6 relative,
+ *        |d y| <= |gamma| * (4e-6 * |x~| + 2e-6 * max|x_row| * rstd) + 1e-6 * |y|.
+ *  slimfit_prune_global_standardized : slimfit_prune_global applied to x~
+ *        without storing it: element j of row r enters as
+ *        fl(fl(x_j - mean[r]) * rstd[r]) (two fp32 operations), vals receive
+ *        those values.  n = rows * H; H a multiple of 4, >= 4; fp32 only
+ *        (bf16: UNSUPPORTED).  mean, rstd: DEVICE float[n / H].
+ *  slimfit_layernorm_backward_pruned : x^ from the pairs (vals, idx, tile_ptr as
+ *        slimfit_prune_global_standardized emits them; tile_ptr is required),
+ *        rstd, gamma and y^ (dy); a pair whose index does not fall in the row
+ *        the pointers file it under is skipped.
+ *        |d x^| <= 4e-6 * (H * |g| + sum_H |g| + |x~| * sum_H |g * x~|).
+ *  x, y, dy, dx : DEVICE float[rows * H], 16-byte aligned, outputs distinct from
+ *  inputs; gamma, beta : DEVICE float[H], 16-byte aligned.
+ *  4 <= H <= 4096, H % 4 == 0, rows * H < 2^31 (else INVALID_ARG / UNSUPPORTED).
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_layernorm_forward(const float *x, const float *gamma, const float *beta, int64_t rows, int64_t H,
+                                  float eps, float *y, float *mean, float *rstd, void *stream);
+
+int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, int64_t H,
+                                          const float *mean, const float *rstd, int64_t k, int32_t by_magnitude,
+                                          void *vals, int32_t *idx, int32_t *tile_ptr,
+                                          void *workspace, size_t workspace_bytes, void *stream);
+
+int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *tile_ptr, int64_t k,
+                                          const float *rstd, const float *gamma, const float *dy,
+                                          int64_t rows, int64_t H, float *dx, void *stream);
+
+/* ------------------------------------------------------------------------
  * (d) Inter-layer scheduling on the host -- Alg. 1 and Sec. 3.2 / Fig. 4:
  *        idx = argsort(d)[: int(L*F)]   -> these layers are frozen;
  *     afterwards only the layers that were active take their new distance,

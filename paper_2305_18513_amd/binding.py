@@ -34,7 +34,8 @@ EXPORTS = (
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
-    "slimfit_restore_global", "slimfit_freeze_count", "slimfit_ils_select",
+    "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
+    "slimfit_layernorm_backward_pruned", "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update",
 )
 
@@ -311,6 +312,51 @@ def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Ten
         _dev(vals), _dev(idx), _dev(tile_ptr), C.c_int64(k), C.c_int32(_dt(out)), C.c_int64(out.numel()),
         _dev(out), _stream(stream))
     _check(rc, "restore_global")
+
+
+# ---------------------------------------------------------------- (c-ln) LayerNorm around the pruned cache
+
+def layernorm_forward(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float, y: torch.Tensor,
+                      mean: torch.Tensor, rstd: torch.Tensor, stream=None) -> None:
+    assert x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape
+    assert all(t.dtype == torch.float32 for t in (x, gamma, beta, y, mean, rstd))
+    rows, H = x.shape
+    assert gamma.numel() == H and beta.numel() == H and mean.numel() >= rows and rstd.numel() >= rows
+    rc = lib().slimfit_layernorm_forward(_dev(x), _dev(gamma), _dev(beta), C.c_int64(rows), C.c_int64(H),
+                                         C.c_float(eps), _dev(y), _dev(mean), _dev(rstd), _stream(stream))
+    _check(rc, "layernorm_forward")
+
+
+def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, k: int, vals: torch.Tensor,
+                              idx: torch.Tensor, by_magnitude: bool = True, tile_ptr: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """prune_global of the standardised rows of ``x`` (rows, H), formed on the fly from mean / rstd."""
+    assert x.dim() == 2 and x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32
+    assert mean.dtype == torch.float32 and rstd.dtype == torch.float32
+    rows, H = x.shape
+    n = x.numel()
+    assert mean.numel() >= rows and rstd.numel() >= rows and vals.numel() >= k and idx.numel() >= k
+    assert tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n))
+    if workspace is None:
+        workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
+    rc = lib().slimfit_prune_global_standardized(
+        _dev(x), C.c_int32(_dt(x)), C.c_int64(n), C.c_int64(H), _dev(mean), _dev(rstd), C.c_int64(k),
+        C.c_int32(int(bool(by_magnitude))), _dev(vals), _dev(idx), _dev(tile_ptr), _dev(workspace),
+        C.c_size_t(workspace.numel()), _stream(stream))
+    _check(rc, "prune_global_standardized")
+
+
+def layernorm_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, tile_ptr: torch.Tensor, k: int,
+                              rstd: torch.Tensor, gamma: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
+                              stream=None) -> None:
+    assert dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape
+    assert all(t.dtype == torch.float32 for t in (vals, rstd, gamma, dy, dx))
+    assert idx.dtype == torch.int32 and tile_ptr.dtype == torch.int32
+    rows, H = dy.shape
+    rc = lib().slimfit_layernorm_backward_pruned(
+        _dev(vals), _dev(idx), _dev(tile_ptr), C.c_int64(k), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
+        C.c_int64(H), _dev(dx), _stream(stream))
+    _check(rc, "layernorm_backward_pruned")
 
 
 # ---------------------------------------------------------------- (d) Alg. 1 (host)

@@ -1,0 +1,289 @@
+// LayerNorm around the pruned cache of its standardised input (Sec. 4):
+//
+//   layernorm_forward_kernel          y = x~ * gamma + beta and the row
+//                                     statistics (mean, 1/sqrt(Var + eps)) that
+//                                     let the whole-tensor pruner form x~ on the
+//                                     fly instead of reading a stored copy;
+//   layernorm_backward_pruned_kernel  the input gradient of a frozen LayerNorm,
+//                                     x^ = H g - sum g - x~ sum(g x~),
+//                                     g = gamma y^ / (H sqrt(Var + eps)), with
+//                                     x~ given as the (value, flat index) pairs
+//                                     Alg. 5 kept: the dense x~ is never rebuilt
+//                                     in memory.
+//
+// Both give a row of H elements to one wave: lane l holds the 16-byte vectors
+// l, l+64, ... of the row (NV of them), sums run over the lanes with DPP in a
+// fixed order, and nothing is read twice.  The backward kernel stages g and
+// then the output row in the wave's LDS region so that the kept pairs, which
+// arrive in index order and not in lane order, can be applied to it.
+#include "common.hpp"
+
+namespace slimfit {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kMaxH = 4096;                 // NV <= 16 vectors of 4 per lane
+constexpr int64_t kPtrTile = SLIMFIT_GLOBAL_TILE;
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add_f32(float v)      // absent sources contribute +0
+{
+    return v + __builtin_bit_cast(float,
+                                  __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+// sum of one float per lane, in a fixed order; result uniform
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+    v = dpp_add_f32<0x111, 0xF>(v);        // row_shr:1
+    v = dpp_add_f32<0x112, 0xF>(v);        // row_shr:2
+    v = dpp_add_f32<0x114, 0xF>(v);        // row_shr:4
+    v = dpp_add_f32<0x118, 0xF>(v);        // row_shr:8
+    v = dpp_add_f32<0x142, 0xA>(v);        // row_bcast:15 into rows 1 and 3
+    v = dpp_add_f32<0x143, 0xC>(v);        // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// lane's vectors of a row; vectors past the row's end read as zeros
+template <int NV>
+__device__ __forceinline__ void load_row(const float *__restrict__ row, int nvec, int lane, f32x4 (&v)[NV], bool stream)
+{
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        v[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (q < nvec) {
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(row) + q;
+            v[i] = stream ? __builtin_nontemporal_load(src) : *src;
+        }
+    }
+}
+
+template <int NV>
+__global__ void __launch_bounds__(kThreads)
+layernorm_forward_kernel(const float *__restrict__ x, const float *__restrict__ gamma, const float *__restrict__ beta,
+                         int64_t rows, int H, float eps, float *__restrict__ y, float *__restrict__ mean,
+                         float *__restrict__ rstd)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int nvec = H / 4;
+    f32x4 v[NV], ga[NV], be[NV];
+    load_row<NV>(x + r * (int64_t)H, nvec, lane, v, true);
+    load_row<NV>(gamma, nvec, lane, ga, false);
+    load_row<NV>(beta, nvec, lane, be, false);
+
+    float part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) part += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    const float mu = wave_sum_f32(part) / (float)H;
+    part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const bool in = i * kWave + lane < nvec;             // padding vectors must not add mu^2
+        const float a = v[i].x - mu, b = v[i].y - mu, c = v[i].z - mu, d = v[i].w - mu;
+        part += in ? (a * a + b * b) + (c * c + d * d) : 0.0f;
+    }
+    const float var = wave_sum_f32(part) / (float)H;
+    const float rs = 1.0f / __builtin_sqrtf(var + eps);
+    if (lane == 0) {
+        mean[r] = mu;
+        rstd[r] = rs;
+    }
+    f32x4 *dst = reinterpret_cast<f32x4 *>(y + r * (int64_t)H);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        if (q < nvec) {
+            f32x4 o;
+            o.x = ((v[i].x - mu) * rs) * ga[i].x + be[i].x;
+            o.y = ((v[i].y - mu) * rs) * ga[i].y + be[i].y;
+            o.z = ((v[i].z - mu) * rs) * ga[i].z + be[i].z;
+            o.w = ((v[i].w - mu) * rs) * ga[i].w + be[i].w;
+            __builtin_nontemporal_store(o, dst + q);
+        }
+    }
+}
+
+// number of entries of the ascending list idx[a, b) that are below `bound`
+__device__ __forceinline__ int64_t count_below(const int32_t *__restrict__ idx, int64_t a, int64_t b, int64_t bound,
+                                               int lane)
+{
+    int64_t below = 0;
+    for (int64_t s = a; s < b; s += kWave) {                 // wave-uniform trip count
+        const bool lt = s + lane < b && (int64_t)idx[s + lane] < bound;
+        const uint64_t m = __builtin_amdgcn_ballot_w64(lt);
+        below += __builtin_popcountll(m);
+        if (m != ~0ull) break;                               // ascending: nothing further can be below
+    }
+    return below;
+}
+
+template <int NV>
+__global__ void __launch_bounds__(kThreads)
+layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *__restrict__ idx,
+                                 const int32_t *__restrict__ tile_ptr, int64_t k, const float *__restrict__ rstd,
+                                 const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
+                                 float *__restrict__ dx)
+{
+    extern __shared__ __align__(16) float lds[];             // kWaves rows of H floats
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + wave;
+    if (r >= rows) return;
+    float *buf = lds + (size_t)wave * H;
+    const int nvec = H / 4;
+    const int64_t e0 = r * (int64_t)H, e1 = e0 + H, n = rows * (int64_t)H;
+
+    f32x4 g[NV], ga[NV];
+    load_row<NV>(dy + e0, nvec, lane, g, true);
+    load_row<NV>(gamma, nvec, lane, ga, false);
+
+    // the row's pairs: those with e0 <= idx < e1, located through the tile pointers
+    auto clamp_ptr = [&](int64_t p) { return min(max(p, (int64_t)0), k); };
+    const int64_t t0 = e0 / kPtrTile;
+    int64_t a = clamp_ptr(tile_ptr[t0]), b = clamp_ptr(tile_ptr[t0 + 1]);
+    int64_t p0 = a + count_below(idx, a, max(a, b), e0, lane);
+    int64_t p1;
+    if (e1 % kPtrTile == 0 || e1 >= n) {
+        p1 = clamp_ptr(tile_ptr[(e1 + kPtrTile - 1) / kPtrTile]);
+    } else {
+        const int64_t t1 = e1 / kPtrTile;
+        a = clamp_ptr(tile_ptr[t1]);
+        b = clamp_ptr(tile_ptr[t1 + 1]);
+        p1 = a + count_below(idx, a, max(a, b), e1, lane);
+    }
+    p1 = min(max(p1, p0), p0 + H);
+
+    const float scale = rstd[r] / (float)H;
+    float part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        g[i].x = (ga[i].x * g[i].x) * scale;
+        g[i].y = (ga[i].y * g[i].y) * scale;
+        g[i].z = (ga[i].z * g[i].z) * scale;
+        g[i].w = (ga[i].w * g[i].w) * scale;
+        part += (g[i].x + g[i].y) + (g[i].z + g[i].w);
+        const int q = i * kWave + lane;
+        if (q < nvec) reinterpret_cast<f32x4 *>(buf)[q] = g[i];
+    }
+    const float sum_g = wave_sum_f32(part);
+    __builtin_amdgcn_wave_barrier();                          // LDS serves a wave's accesses in order
+
+    part = 0.0f;
+    for (int64_t s = p0 + lane; s < p1; s += kWave) {
+        const int64_t c = (int64_t)idx[s] - e0;
+        if (c >= 0 && c < H) part += buf[c] * vals[s];
+    }
+    const float sum_gx = wave_sum_f32(part);
+    __builtin_amdgcn_wave_barrier();
+
+    const float fH = (float)H;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        if (q < nvec) {
+            f32x4 o;
+            o.x = fH * g[i].x - sum_g;
+            o.y = fH * g[i].y - sum_g;
+            o.z = fH * g[i].z - sum_g;
+            o.w = fH * g[i].w - sum_g;
+            reinterpret_cast<f32x4 *>(buf)[q] = o;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int64_t s = p0 + lane; s < p1; s += kWave) {        // distinct columns: no two lanes touch one slot
+        const int64_t c = (int64_t)idx[s] - e0;
+        if (c >= 0 && c < H) buf[c] -= vals[s] * sum_gx;
+    }
+    __builtin_amdgcn_wave_barrier();
+    f32x4 *dst = reinterpret_cast<f32x4 *>(dx + e0);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        if (q < nvec) __builtin_nontemporal_store(reinterpret_cast<const f32x4 *>(buf)[q], dst + q);
+    }
+}
+
+int32_t validate(int64_t rows, int64_t H)
+{
+    if (rows < 0 || H < 4 || H % 4 != 0) return SLIMFIT_ERR_INVALID_ARG;
+    if (H > kMaxH || rows * H > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;
+    return SLIMFIT_OK;
+}
+
+// vectors a lane has to hold for rows of H elements
+int lane_vectors(int64_t H) { return (int)((H / 4 + kWave - 1) / kWave); }
+
+}  // namespace
+}  // namespace slimfit
+
+using namespace slimfit;
+
+#define SLIMFIT_LN_DISPATCH(NVEXPR, CALL)        \
+    do {                                         \
+        const int nv_ = (NVEXPR);                \
+        if (nv_ <= 1) { constexpr int NV = 1; CALL; }        \
+        else if (nv_ <= 2) { constexpr int NV = 2; CALL; }   \
+        else if (nv_ <= 3) { constexpr int NV = 3; CALL; }   \
+        else if (nv_ <= 4) { constexpr int NV = 4; CALL; }   \
+        else if (nv_ <= 8) { constexpr int NV = 8; CALL; }   \
+        else { constexpr int NV = 16; CALL; }                \
+    } while (0)
+
+extern "C" int32_t slimfit_layernorm_forward(const float *x, const float *gamma, const float *beta, int64_t rows,
+                                             int64_t H, float eps, float *y, float *mean, float *rstd, void *stream)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
+    if (rows == 0) return SLIMFIT_OK;
+    if (!x || !gamma || !beta || !y || !mean || !rstd || x == y) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(x, 16) || !aligned_to(y, 16) || !aligned_to(gamma, 16) || !aligned_to(beta, 16) ||
+        !aligned_to(mean, 4) || !aligned_to(rstd, 4))
+        return SLIMFIT_ERR_ALIGNMENT;
+    const size_t nbytes = (size_t)rows * (size_t)H * 4;
+    if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(y, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(beta, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(mean, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
+    SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_forward_kernel<NV><<<grid, kThreads, 0, s>>>(
+                                             x, gamma, beta, rows, (int)H, eps, y, mean, rstd)));
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *tile_ptr,
+                                                     int64_t k, const float *rstd, const float *gamma, const float *dy,
+                                                     int64_t rows, int64_t H, float *dx, void *stream)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if (k < 0 || k > rows * H) return SLIMFIT_ERR_INVALID_ARG;
+    if (rows == 0) return SLIMFIT_OK;
+    if (!tile_ptr || !rstd || !gamma || !dy || !dx || dy == dx || (k > 0 && (!vals || !idx)))
+        return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(dy, 16) || !aligned_to(dx, 16) || !aligned_to(gamma, 16) || !aligned_to(rstd, 4) ||
+        !aligned_to(tile_ptr, 4) || (k > 0 && (!aligned_to(vals, 4) || !aligned_to(idx, 4))))
+        return SLIMFIT_ERR_ALIGNMENT;
+    const int64_t n = rows * H;
+    if ((rc = check_device_range(dy, (size_t)n * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dx, (size_t)n * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(tile_ptr, (size_t)((n + kPtrTile - 1) / kPtrTile + 1) * 4)) != SLIMFIT_OK) return rc;
+    if (k > 0) {
+        if ((rc = check_device_range(vals, (size_t)k * 4)) != SLIMFIT_OK) return rc;
+        if ((rc = check_device_range(idx, (size_t)k * 4)) != SLIMFIT_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
+    const size_t lds_bytes = (size_t)kWaves * (size_t)H * 4;              // at most 64 KB
+    SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_pruned_kernel<NV><<<grid, kThreads, lds_bytes, s>>>(
+                                             vals, idx, tile_ptr, k, rstd, gamma, dy, rows, (int)H, dx)));
+    return launch_status();
+}

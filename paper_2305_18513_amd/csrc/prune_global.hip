@@ -133,6 +133,33 @@ __device__ __forceinline__ int load_vec(const T *x, int64_t n, int64_t v, uint32
     return valid;
 }
 
+// Optional standardisation on the way in (fp32 tensors): element j of row r
+// enters the selection as x~ = fl(fl(x - mean[r]) * rstd[r]), two fp32 operations
+// that every sweep repeats bit for bit, so the LayerNorm's standardised input is
+// pruned without ever being stored.  r = j / H by a multiply-high with a magic
+// number (exact for j < 2^31: magic = ceil(2^(31+l) / H), l = ceil(log2 H),
+// r = mulhi(j, magic) >> (l - 1)).
+struct Std {
+    const float *mean, *rstd;
+    uint32_t magic, shift;
+};
+template <typename T, bool STD, bool NT = false>
+__device__ __forceinline__ int load_std(const T *x, int64_t n, int64_t v, uint32_t (&bits)[Elem<T>::EPV], const Std &sd)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    const int valid = load_vec<T, NT>(x, n, v, bits);
+    if constexpr (STD) {
+        if (valid) {                                           // H is a multiple of EPV: a vector lies in one row
+            const uint32_t row = __umulhi((uint32_t)(v * EPV), sd.magic) >> sd.shift;
+            const float mu = sd.mean[row], rs = sd.rstd[row];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                bits[e] = __builtin_bit_cast(uint32_t, (__builtin_bit_cast(float, bits[e]) - mu) * rs);
+        }
+    }
+    return valid;
+}
+
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)            // absent sources contribute 0
 {
@@ -172,10 +199,10 @@ __global__ void __launch_bounds__(kSelectThreads) init_kernel(State *st, uint32_
 // ---- one digit of the select: histogram of the keys that match the prefix ------------
 // Source: the tensor (first digit, and every digit on the plain route) or the
 // candidate list.
-template <typename T, bool MAG>
+template <typename T, bool MAG, bool STD>
 __global__ void __launch_bounds__(kHistThreads)
 hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, uint32_t *__restrict__ hist,
-            const u32x2 *__restrict__ tile_cnt, const uint32_t *__restrict__ lists, int64_t ntiles, int shift, int nbins)
+            const u32x2 *__restrict__ tile_cnt, const uint32_t *__restrict__ lists, int64_t ntiles, int shift, int nbins, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
     __shared__ uint32_t bins[kMaxBins];
@@ -208,7 +235,7 @@ hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, ui
             for (int j = 0; j < kVecPerThread; ++j) {
                 const int64_t v = base + (int64_t)j * kHistThreads + threadIdx.x;
                 valid[j] = 0;
-                if (v < nvec) valid[j] = load_vec<T, SLIMFIT_PG_NT != 0>(x, n, v, bits[j]);
+                if (v < nvec) valid[j] = load_std<T, STD, SLIMFIT_PG_NT != 0>(x, n, v, bits[j], sd);
             }
 #pragma unroll
             for (int j = 0; j < kVecPerThread; ++j) {
@@ -304,9 +331,9 @@ __device__ __forceinline__ int64_t tile_vec(int64_t tile, int wave, int j, int l
 
 // ---- list route: per tile, keys above the chosen bin; the bin's own keys go to the tile's list ----
 // Leaves tile_cnt[tile] = (keys above the bin, keys filed).
-template <typename T, bool MAG>
+template <typename T, bool MAG, bool STD>
 __global__ void __launch_bounds__(kTileThreads)
-bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict__ tile_cnt, uint32_t *__restrict__ lists)
+bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict__ tile_cnt, uint32_t *__restrict__ lists, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr uint32_t kSlot = kTileThreads * kVecPerThread * EPV / kListShare;
@@ -323,7 +350,7 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
         valid[j] = 0;
-        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+        if (v < nvec) valid[j] = load_std<T, STD>(x, n, v, bits[j], sd);
     }
     uint32_t gt = 0u, in_bin = 0u;
 #pragma unroll
@@ -376,10 +403,10 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
 // ---- per tile: keys above T, keys equal to T -------------------------------------------
 // plain route: from the tensor; list route: the list's keys are added to the
 // counts that bracket_kernel left.
-template <typename T, bool MAG>
+template <typename T, bool MAG, bool STD>
 __global__ void __launch_bounds__(kTileThreads)
 count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u32x2 *__restrict__ tile_cnt,
-             const uint32_t *__restrict__ lists, int64_t ntiles)
+             const uint32_t *__restrict__ lists, int64_t ntiles, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr uint32_t kTileElems = kTileThreads * kVecPerThread * EPV;
@@ -416,7 +443,7 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
         valid[j] = 0;
-        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+        if (v < nvec) valid[j] = load_std<T, STD>(x, n, v, bits[j], sd);
     }
     uint32_t gt = 0u, eq = 0u;
 #pragma unroll
@@ -537,10 +564,10 @@ template <> __device__ __forceinline__ void store_raw<float>(float *p, uint32_t 
 template <> __device__ __forceinline__ void store_raw<uint16_t>(uint16_t *p, uint32_t bits) { *p = (uint16_t)bits; }
 
 // ---- emit the survivors of a tile in ascending index order ------------------------------
-template <typename T, bool MAG>
+template <typename T, bool MAG, bool STD>
 __global__ void __launch_bounds__(kTileThreads)
 write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
-             T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k)
+             T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int NW = kTileThreads / kWave;
@@ -559,7 +586,7 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
         valid[j] = 0;
-        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+        if (v < nvec) valid[j] = load_std<T, STD>(x, n, v, bits[j], sd);
     }
     uint32_t incl[kVecPerThread];
     uint32_t wave_packed = 0u;
@@ -749,9 +776,9 @@ template <> struct Digits<uint16_t> {
     static constexpr int bits[3] = {12, 4, 0};
 };
 
-template <typename T, bool MAG>
+template <typename T, bool MAG, bool STD>
 void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int32_t *tile_ptr, const Workspace &w,
-                   hipStream_t s)
+                   const Std &sd, hipStream_t s)
 {
     constexpr int EPV = Elem<T>::EPV;
     const int64_t nvec = (n + EPV - 1) / EPV;
@@ -767,17 +794,18 @@ void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int
         const int bits = Digits<T>::bits[d];
         const int shift = hi - bits;
         const bool first = d == 0, last = d == Digits<T>::N - 1;
-        hist_kernel<T, MAG><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists, ntiles, shift,
-                                                              1 << bits);
+        hist_kernel<T, MAG, STD><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists, ntiles,
+                                                                   shift, 1 << bits, sd);
         select_kernel<<<1, kSelectThreads, 0, s>>>(w.st, w.hist, shift, 1 << bits, first ? 1 : 0, last ? 1 : 0,
                                                    w.route_cap);
         if (first && !last)
-            bracket_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists);
+            bracket_kernel<T, MAG, STD><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists, sd);
         hi = shift;
     }
-    count_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists, ntiles);
+    count_kernel<T, MAG, STD><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_cnt, w.lists, ntiles, sd);
     scan_kernel<<<1, kScanThreads, 0, s>>>(w.st, w.tile_cnt, w.tile_base, ntiles);
-    write_kernel<T, MAG><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_base, vals, idx, tile_ptr, k);
+    write_kernel<T, MAG, STD><<<(unsigned)ntiles, kTileThreads, 0, s>>>(x, n, w.st, w.tile_base, vals, idx, tile_ptr, k,
+                                                                         sd);
 }
 
 }  // namespace
@@ -798,17 +826,26 @@ extern "C" int64_t slimfit_global_tile_ptr_len(int64_t n)
     return (n + kPtrTile - 1) / kPtrTile + 1;
 }
 
-extern "C" int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, int64_t k, int32_t by_magnitude,
-                                        void *vals, int32_t *idx, int32_t *tile_ptr, void *workspace,
-                                        size_t workspace_bytes, void *stream)
+namespace {
+
+// Shared body of the two pruning entry points.  H == 0: plain; otherwise the
+// tensor is rows of H elements standardised with mean / rstd on the way in.
+int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, const float *mean, const float *rstd,
+                           int64_t k, int32_t by_magnitude, void *vals, int32_t *idx, int32_t *tile_ptr,
+                           void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dt) || n < 0 || k < 0 || k > n) return SLIMFIT_ERR_INVALID_ARG;
     if (n > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;                 // indices are int32
+    const bool standardised = H != 0;
+    if (standardised) {
+        if (H < 4 || H % 4 != 0 || n % H != 0) return SLIMFIT_ERR_INVALID_ARG;
+        if (dt != SLIMFIT_F32) return SLIMFIT_ERR_UNSUPPORTED;
+    }
     if (k == 0) return SLIMFIT_OK;
-    if (!x || !vals || !idx || !workspace) return SLIMFIT_ERR_INVALID_ARG;
+    if (!x || !vals || !idx || !workspace || (standardised && (!mean || !rstd))) return SLIMFIT_ERR_INVALID_ARG;
     const size_t esz = dtype_size(dt);
     if (!aligned_to(x, 16) || !aligned_to(vals, esz) || !aligned_to(idx, 4) || !aligned_to(workspace, 16) ||
-        (tile_ptr && !aligned_to(tile_ptr, 4)))
+        (tile_ptr && !aligned_to(tile_ptr, 4)) || (standardised && (!aligned_to(mean, 4) || !aligned_to(rstd, 4))))
         return SLIMFIT_ERR_ALIGNMENT;
     const Workspace w = carve(workspace, n);
     if (workspace_bytes < w.bytes) return SLIMFIT_ERR_WORKSPACE;
@@ -819,21 +856,60 @@ extern "C" int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, in
     if ((rc = check_device_range(workspace, w.bytes)) != SLIMFIT_OK) return rc;
     if (tile_ptr && (rc = check_device_range(tile_ptr, (size_t)slimfit_global_tile_ptr_len(n) * 4)) != SLIMFIT_OK)
         return rc;
+    Std sd = {nullptr, nullptr, 0u, 0u};
+    if (standardised) {
+        const size_t rows = (size_t)(n / H);
+        if ((rc = check_device_range(mean, rows * 4)) != SLIMFIT_OK) return rc;
+        if ((rc = check_device_range(rstd, rows * 4)) != SLIMFIT_OK) return rc;
+        int l = 0;
+        while (((int64_t)1 << l) < H) ++l;                              // ceil(log2 H) >= 2
+        const uint64_t pow = (uint64_t)1 << (31 + l);
+        sd.mean = mean;
+        sd.rstd = rstd;
+        sd.magic = (uint32_t)((pow + (uint64_t)H - 1) / (uint64_t)H);   // < 2^32 because H > 2^(l-1)
+        sd.shift = (uint32_t)(l - 1);
+    }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t kk = (uint32_t)k;
     if (dt == SLIMFIT_F32) {
         const float *xf = static_cast<const float *>(x);
         float *vf = static_cast<float *>(vals);
-        if (by_magnitude) launch_select<float, true>(xf, n, kk, vf, idx, tile_ptr, w, s);
-        else launch_select<float, false>(xf, n, kk, vf, idx, tile_ptr, w, s);
+        if (standardised) {
+            if (by_magnitude) launch_select<float, true, true>(xf, n, kk, vf, idx, tile_ptr, w, sd, s);
+            else launch_select<float, false, true>(xf, n, kk, vf, idx, tile_ptr, w, sd, s);
+        } else {
+            if (by_magnitude) launch_select<float, true, false>(xf, n, kk, vf, idx, tile_ptr, w, sd, s);
+            else launch_select<float, false, false>(xf, n, kk, vf, idx, tile_ptr, w, sd, s);
+        }
     } else {
         const uint16_t *xh = static_cast<const uint16_t *>(x);
         uint16_t *vh = static_cast<uint16_t *>(vals);
-        if (by_magnitude) launch_select<uint16_t, true>(xh, n, kk, vh, idx, tile_ptr, w, s);
-        else launch_select<uint16_t, false>(xh, n, kk, vh, idx, tile_ptr, w, s);
+        if (by_magnitude) launch_select<uint16_t, true, false>(xh, n, kk, vh, idx, tile_ptr, w, sd, s);
+        else launch_select<uint16_t, false, false>(xh, n, kk, vh, idx, tile_ptr, w, sd, s);
     }
     return launch_status();
+}
+
+}  // namespace
+
+extern "C" int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, int64_t k, int32_t by_magnitude,
+                                        void *vals, int32_t *idx, int32_t *tile_ptr, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    return prune_global_entry(x, dt, n, 0, nullptr, nullptr, k, by_magnitude, vals, idx, tile_ptr, workspace,
+                              workspace_bytes, stream);
+}
+
+extern "C" int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, int64_t H,
+                                                     const float *mean, const float *rstd, int64_t k,
+                                                     int32_t by_magnitude, void *vals, int32_t *idx,
+                                                     int32_t *tile_ptr, void *workspace, size_t workspace_bytes,
+                                                     void *stream)
+{
+    if (H == 0) return SLIMFIT_ERR_INVALID_ARG;
+    return prune_global_entry(x, dt, n, H, mean, rstd, k, by_magnitude, vals, idx, tile_ptr, workspace,
+                              workspace_bytes, stream);
 }
 
 extern "C" int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32_t *tile_ptr, int64_t k,
