@@ -311,8 +311,11 @@ int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32
  *        fl(fl(x_j - mean[r]) * rstd[r]) (two fp32 operations), vals receive
  *        those values.  n = rows * H; H a multiple of 4, >= 4; fp32 only
  *        (bf16: UNSUPPORTED).  mean, rstd: DEVICE float[n / H].
- *  slimfit_layernorm_backward_pruned : x^ from the pairs (vals, idx, tile_ptr as
- *        slimfit_prune_global_standardized emits them; tile_ptr is required),
+ *        row_ptr: DEVICE int32[n / H + 1] or NULL; row_ptr[r] = number of
+ *        survivors with index below r * H, the last entry = k (the pairs of row
+ *        r are [row_ptr[r], row_ptr[r+1]) of the list).
+ *  slimfit_layernorm_backward_pruned : x^ from the pairs (vals, idx, row_ptr as
+ *        slimfit_prune_global_standardized emits them; row_ptr is required),
  *        rstd, gamma and y^ (dy); a pair whose index does not fall in the row
  *        the pointers file it under is skipped.
  *        |d x^| <= 4e-6 * (H * |g| + sum_H |g| + |x~| * sum_H |g * x~|).
@@ -325,10 +328,10 @@ int32_t slimfit_layernorm_forward(const float *x, const float *gamma, const floa
 
 int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, int64_t H,
                                           const float *mean, const float *rstd, int64_t k, int32_t by_magnitude,
-                                          void *vals, int32_t *idx, int32_t *tile_ptr,
+                                          void *vals, int32_t *idx, int32_t *tile_ptr, int32_t *row_ptr,
                                           void *workspace, size_t workspace_bytes, void *stream);
 
-int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *tile_ptr, int64_t k,
+int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *row_ptr, int64_t k,
                                           const float *rstd, const float *gamma, const float *dy,
                                           int64_t rows, int64_t H, float *dx, void *stream);
 

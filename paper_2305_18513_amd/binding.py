@@ -329,7 +329,8 @@ def layernorm_forward(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, 
 
 def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, k: int, vals: torch.Tensor,
                               idx: torch.Tensor, by_magnitude: bool = True, tile_ptr: Optional[torch.Tensor] = None,
-                              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+                              row_ptr: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                              stream=None) -> None:
     """prune_global of the standardised rows of ``x`` (rows, H), formed on the fly from mean / rstd."""
     assert x.dim() == 2 and x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32
     assert mean.dtype == torch.float32 and rstd.dtype == torch.float32
@@ -337,24 +338,26 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
     n = x.numel()
     assert mean.numel() >= rows and rstd.numel() >= rows and vals.numel() >= k and idx.numel() >= k
     assert tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n))
+    assert row_ptr is None or (row_ptr.dtype == torch.int32 and row_ptr.numel() >= rows + 1)
     if workspace is None:
         workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
     rc = lib().slimfit_prune_global_standardized(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(n), C.c_int64(H), _dev(mean), _dev(rstd), C.c_int64(k),
-        C.c_int32(int(bool(by_magnitude))), _dev(vals), _dev(idx), _dev(tile_ptr), _dev(workspace),
+        C.c_int32(int(bool(by_magnitude))), _dev(vals), _dev(idx), _dev(tile_ptr), _dev(row_ptr), _dev(workspace),
         C.c_size_t(workspace.numel()), _stream(stream))
     _check(rc, "prune_global_standardized")
 
 
-def layernorm_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, tile_ptr: torch.Tensor, k: int,
+def layernorm_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, row_ptr: torch.Tensor, k: int,
                               rstd: torch.Tensor, gamma: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
                               stream=None) -> None:
     assert dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape
     assert all(t.dtype == torch.float32 for t in (vals, rstd, gamma, dy, dx))
-    assert idx.dtype == torch.int32 and tile_ptr.dtype == torch.int32
+    assert idx.dtype == torch.int32 and row_ptr.dtype == torch.int32
     rows, H = dy.shape
+    assert row_ptr.numel() >= rows + 1
     rc = lib().slimfit_layernorm_backward_pruned(
-        _dev(vals), _dev(idx), _dev(tile_ptr), C.c_int64(k), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
+        _dev(vals), _dev(idx), _dev(row_ptr), C.c_int64(k), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
         C.c_int64(H), _dev(dx), _stream(stream))
     _check(rc, "layernorm_backward_pruned")
 

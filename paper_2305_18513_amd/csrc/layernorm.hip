@@ -15,7 +15,9 @@
 // l, l+64, ... of the row (NV of them), sums run over the lanes with DPP in a
 // fixed order, and nothing is read twice.  The backward kernel stages g and
 // then the output row in the wave's LDS region so that the kept pairs, which
-// arrive in index order and not in lane order, can be applied to it.
+// arrive in index order and not in lane order, can be applied to it; the row's
+// pairs are found through row pointers (survivors ahead of every row), which
+// the pruner emits alongside the pairs.
 #include "common.hpp"
 
 namespace slimfit {
@@ -24,7 +26,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kMaxH = 4096;                 // NV <= 16 vectors of 4 per lane
-constexpr int64_t kPtrTile = SLIMFIT_GLOBAL_TILE;
 
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_add_f32(float v)      // absent sources contribute +0
@@ -106,24 +107,10 @@ layernorm_forward_kernel(const float *__restrict__ x, const float *__restrict__ 
     }
 }
 
-// number of entries of the ascending list idx[a, b) that are below `bound`
-__device__ __forceinline__ int64_t count_below(const int32_t *__restrict__ idx, int64_t a, int64_t b, int64_t bound,
-                                               int lane)
-{
-    int64_t below = 0;
-    for (int64_t s = a; s < b; s += kWave) {                 // wave-uniform trip count
-        const bool lt = s + lane < b && (int64_t)idx[s + lane] < bound;
-        const uint64_t m = __builtin_amdgcn_ballot_w64(lt);
-        below += __builtin_popcountll(m);
-        if (m != ~0ull) break;                               // ascending: nothing further can be below
-    }
-    return below;
-}
-
 template <int NV>
 __global__ void __launch_bounds__(kThreads)
 layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *__restrict__ idx,
-                                 const int32_t *__restrict__ tile_ptr, int64_t k, const float *__restrict__ rstd,
+                                 const int32_t *__restrict__ row_ptr, int64_t k, const float *__restrict__ rstd,
                                  const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
                                  float *__restrict__ dx)
 {
@@ -134,27 +121,15 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
     if (r >= rows) return;
     float *buf = lds + (size_t)wave * H;
     const int nvec = H / 4;
-    const int64_t e0 = r * (int64_t)H, e1 = e0 + H, n = rows * (int64_t)H;
+    const int64_t e0 = r * (int64_t)H;
 
     f32x4 g[NV], ga[NV];
     load_row<NV>(dy + e0, nvec, lane, g, true);
     load_row<NV>(gamma, nvec, lane, ga, false);
 
-    // the row's pairs: those with e0 <= idx < e1, located through the tile pointers
-    auto clamp_ptr = [&](int64_t p) { return min(max(p, (int64_t)0), k); };
-    const int64_t t0 = e0 / kPtrTile;
-    int64_t a = clamp_ptr(tile_ptr[t0]), b = clamp_ptr(tile_ptr[t0 + 1]);
-    int64_t p0 = a + count_below(idx, a, max(a, b), e0, lane);
-    int64_t p1;
-    if (e1 % kPtrTile == 0 || e1 >= n) {
-        p1 = clamp_ptr(tile_ptr[(e1 + kPtrTile - 1) / kPtrTile]);
-    } else {
-        const int64_t t1 = e1 / kPtrTile;
-        a = clamp_ptr(tile_ptr[t1]);
-        b = clamp_ptr(tile_ptr[t1 + 1]);
-        p1 = a + count_below(idx, a, max(a, b), e1, lane);
-    }
-    p1 = min(max(p1, p0), p0 + H);
+    // the row's pairs: [row_ptr[r], row_ptr[r + 1]) of the index-ordered list
+    int64_t p0 = min(max((int64_t)row_ptr[r], (int64_t)0), k);
+    int64_t p1 = min(max((int64_t)row_ptr[r + 1], p0), min(k, p0 + H));
 
     const float scale = rstd[r] / (float)H;
     float part = 0.0f;
@@ -171,8 +146,26 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
     const float sum_g = wave_sum_f32(part);
     __builtin_amdgcn_wave_barrier();                          // LDS serves a wave's accesses in order
 
+    // the row's pairs: the first kKeep * 64 stay in registers for both uses below
+    constexpr int kKeep = 4;
+    int kept_col[kKeep];
+    float kept_val[kKeep];
+#pragma unroll
+    for (int u = 0; u < kKeep; ++u) {
+        const int64_t s = p0 + u * kWave + lane;
+        kept_col[u] = -1;
+        kept_val[u] = 0.0f;
+        if (s < p1) {
+            const int64_t c = (int64_t)idx[s] - e0;
+            kept_col[u] = (c >= 0 && c < H) ? (int)c : -1;
+            kept_val[u] = vals[s];
+        }
+    }
     part = 0.0f;
-    for (int64_t s = p0 + lane; s < p1; s += kWave) {
+#pragma unroll
+    for (int u = 0; u < kKeep; ++u)
+        if (kept_col[u] >= 0) part += buf[kept_col[u]] * kept_val[u];
+    for (int64_t s = p0 + kKeep * kWave + lane; s < p1; s += kWave) {
         const int64_t c = (int64_t)idx[s] - e0;
         if (c >= 0 && c < H) part += buf[c] * vals[s];
     }
@@ -193,7 +186,11 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
         }
     }
     __builtin_amdgcn_wave_barrier();
-    for (int64_t s = p0 + lane; s < p1; s += kWave) {        // distinct columns: no two lanes touch one slot
+    // distinct columns: no two lanes touch one slot
+#pragma unroll
+    for (int u = 0; u < kKeep; ++u)
+        if (kept_col[u] >= 0) buf[kept_col[u]] -= kept_val[u] * sum_gx;
+    for (int64_t s = p0 + kKeep * kWave + lane; s < p1; s += kWave) {
         const int64_t c = (int64_t)idx[s] - e0;
         if (c >= 0 && c < H) buf[c] -= vals[s] * sum_gx;
     }
@@ -257,7 +254,7 @@ extern "C" int32_t slimfit_layernorm_forward(const float *x, const float *gamma,
     return launch_status();
 }
 
-extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *tile_ptr,
+extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *row_ptr,
                                                      int64_t k, const float *rstd, const float *gamma, const float *dy,
                                                      int64_t rows, int64_t H, float *dx, void *stream)
 {
@@ -265,17 +262,17 @@ extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const in
     if (rc != SLIMFIT_OK) return rc;
     if (k < 0 || k > rows * H) return SLIMFIT_ERR_INVALID_ARG;
     if (rows == 0) return SLIMFIT_OK;
-    if (!tile_ptr || !rstd || !gamma || !dy || !dx || dy == dx || (k > 0 && (!vals || !idx)))
+    if (!row_ptr || !rstd || !gamma || !dy || !dx || dy == dx || (k > 0 && (!vals || !idx)))
         return SLIMFIT_ERR_INVALID_ARG;
     if (!aligned_to(dy, 16) || !aligned_to(dx, 16) || !aligned_to(gamma, 16) || !aligned_to(rstd, 4) ||
-        !aligned_to(tile_ptr, 4) || (k > 0 && (!aligned_to(vals, 4) || !aligned_to(idx, 4))))
+        !aligned_to(row_ptr, 4) || (k > 0 && (!aligned_to(vals, 4) || !aligned_to(idx, 4))))
         return SLIMFIT_ERR_ALIGNMENT;
     const int64_t n = rows * H;
     if ((rc = check_device_range(dy, (size_t)n * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(dx, (size_t)n * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
-    if ((rc = check_device_range(tile_ptr, (size_t)((n + kPtrTile - 1) / kPtrTile + 1) * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(row_ptr, (size_t)(rows + 1) * 4)) != SLIMFIT_OK) return rc;
     if (k > 0) {
         if ((rc = check_device_range(vals, (size_t)k * 4)) != SLIMFIT_OK) return rc;
         if ((rc = check_device_range(idx, (size_t)k * 4)) != SLIMFIT_OK) return rc;
@@ -284,6 +281,6 @@ extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const in
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
     const size_t lds_bytes = (size_t)kWaves * (size_t)H * 4;              // at most 64 KB
     SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_pruned_kernel<NV><<<grid, kThreads, lds_bytes, s>>>(
-                                             vals, idx, tile_ptr, k, rstd, gamma, dy, rows, (int)H, dx)));
+                                             vals, idx, row_ptr, k, rstd, gamma, dy, rows, (int)H, dx)));
     return launch_status();
 }

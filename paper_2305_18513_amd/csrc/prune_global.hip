@@ -142,22 +142,29 @@ __device__ __forceinline__ int load_vec(const T *x, int64_t n, int64_t v, uint32
 struct Std {
     const float *mean, *rstd;
     uint32_t magic, shift;
+    uint32_t wave_uniform;       // H is a multiple of 64 vectors: the 64 vectors a wave loads together share a row
+    uint32_t last_row;
+    uint32_t H;
+    int32_t *row_ptr;            // optional output: survivors ahead of every row (rows + 1 entries)
 };
-template <typename T, bool STD, bool NT = false>
-__device__ __forceinline__ int load_std(const T *x, int64_t n, int64_t v, uint32_t (&bits)[Elem<T>::EPV], const Std &sd)
+// Applied to a vector after all of the thread's loads have been issued, so that
+// the loads still overlap.
+template <typename T, bool STD>
+__device__ __forceinline__ void standardise(uint32_t (&bits)[Elem<T>::EPV], int valid, int64_t v, const Std &sd)
 {
     constexpr int EPV = Elem<T>::EPV;
-    const int valid = load_vec<T, NT>(x, n, v, bits);
     if constexpr (STD) {
-        if (valid) {                                           // H is a multiple of EPV: a vector lies in one row
-            const uint32_t row = __umulhi((uint32_t)(v * EPV), sd.magic) >> sd.shift;
-            const float mu = sd.mean[row], rs = sd.rstd[row];
+        // H is a multiple of EPV: a vector lies in one row.  No branch on `valid`: a vector past the end
+        // takes the last row's statistics and its result is never looked at, and the statistic loads of
+        // all of a thread's vectors can be issued together.
+        (void)valid;
+        uint32_t row = min(__umulhi((uint32_t)(v * EPV), sd.magic) >> sd.shift, sd.last_row);
+        if (sd.wave_uniform) row = (uint32_t)__builtin_amdgcn_readfirstlane((int)row);   // scalar loads
+        const float mu = sd.mean[row], rs = sd.rstd[row];
 #pragma unroll
-            for (int e = 0; e < EPV; ++e)
-                bits[e] = __builtin_bit_cast(uint32_t, (__builtin_bit_cast(float, bits[e]) - mu) * rs);
-        }
+        for (int e = 0; e < EPV; ++e)
+            bits[e] = __builtin_bit_cast(uint32_t, (__builtin_bit_cast(float, bits[e]) - mu) * rs);
     }
-    return valid;
 }
 
 template <int CTRL, int ROW_MASK>
@@ -235,8 +242,11 @@ hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, ui
             for (int j = 0; j < kVecPerThread; ++j) {
                 const int64_t v = base + (int64_t)j * kHistThreads + threadIdx.x;
                 valid[j] = 0;
-                if (v < nvec) valid[j] = load_std<T, STD, SLIMFIT_PG_NT != 0>(x, n, v, bits[j], sd);
+                if (v < nvec) valid[j] = load_vec<T, SLIMFIT_PG_NT != 0>(x, n, v, bits[j]);
             }
+#pragma unroll
+            for (int j = 0; j < kVecPerThread; ++j)
+                standardise<T, STD>(bits[j], valid[j], base + (int64_t)j * kHistThreads + threadIdx.x, sd);
 #pragma unroll
             for (int j = 0; j < kVecPerThread; ++j) {
 #pragma unroll
@@ -350,8 +360,10 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
         valid[j] = 0;
-        if (v < nvec) valid[j] = load_std<T, STD>(x, n, v, bits[j], sd);
+        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
     }
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) standardise<T, STD>(bits[j], valid[j], tile_vec(blockIdx.x, wave, j, lane), sd);
     uint32_t gt = 0u, in_bin = 0u;
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
@@ -443,8 +455,10 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
         valid[j] = 0;
-        if (v < nvec) valid[j] = load_std<T, STD>(x, n, v, bits[j], sd);
+        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
     }
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) standardise<T, STD>(bits[j], valid[j], tile_vec(blockIdx.x, wave, j, lane), sd);
     uint32_t gt = 0u, eq = 0u;
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
@@ -586,8 +600,10 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
         valid[j] = 0;
-        if (v < nvec) valid[j] = load_std<T, STD>(x, n, v, bits[j], sd);
+        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
     }
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) standardise<T, STD>(bits[j], valid[j], tile_vec(blockIdx.x, wave, j, lane), sd);
     uint32_t incl[kVecPerThread];
     uint32_t wave_packed = 0u;
 #pragma unroll
@@ -622,12 +638,21 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
             tile_ptr[wave_start / kPtrTile] = (int32_t)(out_base + run_gt + min(run_eq, budget));
         if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) tile_ptr[(n + kPtrTile - 1) / kPtrTile] = (int32_t)k;
     }
+    if constexpr (STD) {
+        if (sd.row_ptr && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) sd.row_ptr[sd.last_row + 1u] = (int32_t)k;
+    }
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
         const uint32_t excl = incl[j] - packed[j];
         uint32_t my_gt = run_gt + (excl & 0xFFFFu);
         uint32_t my_eq = run_eq + (excl >> 16);
         const int64_t e0 = tile_vec(blockIdx.x, wave, j, lane) * EPV;
+        if constexpr (STD) {
+            if (sd.row_ptr && valid[j]) {                       // rows start on vector boundaries
+                const uint32_t row = __umulhi((uint32_t)e0, sd.magic) >> sd.shift;
+                if ((uint32_t)e0 == row * sd.H) sd.row_ptr[row] = (int32_t)(out_base + my_gt + min(my_eq, budget));
+            }
+        }
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
             if (e < valid[j]) {
@@ -832,7 +857,7 @@ namespace {
 // tensor is rows of H elements standardised with mean / rstd on the way in.
 int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, const float *mean, const float *rstd,
                            int64_t k, int32_t by_magnitude, void *vals, int32_t *idx, int32_t *tile_ptr,
-                           void *workspace, size_t workspace_bytes, void *stream)
+                           int32_t *row_ptr, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dt) || n < 0 || k < 0 || k > n) return SLIMFIT_ERR_INVALID_ARG;
     if (n > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;                 // indices are int32
@@ -845,7 +870,8 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
     if (!x || !vals || !idx || !workspace || (standardised && (!mean || !rstd))) return SLIMFIT_ERR_INVALID_ARG;
     const size_t esz = dtype_size(dt);
     if (!aligned_to(x, 16) || !aligned_to(vals, esz) || !aligned_to(idx, 4) || !aligned_to(workspace, 16) ||
-        (tile_ptr && !aligned_to(tile_ptr, 4)) || (standardised && (!aligned_to(mean, 4) || !aligned_to(rstd, 4))))
+        (tile_ptr && !aligned_to(tile_ptr, 4)) || (row_ptr && !aligned_to(row_ptr, 4)) ||
+        (standardised && (!aligned_to(mean, 4) || !aligned_to(rstd, 4))))
         return SLIMFIT_ERR_ALIGNMENT;
     const Workspace w = carve(workspace, n);
     if (workspace_bytes < w.bytes) return SLIMFIT_ERR_WORKSPACE;
@@ -856,11 +882,12 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
     if ((rc = check_device_range(workspace, w.bytes)) != SLIMFIT_OK) return rc;
     if (tile_ptr && (rc = check_device_range(tile_ptr, (size_t)slimfit_global_tile_ptr_len(n) * 4)) != SLIMFIT_OK)
         return rc;
-    Std sd = {nullptr, nullptr, 0u, 0u};
+    Std sd = {nullptr, nullptr, 0u, 0u, 0u, 0u, 0u, nullptr};
     if (standardised) {
         const size_t rows = (size_t)(n / H);
         if ((rc = check_device_range(mean, rows * 4)) != SLIMFIT_OK) return rc;
         if ((rc = check_device_range(rstd, rows * 4)) != SLIMFIT_OK) return rc;
+        if (row_ptr && (rc = check_device_range(row_ptr, (rows + 1) * 4)) != SLIMFIT_OK) return rc;
         int l = 0;
         while (((int64_t)1 << l) < H) ++l;                              // ceil(log2 H) >= 2
         const uint64_t pow = (uint64_t)1 << (31 + l);
@@ -868,6 +895,10 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
         sd.rstd = rstd;
         sd.magic = (uint32_t)((pow + (uint64_t)H - 1) / (uint64_t)H);   // < 2^32 because H > 2^(l-1)
         sd.shift = (uint32_t)(l - 1);
+        sd.wave_uniform = (H % (kWave * 4) == 0) ? 1u : 0u;             // fp32: 4 elements a vector
+        sd.last_row = (uint32_t)(rows - 1);
+        sd.H = (uint32_t)H;
+        sd.row_ptr = row_ptr;
     }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -897,18 +928,18 @@ extern "C" int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, in
                                         void *vals, int32_t *idx, int32_t *tile_ptr, void *workspace,
                                         size_t workspace_bytes, void *stream)
 {
-    return prune_global_entry(x, dt, n, 0, nullptr, nullptr, k, by_magnitude, vals, idx, tile_ptr, workspace,
+    return prune_global_entry(x, dt, n, 0, nullptr, nullptr, k, by_magnitude, vals, idx, tile_ptr, nullptr, workspace,
                               workspace_bytes, stream);
 }
 
 extern "C" int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, int64_t H,
                                                      const float *mean, const float *rstd, int64_t k,
                                                      int32_t by_magnitude, void *vals, int32_t *idx,
-                                                     int32_t *tile_ptr, void *workspace, size_t workspace_bytes,
-                                                     void *stream)
+                                                     int32_t *tile_ptr, int32_t *row_ptr, void *workspace,
+                                                     size_t workspace_bytes, void *stream)
 {
     if (H == 0) return SLIMFIT_ERR_INVALID_ARG;
-    return prune_global_entry(x, dt, n, H, mean, rstd, k, by_magnitude, vals, idx, tile_ptr, workspace,
+    return prune_global_entry(x, dt, n, H, mean, rstd, k, by_magnitude, vals, idx, tile_ptr, row_ptr, workspace,
                               workspace_bytes, stream);
 }
 

@@ -56,17 +56,20 @@ def _prune_both(x, mean, rstd, k, by_mag=True):
     vals = Guarded(k, torch.float32)
     idx = Guarded(k, torch.int32)
     ptr = Guarded(sf.global_tile_ptr_len(n), torch.int32)
+    rptr = Guarded(rows + 1, torch.int32)
     ws = Guarded(sf.prune_global_workspace(n), torch.uint8)
-    sf.prune_global_standardized(x, mean, rstd, k, vals.t, idx.t, by_mag, ptr.t, ws.t)
+    sf.prune_global_standardized(x, mean, rstd, k, vals.t, idx.t, by_mag, ptr.t, rptr.t, ws.t)
     torch.cuda.synchronize()
-    vals.check(); idx.check(); ptr.check(); ws.check()
+    vals.check(); idx.check(); ptr.check(); rptr.check(); ws.check()
     xs = ref.standardize(to_np(x), to_np(mean), to_np(rstd)).reshape(-1)
     ov, oi = ref.prune_global(xs, k, by_magnitude=by_mag)
     np.testing.assert_array_equal(to_np(idx.t), oi)
     np.testing.assert_array_equal(to_np(vals.t).view(np.uint32), ov.view(np.uint32))
     edges = np.arange(ptr.t.numel(), dtype=np.int64) * sf.GLOBAL_TILE
     np.testing.assert_array_equal(to_np(ptr.t), np.searchsorted(oi, edges, side="left").astype(np.int32))
-    return vals.t, idx.t, ptr.t
+    row_edges = np.arange(rows + 1, dtype=np.int64) * H
+    np.testing.assert_array_equal(to_np(rptr.t), np.searchsorted(oi, row_edges, side="left").astype(np.int32))
+    return vals.t, idx.t, rptr.t
 
 
 def _backward_both(vals, idx, ptr, k, rstd, gamma, dy):
@@ -122,10 +125,10 @@ def test_backward_with_nothing_kept_and_inconsistent_pointers():
     x, gamma, beta, dy = _inputs(5, rows, H)
     mean, rstd = _forward_both(x, gamma, beta)
     n = rows * H
-    ptr0 = torch.zeros(sf.global_tile_ptr_len(n), dtype=torch.int32, device="cuda")
+    ptr0 = torch.zeros(rows + 1, dtype=torch.int32, device="cuda")
     _backward_both(torch.empty(0, device="cuda"), torch.empty(0, dtype=torch.int32, device="cuda"), ptr0, 0, rstd,
                    gamma, dy)
-    # pointers that file the pairs under wrong tiles: no fault, pairs outside their row are dropped
+    # pointers that file the pairs under wrong rows: no fault, pairs outside their row are dropped
     k = n // 10
     vals, idx, ptr = _prune_both(x, mean, rstd, k)
     dx = Guarded(n, torch.float32)
