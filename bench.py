@@ -289,6 +289,46 @@ def main() -> int:
                             "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                             "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del probs
+        # LayerNorm around the pruned cache (fp32 tensors only): forward with row statistics, 10 % of the
+        # standardised input kept without storing it, input gradient of the frozen layer from the kept pairs
+        if cfg.act_dtype == torch.float32:
+            H = cfg.hidden
+            lnx = [s.ln[0].view(-1, H) for s in sets]
+            rows_l = lnx[0].shape[0]
+            n_l = rows_l * H
+            k_l = sf.keep_count(n_l, 100000)
+            gam = torch.rand(H, device="cuda") + 0.5
+            bet = torch.rand(H, device="cuda") - 0.5
+            lny = [torch.empty_like(x) for x in lnx]
+            mu = [torch.empty(rows_l, device="cuda") for _ in sets]
+            rs = [torch.empty(rows_l, device="cuda") for _ in sets]
+            pv = [torch.empty(k_l, device="cuda") for _ in sets]
+            pi = [torch.empty(k_l, dtype=torch.int32, device="cuda") for _ in sets]
+            rp = [torch.empty(rows_l + 1, dtype=torch.int32, device="cuda") for _ in sets]
+            lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
+            ln_runs = {
+                "layernorm_forward[ln_in]": (8 * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
+                    lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
+                "prune_global_standardized[ln_in, 10%]": (4 * n_l + 8 * k_l + 12 * rows_l, lambda i:
+                    sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
+                "layernorm_backward_pruned[ln_in]": (8 * n_l + 8 * k_l + 8 * rows_l, lambda i:
+                    sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
+            }
+            for name, (nb, fn) in ln_runs.items():
+                for i in range(len(sets)):
+                    fn(i)
+                torch.cuda.synchronize()
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+                for i, (a, b) in enumerate(ev):
+                    a.record()
+                    fn(i % n_sets)
+                    b.record()
+                torch.cuda.synchronize()
+                ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del lny, mu, rs, pv, pi, rp, lws
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
