@@ -49,7 +49,8 @@ def lib():
                          "prune_scores", "restore_scores", "ils_select",
                          "ils_update", "freeze_count", "keep_count",
                          "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune",
-                         "layernorm_forward", "standardize", "layernorm_backward_pruned"):
+                         "layernorm_forward", "standardize", "layernorm_backward_pruned",
+                         "splitmix64", "schedule_random", "schedule_progressive"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
         return _lib
 
@@ -303,3 +304,29 @@ def ils_update(d, new_scores, frozen_mask):
                                       _ptr(frozen_mask), C.c_int(d.size))
     _check(rc, "ils_update")
     return d
+
+
+def splitmix64(state, n):
+    """n raw outputs of the SplitMix64 stream started at ``state``."""
+    out = np.zeros(n, dtype=np.uint64)
+    _check(lib().slimfit_ref_splitmix64(C.c_uint64(state), C.c_int(n), _ptr(out)), "splitmix64")
+    return out
+
+
+def schedule_random(L, n_freeze, seed, iteration):
+    """Random freezing schedule.  Returns (frozen_idx int32[n_freeze] in draw order, mask uint8[L])."""
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(L, dtype=np.uint8)
+    rc = lib().slimfit_ref_schedule_random(C.c_int(L), C.c_int(n_freeze), C.c_uint64(seed), C.c_uint64(iteration),
+                                           _ptr(frozen), _ptr(mask))
+    _check(rc, "schedule_random")
+    return frozen, mask
+
+
+def schedule_progressive(L, n_freeze):
+    """Progressive freezing schedule: the earliest n_freeze layers."""
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(L, dtype=np.uint8)
+    rc = lib().slimfit_ref_schedule_progressive(C.c_int(L), C.c_int(n_freeze), _ptr(frozen), _ptr(mask))
+    _check(rc, "schedule_progressive")
+    return frozen, mask

@@ -794,3 +794,75 @@ int slimfit_ref_ils_update(float *d, const float *new_scores,
             d[i] = new_scores[i];
     return REF_OK;
 }
+
+/* ------------------------------------------------------------------ */
+/* The two other freezing schedules the paper compares ILS with (the    */
+/* ablation on freezing schedules): "random" picks the int(L*F) frozen  */
+/* layers uniformly at random at every iteration, "progressive" keeps   */
+/* the earliest layers frozen and updates the later ones throughout.    */
+/* The random draw is a counter-based recipe both sides implement:      */
+/*   stream  SplitMix64 with state s0 = seed XOR (iteration *            */
+/*           0xD6E8FEB86659FD93), each output advancing the state by     */
+/*           0x9E3779B97F4A7C15 and mixing it with the 30/27/31 shifts   */
+/*           and the two multipliers of that generator;                  */
+/*   choice  the first n_freeze steps of a Fisher-Yates shuffle of        */
+/*           0..L-1: at step i, j = i + (next() mod (L - i)), swap;       */
+/*   frozen_idx lists the picks in the order they were drawn.            */
+/* ------------------------------------------------------------------ */
+
+static uint64_t splitmix64_next(uint64_t *state)
+{
+    uint64_t z = (*state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+/* n raw outputs of the stream started at `state` (for the known-answer pin) */
+int slimfit_ref_splitmix64(uint64_t state, int n, uint64_t *out)
+{
+    if (n < 0 || (n > 0 && !out))
+        return REF_BAD;
+    for (int i = 0; i < n; ++i)
+        out[i] = splitmix64_next(&state);
+    return REF_OK;
+}
+
+int slimfit_ref_schedule_random(int L, int n_freeze, uint64_t seed, uint64_t iteration,
+                                int32_t *frozen_idx, uint8_t *mask)
+{
+    if (L < 0 || n_freeze < 0 || n_freeze > L || (n_freeze > 0 && !frozen_idx))
+        return REF_BAD;
+    int32_t *perm = (int32_t *)malloc(sizeof(int32_t) * (size_t)(L > 0 ? L : 1));
+    if (!perm)
+        return REF_BAD;
+    for (int i = 0; i < L; ++i) {
+        perm[i] = i;
+        if (mask)
+            mask[i] = 0;
+    }
+    uint64_t state = seed ^ (iteration * 0xD6E8FEB86659FD93ull);
+    for (int i = 0; i < n_freeze; ++i) {
+        const int j = i + (int)(splitmix64_next(&state) % (uint64_t)(L - i));
+        const int32_t t = perm[i];
+        perm[i] = perm[j];
+        perm[j] = t;
+        frozen_idx[i] = perm[i];
+        if (mask)
+            mask[perm[i]] = 1;
+    }
+    free(perm);
+    return REF_OK;
+}
+
+int slimfit_ref_schedule_progressive(int L, int n_freeze, int32_t *frozen_idx, uint8_t *mask)
+{
+    if (L < 0 || n_freeze < 0 || n_freeze > L || (n_freeze > 0 && !frozen_idx))
+        return REF_BAD;
+    for (int i = 0; i < L; ++i)
+        if (mask)
+            mask[i] = i < n_freeze ? 1 : 0;
+    for (int i = 0; i < n_freeze; ++i)
+        frozen_idx[i] = i;
+    return REF_OK;
+}
