@@ -357,6 +357,27 @@ int32_t slimfit_ils_select(const float *d, int32_t L, int32_t n_freeze,
 int32_t slimfit_ils_update(float *d, const float *new_scores,
                            const uint8_t *frozen_mask, int32_t L);
 
+/* ------------------------------------------------------------------------
+ * (d') The two schedules the paper compares ILS with (its ablation of freezing
+ *     schedules): "random" draws the int(L*F) frozen layers uniformly at random
+ *     at every iteration, "progressive" keeps the earliest layers frozen and
+ *     updates the later ones throughout.  HOST pointers, same outputs as
+ *     slimfit_ils_select.
+ *
+ *  slimfit_schedule_random : a function of (seed, iteration) only.  The draw is
+ *     the first n_freeze steps of a Fisher-Yates shuffle of 0..L-1 (step i swaps
+ *     entry i with entry i + next() mod (L - i)), next() being SplitMix64
+ *     started at seed XOR (iteration * 0xD6E8FEB86659FD93).  frozen_idx lists
+ *     the picks in the order drawn.
+ *  slimfit_schedule_progressive : frozen_idx = 0 .. n_freeze-1.
+ *  INVALID_ARG if L < 0, n_freeze outside [0, L] or frozen_idx is NULL with
+ *  n_freeze > 0; mask may be NULL.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_schedule_random(int32_t L, int32_t n_freeze, uint64_t seed, uint64_t iteration,
+                                int32_t *frozen_idx, uint8_t *mask);
+
+int32_t slimfit_schedule_progressive(int32_t L, int32_t n_freeze, int32_t *frozen_idx, uint8_t *mask);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,7 +36,7 @@ EXPORTS = (
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
     "slimfit_layernorm_backward_pruned", "slimfit_freeze_count", "slimfit_ils_select",
-    "slimfit_ils_update",
+    "slimfit_ils_update", "slimfit_schedule_random", "slimfit_schedule_progressive",
 )
 
 
@@ -389,3 +389,23 @@ def ils_update(d: np.ndarray, new_scores: np.ndarray, frozen_mask: np.ndarray) -
                                   C.c_void_p(frozen_mask.ctypes.data), C.c_int32(d.size))
     _check(rc, "ils_update")
     return d
+
+
+def schedule_random(L: int, n_freeze: int, seed: int, iteration: int):
+    """Random freezing schedule.  Returns (frozen_idx int32[n_freeze] in draw order, mask uint8[L])."""
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(max(L, 0), dtype=np.uint8)
+    rc = lib().slimfit_schedule_random(C.c_int32(L), C.c_int32(n_freeze), C.c_uint64(seed), C.c_uint64(iteration),
+                                       C.c_void_p(frozen.ctypes.data), C.c_void_p(mask.ctypes.data))
+    _check(rc, "schedule_random")
+    return frozen, mask
+
+
+def schedule_progressive(L: int, n_freeze: int):
+    """Progressive freezing schedule: the earliest n_freeze layers."""
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(max(L, 0), dtype=np.uint8)
+    rc = lib().slimfit_schedule_progressive(C.c_int32(L), C.c_int32(n_freeze), C.c_void_p(frozen.ctypes.data),
+                                            C.c_void_p(mask.ctypes.data))
+    _check(rc, "schedule_progressive")
+    return frozen, mask

@@ -104,3 +104,48 @@ extern "C" int32_t slimfit_ils_update(float *d, const float *new_scores, const u
         if (!frozen_mask[i]) d[i] = new_scores[i];
     return SLIMFIT_OK;
 }
+
+// ---- the other two freezing schedules of the paper's ablation -------------------------
+namespace {
+
+// SplitMix64: the state advances by the 64-bit golden ratio, the output is the
+// state passed through two xor-shift-multiply rounds and a final xor-shift.
+inline uint64_t splitmix64(uint64_t &state)
+{
+    state += 0x9E3779B97F4A7C15ull;
+    uint64_t z = state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+}  // namespace
+
+extern "C" int32_t slimfit_schedule_random(int32_t L, int32_t n_freeze, uint64_t seed, uint64_t iteration,
+                                           int32_t *frozen_idx, uint8_t *mask)
+{
+    if (L < 0 || n_freeze < 0 || n_freeze > L) return SLIMFIT_ERR_INVALID_ARG;
+    if (n_freeze > 0 && !frozen_idx) return SLIMFIT_ERR_INVALID_ARG;
+    if (mask) std::fill(mask, mask + L, (uint8_t)0);
+    std::vector<int32_t> pool((size_t)L);
+    std::iota(pool.begin(), pool.end(), 0);
+    uint64_t state = seed ^ (iteration * 0xD6E8FEB86659FD93ull);
+    for (int32_t i = 0; i < n_freeze; ++i) {                 // the first n_freeze steps of a Fisher-Yates shuffle
+        const uint64_t span = (uint64_t)(L - i);
+        const size_t j = (size_t)i + (size_t)(splitmix64(state) % span);
+        std::swap(pool[(size_t)i], pool[j]);
+        frozen_idx[i] = pool[(size_t)i];
+        if (mask) mask[pool[(size_t)i]] = 1;
+    }
+    return SLIMFIT_OK;
+}
+
+extern "C" int32_t slimfit_schedule_progressive(int32_t L, int32_t n_freeze, int32_t *frozen_idx, uint8_t *mask)
+{
+    if (L < 0 || n_freeze < 0 || n_freeze > L) return SLIMFIT_ERR_INVALID_ARG;
+    if (n_freeze > 0 && !frozen_idx) return SLIMFIT_ERR_INVALID_ARG;
+    if (mask)
+        for (int32_t i = 0; i < L; ++i) mask[i] = i < n_freeze ? 1 : 0;
+    for (int32_t i = 0; i < n_freeze; ++i) frozen_idx[i] = i;
+    return SLIMFIT_OK;
+}

@@ -188,3 +188,22 @@ def test_ils_argument_errors(lib):
     assert rc == sf.ERR_INVALID_ARG
     assert lib.slimfit_ils_update(C.c_void_p(0), C.c_void_p(0), C.c_void_p(0), C.c_int32(0)) == sf.OK
     assert lib.slimfit_ils_update(C.c_void_p(0), C.c_void_p(0), C.c_void_p(0), C.c_int32(3)) == sf.ERR_INVALID_ARG
+
+
+def test_schedule_variants_match_the_oracle():
+    """Random and progressive freezing (host code): the library against the oracle, draw for draw."""
+    for L, n in ((1, 1), (8, 4), (12, 0), (74, 55), (198, 198), (300, 1), (0, 0)):
+        for seed, it in ((0, 0), (7, 1), (2 ** 63 + 5, 10 ** 12), (2 ** 64 - 1, 2 ** 64 - 1)):
+            gi, gm = sf.schedule_random(L, n, seed, it)
+            oi, om = ref.schedule_random(L, n, seed, it)
+            np.testing.assert_array_equal(gi, oi)
+            np.testing.assert_array_equal(gm, om)
+        gi, gm = sf.schedule_progressive(L, n)
+        oi, om = ref.schedule_progressive(L, n)
+        np.testing.assert_array_equal(gi, oi)
+        np.testing.assert_array_equal(gm, om)
+    for bad in ((4, 5), (-1, 0), (4, -1)):
+        with pytest.raises(sf.SlimfitError):
+            sf.schedule_random(bad[0], bad[1], 0, 0)
+        with pytest.raises(sf.SlimfitError):
+            sf.schedule_progressive(*bad)
