@@ -1,0 +1,134 @@
+"""torch.autograd wrappers over the C ABI (Alg. 4 and Sec. 4 of the paper).
+
+Each Function runs its forward through the library, keeps only the compressed
+form of the activation its backward needs, and skips the weight gradient of a
+frozen layer.  Nothing here computes on its own what a kernel of the library
+computes; the dense matrix products of the linear layer are torch's.
+
+  GeluFunction       y = GELU(x); caches x in `bits` bits (per-block scales);
+                     backward multiplies by GELU'(x^) straight from the cache.
+  LayerNormFunction  frozen: caches the `keep_ppm` largest |x~| of the whole
+                     tensor with int32 indices, row pointers and rstd; backward
+                     is the paper's input-gradient formula on those pairs, and
+                     gamma / beta get no gradient.  Active: caches x exactly
+                     and returns all three gradients.
+  LinearFunction     Alg. 4: an active layer caches its input in `bits` bits and
+                     computes grad_weight from the dequantised input; a frozen
+                     layer caches nothing but the weight and returns
+                     grad_weight = None.
+
+All tensors are CUDA tensors; the kernels run on torch's current stream.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as sf
+
+
+def _flat(t: torch.Tensor) -> torch.Tensor:
+    return t.contiguous().view(-1)
+
+
+class GeluFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x: torch.Tensor, bits: int = 4, block: int = 64):
+        xf = _flat(x)
+        n = xf.numel()
+        y = torch.empty_like(xf)
+        codes = torch.empty(sf.packed_bytes(n, bits), dtype=torch.uint8, device=x.device)
+        scales = torch.empty(sf.num_blocks(n, block), dtype=torch.float32, device=x.device)
+        sf.gelu_quant_pack(xf, sf.Q_BLOCK, bits, block, 0, y, codes, scales)
+        ctx.save_for_backward(codes, scales)
+        ctx.quant = (bits, block)
+        return y.view(x.shape)
+
+    @staticmethod
+    def backward(ctx, grad_output: torch.Tensor):
+        codes, scales = ctx.saved_tensors
+        bits, block = ctx.quant
+        dy = _flat(grad_output)
+        dx = torch.empty_like(dy)
+        sf.gelu_backward_dequant(codes, scales, sf.Q_BLOCK, bits, block, 0, dy, dx)
+        return dx.view(grad_output.shape), None, None
+
+
+class LayerNormFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float = 1e-5,
+                frozen: bool = False, keep_ppm: int = 100000):
+        H = x.shape[-1]
+        x2 = x.contiguous().view(-1, H)
+        rows = x2.shape[0]
+        y = torch.empty_like(x2)
+        mean = torch.empty(rows, dtype=torch.float32, device=x.device)
+        rstd = torch.empty(rows, dtype=torch.float32, device=x.device)
+        sf.layernorm_forward(x2, gamma, beta, eps, y, mean, rstd)
+        ctx.frozen = frozen
+        if frozen:
+            n = x2.numel()
+            k = sf.keep_count(n, keep_ppm)
+            vals = torch.empty(k, dtype=torch.float32, device=x.device)
+            idx = torch.empty(k, dtype=torch.int32, device=x.device)
+            row_ptr = torch.empty(rows + 1, dtype=torch.int32, device=x.device)
+            if k > 0:
+                sf.prune_global_standardized(x2, mean, rstd, k, vals, idx, True, None, row_ptr)
+            else:
+                row_ptr.zero_()
+            ctx.k = k
+            ctx.save_for_backward(vals, idx, row_ptr, rstd, gamma)
+        else:
+            ctx.save_for_backward(x2, mean, rstd, gamma)
+        return y.view(x.shape)
+
+    @staticmethod
+    def backward(ctx, grad_output: torch.Tensor):
+        H = grad_output.shape[-1]
+        dy = grad_output.contiguous().view(-1, H)
+        if ctx.frozen:
+            vals, idx, row_ptr, rstd, gamma = ctx.saved_tensors
+            dx = torch.empty_like(dy)
+            sf.layernorm_backward_pruned(vals, idx, row_ptr, ctx.k, rstd, gamma, dy, dx)
+            return dx.view(grad_output.shape), None, None, None, None, None
+        x2, mean, rstd, gamma = ctx.saved_tensors
+        xt = (x2 - mean[:, None]) * rstd[:, None]
+        g = dy * gamma * (rstd[:, None] / H)
+        dx = H * g - g.sum(1, keepdim=True) - xt * (g * xt).sum(1, keepdim=True)
+        return dx.view(grad_output.shape), (dy * xt).sum(0), dy.sum(0), None, None, None
+
+
+class LinearFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, input: torch.Tensor, weight: torch.Tensor, bias, requires_grad: bool = True, bits: int = 8,
+                block: int = 64):
+        out = torch.nn.functional.linear(input, weight, bias)
+        ctx.requires_weight_grad = requires_grad
+        ctx.has_bias = bias is not None
+        if requires_grad:
+            xf = _flat(input)
+            n = xf.numel()
+            codes = torch.empty(sf.packed_bytes(n, bits), dtype=torch.uint8, device=input.device)
+            scales = torch.empty(sf.num_blocks(n, block), dtype=torch.float32, device=input.device)
+            sf.quant_pack(xf, sf.Q_BLOCK, bits, block, 0, codes, scales)
+            ctx.save_for_backward(codes, scales, weight)
+            ctx.quant = (bits, block, input.shape, input.dtype)
+        else:
+            ctx.save_for_backward(weight)
+        return out
+
+    @staticmethod
+    def backward(ctx, grad_output: torch.Tensor):
+        if ctx.requires_weight_grad:
+            codes, scales, weight = ctx.saved_tensors
+            bits, block, shape, dtype = ctx.quant
+            x_hat = torch.empty(shape, dtype=dtype, device=grad_output.device)
+            sf.dequant_unpack(codes, scales, sf.Q_BLOCK, bits, block, 0, x_hat.view(-1))
+            go2 = grad_output.reshape(-1, grad_output.shape[-1])
+            grad_weight = go2.t().mm(x_hat.view(-1, shape[-1]))
+            grad_bias = go2.sum(0) if ctx.has_bias else None
+        else:
+            (weight,) = ctx.saved_tensors
+            grad_weight = None
+            grad_bias = None
+        grad_input = grad_output.matmul(weight)
+        return grad_input, grad_weight, grad_bias, None, None, None

@@ -1,0 +1,144 @@
+"""GPU: the torch.autograd wrappers (Alg. 4) marshal into the library correctly -- each Function's results are
+those of the same C-ABI calls made by hand (the kernels themselves are compared with the oracle elsewhere) --
+frozen layers return no weight gradient, and the cached activations are the compressed ones."""
+import pytest
+import torch
+
+from paper_2305_18513_amd import autograd as ag
+from paper_2305_18513_amd import binding as sf
+from tests.gpu_util import require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _saved_bytes(out: torch.Tensor) -> int:
+    return sum(t.numel() * t.element_size() for t in out.grad_fn.saved_tensors if not isinstance(t, torch.nn.Parameter))
+
+
+def test_gelu_function_equals_the_fused_calls_and_caches_four_bits():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(0)
+    x = (torch.randn(6, 50, 300, generator=g, device="cuda") * 2).requires_grad_(True)
+    dy = torch.randn(6, 50, 300, generator=g, device="cuda")
+    y = ag.GeluFunction.apply(x, 4, 64)
+    assert _saved_bytes(y) == sf.packed_bytes(x.numel(), 4) + 4 * sf.num_blocks(x.numel(), 64)
+    y.backward(dy)
+    n = x.numel()
+    y2 = torch.empty(n, device="cuda")
+    codes = torch.empty(sf.packed_bytes(n, 4), dtype=torch.uint8, device="cuda")
+    scales = torch.empty(sf.num_blocks(n, 64), device="cuda")
+    sf.gelu_quant_pack(x.detach().view(-1), sf.Q_BLOCK, 4, 64, 0, y2, codes, scales)
+    dx2 = torch.empty(n, device="cuda")
+    sf.gelu_backward_dequant(codes, scales, sf.Q_BLOCK, 4, 64, 0, dy.view(-1), dx2)
+    assert torch.equal(y.detach().view(-1), y2) and torch.equal(x.grad.view(-1), dx2)
+    exact = torch.nn.functional.gelu(x.detach())
+    assert torch.allclose(y.detach(), exact, rtol=1e-5, atol=1e-5)
+
+
+def test_layernorm_function_frozen_and_active():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(1)
+    rows, H = 96, 768
+    x = torch.randn(4, 24, H, generator=g, device="cuda").requires_grad_(True)
+    gamma = torch.nn.Parameter(torch.rand(H, generator=g, device="cuda") + 0.5)
+    beta = torch.nn.Parameter(torch.rand(H, generator=g, device="cuda") - 0.5)
+    dy = torch.randn(4, 24, H, generator=g, device="cuda")
+
+    # frozen: 10 % of the standardised input + indices + row pointers + rstd, no gradient for gamma / beta
+    y = ag.LayerNormFunction.apply(x, gamma, beta, 1e-5, True, 100000)
+    k = sf.keep_count(rows * H, 100000)
+    assert _saved_bytes(y) == 8 * k + 4 * (rows + 1) + 4 * rows
+    y.backward(dy)
+    assert gamma.grad is None and beta.grad is None
+    y2 = torch.empty(rows, H, device="cuda")
+    mean, rstd = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    sf.layernorm_forward(x.detach().view(rows, H), gamma.detach(), beta.detach(), 1e-5, y2, mean, rstd)
+    vals, idx = torch.empty(k, device="cuda"), torch.empty(k, dtype=torch.int32, device="cuda")
+    rp = torch.empty(rows + 1, dtype=torch.int32, device="cuda")
+    sf.prune_global_standardized(x.detach().view(rows, H), mean, rstd, k, vals, idx, True, None, rp)
+    dx2 = torch.empty(rows, H, device="cuda")
+    sf.layernorm_backward_pruned(vals, idx, rp, k, rstd, gamma.detach(), dy.view(rows, H), dx2)
+    assert torch.equal(y.detach().view(rows, H), y2) and torch.equal(x.grad.view(rows, H), dx2)
+    frozen_grad = x.grad.clone()
+
+    # active: exact gradients, equal to torch's own layer norm within fp32 rounding
+    x.grad = None
+    y = ag.LayerNormFunction.apply(x, gamma, beta, 1e-5, False, 100000)
+    y.backward(dy)
+    xr = x.detach().clone().requires_grad_(True)
+    gr, br = gamma.detach().clone().requires_grad_(True), beta.detach().clone().requires_grad_(True)
+    torch.nn.functional.layer_norm(xr, (H,), gr, br, 1e-5).backward(dy)
+    assert torch.allclose(x.grad, xr.grad, rtol=1e-4, atol=1e-5)
+    assert torch.allclose(gamma.grad, gr.grad, rtol=1e-4, atol=1e-4) and torch.allclose(beta.grad, br.grad, rtol=1e-4, atol=1e-4)
+    # the pruned gradient approximates the exact one: it only drops part of the last term of the paper's formula
+    rel = (frozen_grad - xr.grad).norm() / xr.grad.norm()
+    assert float(rel) < 0.5
+
+
+def test_linear_function_skips_the_weight_gradient_when_frozen():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(2)
+    x = torch.randn(8, 32, 256, generator=g, device="cuda").requires_grad_(True)
+    w = torch.nn.Parameter(torch.randn(512, 256, generator=g, device="cuda") * 0.05)
+    b = torch.nn.Parameter(torch.zeros(512, device="cuda"))
+    dy = torch.randn(8, 32, 512, generator=g, device="cuda")
+
+    out = ag.LinearFunction.apply(x, w, b, False, 8, 64)
+    assert _saved_bytes(out) == 0                                       # only the weight (a Parameter) is kept
+    out.backward(dy)
+    assert w.grad is None and b.grad is None
+    assert torch.allclose(x.grad, dy.matmul(w.detach()), rtol=1e-5, atol=1e-5)
+
+    x.grad = None
+    out = ag.LinearFunction.apply(x, w, b, True, 8, 64)
+    n = x.numel()
+    assert _saved_bytes(out) == sf.packed_bytes(n, 8) + 4 * sf.num_blocks(n, 64)       # 8-bit cache of the input
+    out.backward(dy)
+    codes = torch.empty(sf.packed_bytes(n, 8), dtype=torch.uint8, device="cuda")
+    scales = torch.empty(sf.num_blocks(n, 64), device="cuda")
+    sf.quant_pack(x.detach().view(-1), sf.Q_BLOCK, 8, 64, 0, codes, scales)
+    xh = torch.empty(n, device="cuda")
+    sf.dequant_unpack(codes, scales, sf.Q_BLOCK, 8, 64, 0, xh)
+    want = dy.view(-1, 512).t().mm(xh.view(-1, 256))
+    assert torch.allclose(w.grad, want, rtol=1e-5, atol=1e-4)
+    assert torch.allclose(b.grad, dy.view(-1, 512).sum(0), rtol=1e-5, atol=1e-4)
+    exact = dy.view(-1, 512).t().mm(x.detach().view(-1, 256))
+    assert float((w.grad - exact).norm() / exact.norm()) < 0.01           # 8-bit cache: below 1 % in norm
+
+
+def test_feed_forward_block_keeps_less_memory_when_wrapped():
+    """x -> Linear(H, 4H) -> GELU -> Linear(4H, H) -> LayerNorm, everything frozen: activation memory held
+    between forward and backward, wrapped vs plain torch."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    B, T, H = 16, 128, 512
+    x = torch.randn(B, T, H, generator=g, device="cuda").requires_grad_(True)
+    w1 = torch.nn.Parameter(torch.randn(4 * H, H, generator=g, device="cuda") * 0.03)
+    w2 = torch.nn.Parameter(torch.randn(H, 4 * H, generator=g, device="cuda") * 0.03)
+    gamma = torch.nn.Parameter(torch.ones(H, device="cuda"))
+    beta = torch.nn.Parameter(torch.zeros(H, device="cuda"))
+
+    def held(fn):
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        before = torch.cuda.memory_allocated()
+        out = fn()
+        torch.cuda.synchronize()
+        kept = torch.cuda.memory_allocated() - before - out.numel() * out.element_size()
+        out.sum().backward()
+        return kept
+
+    def plain():
+        h = torch.nn.functional.linear(x, w1)
+        h = torch.nn.functional.gelu(h)
+        h = torch.nn.functional.linear(h, w2)
+        return torch.nn.functional.layer_norm(h, (H,), gamma, beta, 1e-5)
+
+    def wrapped():
+        h = ag.LinearFunction.apply(x, w1, None, False, 8, 64)
+        h = ag.GeluFunction.apply(h, 4, 64)
+        h = ag.LinearFunction.apply(h, w2, None, False, 8, 64)
+        return ag.LayerNormFunction.apply(h, gamma, beta, 1e-5, True, 100000)
+
+    kept_plain, kept_wrapped = held(plain), held(wrapped)
+    assert kept_wrapped < 0.25 * kept_plain, (kept_plain, kept_wrapped)
