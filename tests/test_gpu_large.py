@@ -1,0 +1,137 @@
+"""GPU: the largest shapes the entry points accept in practice -- tensors whose element or byte offsets
+pass 2^31 and 2^32.  The oracle checks sampled units that it can compute one by one (quantisation
+blocks, score rows) or closed forms; the whole-tensor pruner is checked through the properties that
+define its result at any size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2305_18513_amd import binding as sf
+from tests.gpu_util import require_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _need(gib):
+    require_gpu()
+    free, _ = torch.cuda.mem_get_info()
+    if free < gib * (1 << 30):
+        pytest.skip("needs %d GiB of free device memory" % gib)
+
+
+def test_quant_dequant_past_two_to_the_32_elements():
+    _need(30)
+    n = (1 << 32) + 4099                                        # ragged tail, offsets beyond 32 bits
+    bits, block = 4, 32
+    g = torch.Generator(device="cuda").manual_seed(1)
+    x = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    step = 1 << 28
+    for s in range(0, n, step):                                 # generated in slices to bound temporaries
+        m = min(step, n - s)
+        x[s:s + m] = torch.randn(m, generator=g, device="cuda").to(torch.bfloat16)
+    codes = torch.empty(sf.packed_bytes(n, bits), dtype=torch.uint8, device="cuda")
+    scales = torch.empty(sf.num_blocks(n, block), dtype=torch.float32, device="cuda")
+    y = torch.empty_like(x)
+    sf.quant_pack(x, sf.Q_BLOCK, bits, block, 0, codes, scales)
+    sf.dequant_unpack(codes, scales, sf.Q_BLOCK, bits, block, 0, y)
+    torch.cuda.synchronize()
+    nb = sf.num_blocks(n, block)
+    rng = np.random.default_rng(0)
+    picks = sorted(set([0, 1, nb - 1, nb - 2, (1 << 31) // block, (1 << 32) // block - 1, (1 << 32) // block,
+                        (1 << 32) // block + 1] + rng.integers(0, nb, 300).tolist()))
+    for b in picks:
+        lo, hi = b * block, min((b + 1) * block, n)
+        xb = to_np(x[lo:hi])
+        oc, osc = ref.quant_pack(xb, mode=ref.Q_BLOCK, bits=bits, block=block)
+        got_c = to_np(codes[lo * bits // 8:(hi * bits + 7) // 8])
+        assert np.array_equal(got_c, oc), "codes of block %d" % b
+        assert to_np(scales[b:b + 1]).view(np.uint32)[0] == osc.view(np.uint32)[0], "scale of block %d" % b
+        oy = ref.dequant_unpack(oc, osc, hi - lo, mode=ref.Q_BLOCK, bits=bits, block=block, out_dtype=np.uint16)
+        assert np.array_equal(to_np(y[lo:hi]), oy), "dequantised block %d" % b
+
+
+def test_prune_and_restore_rows_past_two_to_the_32_elements():
+    _need(60)
+    rows, cols, k = 11_200_000, 384, 38                         # 4.3e9 elements, 17 GB
+    g = torch.Generator(device="cuda").manual_seed(2)
+    p = torch.empty(rows, cols, device="cuda")
+    step = 1_400_000
+    for s in range(0, rows, step):
+        p[s:s + step] = torch.softmax(torch.randn(min(step, rows - s), cols, generator=g, device="cuda") / 32 ** 0.5, dim=1)
+    vals = torch.empty(rows, k, device="cuda")
+    idx = torch.empty(rows, k, dtype=torch.uint16, device="cuda")
+    counts = torch.empty(rows, dtype=torch.int32, device="cuda")
+    sf.prune_scores(p, k, sf.PRUNE_TOPK, 0.0, vals, idx, counts)
+    out = torch.empty_like(p)
+    sf.restore_scores(vals, idx, counts, out)
+    torch.cuda.synchronize()
+    assert bool((counts == k).all())
+    rng = np.random.default_rng(1)
+    first_past = (1 << 32) // cols
+    picks = sorted(set([0, rows - 1, first_past - 1, first_past, first_past + 1, (1 << 31) // cols]
+                       + rng.integers(0, rows, 400).tolist()))
+    sel = torch.tensor(picks, device="cuda")
+    ov, oi, _ = ref.prune_scores(to_np(p[sel]), k)
+    assert np.array_equal(to_np(idx.view(torch.int16)[sel]).view(np.uint16), oi)
+    assert np.array_equal(to_np(vals[sel]).view(np.uint32), ov.view(np.uint32))
+    assert np.array_equal(to_np(out[sel]), ref.restore_scores(ov, oi, None, cols))
+    # every row of the restored tensor holds exactly k entries, each a copy of the input's
+    nz = out != 0
+    assert bool((nz.sum(1) == k).all()) and bool(((out == p) | ~nz).all())
+
+
+def test_layer_delta_closed_form_past_two_to_the_32_elements():
+    _need(40)
+    n = (1 << 32) + 16384 * 3 + 5
+    g = torch.Generator(device="cuda").manual_seed(3)
+    w = torch.empty(n, device="cuda")
+    step = 1 << 28
+    for s in range(0, n, step):
+        m = min(step, n - s)
+        t = (torch.randn(m, generator=g, device="cuda") * 0.02).to(torch.bfloat16).float()      # 8-bit mantissas
+        w[s:s + m] = torch.where(t == 0, torch.full_like(t, 0.5), t)
+    cur = w * (1 + 2.0 ** -7)                                   # exact in fp32: every term is 2^-7
+    small = torch.ones(1000, device="cuda")
+    prev_l, cur_l = [small, w, small], [small * 1.5, cur, small.clone()]
+    numel = [t.numel() for t in prev_l]
+    ws = torch.empty(sf.layer_delta_workspace(numel), dtype=torch.uint8, device="cuda")
+    d = torch.empty(3, device="cuda")
+    sf.layer_delta(prev_l, cur_l, False, 0.0, d, ws)
+    torch.cuda.synchronize()
+    assert d.tolist() == [0.5, 2.0 ** -7, 0.0]
+
+
+def test_whole_tensor_pruning_at_the_int32_limit():
+    _need(60)
+    n = (1 << 31) - 8
+    k = n // 10
+    g = torch.Generator(device="cuda").manual_seed(4)
+    x = torch.empty(n, device="cuda")
+    step = 1 << 28
+    for s in range(0, n, step):
+        m = min(step, n - s)
+        x[s:s + m] = (torch.randn(m, generator=g, device="cuda") * 64).round() / 64      # ties at the cut are certain
+    vals = torch.empty(k, device="cuda")
+    idx = torch.empty(k, dtype=torch.int32, device="cuda")
+    ptr = torch.empty(sf.global_tile_ptr_len(n), dtype=torch.int32, device="cuda")
+    sf.prune_global(x, k, vals, idx, True, ptr)
+    torch.cuda.synchronize()
+    il = idx.long()
+    assert int(il.min()) >= 0 and int(il.max()) < n and bool((il[1:] > il[:-1]).all())          # ascending, in range
+    assert bool((x[il] == vals).all())                                                         # bit copies (no NaN here)
+    T = float(vals.abs().min())
+    ax = x.abs()
+    above, at = int((ax > T).sum()), int((ax == T).sum())
+    assert above < k <= above + at                                  # T is the k-th largest magnitude
+    assert int((vals.abs() > T).sum()) == above                     # everything above it is kept
+    kept_eq = il[vals.abs() == T]
+    all_eq = torch.nonzero(ax == T).view(-1)
+    assert torch.equal(kept_eq, all_eq[: kept_eq.numel()])          # ties go to the lowest indices
+    del ax, all_eq, kept_eq
+    edges = torch.arange(ptr.numel(), device="cuda", dtype=torch.int64) * sf.GLOBAL_TILE
+    assert torch.equal(ptr.long(), torch.searchsorted(il, edges))
+    out = torch.empty_like(x)
+    sf.restore_global(vals, idx, k, out, ptr)
+    torch.cuda.synchronize()
+    assert int((out != 0).sum()) == int((vals != 0).sum()) and bool((out[il] == vals).all())
