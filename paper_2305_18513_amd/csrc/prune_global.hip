@@ -43,6 +43,8 @@
 // 1, bracket, write) and 2 + number of digits times on the plain one.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace slimfit {
 namespace {
 
@@ -133,6 +135,32 @@ __device__ __forceinline__ int load_vec(const T *x, int64_t n, int64_t v, uint32
     return valid;
 }
 
+// INSIDE: the caller has established (uniformly for the workgroup) that every vector it touches lies
+// wholly below n, so the load is unconditional and the code after it is straight-line; otherwise the
+// vector may straddle n or lie past it.
+template <typename T, bool INSIDE, bool NT = false>
+__device__ __forceinline__ int load_tile_vec(const T *x, int64_t n, int64_t nvec, int64_t v,
+                                             uint32_t (&bits)[Elem<T>::EPV])
+{
+    constexpr int EPV = Elem<T>::EPV;
+    if constexpr (INSIDE) {
+        const u32x4 w = load_global<NT>(reinterpret_cast<const u32x4 *>(x + v * EPV));
+        if constexpr (EPV == 4) {
+            bits[0] = w.x; bits[1] = w.y; bits[2] = w.z; bits[3] = w.w;
+        } else {
+            bits[0] = w.x & 0xFFFFu; bits[1] = w.x >> 16;
+            bits[2] = w.y & 0xFFFFu; bits[3] = w.y >> 16;
+            bits[4] = w.z & 0xFFFFu; bits[5] = w.z >> 16;
+            bits[6] = w.w & 0xFFFFu; bits[7] = w.w >> 16;
+        }
+        return EPV;
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) bits[e] = 0u;
+        return v < nvec ? load_vec<T, NT>(x, n, v, bits) : 0;
+    }
+}
+
 // Optional standardisation on the way in (fp32 tensors): element j of row r
 // enters the selection as x~ = fl(fl(x - mean[r]) * rstd[r]), two fp32 operations
 // that every sweep repeats bit for bit, so the LayerNorm's standardised input is
@@ -206,7 +234,7 @@ __global__ void __launch_bounds__(kSelectThreads) init_kernel(State *st, uint32_
 // ---- one digit of the select: histogram of the keys that match the prefix ------------
 // Source: the tensor (first digit, and every digit on the plain route) or the
 // candidate list.
-template <typename T, bool MAG, bool STD>
+template <typename T, bool MAG, bool STD, bool FIRST>
 __global__ void __launch_bounds__(kHistThreads)
 hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, uint32_t *__restrict__ hist,
             const u32x2 *__restrict__ tile_cnt, const uint32_t *__restrict__ lists, int64_t ntiles, int shift, int nbins, Std sd)
@@ -234,15 +262,16 @@ hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, ui
         }
     } else {
         const int64_t nvec = (n + EPV - 1) / EPV;
+        const int64_t nfull = n / EPV;                            // vectors wholly below n
         const int64_t chunk = (int64_t)kHistThreads * kVecPerThread;
-        for (int64_t base = (int64_t)blockIdx.x * chunk; base < nvec; base += (int64_t)gridDim.x * chunk) {
+        auto sweep = [&](auto inside_tag, int64_t base) {
+            constexpr bool INSIDE = decltype(inside_tag)::value;
             uint32_t bits[kVecPerThread][EPV];
             int valid[kVecPerThread];
 #pragma unroll
             for (int j = 0; j < kVecPerThread; ++j) {
                 const int64_t v = base + (int64_t)j * kHistThreads + threadIdx.x;
-                valid[j] = 0;
-                if (v < nvec) valid[j] = load_vec<T, SLIMFIT_PG_NT != 0>(x, n, v, bits[j]);
+                valid[j] = load_tile_vec<T, INSIDE, SLIMFIT_PG_NT != 0>(x, n, nvec, v, bits[j]);
             }
 #pragma unroll
             for (int j = 0; j < kVecPerThread; ++j)
@@ -251,12 +280,17 @@ hist_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, ui
             for (int j = 0; j < kVecPerThread; ++j) {
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) {
-                    if (e < valid[j]) {
+                    if (INSIDE || e < valid[j]) {
                         const uint32_t key = make_key<T, MAG>(bits[j][e]);
-                        if ((key & mask) == prefix) atomicAdd(&bins[(key >> shift) & digit_mask], 1u);
+                        // the first digit counts every key: no prefix to match, no branch around the ds_add
+                        if (FIRST || (key & mask) == prefix) atomicAdd(&bins[(key >> shift) & digit_mask], 1u);
                     }
                 }
             }
+        };
+        for (int64_t base = (int64_t)blockIdx.x * chunk; base < nvec; base += (int64_t)gridDim.x * chunk) {
+            if (base + chunk <= nfull) sweep(std::true_type{}, base);      // workgroup-uniform
+            else sweep(std::false_type{}, base);
         }
     }
     __syncthreads();
@@ -341,9 +375,9 @@ __device__ __forceinline__ int64_t tile_vec(int64_t tile, int wave, int j, int l
 
 // ---- list route: per tile, keys above the chosen bin; the bin's own keys go to the tile's list ----
 // Leaves tile_cnt[tile] = (keys above the bin, keys filed).
-template <typename T, bool MAG, bool STD>
-__global__ void __launch_bounds__(kTileThreads)
-bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict__ tile_cnt, uint32_t *__restrict__ lists, Std sd)
+template <typename T, bool MAG, bool STD, bool INSIDE>
+__device__ __forceinline__ void
+bracket_tile(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict__ tile_cnt, uint32_t *__restrict__ lists, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr uint32_t kSlot = kTileThreads * kVecPerThread * EPV / kListShare;
@@ -359,8 +393,7 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
-        valid[j] = 0;
-        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+        valid[j] = load_tile_vec<T, INSIDE>(x, n, nvec, v, bits[j]);
     }
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) standardise<T, STD>(bits[j], valid[j], tile_vec(blockIdx.x, wave, j, lane), sd);
@@ -369,7 +402,7 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
     for (int j = 0; j < kVecPerThread; ++j) {
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            if (e < valid[j]) {
+            if (INSIDE || e < valid[j]) {
                 const uint32_t top = make_key<T, MAG>(bits[j][e]) & mask;
                 gt += top > prefix ? 1u : 0u;
                 in_bin += top == prefix ? 1u : 0u;
@@ -392,7 +425,7 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
         for (int j = 0; j < kVecPerThread; ++j) {
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                if (e < valid[j]) {
+                if (INSIDE || e < valid[j]) {
                     const uint32_t key = make_key<T, MAG>(bits[j][e]);
                     if ((key & mask) == prefix) {
                         if (slot < kSlot) keys[slot] = key;
@@ -412,12 +445,24 @@ bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict_
     }
 }
 
+template <typename T, bool MAG, bool STD>
+__global__ void __launch_bounds__(kTileThreads)
+bracket_kernel(const T *__restrict__ x, int64_t n, State *st, u32x2 *__restrict__ tile_cnt, uint32_t *__restrict__ lists, Std sd)
+{
+    // workgroup-uniform: the whole tile lies below n
+    constexpr int64_t kTileElems = (int64_t)kTileThreads * kVecPerThread * Elem<T>::EPV;
+    if (((int64_t)blockIdx.x + 1) * kTileElems <= n)
+        bracket_tile<T, MAG, STD, true>(x, n, st, tile_cnt, lists, sd);
+    else
+        bracket_tile<T, MAG, STD, false>(x, n, st, tile_cnt, lists, sd);
+}
+
 // ---- per tile: keys above T, keys equal to T -------------------------------------------
 // plain route: from the tensor; list route: the list's keys are added to the
 // counts that bracket_kernel left.
-template <typename T, bool MAG, bool STD>
-__global__ void __launch_bounds__(kTileThreads)
-count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u32x2 *__restrict__ tile_cnt,
+template <typename T, bool MAG, bool STD, bool INSIDE>
+__device__ __forceinline__ void
+count_tile(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u32x2 *__restrict__ tile_cnt,
              const uint32_t *__restrict__ lists, int64_t ntiles, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
@@ -454,8 +499,7 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
-        valid[j] = 0;
-        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+        valid[j] = load_tile_vec<T, INSIDE>(x, n, nvec, v, bits[j]);
     }
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) standardise<T, STD>(bits[j], valid[j], tile_vec(blockIdx.x, wave, j, lane), sd);
@@ -464,7 +508,7 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
     for (int j = 0; j < kVecPerThread; ++j) {
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            if (e < valid[j]) {
+            if (INSIDE || e < valid[j]) {
                 const uint32_t key = make_key<T, MAG>(bits[j][e]);
                 gt += key > Tk ? 1u : 0u;
                 eq += key == Tk ? 1u : 0u;
@@ -486,6 +530,19 @@ count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u
         }
         tile_cnt[blockIdx.x] = c;
     }
+}
+
+template <typename T, bool MAG, bool STD>
+__global__ void __launch_bounds__(kTileThreads)
+count_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, u32x2 *__restrict__ tile_cnt,
+             const uint32_t *__restrict__ lists, int64_t ntiles, Std sd)
+{
+    // workgroup-uniform: the whole tile lies below n
+    constexpr int64_t kTileElems = (int64_t)kTileThreads * kVecPerThread * Elem<T>::EPV;
+    if (((int64_t)blockIdx.x + 1) * kTileElems <= n)
+        count_tile<T, MAG, STD, true>(x, n, st, tile_cnt, lists, ntiles, sd);
+    else
+        count_tile<T, MAG, STD, false>(x, n, st, tile_cnt, lists, ntiles, sd);
 }
 
 // ---- tile counts -> first output slot and tie budget of every tile ----------------------
@@ -578,9 +635,9 @@ template <> __device__ __forceinline__ void store_raw<float>(float *p, uint32_t 
 template <> __device__ __forceinline__ void store_raw<uint16_t>(uint16_t *p, uint32_t bits) { *p = (uint16_t)bits; }
 
 // ---- emit the survivors of a tile in ascending index order ------------------------------
-template <typename T, bool MAG, bool STD>
-__global__ void __launch_bounds__(kTileThreads)
-write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
+template <typename T, bool MAG, bool STD, bool INSIDE>
+__device__ __forceinline__ void
+write_tile(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
              T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k, Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
@@ -599,8 +656,7 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t v = tile_vec(blockIdx.x, wave, j, lane);
-        valid[j] = 0;
-        if (v < nvec) valid[j] = load_vec<T>(x, n, v, bits[j]);
+        valid[j] = load_tile_vec<T, INSIDE>(x, n, nvec, v, bits[j]);
     }
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) standardise<T, STD>(bits[j], valid[j], tile_vec(blockIdx.x, wave, j, lane), sd);
@@ -611,7 +667,7 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
         uint32_t gt = 0u, eq = 0u;
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            if (e < valid[j]) {
+            if (INSIDE || e < valid[j]) {
                 const uint32_t key = make_key<T, MAG>(bits[j][e]);
                 gt += key > Tk ? 1u : 0u;
                 eq += key == Tk ? 1u : 0u;
@@ -655,7 +711,7 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
         }
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            if (e < valid[j]) {
+            if (INSIDE || e < valid[j]) {
                 const uint32_t key = make_key<T, MAG>(bits[j][e]);
                 const bool above = key > Tk;
                 const bool tie = key == Tk;
@@ -674,6 +730,19 @@ write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, c
         run_gt += group & 0xFFFFu;
         run_eq += group >> 16;
     }
+}
+
+template <typename T, bool MAG, bool STD>
+__global__ void __launch_bounds__(kTileThreads)
+write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
+             T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k, Std sd)
+{
+    // workgroup-uniform: the whole tile lies below n
+    constexpr int64_t kTileElems = (int64_t)kTileThreads * kVecPerThread * Elem<T>::EPV;
+    if (((int64_t)blockIdx.x + 1) * kTileElems <= n)
+        write_tile<T, MAG, STD, true>(x, n, st, tile_base, vals, idx, tile_ptr, k, sd);
+    else
+        write_tile<T, MAG, STD, false>(x, n, st, tile_base, vals, idx, tile_ptr, k, sd);
 }
 
 // ---- restore without tile pointers: zeros, then scatter -----------------------------------
@@ -819,8 +888,12 @@ void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int
         const int bits = Digits<T>::bits[d];
         const int shift = hi - bits;
         const bool first = d == 0, last = d == Digits<T>::N - 1;
-        hist_kernel<T, MAG, STD><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists, ntiles,
-                                                                   shift, 1 << bits, sd);
+        if (first)
+            hist_kernel<T, MAG, STD, true><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists,
+                                                                             ntiles, shift, 1 << bits, sd);
+        else
+            hist_kernel<T, MAG, STD, false><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists,
+                                                                              ntiles, shift, 1 << bits, sd);
         select_kernel<<<1, kSelectThreads, 0, s>>>(w.st, w.hist, shift, 1 << bits, first ? 1 : 0, last ? 1 : 0,
                                                    w.route_cap);
         if (first && !last)
