@@ -49,7 +49,7 @@ def lib():
                          "prune_scores", "restore_scores", "ils_select",
                          "ils_update", "freeze_count", "keep_count",
                          "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune",
-                         "layernorm_forward", "standardize", "layernorm_backward_pruned",
+                         "layernorm_forward", "standardize", "layernorm_backward_pruned", "layernorm_param_grads",
                          "splitmix64", "schedule_random", "schedule_progressive"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
         return _lib
@@ -247,6 +247,22 @@ def layernorm_backward_pruned(vals, idx, rstd, gamma, dy):
                                                      _ptr(gamma), _ptr(dy), C.c_int64(rows), C.c_int(H), _ptr(dx))
     _check(rc, "layernorm_backward_pruned")
     return dx
+
+
+def layernorm_param_grads(x, mean, rstd, dy):
+    """(dgamma, dbeta) of an active LayerNorm from x, the fp32 row statistics and dy; fp64 sums."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    dy = np.ascontiguousarray(dy, dtype=np.float32)
+    rows, H = x.shape
+    mean = np.ascontiguousarray(mean, dtype=np.float32)
+    rstd = np.ascontiguousarray(rstd, dtype=np.float32)
+    assert dy.shape == x.shape and mean.size == rows and rstd.size == rows
+    dgamma = np.empty(H, dtype=np.float32)
+    dbeta = np.empty(H, dtype=np.float32)
+    rc = lib().slimfit_ref_layernorm_param_grads(_ptr(x), _ptr(mean), _ptr(rstd), _ptr(dy), C.c_int64(rows), C.c_int(H),
+                                                 _ptr(dgamma), _ptr(dbeta))
+    _check(rc, "layernorm_param_grads")
+    return dgamma, dbeta
 
 
 def gelu(x):

@@ -710,6 +710,28 @@ int slimfit_ref_layernorm_backward_pruned(const float *vals, const int32_t *idx,
     return REF_OK;
 }
 
+/* Parameter gradients of an active LayerNorm (Sec. 4):  gamma^ = sum over rows of  */
+/* x~ * y^,  beta^ = sum over rows of y^,  with x~ = (x - mean_r) * rstd_r from the   */
+/* given fp32 statistics, everything else in fp64, rounded once to fp32.               */
+int slimfit_ref_layernorm_param_grads(const float *x, const float *mean, const float *rstd,
+                                      const float *dy, int64_t rows, int H,
+                                      float *dgamma, float *dbeta)
+{
+    if (rows < 0 || H < 1 || !dgamma || !dbeta || (rows > 0 && (!x || !mean || !rstd || !dy)))
+        return REF_BAD;
+    for (int j = 0; j < H; ++j) {
+        double sg = 0.0, sb = 0.0;
+        for (int64_t r = 0; r < rows; ++r) {
+            const double xt = ((double)x[r * (int64_t)H + j] - (double)mean[r]) * (double)rstd[r];
+            sg += xt * (double)dy[r * (int64_t)H + j];
+            sb += (double)dy[r * (int64_t)H + j];
+        }
+        dgamma[j] = (float)sg;
+        dbeta[j] = (float)sb;
+    }
+    return REF_OK;
+}
+
 /* ------------------------------------------------------------------ */
 /* Alg. 1 -- inter-layer scheduling on the host                         */
 /*   idx = argsort(d)[:int(L*F)]  -> those layers are frozen            */

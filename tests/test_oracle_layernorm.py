@@ -87,6 +87,24 @@ def test_pruned_backward_is_the_formula_on_the_restored_tensor():
     np.testing.assert_allclose(none.astype(np.float64), H * g - g.sum(1, keepdims=True), rtol=1e-6, atol=1e-7)
 
 
+@pytest.mark.parametrize("rows,H", [(1, 8), (50, 64), (33, 768)])
+def test_parameter_gradients_are_the_derivative_of_layer_norm(rows, H):
+    x, gamma, beta, dy = _case(rows + 2 * H, rows, H)
+    gt = torch.from_numpy(gamma).double().requires_grad_(True)
+    bt = torch.from_numpy(beta).double().requires_grad_(True)
+    out = torch.nn.functional.layer_norm(torch.from_numpy(x).double(), (H,), gt, bt, eps=1e-5)
+    out.backward(torch.from_numpy(dy).double())
+    _, mean, rstd = ref.layernorm_forward(x, gamma, beta, eps=1e-5)
+    dg, db = ref.layernorm_param_grads(x, mean, rstd, dy)
+    scale = np.abs(dy.astype(np.float64)).sum(0).max() * 4
+    np.testing.assert_allclose(dg.astype(np.float64), gt.grad.numpy(), rtol=0, atol=1e-6 * scale)
+    np.testing.assert_allclose(db.astype(np.float64), bt.grad.numpy(), rtol=1e-6, atol=1e-6 * scale)
+    # column sums written out in NumPy float64 from the same fp32 statistics
+    xt = (x.astype(np.float64) - mean.astype(np.float64)[:, None]) * rstd.astype(np.float64)[:, None]
+    np.testing.assert_allclose(dg, (xt * dy).sum(0), rtol=2e-7, atol=1e-30)
+    np.testing.assert_allclose(db, dy.astype(np.float64).sum(0), rtol=2e-7, atol=1e-30)
+
+
 def test_bad_arguments_rejected():
     with pytest.raises(ValueError):
         ref.layernorm_backward_pruned(np.ones(1, np.float32), np.array([99], np.int32), np.ones(2, np.float32),
