@@ -331,6 +331,19 @@ int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, 
                                           void *vals, int32_t *idx, int32_t *tile_ptr, int32_t *row_ptr,
                                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* Parameter gradients of an active (not frozen) LayerNorm, Sec. 4:
+ *   gamma^_j = sum over rows of x~_rj * y^_rj,   beta^_j = sum over rows of y^_rj,
+ * x~ = (x - mean[r]) * rstd[r] from the statistics slimfit_layernorm_forward returned.
+ * fp32 products and slab sums (64 rows), fp64 across slabs, fixed order (no atomics):
+ * within 4e-6 * sum_r |x~ * y^| (resp. |y^|) of the fp64 value.
+ * dgamma, dbeta : DEVICE float[H].  workspace: DEVICE, 16-byte aligned, at least
+ * slimfit_layernorm_param_grads_workspace(rows, H) bytes; contents overwritten. */
+int32_t slimfit_layernorm_param_grads_workspace(int64_t rows, int64_t H, size_t *bytes);
+
+int32_t slimfit_layernorm_param_grads(const float *x, const float *mean, const float *rstd, const float *dy,
+                                      int64_t rows, int64_t H, float *dgamma, float *dbeta,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *row_ptr, int64_t k,
                                           const float *rstd, const float *gamma, const float *dy,
                                           int64_t rows, int64_t H, float *dx, void *stream);

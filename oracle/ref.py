@@ -49,7 +49,7 @@ def lib():
                          "prune_scores", "restore_scores", "ils_select",
                          "ils_update", "freeze_count", "keep_count",
                          "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune",
-                         "layernorm_forward", "standardize", "layernorm_backward_pruned", "layernorm_param_grads",
+                         "layernorm_forward", "standardize", "layernorm_backward_pruned", "layernorm_param_grads", "layernorm_backward",
                          "splitmix64", "schedule_random", "schedule_progressive"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
         return _lib
@@ -246,6 +246,22 @@ def layernorm_backward_pruned(vals, idx, rstd, gamma, dy):
     rc = lib().slimfit_ref_layernorm_backward_pruned(_ptr(vals), _ptr(idx), C.c_int64(vals.size), _ptr(rstd),
                                                      _ptr(gamma), _ptr(dy), C.c_int64(rows), C.c_int(H), _ptr(dx))
     _check(rc, "layernorm_backward_pruned")
+    return dx
+
+
+def layernorm_backward(x, mean, rstd, gamma, dy):
+    """Input gradient of an active LayerNorm from x, the fp32 row statistics, gamma and dy; fp64."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    dy = np.ascontiguousarray(dy, dtype=np.float32)
+    rows, H = x.shape
+    mean = np.ascontiguousarray(mean, dtype=np.float32)
+    rstd = np.ascontiguousarray(rstd, dtype=np.float32)
+    gamma = np.ascontiguousarray(gamma, dtype=np.float32)
+    assert dy.shape == x.shape and mean.size == rows and rstd.size == rows and gamma.size == H
+    dx = np.empty_like(x)
+    rc = lib().slimfit_ref_layernorm_backward(_ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(dy), C.c_int64(rows),
+                                              C.c_int(H), _ptr(dx))
+    _check(rc, "layernorm_backward")
     return dx
 
 

@@ -710,6 +710,32 @@ int slimfit_ref_layernorm_backward_pruned(const float *vals, const int32_t *idx,
     return REF_OK;
 }
 
+/* Input gradient of an active LayerNorm: the same formula with every x~ present,  */
+/* x~ = (x - mean_r) * rstd_r from the given fp32 statistics, evaluated in fp64.     */
+int slimfit_ref_layernorm_backward(const float *x, const float *mean, const float *rstd,
+                                   const float *gamma, const float *dy, int64_t rows, int H,
+                                   float *dx)
+{
+    if (rows < 0 || H < 1 || (rows > 0 && (!x || !mean || !rstd || !gamma || !dy || !dx)))
+        return REF_BAD;
+    for (int64_t r = 0; r < rows; ++r) {
+        const int64_t base = r * (int64_t)H;
+        double sum_g = 0.0, sum_gx = 0.0;
+        for (int j = 0; j < H; ++j) {
+            const double xt = ((double)x[base + j] - (double)mean[r]) * (double)rstd[r];
+            const double g = (double)gamma[j] * (double)dy[base + j] * (double)rstd[r] / (double)H;
+            sum_g += g;
+            sum_gx += g * xt;
+        }
+        for (int j = 0; j < H; ++j) {
+            const double xt = ((double)x[base + j] - (double)mean[r]) * (double)rstd[r];
+            const double g = (double)gamma[j] * (double)dy[base + j] * (double)rstd[r] / (double)H;
+            dx[base + j] = (float)((double)H * g - sum_g - xt * sum_gx);
+        }
+    }
+    return REF_OK;
+}
+
 /* Parameter gradients of an active LayerNorm (Sec. 4):  gamma^ = sum over rows of  */
 /* x~ * y^,  beta^ = sum over rows of y^,  with x~ = (x - mean_r) * rstd_r from the   */
 /* given fp32 statistics, everything else in fp64, rounded once to fp32.               */

@@ -35,7 +35,8 @@ EXPORTS = (
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
-    "slimfit_layernorm_backward_pruned", "slimfit_freeze_count", "slimfit_ils_select",
+    "slimfit_layernorm_backward_pruned", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
+    "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update", "slimfit_schedule_random", "slimfit_schedule_progressive",
 )
 
@@ -346,6 +347,25 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
         C.c_int32(int(bool(by_magnitude))), _dev(vals), _dev(idx), _dev(tile_ptr), _dev(row_ptr), _dev(workspace),
         C.c_size_t(workspace.numel()), _stream(stream))
     _check(rc, "prune_global_standardized")
+
+
+def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, dy: torch.Tensor,
+                          dgamma: torch.Tensor, dbeta: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                          stream=None) -> None:
+    """gamma^ and beta^ of an active LayerNorm: column sums over the rows of ``x`` / ``dy`` (rows, H)."""
+    assert x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dy.shape == x.shape
+    assert all(t.dtype == torch.float32 for t in (x, mean, rstd, dy, dgamma, dbeta))
+    rows, H = x.shape
+    assert mean.numel() >= rows and rstd.numel() >= rows and dgamma.numel() == H and dbeta.numel() == H
+    need = C.c_size_t(0)
+    _check(lib().slimfit_layernorm_param_grads_workspace(C.c_int64(rows), C.c_int64(H), C.byref(need)),
+           "layernorm_param_grads_workspace")
+    if workspace is None:
+        workspace = torch.empty(int(need.value), dtype=torch.uint8, device=x.device)
+    rc = lib().slimfit_layernorm_param_grads(
+        _dev(x), _dev(mean), _dev(rstd), _dev(dy), C.c_int64(rows), C.c_int64(H), _dev(dgamma), _dev(dbeta),
+        _dev(workspace), C.c_size_t(workspace.numel()), _stream(stream))
+    _check(rc, "layernorm_param_grads")
 
 
 def layernorm_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, row_ptr: torch.Tensor, k: int,

@@ -4,6 +4,8 @@
 //                                     statistics (mean, 1/sqrt(Var + eps)) that
 //                                     let the whole-tensor pruner form x~ on the
 //                                     fly instead of reading a stored copy;
+//   param_grad_*_kernel               gamma^ and beta^ of an active LayerNorm
+//                                     (column sums over all rows, two stages);
 //   layernorm_backward_pruned_kernel  the input gradient of a frozen LayerNorm,
 //                                     x^ = H g - sum g - x~ sum(g x~),
 //                                     g = gamma y^ / (H sqrt(Var + eps)), with
@@ -203,6 +205,85 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
     }
 }
 
+// ---- parameter gradients of an active LayerNorm: column sums over all rows --------------
+// gamma^_j = sum_r x~_rj * y^_rj,  beta^_j = sum_r y^_rj.  A workgroup owns a slab of
+// kSlabRows consecutive rows; thread t walks down the slab holding the 16-byte column
+// vectors t, t+256, ... (a wave reads 1 KiB of a row at a time), accumulates in fp32 and
+// writes one partial per slab and column; the second kernel adds the slabs' partials in
+// fp64 in slab order.  No atomics: the result does not depend on scheduling.
+constexpr int kSlabRows = 64;
+constexpr int kColVecs = 4;                 // column vectors per thread: H <= 256 * 4 * 4
+
+__global__ void __launch_bounds__(kThreads)
+param_grad_partials_kernel(const float *__restrict__ x, const float *__restrict__ mean, const float *__restrict__ rstd,
+                           const float *__restrict__ dy, int64_t rows, int H, float *__restrict__ partials)
+{
+    const int nvec = H / 4;
+    const int64_t r0 = (int64_t)blockIdx.x * kSlabRows;
+    const int n_rows = (int)min((int64_t)kSlabRows, rows - r0);
+    f32x4 sg[kColVecs], sb[kColVecs];
+#pragma unroll
+    for (int c = 0; c < kColVecs; ++c) sg[c] = sb[c] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int i = 0; i < n_rows; ++i) {                         // workgroup-uniform
+        const int64_t r = r0 + i;
+        const float mu = mean[r], rs = rstd[r];                // uniform: scalar loads
+        const f32x4 *xr = reinterpret_cast<const f32x4 *>(x + r * (int64_t)H);
+        const f32x4 *gr = reinterpret_cast<const f32x4 *>(dy + r * (int64_t)H);
+#pragma unroll
+        for (int c = 0; c < kColVecs; ++c) {
+            const int q = c * kThreads + threadIdx.x;
+            if (q < nvec) {
+                const f32x4 xv = __builtin_nontemporal_load(xr + q);
+                const f32x4 gv = __builtin_nontemporal_load(gr + q);
+                sg[c].x += ((xv.x - mu) * rs) * gv.x;
+                sg[c].y += ((xv.y - mu) * rs) * gv.y;
+                sg[c].z += ((xv.z - mu) * rs) * gv.z;
+                sg[c].w += ((xv.w - mu) * rs) * gv.w;
+                sb[c].x += gv.x;
+                sb[c].y += gv.y;
+                sb[c].z += gv.z;
+                sb[c].w += gv.w;
+            }
+        }
+    }
+    // partials: [slab][2][H]
+    f32x4 *out_g = reinterpret_cast<f32x4 *>(partials + (int64_t)blockIdx.x * 2 * H);
+    f32x4 *out_b = reinterpret_cast<f32x4 *>(partials + (int64_t)blockIdx.x * 2 * H + H);
+#pragma unroll
+    for (int c = 0; c < kColVecs; ++c) {
+        const int q = c * kThreads + threadIdx.x;
+        if (q < nvec) {
+            out_g[q] = sg[c];
+            out_b[q] = sb[c];
+        }
+    }
+}
+
+// 32 columns (of the 2H outputs: gamma^ then beta^) per workgroup; the 8 groups of 32 threads take every
+// eighth slab each and their fp64 sums are added in group order.
+constexpr int kFinishCols = 32;
+constexpr int kFinishGroups = kThreads / kFinishCols;
+__global__ void __launch_bounds__(kThreads)
+param_grad_finish_kernel(const float *__restrict__ partials, int64_t slabs, int H, float *__restrict__ dgamma,
+                         float *__restrict__ dbeta)
+{
+    __shared__ double part[kFinishGroups][kFinishCols];
+    const int c = threadIdx.x % kFinishCols, grp = threadIdx.x / kFinishCols;
+    const int col = blockIdx.x * kFinishCols + c;               // 0 .. 2H-1; 2H is a multiple of 8, not always of 32
+    double acc = 0.0;
+    if (col < 2 * H)
+        for (int64_t s = grp; s < slabs; s += kFinishGroups) acc += (double)partials[s * 2 * H + col];
+    part[grp][c] = acc;
+    __syncthreads();
+    if (grp == 0 && col < 2 * H) {
+        double total = 0.0;
+#pragma unroll
+        for (int g = 0; g < kFinishGroups; ++g) total += part[g][c];
+        if (col < H) dgamma[col] = (float)total;
+        else dbeta[col - H] = (float)total;
+    }
+}
+
 int32_t validate(int64_t rows, int64_t H)
 {
     if (rows < 0 || H < 4 || H % 4 != 0) return SLIMFIT_ERR_INVALID_ARG;
@@ -282,5 +363,48 @@ extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const in
     const size_t lds_bytes = (size_t)kWaves * (size_t)H * 4;              // at most 64 KB
     SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_pruned_kernel<NV><<<grid, kThreads, lds_bytes, s>>>(
                                              vals, idx, row_ptr, k, rstd, gamma, dy, rows, (int)H, dx)));
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_layernorm_param_grads_workspace(int64_t rows, int64_t H, size_t *bytes)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if (!bytes) return SLIMFIT_ERR_INVALID_ARG;
+    const int64_t slabs = (rows + kSlabRows - 1) / kSlabRows;
+    *bytes = (size_t)(slabs > 0 ? slabs : 1) * 2 * (size_t)H * 4;
+    return SLIMFIT_OK;
+}
+
+extern "C" int32_t slimfit_layernorm_param_grads(const float *x, const float *mean, const float *rstd, const float *dy,
+                                                 int64_t rows, int64_t H, float *dgamma, float *dbeta, void *workspace,
+                                                 size_t workspace_bytes, void *stream)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if (!dgamma || !dbeta || !workspace || (rows > 0 && (!x || !mean || !rstd || !dy))) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(dgamma, 4) || !aligned_to(dbeta, 4) || !aligned_to(workspace, 16) ||
+        (rows > 0 && (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(mean, 4) || !aligned_to(rstd, 4))))
+        return SLIMFIT_ERR_ALIGNMENT;
+    size_t need = 0;
+    slimfit_layernorm_param_grads_workspace(rows, H, &need);
+    if (workspace_bytes < need) return SLIMFIT_ERR_WORKSPACE;
+    if ((rc = check_device_range(dgamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dbeta, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(workspace, need)) != SLIMFIT_OK) return rc;
+    if (rows > 0) {
+        const size_t nbytes = (size_t)rows * (size_t)H * 4;
+        if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
+        if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
+        if ((rc = check_device_range(mean, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+        if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t slabs = (rows + kSlabRows - 1) / kSlabRows;
+    float *partials = static_cast<float *>(workspace);
+    if (slabs > 0)
+        param_grad_partials_kernel<<<(unsigned)slabs, kThreads, 0, s>>>(x, mean, rstd, dy, rows, (int)H, partials);
+    const unsigned fgrid = (unsigned)((2 * H + kFinishCols - 1) / kFinishCols);
+    param_grad_finish_kernel<<<fgrid, kThreads, 0, s>>>(partials, slabs, (int)H, dgamma, dbeta);
     return launch_status();
 }

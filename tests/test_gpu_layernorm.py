@@ -106,6 +106,25 @@ def test_forward_prune_backward_chain(rows, H):
     _prune_both(x, mean, rstd, max(1, n // 10), by_mag=False)
 
 
+@pytest.mark.parametrize("rows,H", [(1, 4), (63, 64), (64, 252), (65, 768), (1000, 1024), (130, 4096), (257, 20)])
+def test_parameter_gradients(rows, H):
+    require_gpu()
+    x, gamma, beta, dy = _inputs(rows * 3 + H, rows, H)
+    xh, dyh = to_np(x), to_np(dy)
+    _, om, orr = ref.layernorm_forward(xh, to_np(gamma), to_np(beta), eps=1e-5, threads=4)
+    mean, rstd = torch.from_numpy(om).cuda(), torch.from_numpy(orr).cuda()
+    dg, db = Guarded(H, torch.float32), Guarded(H, torch.float32)
+    sf.layernorm_param_grads(x, mean, rstd, dy, dg.t, db.t)
+    torch.cuda.synchronize()
+    dg.check(); db.check()
+    wg, wb = ref.layernorm_param_grads(xh, om, orr, dyh)
+    xt = (xh.astype(np.float64) - om.astype(np.float64)[:, None]) * orr.astype(np.float64)[:, None]
+    tol_g = 4e-6 * np.abs(xt * dyh).sum(0) + 1e-30
+    tol_b = 4e-6 * np.abs(dyh.astype(np.float64)).sum(0) + 1e-30
+    assert np.all(np.abs(to_np(dg.t).astype(np.float64) - wg) <= tol_g)
+    assert np.all(np.abs(to_np(db.t).astype(np.float64) - wb) <= tol_b)
+
+
 def test_prune_with_arbitrary_statistics_and_ties():
     """The selection only depends on the two fp32 operations, whatever the statistics are."""
     require_gpu()

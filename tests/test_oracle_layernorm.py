@@ -87,6 +87,24 @@ def test_pruned_backward_is_the_formula_on_the_restored_tensor():
     np.testing.assert_allclose(none.astype(np.float64), H * g - g.sum(1, keepdims=True), rtol=1e-6, atol=1e-7)
 
 
+@pytest.mark.parametrize("rows,H", [(1, 8), (4, 64), (3, 768), (2, 1024)])
+def test_dense_backward_is_the_derivative_of_layer_norm(rows, H):
+    x, gamma, beta, dy = _case(rows * 5 + H, rows, H)
+    xt = torch.from_numpy(x).double().requires_grad_(True)
+    out = torch.nn.functional.layer_norm(xt, (H,), torch.from_numpy(gamma).double(), torch.from_numpy(beta).double(),
+                                         eps=1e-5)
+    out.backward(torch.from_numpy(dy).double())
+    want = xt.grad.numpy()
+    _, mean, rstd = ref.layernorm_forward(x, gamma, beta, eps=1e-5)
+    dx = ref.layernorm_backward(x, mean, rstd, gamma, dy)
+    np.testing.assert_allclose(dx.astype(np.float64), want, rtol=0, atol=2e-6 * np.abs(want).max())
+    # and it agrees with the pair form when every x~ is handed over
+    xs = ((x.astype(np.float64) - mean.astype(np.float64)[:, None]) * rstd.astype(np.float64)[:, None])
+    full = ref.layernorm_backward_pruned(xs.reshape(-1).astype(np.float32), np.arange(rows * H, dtype=np.int32), rstd,
+                                         gamma, dy)
+    np.testing.assert_allclose(dx, full, rtol=0, atol=1e-6 * np.abs(want).max())
+
+
 @pytest.mark.parametrize("rows,H", [(1, 8), (50, 64), (33, 768)])
 def test_parameter_gradients_are_the_derivative_of_layer_norm(rows, H):
     x, gamma, beta, dy = _case(rows + 2 * H, rows, H)
