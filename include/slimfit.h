@@ -331,6 +331,12 @@ int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, 
                                           void *vals, int32_t *idx, int32_t *tile_ptr, int32_t *row_ptr,
                                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* Input gradient of an active (not frozen) LayerNorm, Sec. 4: the formula above with every
+ * x~ present, x~ = (x - mean[r]) * rstd[r] from the statistics slimfit_layernorm_forward
+ * returned; same tolerance as slimfit_layernorm_backward_pruned.  dx must be neither x nor dy. */
+int32_t slimfit_layernorm_backward(const float *x, const float *mean, const float *rstd, const float *gamma,
+                                   const float *dy, int64_t rows, int64_t H, float *dx, void *stream);
+
 /* Parameter gradients of an active (not frozen) LayerNorm, Sec. 4:
  *   gamma^_j = sum over rows of x~_rj * y^_rj,   beta^_j = sum over rows of y^_rj,
  * x~ = (x - mean[r]) * rstd[r] from the statistics slimfit_layernorm_forward returned.

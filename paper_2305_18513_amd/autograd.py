@@ -11,9 +11,7 @@ computes; the dense matrix products of the linear layer are torch's.
                      tensor with int32 indices, row pointers and rstd; backward
                      is the paper's input-gradient formula on those pairs, and
                      gamma / beta get no gradient.  Active: caches x exactly
-                     and returns all three gradients (gamma^ and beta^ from the
-                     library's column-sum kernels, the dense input gradient from
-                     torch ops).
+                     and returns all three gradients.
   LinearFunction     Alg. 4: an active layer caches its input in `bits` bits and
                      computes grad_weight from the dequantised input; a frozen
                      layer caches nothing but the weight and returns
@@ -95,10 +93,8 @@ class LayerNormFunction(torch.autograd.Function):
         x2, mean, rstd, gamma = ctx.saved_tensors
         dgamma, dbeta = torch.empty_like(gamma), torch.empty_like(gamma)
         sf.layernorm_param_grads(x2, mean, rstd, dy, dgamma, dbeta)
-        # the exact input gradient of an active layer: the formula of the frozen case with every x~ present
-        xt = (x2 - mean[:, None]) * rstd[:, None]
-        g = dy * gamma * (rstd[:, None] / H)
-        dx = H * g - g.sum(1, keepdim=True) - xt * (g * xt).sum(1, keepdim=True)
+        dx = torch.empty_like(dy)
+        sf.layernorm_backward(x2, mean, rstd, gamma, dy, dx)
         return dx.view(grad_output.shape), dgamma, dbeta, None, None, None
 
 

@@ -35,7 +35,7 @@ EXPORTS = (
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
-    "slimfit_layernorm_backward_pruned", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
+    "slimfit_layernorm_backward_pruned", "slimfit_layernorm_backward", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
     "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update", "slimfit_schedule_random", "slimfit_schedule_progressive",
 )
@@ -347,6 +347,19 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
         C.c_int32(int(bool(by_magnitude))), _dev(vals), _dev(idx), _dev(tile_ptr), _dev(row_ptr), _dev(workspace),
         C.c_size_t(workspace.numel()), _stream(stream))
     _check(rc, "prune_global_standardized")
+
+
+def layernorm_backward(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, gamma: torch.Tensor,
+                       dy: torch.Tensor, dx: torch.Tensor, stream=None) -> None:
+    """Input gradient of an active LayerNorm (every standardised input present)."""
+    assert x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dx.is_contiguous()
+    assert dy.shape == x.shape and dx.shape == x.shape
+    assert all(t.dtype == torch.float32 for t in (x, mean, rstd, gamma, dy, dx))
+    rows, H = x.shape
+    assert mean.numel() >= rows and rstd.numel() >= rows and gamma.numel() == H
+    rc = lib().slimfit_layernorm_backward(_dev(x), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
+                                          C.c_int64(H), _dev(dx), _stream(stream))
+    _check(rc, "layernorm_backward")
 
 
 def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, dy: torch.Tensor,

@@ -4,6 +4,9 @@
 //                                     statistics (mean, 1/sqrt(Var + eps)) that
 //                                     let the whole-tensor pruner form x~ on the
 //                                     fly instead of reading a stored copy;
+//   layernorm_backward_kernel         the input gradient of an active LayerNorm
+//                                     (the same formula with every x~ present,
+//                                     formed from x and the row statistics);
 //   param_grad_*_kernel               gamma^ and beta^ of an active LayerNorm
 //                                     (column sums over all rows, two stages);
 //   layernorm_backward_pruned_kernel  the input gradient of a frozen LayerNorm,
@@ -202,6 +205,56 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
         if (q < nvec) __builtin_nontemporal_store(reinterpret_cast<const f32x4 *>(buf)[q], dst + q);
+    }
+}
+
+// ---- input gradient of an active LayerNorm: the row formula with every x~ present ----------
+template <int NV>
+__global__ void __launch_bounds__(kThreads)
+layernorm_backward_kernel(const float *__restrict__ x, const float *__restrict__ mean, const float *__restrict__ rstd,
+                          const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
+                          float *__restrict__ dx)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int nvec = H / 4;
+    f32x4 xt[NV], g[NV], ga[NV];
+    load_row<NV>(x + r * (int64_t)H, nvec, lane, xt, true);
+    load_row<NV>(dy + r * (int64_t)H, nvec, lane, g, true);
+    load_row<NV>(gamma, nvec, lane, ga, false);
+    const float mu = mean[r], rs = rstd[r];
+    const float scale = rs / (float)H;
+    float part_g = 0.0f, part_gx = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const bool in = i * kWave + lane < nvec;                 // padding vectors hold zeros: x~ must be 0 there too
+        xt[i].x = in ? (xt[i].x - mu) * rs : 0.0f;
+        xt[i].y = in ? (xt[i].y - mu) * rs : 0.0f;
+        xt[i].z = in ? (xt[i].z - mu) * rs : 0.0f;
+        xt[i].w = in ? (xt[i].w - mu) * rs : 0.0f;
+        g[i].x = (ga[i].x * g[i].x) * scale;
+        g[i].y = (ga[i].y * g[i].y) * scale;
+        g[i].z = (ga[i].z * g[i].z) * scale;
+        g[i].w = (ga[i].w * g[i].w) * scale;
+        part_g += (g[i].x + g[i].y) + (g[i].z + g[i].w);
+        part_gx += (g[i].x * xt[i].x + g[i].y * xt[i].y) + (g[i].z * xt[i].z + g[i].w * xt[i].w);
+    }
+    const float sum_g = wave_sum_f32(part_g);
+    const float sum_gx = wave_sum_f32(part_gx);
+    const float fH = (float)H;
+    f32x4 *dst = reinterpret_cast<f32x4 *>(dx + r * (int64_t)H);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        if (q < nvec) {
+            f32x4 o;
+            o.x = (fH * g[i].x - sum_g) - xt[i].x * sum_gx;
+            o.y = (fH * g[i].y - sum_g) - xt[i].y * sum_gx;
+            o.z = (fH * g[i].z - sum_g) - xt[i].z * sum_gx;
+            o.w = (fH * g[i].w - sum_g) - xt[i].w * sum_gx;
+            __builtin_nontemporal_store(o, dst + q);
+        }
     }
 }
 
@@ -406,5 +459,29 @@ extern "C" int32_t slimfit_layernorm_param_grads(const float *x, const float *me
         param_grad_partials_kernel<<<(unsigned)slabs, kThreads, 0, s>>>(x, mean, rstd, dy, rows, (int)H, partials);
     const unsigned fgrid = (unsigned)((2 * H + kFinishCols - 1) / kFinishCols);
     param_grad_finish_kernel<<<fgrid, kThreads, 0, s>>>(partials, slabs, (int)H, dgamma, dbeta);
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_layernorm_backward(const float *x, const float *mean, const float *rstd, const float *gamma,
+                                              const float *dy, int64_t rows, int64_t H, float *dx, void *stream)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if (rows == 0) return SLIMFIT_OK;
+    if (!x || !mean || !rstd || !gamma || !dy || !dx || dx == x || dx == dy) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16) || !aligned_to(gamma, 16) ||
+        !aligned_to(mean, 4) || !aligned_to(rstd, 4))
+        return SLIMFIT_ERR_ALIGNMENT;
+    const size_t nbytes = (size_t)rows * (size_t)H * 4;
+    if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dx, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(mean, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
+    SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_kernel<NV><<<grid, kThreads, 0, s>>>(
+                                             x, mean, rstd, gamma, dy, rows, (int)H, dx)));
     return launch_status();
 }

@@ -107,7 +107,7 @@ def test_forward_prune_backward_chain(rows, H):
 
 
 @pytest.mark.parametrize("rows,H", [(1, 4), (63, 64), (64, 252), (65, 768), (1000, 1024), (130, 4096), (257, 20)])
-def test_parameter_gradients(rows, H):
+def test_active_layer_gradients(rows, H):
     require_gpu()
     x, gamma, beta, dy = _inputs(rows * 3 + H, rows, H)
     xh, dyh = to_np(x), to_np(dy)
@@ -117,6 +117,16 @@ def test_parameter_gradients(rows, H):
     sf.layernorm_param_grads(x, mean, rstd, dy, dg.t, db.t)
     torch.cuda.synchronize()
     dg.check(); db.check()
+    dx = Guarded(rows * H, torch.float32)
+    sf.layernorm_backward(x, mean, rstd, gamma, dy, dx.t.view(rows, H))
+    torch.cuda.synchronize()
+    dx.check()
+    want = ref.layernorm_backward(xh, om, orr, to_np(gamma), dyh).astype(np.float64)
+    xt64 = (xh.astype(np.float64) - om.astype(np.float64)[:, None]) * orr.astype(np.float64)[:, None]
+    g64 = to_np(gamma).astype(np.float64) * dyh.astype(np.float64) * orr.astype(np.float64)[:, None] / H
+    tol = 4e-6 * (H * np.abs(g64) + np.abs(g64).sum(1, keepdims=True) + np.abs(xt64) * np.abs(g64 * xt64).sum(1, keepdims=True)) + 1e-30
+    got = to_np(dx.t).reshape(rows, H).astype(np.float64)
+    assert np.all(np.abs(got - want) <= tol), "dense dx: worst ratio %.3g" % float((np.abs(got - want) / tol).max())
     wg, wb = ref.layernorm_param_grads(xh, om, orr, dyh)
     xt = (xh.astype(np.float64) - om.astype(np.float64)[:, None]) * orr.astype(np.float64)[:, None]
     tol_g = 4e-6 * np.abs(xt * dyh).sum(0) + 1e-30
