@@ -340,7 +340,7 @@ int32_t slimfit_layernorm_backward(const float *x, const float *mean, const floa
 /* Parameter gradients of an active (not frozen) LayerNorm, Sec. 4:
  *   gamma^_j = sum over rows of x~_rj * y^_rj,   beta^_j = sum over rows of y^_rj,
  * x~ = (x - mean[r]) * rstd[r] from the statistics slimfit_layernorm_forward returned.
- * fp32 products and slab sums (64 rows), fp64 across slabs, fixed order (no atomics):
+ * fp32 products and slab sums (256 rows, four interleaved quarters), fp64 across slabs, fixed order (no atomics):
  * within 4e-6 * sum_r |x~ * y^| (resp. |y^|) of the fp64 value.
  * dgamma, dbeta : DEVICE float[H].  workspace: DEVICE, 16-byte aligned, at least
  * slimfit_layernorm_param_grads_workspace(rows, H) bytes; contents overwritten. */
