@@ -412,6 +412,42 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
+
+    # what a plain device copy of 1 GiB reaches on this machine (read + write bytes), for scale
+    csrc = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    cdst = torch.empty_like(csrc)
+    for _ in range(3):
+        cdst.copy_(csrc)
+    torch.cuda.synchronize()
+    cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for a, b in cev:
+        a.record()
+        cdst.copy_(csrc)
+        b.record()
+    torch.cuda.synchronize()
+    copy_ms = sorted(a.elapsed_time(b) for a, b in cev)[len(cev) // 2]
+    copy_gbs = 2 * csrc.numel() * 4 / (copy_ms * 1e-3) / 1e9
+    del csrc, cdst
+
+    # host side of the step alone: ils_update + ils_select over the L scores
+    lat = []
+    probe_d, probe_new = d_vec.copy(), d_host_pinned.numpy().copy()
+    for _ in range(50):
+        th = time.perf_counter()
+        sf.ils_update(probe_d, probe_new, mask)
+        sf.ils_select(probe_d, n_freeze)
+        lat.append((time.perf_counter() - th) * 1e6)
+    host_ils_us = sorted(lat)[len(lat) // 2]
+
+    def checksum(t):
+        """sum of the tensor's 32-bit words modulo 2^32 (identifies the generated input)"""
+        w = t.contiguous().view(-1).view(torch.uint8)
+        w = w[: w.numel() // 4 * 4].view(torch.int32)
+        return int(w.sum(dtype=torch.int64).item()) & 0xFFFFFFFF
+
+    input_checksum = {"gelu_in": checksum(sets[0].gelu), "ln_in": checksum(sets[0].ln[0]),
+                      "scores": checksum(sets[0].scores), "w_prev[0]": checksum(prev[0])}
 
     ms_per_step = wall * 1e3 / args.steps
     value = step_bytes / (wall / args.steps) / 1e9
@@ -431,7 +467,8 @@ def main() -> int:
     roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"],
                 "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index, {}).get(dom),
-                "algorithmic_bytes": kernels[dom]["bytes_per_launch"], "avg_ms": kernels[dom]["avg_ms"]}
+                "algorithmic_bytes": kernels[dom]["bytes_per_launch"], "avg_ms": kernels[dom]["avg_ms"],
+                "measured_copy_GBps": round(copy_gbs, 1), "frac_of_measured_copy": round(kernels[dom]["GBps"] / copy_gbs, 4)}
 
     out = {
         "metric": "activation-compression + freeze-score GB/s per fine-tune step; % of HBM peak",
@@ -444,7 +481,8 @@ def main() -> int:
                    "quant": "%d-bit block-%d" % (bits, block), "keep_k": cfg.keep_k, "score_cols": cfg.score_cols,
                    "prune_mode": "threshold" if cfg.threshold_variant else "topk",
                    "layers_scored": L, "n_freeze": n_freeze, "step_bytes": step_bytes,
-                   "buffer_sets": n_sets},
+                   "buffer_sets": n_sets, "input_checksum": input_checksum},
+        "host_ils_us": round(host_ils_us, 1),
         "roofline": roofline,
         "kernels": kernels,
         "extras": extras,
@@ -489,8 +527,19 @@ def cpu_baseline(cfg, bits, block, mode, tau, sets, prev, cur):
     nbytes += sum(p.size for p in hp) * (esize(cfg.w_dtype) + 4)
     ref.ils_select(d, ref.freeze_count(d.size, cfg.freeze_rate))
     dt = time.perf_counter() - t0
+    # the same oracle on one thread, on a slice it finishes in a few seconds: 1/16 of the first block's rows
+    a0 = acts[0][0][: acts[0][0].size // 16 // block * block]
+    s0 = scores[0][: scores[0].shape[0] // 16]
+    t1 = time.perf_counter()
+    c1, sc1 = ref.quant_pack(a0, mode=ref.Q_BLOCK, bits=bits, block=block, threads=1)
+    ref.dequant_unpack(c1, sc1, a0.size, mode=ref.Q_BLOCK, bits=bits, block=block, out_dtype=a0.dtype, threads=1)
+    ref.prune_scores(s0, cfg.keep_k, mode=mode, tau=tau, threads=1)
+    dt1 = time.perf_counter() - t1
+    nb1 = 2 * quant_bytes(a0.size, in_sz, bits, block) + prune_bytes(s0.shape[0], s0.shape[1], cfg.keep_k, in_sz)
     return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "seconds": round(dt, 2), "bytes": nbytes,
+            "single_thread": {"value": round(nb1 / dt1 / 1e9, 3), "unit": "GB/s", "seconds": round(dt1, 2),
+                              "sample": "quant + dequant of 1/16 of one GELU input and prune of 1/16 of one score tensor"},
             "sample": "%d of the %d encoder blocks at full batch (quant x3, prune, dequant x3 each) plus "
                       "layer_delta over all %d weight tensors and one ils_select; OpenMP over independent "
                       "blocks/rows/layers" % (n_blocks, cfg.n_blocks, len(hp))}
