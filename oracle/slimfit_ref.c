@@ -24,12 +24,17 @@
  * repeat-argmax selector and a library stable argsort for the pruner (row-wise
  * and whole-tensor forms); textbook values, the reflection identity, a library
  * normal CDF and numerical differentiation for GELU and its derivative; a
- * library layer norm and its automatic derivative (fp64) for LayerNorm and the
- * paper's input-gradient formula.
+ * library layer norm and its automatic derivative (fp64) for LayerNorm, the
+ * paper's input-gradient formula and the parameter gradients; a library
+ * softmax and brute force on the exact probabilities for the fused softmax +
+ * pruning; the generator's published known answers, big-integer arithmetic
+ * and a chi-square test for the random freezing schedule.
  * Parity unpinned by the paper (it prints no worked numbers for them): the
  * per-block-scale mode, the 4-bit split of integer/fraction bits, the
- * threshold pruning mode and bf16 I/O.  Those are pinned by brute force and
- * invariants only.
+ * threshold pruning mode, bf16 I/O, and everything beyond its Fig. 4 example
+ * (the paper prints formulas, not values, for GELU, Softmax, LayerNorm and
+ * Alg. 5).  Those are pinned by brute force, closed forms, library routines
+ * and invariants only.
  */
 #include <math.h>
 #include <stdint.h>
