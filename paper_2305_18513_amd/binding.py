@@ -47,6 +47,12 @@ class SlimfitError(RuntimeError):
         super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
 
 
+def _require(ok: bool) -> None:
+    """Shape / dtype agreement of the tensors handed to a wrapper (the C side checks sizes and pointers)."""
+    if not ok:
+        raise ValueError("tensor arguments do not agree in shape or dtype with what the call expects")
+
+
 _lib = None
 
 
@@ -142,10 +148,10 @@ def _ptr_array(tensors: Sequence[torch.Tensor]):
 def layer_delta_plan(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor],
                      workspace: torch.Tensor, stream=None) -> None:
     L = len(w_prev)
-    assert len(w_cur) == L
+    _require(len(w_cur) == L)
     numel = _numel_array([t.numel() for t in w_prev])
     for a, b in zip(w_prev, w_cur):
-        assert a.numel() == b.numel()
+        _require(a.numel() == b.numel())
     pdt = _dt(w_prev[0]) if L else F32
     cdt = _dt(w_cur[0]) if L else F32
     rc = lib().slimfit_layer_delta_plan(
@@ -158,7 +164,7 @@ def layer_delta_plan(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tenso
 def layer_delta_run(numel: Sequence[int], prev_dt: int, cur_dt: int, cur_is_delta: bool,
                     eps: float, d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
     n = _numel_array(numel)
-    assert d_out.dtype == torch.float32 and d_out.numel() >= n.size
+    _require(d_out.dtype == torch.float32 and d_out.numel() >= n.size)
     rc = lib().slimfit_layer_delta_run(
         C.c_void_p(n.ctypes.data), C.c_int32(n.size), C.c_int32(prev_dt), C.c_int32(cur_dt),
         C.c_int32(int(bool(cur_is_delta))), C.c_float(eps), _dev(d_out), _dev(workspace),
@@ -169,11 +175,11 @@ def layer_delta_run(numel: Sequence[int], prev_dt: int, cur_dt: int, cur_is_delt
 def layer_delta(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor], cur_is_delta: bool,
                 eps: float, d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
     L = len(w_prev)
-    assert len(w_cur) == L
+    _require(len(w_cur) == L)
     numel = _numel_array([t.numel() for t in w_prev])
     pdt = _dt(w_prev[0]) if L else F32
     cdt = _dt(w_cur[0]) if L else F32
-    assert d_out.dtype == torch.float32 and d_out.numel() >= L
+    _require(d_out.dtype == torch.float32 and d_out.numel() >= L)
     rc = lib().slimfit_layer_delta(
         _ptr_array(w_prev), C.c_int32(pdt), _ptr_array(w_cur), C.c_int32(cdt),
         C.c_int32(int(bool(cur_is_delta))), C.c_void_p(numel.ctypes.data), C.c_int32(L),
@@ -194,7 +200,7 @@ def num_blocks(n: int, block: int) -> int:
 
 def quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int,
                codes: torch.Tensor, scales: Optional[torch.Tensor], stream=None) -> None:
-    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
     rc = lib().slimfit_quant_pack(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(x.numel()), C.c_int32(mode), C.c_int32(bits),
         C.c_int32(block), C.c_int32(frac_bits), _dev(codes), _dev(scales), _stream(stream))
@@ -203,7 +209,7 @@ def quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int
 
 def dequant_unpack(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: int, bits: int,
                    block: int, frac_bits: int, y: torch.Tensor, stream=None) -> None:
-    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
     rc = lib().slimfit_dequant_unpack(
         _dev(codes), _dev(scales), C.c_int64(y.numel()), C.c_int32(mode), C.c_int32(bits),
         C.c_int32(block), C.c_int32(frac_bits), _dev(y), C.c_int32(_dt(y)), _stream(stream))
@@ -215,8 +221,8 @@ def dequant_unpack(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: in
 def gelu_quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int, y: torch.Tensor,
                     codes: torch.Tensor, scales: Optional[torch.Tensor], stream=None) -> None:
     """y = GELU(x) and (codes, scales) = quant_pack(x) in one pass over x."""
-    assert x.is_contiguous() and y.is_contiguous() and y.dtype == x.dtype and y.numel() == x.numel()
-    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    _require(x.is_contiguous() and y.is_contiguous() and y.dtype == x.dtype and y.numel() == x.numel())
+    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
     rc = lib().slimfit_gelu_quant_pack(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(x.numel()), C.c_int32(mode), C.c_int32(bits), C.c_int32(block),
         C.c_int32(frac_bits), _dev(y), _dev(codes), _dev(scales), _stream(stream))
@@ -226,8 +232,8 @@ def gelu_quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits
 def gelu_backward_dequant(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: int, bits: int, block: int,
                           frac_bits: int, dy: torch.Tensor, dx: torch.Tensor, stream=None) -> None:
     """dx = dy * GELU'(dequantised cache); the dequantised values stay in registers."""
-    assert dy.is_contiguous() and dx.is_contiguous() and dx.dtype == dy.dtype and dx.numel() == dy.numel()
-    assert codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32)
+    _require(dy.is_contiguous() and dx.is_contiguous() and dx.dtype == dy.dtype and dx.numel() == dy.numel())
+    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
     rc = lib().slimfit_gelu_backward_dequant(
         _dev(codes), _dev(scales), C.c_int64(dx.numel()), C.c_int32(mode), C.c_int32(bits), C.c_int32(block),
         C.c_int32(frac_bits), _dev(dy), _dev(dx), C.c_int32(_dt(dx)), _stream(stream))
@@ -242,8 +248,8 @@ def keep_count(cols: int, keep_ppm: int) -> int:
 
 def prune_scores(p: torch.Tensor, k: int, mode: int, tau: float, vals: torch.Tensor,
                  idx: torch.Tensor, counts: Optional[torch.Tensor], stream=None) -> None:
-    assert p.dim() == 2 and vals.dtype == p.dtype and idx.dtype == torch.uint16
-    assert counts is None or counts.dtype == torch.int32
+    _require(p.dim() == 2 and vals.dtype == p.dtype and idx.dtype == torch.uint16)
+    _require(counts is None or counts.dtype == torch.int32)
     rows, cols = p.shape
     rc = lib().slimfit_prune_scores(
         _dev(p), C.c_int32(_dt(p)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
@@ -253,7 +259,7 @@ def prune_scores(p: torch.Tensor, k: int, mode: int, tau: float, vals: torch.Ten
 
 def restore_scores(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch.Tensor],
                    out: torch.Tensor, stream=None) -> None:
-    assert out.dim() == 2 and vals.dtype == out.dtype and idx.dtype == torch.uint16
+    _require(out.dim() == 2 and vals.dtype == out.dtype and idx.dtype == torch.uint16)
     rows, cols = out.shape
     k = vals.shape[1]
     rc = lib().slimfit_restore_scores(
@@ -265,9 +271,9 @@ def restore_scores(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch
 def softmax_prune(logits: torch.Tensor, k: int, probs: torch.Tensor, vals: torch.Tensor, idx: torch.Tensor,
                   stream=None) -> None:
     """probs = softmax(logits) per row; (vals, idx) = the k largest of every row (decided on the logits)."""
-    assert logits.dim() == 2 and logits.is_contiguous() and probs.is_contiguous()
-    assert probs.shape == logits.shape and probs.dtype == logits.dtype
-    assert vals.dtype == logits.dtype and idx.dtype == torch.uint16
+    _require(logits.dim() == 2 and logits.is_contiguous() and probs.is_contiguous())
+    _require(probs.shape == logits.shape and probs.dtype == logits.dtype)
+    _require(vals.dtype == logits.dtype and idx.dtype == torch.uint16)
     rows, cols = logits.shape
     rc = lib().slimfit_softmax_prune(
         _dev(logits), C.c_int32(_dt(logits)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
@@ -293,10 +299,10 @@ def prune_global(x: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor,
                  tile_ptr: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                  stream=None) -> None:
     """Keeps the k largest entries of the flattened ``x``; ``workspace`` is a uint8 device tensor."""
-    assert x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32
-    assert vals.numel() >= k and idx.numel() >= k
+    _require(x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32)
+    _require(vals.numel() >= k and idx.numel() >= k)
     n = x.numel()
-    assert tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n))
+    _require(tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n)))
     if workspace is None:
         workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
     rc = lib().slimfit_prune_global(
@@ -307,8 +313,8 @@ def prune_global(x: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor,
 
 def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Tensor,
                    tile_ptr: Optional[torch.Tensor] = None, stream=None) -> None:
-    assert out.is_contiguous() and vals.dtype == out.dtype and idx.dtype == torch.int32
-    assert tile_ptr is None or tile_ptr.dtype == torch.int32
+    _require(out.is_contiguous() and vals.dtype == out.dtype and idx.dtype == torch.int32)
+    _require(tile_ptr is None or tile_ptr.dtype == torch.int32)
     rc = lib().slimfit_restore_global(
         _dev(vals), _dev(idx), _dev(tile_ptr), C.c_int64(k), C.c_int32(_dt(out)), C.c_int64(out.numel()),
         _dev(out), _stream(stream))
@@ -319,10 +325,10 @@ def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Ten
 
 def layernorm_forward(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float, y: torch.Tensor,
                       mean: torch.Tensor, rstd: torch.Tensor, stream=None) -> None:
-    assert x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape
-    assert all(t.dtype == torch.float32 for t in (x, gamma, beta, y, mean, rstd))
+    _require(x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape)
+    _require(all(t.dtype == torch.float32 for t in (x, gamma, beta, y, mean, rstd)))
     rows, H = x.shape
-    assert gamma.numel() == H and beta.numel() == H and mean.numel() >= rows and rstd.numel() >= rows
+    _require(gamma.numel() == H and beta.numel() == H and mean.numel() >= rows and rstd.numel() >= rows)
     rc = lib().slimfit_layernorm_forward(_dev(x), _dev(gamma), _dev(beta), C.c_int64(rows), C.c_int64(H),
                                          C.c_float(eps), _dev(y), _dev(mean), _dev(rstd), _stream(stream))
     _check(rc, "layernorm_forward")
@@ -333,13 +339,13 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
                               row_ptr: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                               stream=None) -> None:
     """prune_global of the standardised rows of ``x`` (rows, H), formed on the fly from mean / rstd."""
-    assert x.dim() == 2 and x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32
-    assert mean.dtype == torch.float32 and rstd.dtype == torch.float32
+    _require(x.dim() == 2 and x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32)
+    _require(mean.dtype == torch.float32 and rstd.dtype == torch.float32)
     rows, H = x.shape
     n = x.numel()
-    assert mean.numel() >= rows and rstd.numel() >= rows and vals.numel() >= k and idx.numel() >= k
-    assert tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n))
-    assert row_ptr is None or (row_ptr.dtype == torch.int32 and row_ptr.numel() >= rows + 1)
+    _require(mean.numel() >= rows and rstd.numel() >= rows and vals.numel() >= k and idx.numel() >= k)
+    _require(tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n)))
+    _require(row_ptr is None or (row_ptr.dtype == torch.int32 and row_ptr.numel() >= rows + 1))
     if workspace is None:
         workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
     rc = lib().slimfit_prune_global_standardized(
@@ -352,11 +358,11 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
 def layernorm_backward(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, gamma: torch.Tensor,
                        dy: torch.Tensor, dx: torch.Tensor, stream=None) -> None:
     """Input gradient of an active LayerNorm (every standardised input present)."""
-    assert x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dx.is_contiguous()
-    assert dy.shape == x.shape and dx.shape == x.shape
-    assert all(t.dtype == torch.float32 for t in (x, mean, rstd, gamma, dy, dx))
+    _require(x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dx.is_contiguous())
+    _require(dy.shape == x.shape and dx.shape == x.shape)
+    _require(all(t.dtype == torch.float32 for t in (x, mean, rstd, gamma, dy, dx)))
     rows, H = x.shape
-    assert mean.numel() >= rows and rstd.numel() >= rows and gamma.numel() == H
+    _require(mean.numel() >= rows and rstd.numel() >= rows and gamma.numel() == H)
     rc = lib().slimfit_layernorm_backward(_dev(x), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
                                           C.c_int64(H), _dev(dx), _stream(stream))
     _check(rc, "layernorm_backward")
@@ -366,10 +372,10 @@ def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tenso
                           dgamma: torch.Tensor, dbeta: torch.Tensor, workspace: Optional[torch.Tensor] = None,
                           stream=None) -> None:
     """gamma^ and beta^ of an active LayerNorm: column sums over the rows of ``x`` / ``dy`` (rows, H)."""
-    assert x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dy.shape == x.shape
-    assert all(t.dtype == torch.float32 for t in (x, mean, rstd, dy, dgamma, dbeta))
+    _require(x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dy.shape == x.shape)
+    _require(all(t.dtype == torch.float32 for t in (x, mean, rstd, dy, dgamma, dbeta)))
     rows, H = x.shape
-    assert mean.numel() >= rows and rstd.numel() >= rows and dgamma.numel() == H and dbeta.numel() == H
+    _require(mean.numel() >= rows and rstd.numel() >= rows and dgamma.numel() == H and dbeta.numel() == H)
     need = C.c_size_t(0)
     _check(lib().slimfit_layernorm_param_grads_workspace(C.c_int64(rows), C.c_int64(H), C.byref(need)),
            "layernorm_param_grads_workspace")
@@ -384,11 +390,11 @@ def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tenso
 def layernorm_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, row_ptr: torch.Tensor, k: int,
                               rstd: torch.Tensor, gamma: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
                               stream=None) -> None:
-    assert dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape
-    assert all(t.dtype == torch.float32 for t in (vals, rstd, gamma, dy, dx))
-    assert idx.dtype == torch.int32 and row_ptr.dtype == torch.int32
+    _require(dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape)
+    _require(all(t.dtype == torch.float32 for t in (vals, rstd, gamma, dy, dx)))
+    _require(idx.dtype == torch.int32 and row_ptr.dtype == torch.int32)
     rows, H = dy.shape
-    assert row_ptr.numel() >= rows + 1
+    _require(row_ptr.numel() >= rows + 1)
     rc = lib().slimfit_layernorm_backward_pruned(
         _dev(vals), _dev(idx), _dev(row_ptr), C.c_int64(k), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
         C.c_int64(H), _dev(dx), _stream(stream))
@@ -414,10 +420,10 @@ def ils_select(d: np.ndarray, n_freeze: int):
 
 def ils_update(d: np.ndarray, new_scores: np.ndarray, frozen_mask: np.ndarray) -> np.ndarray:
     """In place on ``d`` (float32, contiguous); returns it."""
-    assert d.dtype == np.float32 and d.flags.c_contiguous
+    _require(d.dtype == np.float32 and d.flags.c_contiguous)
     new_scores = np.ascontiguousarray(new_scores, dtype=np.float32)
     frozen_mask = np.ascontiguousarray(frozen_mask, dtype=np.uint8)
-    assert d.size == new_scores.size == frozen_mask.size
+    _require(d.size == new_scores.size == frozen_mask.size)
     rc = lib().slimfit_ils_update(C.c_void_p(d.ctypes.data), C.c_void_p(new_scores.ctypes.data),
                                   C.c_void_p(frozen_mask.ctypes.data), C.c_int32(d.size))
     _check(rc, "ils_update")

@@ -150,7 +150,8 @@ def activation(cfg: WorkloadConfig, kind: str, device="cpu", block: int = 0,
     0.001.  "student_t": a seeded 1 % of the channels (last dimension) is
     drawn from Student-t with 3 degrees of freedom instead.
     """
-    assert kind in ("gelu_in", "ln_in")
+    if kind not in ("gelu_in", "ln_in"):
+        raise ValueError("kind must be gelu_in or ln_in")
     b = cfg.batch if batch is None else batch
     width = cfg.ffn if kind == "gelu_in" else cfg.hidden
     g = _gen(cfg, kind, block, device)
