@@ -48,7 +48,7 @@ def lib():
             for name in ("layer_delta", "quant_pack", "dequant_unpack",
                          "prune_scores", "restore_scores", "ils_select",
                          "ils_update", "freeze_count", "keep_count",
-                         "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune",
+                         "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune", "softmax_backward_pruned",
                          "layernorm_forward", "standardize", "layernorm_backward_pruned", "layernorm_param_grads", "layernorm_backward",
                          "splitmix64", "schedule_random", "schedule_progressive"):
                 getattr(_lib, "slimfit_ref_" + name).restype = C.c_int
@@ -279,6 +279,24 @@ def layernorm_param_grads(x, mean, rstd, dy):
                                                  _ptr(dgamma), _ptr(dbeta))
     _check(rc, "layernorm_param_grads")
     return dgamma, dbeta
+
+
+def softmax_backward_pruned(vals, idx, counts, dp, threads=1):
+    """Softmax backward from the kept (value, column) pairs of every row; dp is (rows, cols).  Dense result."""
+    dp = np.ascontiguousarray(dp)
+    rows, cols = dp.shape
+    vals = np.ascontiguousarray(vals)
+    idx = np.ascontiguousarray(idx, dtype=np.uint16)
+    k = vals.shape[1]
+    assert vals.shape == (rows, k) and idx.shape == (rows, k) and vals.dtype == dp.dtype
+    if counts is not None:
+        counts = np.ascontiguousarray(counts, dtype=np.int32)
+    ds = np.empty_like(dp)
+    rc = lib().slimfit_ref_softmax_backward_pruned(_ptr(vals), _ptr(idx), _ptr(counts), _ptr(dp), C.c_int(_dt(dp)),
+                                                   C.c_int64(rows), C.c_int(cols), C.c_int(k), _ptr(ds),
+                                                   C.c_int(threads))
+    _check(rc, "softmax_backward_pruned")
+    return ds
 
 
 def gelu(x):

@@ -27,7 +27,8 @@
  * library layer norm and its automatic derivative (fp64) for LayerNorm, the
  * paper's input-gradient formula and the parameter gradients; a library
  * softmax and brute force on the exact probabilities for the fused softmax +
- * pruning; the generator's published known answers, big-integer arithmetic
+ * pruning, the automatic derivative of a library softmax for its backward
+ * pass; the generator's published known answers, big-integer arithmetic
  * and a chi-square test for the random freezing schedule.
  * Parity unpinned by the paper (it prints no worked numbers for them): the
  * per-block-scale mode, the 4-bit split of integer/fraction bits, the
@@ -534,6 +535,45 @@ int slimfit_ref_softmax_prune(const void *logits, int dt, int64_t rows, int cols
         free(kept);
     }
     return bad ? REF_BAD : REF_OK;
+}
+
+/* Backward pass of Softmax from the pruned probabilities: with p^ the row that  */
+/* Alg. 5's restoring process rebuilds (the kept p_j, zeros elsewhere) and dp the */
+/* gradient with respect to the probabilities,                                    */
+/*     ds_j = p^_j * (dp_j - sum_i p^_i dp_i),                                     */
+/* the derivative of softmax with p^ in place of p; it is zero wherever p^ is.    */
+/* counts may be NULL (k pairs per row); an index 0xFFFF marks an unused slot.    */
+/* fp64 on the widened inputs, rounded once to dt.                                */
+int slimfit_ref_softmax_backward_pruned(const void *vals, const uint16_t *idx, const int32_t *counts,
+                                        const void *dp, int dt, int64_t rows, int cols, int k,
+                                        void *ds, int threads)
+{
+    if (!dtype_ok(dt) || rows < 0 || cols < 1 || cols > 65536 || k < 1 || k > cols)
+        return REF_BAD;
+    if (rows > 0 && (!vals || !idx || !dp || !ds))
+        return REF_BAD;
+    (void)threads;
+#pragma omp parallel for num_threads(threads > 1 ? threads : 1) schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const int cnt = counts ? counts[r] : k;
+        double dot = 0.0;
+        for (int s = 0; s < cnt && s < k; ++s) {
+            const int c = idx[r * (int64_t)k + s];
+            if (c < cols)
+                dot += (double)load_elem(vals, dt, r * (int64_t)k + s) * (double)load_elem(dp, dt, r * (int64_t)cols + c);
+        }
+        for (int c = 0; c < cols; ++c)
+            store_elem(ds, dt, r * (int64_t)cols + c, 0.0f);
+        for (int s = 0; s < cnt && s < k; ++s) {
+            const int c = idx[r * (int64_t)k + s];
+            if (c < cols) {
+                const double v = (double)load_elem(vals, dt, r * (int64_t)k + s);
+                store_elem(ds, dt, r * (int64_t)cols + c,
+                           (float)(v * ((double)load_elem(dp, dt, r * (int64_t)cols + c) - dot)));
+            }
+        }
+    }
+    return REF_OK;
 }
 
 /* ------------------------------------------------------------------ */

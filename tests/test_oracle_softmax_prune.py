@@ -65,6 +65,42 @@ def test_large_logits_do_not_overflow_and_bf16_rounds_once():
     np.testing.assert_array_equal(vb, np.take_along_axis(pb, ib.astype(np.int64), axis=1))
 
 
+def test_backward_with_everything_kept_is_the_derivative_of_softmax():
+    import torch
+    rows, cols = 7, 53
+    l = _rows(11, rows, cols, 2.0)
+    dp = _rows(12, rows, cols)
+    lt = torch.from_numpy(l).double().requires_grad_(True)
+    torch.softmax(lt, dim=1).backward(torch.from_numpy(dp).double())
+    p, vals, idx = ref.softmax_prune(l, cols)                      # nothing pruned
+    ds = ref.softmax_backward_pruned(vals, idx, None, dp)
+    np.testing.assert_allclose(ds.astype(np.float64), lt.grad.numpy(), rtol=0, atol=3e-7 * np.abs(lt.grad.numpy()).max())
+
+
+def test_backward_is_the_formula_on_the_restored_rows():
+    rows, cols, k = 40, 197, 9
+    l = _rows(13, rows, cols, 2.0)
+    dp = _rows(14, rows, cols)
+    _, vals, idx = ref.softmax_prune(l, k)
+    ds = ref.softmax_backward_pruned(vals, idx, None, dp)
+    dense = ref.restore_scores(vals, idx, None, cols).astype(np.float64)
+    want = dense * (dp.astype(np.float64) - (dense * dp).sum(1, keepdims=True))
+    np.testing.assert_allclose(ds.astype(np.float64), want, rtol=2e-7, atol=1e-30)
+    assert np.all((ds != 0) <= (dense != 0))                        # zero wherever nothing was kept
+    # counts and unused slots (threshold mode leaves value 0 / index 0xFFFF)
+    counts = np.full(rows, k, np.int32)
+    counts[::3] = 4
+    v2, i2 = vals.copy(), idx.copy()
+    v2[::3, 4:] = 0
+    i2[::3, 4:] = 0xFFFF
+    a = ref.softmax_backward_pruned(v2, i2, counts, dp)
+    b = ref.softmax_backward_pruned(v2, i2, None, dp)              # the sentinel alone also skips them
+    np.testing.assert_array_equal(a, b)
+    dense2 = ref.restore_scores(v2, i2, counts, cols).astype(np.float64)
+    np.testing.assert_allclose(a.astype(np.float64), dense2 * (dp - (dense2 * dp).sum(1, keepdims=True)), rtol=2e-7,
+                               atol=1e-30)
+
+
 def test_bad_arguments_rejected():
     l = np.zeros((2, 4), np.float32)
     for k in (0, 5):
