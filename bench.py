@@ -349,6 +349,12 @@ def main() -> int:
                 sets[i].codes[0], sets[i].scales[0], sf.Q_BLOCK, bits, block, 0, sets[i].gelu, sets[i].deq[0])),
             "softmax_prune[scores as logits]": (nb_s, lambda i: sf.softmax_prune(
                 sets[i].scores, cfg.keep_k, probs[i], sets[i].vals, sets[i].idx)),
+            # consumes the pairs the line above left; the score tensor stands in for the incoming gradient
+            # (only its kept columns are read: k elements per row are the algorithmic bytes, although at
+            # 10 % kept nearly every 128-byte line of it is touched)
+            "softmax_backward_pruned[scores]": (
+                rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (2 * in_sz + 2),
+                lambda i: sf.softmax_backward_pruned(sets[i].vals, sets[i].idx, None, sets[i].scores, probs[i])),
         }
         for name, (nb, fn) in fused.items():
             for i in range(len(sets)):

@@ -246,6 +246,32 @@ int32_t slimfit_softmax_prune(const void *logits, int32_t dt, int64_t rows, int3
                               void *probs, void *vals, uint16_t *idx, void *stream);
 
 /* ------------------------------------------------------------------------
+ * (c-back) Backward pass of Softmax straight from the pruned probabilities -- the
+ *     consumer of the pairs that (c) and (c'') emit (Sec. 4 caches Softmax's
+ *     output for its backward pass; Alg. 5's restoring process rebuilds it as
+ *     p^ = zeros + scatter).  With p^ in place of p in the derivative of Softmax,
+ *
+ *         ds_j = p^_j * (dp_j - sum_i p^_i dp_i),
+ *
+ *     which is zero wherever nothing was kept; the dense p^ is never written.
+ *     fp32 arithmetic: the sum runs over a row's pairs in a fixed order (lane
+ *     partials, then the wave), ds_j within
+ *     |p^_j| * ((8 + k/64) * 6e-8 * sum_i |p^_i dp_i| + 1.2e-7 * |dp_j|) + 6e-8 * |ds_j|
+ *     of the exact value; bf16 results within one further bf16 rounding.
+ *
+ *  vals, idx, counts : DEVICE, as (c) wrote them (counts may be NULL: k pairs per
+ *                      row; an index >= cols marks an unused slot).
+ *  dp                : DEVICE, rows*cols elements of dt, the gradient w.r.t. the
+ *                      probabilities; only the kept columns are read.
+ *  ds                : DEVICE, rows*cols elements of dt, 16-byte aligned, not dp;
+ *                      every element is written once.
+ *  1 <= k <= cols <= 65536.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_softmax_backward_pruned(const void *vals, const uint16_t *idx, const int32_t *counts,
+                                        const void *dp, int32_t dt, int64_t rows, int32_t cols, int32_t k,
+                                        void *ds, void *stream);
+
+/* ------------------------------------------------------------------------
  * (c') Alg. 5 on a whole flattened tensor -- the form the paper applies to the
  *     standardised input of LayerNorm: sort all n entries from largest to
  *     smallest with their indices, keep the first k = int(n * 0.1), store the

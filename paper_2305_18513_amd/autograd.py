@@ -12,6 +12,10 @@ computes; the dense matrix products of the linear layer are torch's.
                      is the paper's input-gradient formula on those pairs, and
                      gamma / beta get no gradient.  Active: caches x exactly
                      and returns all three gradients.
+  SoftmaxFunction    p = softmax(logits) over the last dimension (at most 1024
+                     wide); caches the `keep_ppm` largest probabilities of every
+                     row with uint16 columns; backward is the derivative of
+                     softmax with the restored (sparse) row in place of p.
   LinearFunction     Alg. 4: an active layer caches its input in `bits` bits and
                      computes grad_weight from the dequantised input; a frozen
                      layer caches nothing but the weight and returns
@@ -96,6 +100,30 @@ class LayerNormFunction(torch.autograd.Function):
         dx = torch.empty_like(dy)
         sf.layernorm_backward(x2, mean, rstd, gamma, dy, dx)
         return dx.view(grad_output.shape), dgamma, dbeta, None, None, None
+
+
+class SoftmaxFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, logits: torch.Tensor, keep_ppm: int = 100000):
+        cols = logits.shape[-1]
+        l2 = logits.contiguous().view(-1, cols)
+        rows = l2.shape[0]
+        k = max(1, sf.keep_count(cols, keep_ppm))
+        probs = torch.empty_like(l2)
+        vals = torch.empty(rows, k, dtype=l2.dtype, device=l2.device)
+        idx = torch.empty(rows, k, dtype=torch.uint16, device=l2.device)
+        sf.softmax_prune(l2, k, probs, vals, idx)
+        ctx.save_for_backward(vals, idx)
+        return probs.view(logits.shape)
+
+    @staticmethod
+    def backward(ctx, grad_output: torch.Tensor):
+        vals, idx = ctx.saved_tensors
+        cols = grad_output.shape[-1]
+        dp = grad_output.contiguous().view(-1, cols)
+        ds = torch.empty_like(dp)
+        sf.softmax_backward_pruned(vals, idx, None, dp, ds)
+        return ds.view(grad_output.shape), None
 
 
 class LinearFunction(torch.autograd.Function):

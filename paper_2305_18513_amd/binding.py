@@ -33,7 +33,7 @@ EXPORTS = (
     "slimfit_layer_delta_run", "slimfit_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
-    "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
+    "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_softmax_backward_pruned", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
     "slimfit_layernorm_backward_pruned", "slimfit_layernorm_backward", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
     "slimfit_freeze_count", "slimfit_ils_select",
@@ -279,6 +279,20 @@ def softmax_prune(logits: torch.Tensor, k: int, probs: torch.Tensor, vals: torch
         _dev(logits), C.c_int32(_dt(logits)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
         _dev(probs), _dev(vals), _dev(idx), _stream(stream))
     _check(rc, "softmax_prune")
+
+
+def softmax_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch.Tensor],
+                            dp: torch.Tensor, ds: torch.Tensor, stream=None) -> None:
+    """ds = p^ * (dp - sum(p^ * dp)) per row, p^ being the rows that restore_scores would rebuild."""
+    _require(dp.dim() == 2 and dp.is_contiguous() and ds.is_contiguous())
+    _require(ds.shape == dp.shape and ds.dtype == dp.dtype)
+    _require(vals.dtype == dp.dtype and idx.dtype == torch.uint16 and vals.shape == idx.shape)
+    rows, cols = dp.shape
+    k = vals.shape[1]
+    rc = lib().slimfit_softmax_backward_pruned(
+        _dev(vals), _dev(idx), _dev(counts), _dev(dp), C.c_int32(_dt(dp)), C.c_int64(rows),
+        C.c_int32(cols), C.c_int32(k), _dev(ds), _stream(stream))
+    _check(rc, "softmax_backward_pruned")
 
 
 # ---------------------------------------------------------------- (c') Alg. 5, whole tensor

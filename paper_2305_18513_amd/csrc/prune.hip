@@ -9,6 +9,7 @@
 //   prune_rows_wide_kernel  wider rows, one workgroup per row, the row re-read
 //                           from cache for every probe
 //   restore_tile_kernel     the restoring process: zeros + scatter in one pass
+//   softmax_backward_tile_kernel  the Softmax input gradient from the kept pairs
 #include "common.hpp"
 
 #include <cfloat>
@@ -652,6 +653,105 @@ __global__ __launch_bounds__(kThreads) void restore_tile_kernel(const T *__restr
     for (int e = n_vec * PER16 + tid; e < n; e += kThreads) dst[e] = tile[e];
 }
 
+// ---------------------------------------------------------------------------
+// softmax backward from the kept probabilities
+// ---------------------------------------------------------------------------
+// ds_j = p^_j (dp_j - sum_i p^_i dp_i) with p^ the restored row: zero wherever
+// nothing was kept.  Same tiling as the restore kernel (a workgroup owns kTile
+// consecutive output elements, builds them in LDS and streams them out), with a
+// wave per intersecting row: its lanes fetch the row's records, gather dp at
+// the kept columns, sum the products over the wave in a fixed order and drop
+// p^_j (dp_j - sum) into the tile.  A row that straddles two tiles is summed by
+// both workgroups (identically).  kBackRows rows of a wave are in flight at once.
+template <typename T> struct Narrow;
+template <> struct Narrow<float> {
+    __device__ static float from(float f) { return f; }
+};
+template <> struct Narrow<uint16_t> {
+    __device__ static uint16_t from(float f) { return (uint16_t)bf16_narrow(f); }
+};
+
+constexpr int kBackRows = 4;
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void softmax_backward_tile_kernel(const T *__restrict__ vals,
+                                                                         const uint16_t *__restrict__ idx,
+                                                                         const int32_t *__restrict__ counts,
+                                                                         const T *__restrict__ dp, int64_t rows,
+                                                                         int cols, int k, T *__restrict__ out)
+{
+    __shared__ alignas(16) T tile[kTile];
+    constexpr int PER16 = 16 / (int)sizeof(T);
+    constexpr int kVecs = kTile / PER16;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t total = rows * (int64_t)cols;
+    const int64_t t0 = (int64_t)blockIdx.x * kTile;
+    const int n = (int)min((int64_t)kTile, total - t0);         // >= 1 by the launch size
+    const int64_t r_lo = t0 / cols, r_hi = (t0 + n - 1) / cols; // rows touching this tile
+    const int n_rows = (int)(r_hi - r_lo + 1);
+
+    for (int v = tid; v < kVecs; v += kThreads) reinterpret_cast<uint4 *>(tile)[v] = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+
+    for (int rb = wave * kBackRows; rb < n_rows; rb += kWavesPerBlock * kBackRows) {
+        // first chunk of up to kBackRows rows: records, then the gathered dp, all loads issued before any use
+        int col[kBackRows];
+        float v[kBackRows], d[kBackRows];
+        bool ok[kBackRows];
+        int cnt[kBackRows];
+#pragma unroll
+        for (int u = 0; u < kBackRows; ++u) {
+            const int64_t r = r_lo + rb + u;
+            const bool row_ok = rb + u < n_rows;
+            cnt[u] = row_ok ? (counts ? min(counts[r], k) : k) : 0;
+            ok[u] = lane < cnt[u];
+            col[u] = 0xFFFF;
+            v[u] = 0.0f;
+            if (ok[u]) {
+                col[u] = idx[r * (int64_t)k + lane];
+                v[u] = Elem<T>::load(vals + r * (int64_t)k + lane);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBackRows; ++u) {
+            ok[u] = ok[u] && col[u] < cols;
+            d[u] = ok[u] ? Elem<T>::load(dp + (r_lo + rb + u) * (int64_t)cols + col[u]) : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kBackRows; ++u) {
+            if (rb + u >= n_rows) break;                        // wave-uniform
+            const int64_t r = r_lo + rb + u;
+            const T *rv = vals + r * (int64_t)k;
+            const uint16_t *ri = idx + r * (int64_t)k;
+            const T *rd = dp + r * (int64_t)cols;
+            float part = ok[u] ? v[u] * d[u] : 0.0f;
+            for (int s = lane + kWave; s < cnt[u]; s += kWave) {        // records past the first 64
+                const int c = ri[s];
+                if (c < cols) part = fmaf(Elem<T>::load(rv + s), Elem<T>::load(rd + c), part);
+            }
+            const float dot = wave_sum_f32(part);
+            const int64_t base = r * (int64_t)cols - t0;                // the row's start relative to the tile
+            if (ok[u]) {
+                const int64_t at = base + col[u];
+                if (at >= 0 && at < n) tile[at] = Narrow<T>::from(v[u] * (d[u] - dot));
+            }
+            for (int s = lane + kWave; s < cnt[u]; s += kWave) {
+                const int c = ri[s];
+                const int64_t at = base + c;
+                if (c < cols && at >= 0 && at < n)
+                    tile[at] = Narrow<T>::from(Elem<T>::load(rv + s) * (Elem<T>::load(rd + c) - dot));
+            }
+        }
+    }
+    __syncthreads();
+
+    T *dst = out + t0;
+    const int n_vec = n / PER16;
+    for (int e = tid; e < n_vec; e += kThreads)
+        store_global<true>(reinterpret_cast<u32x4 *>(dst) + e, reinterpret_cast<const u32x4 *>(tile)[e]);
+    for (int e = n_vec * PER16 + tid; e < n; e += kThreads) dst[e] = tile[e];
+}
+
 template <typename T, bool SOFTMAX>
 void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float tau, void *vals, uint16_t *idx,
                   int32_t *counts, void *probs, hipStream_t st)
@@ -782,5 +882,38 @@ extern "C" int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx,
         restore_tile_kernel<uint16_t><<<(unsigned)tiles, kThreads, 0, st>>>(static_cast<const uint16_t *>(vals), idx,
                                                                             counts, rows, cols, k,
                                                                             static_cast<uint16_t *>(out));
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_softmax_backward_pruned(const void *vals, const uint16_t *idx, const int32_t *counts,
+                                                   const void *dp, int32_t dt, int64_t rows, int32_t cols, int32_t k,
+                                                   void *ds, void *stream)
+{
+    int32_t rc = validate(dt, rows, cols, k);
+    if (rc != SLIMFIT_OK) return rc;
+    if (rows == 0) return SLIMFIT_OK;
+    if (!vals || !idx || !dp || !ds || dp == ds) return SLIMFIT_ERR_INVALID_ARG;
+    const size_t esz = dtype_size(dt);
+    if (!aligned_to(ds, 16) || !aligned_to(dp, esz) || !aligned_to(vals, esz) || !aligned_to(idx, 2) ||
+        (counts && !aligned_to(counts, 4)))
+        return SLIMFIT_ERR_ALIGNMENT;
+    const size_t dense_bytes = (size_t)rows * (size_t)cols * esz;
+    if ((rc = check_device_range(ds, dense_bytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dp, dense_bytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(vals, (size_t)rows * (size_t)k * esz)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(idx, (size_t)rows * (size_t)k * 2)) != SLIMFIT_OK) return rc;
+    if (counts && (rc = check_device_range(counts, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t total = rows * (int64_t)cols;
+    const int64_t tiles = (total + kTile - 1) / kTile;
+    if (tiles > 0x7FFFFFFF) return SLIMFIT_ERR_UNSUPPORTED;
+    if (dt == SLIMFIT_F32)
+        softmax_backward_tile_kernel<float><<<(unsigned)tiles, kThreads, 0, st>>>(
+            static_cast<const float *>(vals), idx, counts, static_cast<const float *>(dp), rows, cols, k,
+            static_cast<float *>(ds));
+    else
+        softmax_backward_tile_kernel<uint16_t><<<(unsigned)tiles, kThreads, 0, st>>>(
+            static_cast<const uint16_t *>(vals), idx, counts, static_cast<const uint16_t *>(dp), rows, cols, k,
+            static_cast<uint16_t *>(ds));
     return launch_status();
 }

@@ -75,6 +75,31 @@ def test_layernorm_function_frozen_and_active():
     assert float(rel) < 0.5
 
 
+def test_softmax_function_equals_the_fused_calls_and_caches_a_tenth():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    B, h, T = 3, 4, 197
+    l = (torch.randn(B, h, T, T, generator=g, device="cuda") * 2).requires_grad_(True)
+    dp = torch.randn(B, h, T, T, generator=g, device="cuda")
+    p = ag.SoftmaxFunction.apply(l, 100000)
+    rows, k = B * h * T, sf.keep_count(T, 100000)
+    assert _saved_bytes(p) == rows * k * (4 + 2)
+    p.backward(dp)
+    p2 = torch.empty(rows, T, device="cuda")
+    vals, idx = torch.empty(rows, k, device="cuda"), torch.empty(rows, k, dtype=torch.uint16, device="cuda")
+    sf.softmax_prune(l.detach().view(rows, T), k, p2, vals, idx)
+    ds2 = torch.empty(rows, T, device="cuda")
+    sf.softmax_backward_pruned(vals, idx, None, dp.view(rows, T), ds2)
+    assert torch.equal(p.detach().view(rows, T), p2) and torch.equal(l.grad.view(rows, T), ds2)
+    assert torch.allclose(p.detach(), torch.softmax(l.detach(), dim=-1), rtol=1e-5, atol=1e-8)
+    # with every column kept the gradient is the dense one
+    l3 = l.detach().clone().requires_grad_(True)
+    ag.SoftmaxFunction.apply(l3, 1000000).backward(dp)
+    l4 = l.detach().clone().requires_grad_(True)
+    torch.softmax(l4, dim=-1).backward(dp)
+    assert torch.allclose(l3.grad, l4.grad, rtol=1e-4, atol=1e-6)
+
+
 def test_linear_function_skips_the_weight_gradient_when_frozen():
     require_gpu()
     g = torch.Generator(device="cuda").manual_seed(2)
