@@ -388,6 +388,7 @@ def main() -> int:
             pi = [torch.empty(k_l, dtype=torch.int32, device="cuda") for _ in sets]
             rp = [torch.empty(rows_l + 1, dtype=torch.int32, device="cuda") for _ in sets]
             lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
+            nb_lq = 8 * n_l + sf.packed_bytes(n_l, bits) + 4 * sf.num_blocks(n_l, block) + 8 * rows_l
             ln_runs = {
                 "layernorm_forward[ln_in]": (8 * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
                     lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
@@ -395,6 +396,12 @@ def main() -> int:
                     sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
                 "layernorm_backward_pruned[ln_in]": (8 * n_l + 8 * k_l + 8 * rows_l, lambda i:
                     sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
+                # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
+                # reads the input anyway, and the input gradient straight from that cache
+                "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
+                    lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
+                "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
+                    sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
             }
             for name, (nb, fn) in ln_runs.items():
                 for i in range(len(sets)):

@@ -380,6 +380,26 @@ int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx,
                                           const float *rstd, const float *gamma, const float *dy,
                                           int64_t rows, int64_t H, float *dx, void *stream);
 
+/* LayerNorm with the low-bit cache of its input (Alg. 2, one scale per block; Sec. 4 and 5) fused in.
+ *   slimfit_layernorm_forward_quant_pack : slimfit_layernorm_forward and, from the same read of x,
+ *        the codes and scales slimfit_quant_pack(x, F32, rows*H, BLOCK, bits, block) produces --
+ *        bit for bit -- so the input is read once instead of twice.
+ *   slimfit_layernorm_backward_dequant   : slimfit_layernorm_backward on x^ = code * scale (one fp32
+ *        multiplication, the value slimfit_dequant_unpack would store) without storing x^:
+ *        x~ = (x^ - mean[r]) * rstd[r] with the statistics the forward pass returned (those of the
+ *        exact input).  Same tolerance as slimfit_layernorm_backward.
+ * bits 4 | 8; block 32 | 64 | 128 | 256 and H % block == 0, so that no block straddles two rows (else
+ * UNSUPPORTED).  codes: DEVICE uint8[rows*H*bits/8]; scales: DEVICE float[rows*H/block]; both 16-byte
+ * aligned.  Everything else as slimfit_layernorm_forward / slimfit_layernorm_backward. */
+int32_t slimfit_layernorm_forward_quant_pack(const float *x, const float *gamma, const float *beta,
+                                             int64_t rows, int64_t H, float eps, int32_t bits, int32_t block,
+                                             float *y, float *mean, float *rstd, uint8_t *codes, float *scales,
+                                             void *stream);
+
+int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, const float *scales, int32_t bits, int32_t block,
+                                           const float *mean, const float *rstd, const float *gamma,
+                                           const float *dy, int64_t rows, int64_t H, float *dx, void *stream);
+
 /* ------------------------------------------------------------------------
  * (d) Inter-layer scheduling on the host -- Alg. 1 and Sec. 3.2 / Fig. 4:
  *        idx = argsort(d)[: int(L*F)]   -> these layers are frozen;

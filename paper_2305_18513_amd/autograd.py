@@ -11,7 +11,11 @@ computes; the dense matrix products of the linear layer are torch's.
                      tensor with int32 indices, row pointers and rstd; backward
                      is the paper's input-gradient formula on those pairs, and
                      gamma / beta get no gradient.  Active: caches x exactly
-                     and returns all three gradients.
+                     and returns all three gradients.  With `quant_bits` the
+                     cache is instead the block-scaled codes of x written by the
+                     forward kernel itself (plus mean and rstd); backward rebuilds
+                     x^ in registers, and an active layer's gamma / beta gradients
+                     use the dequantised x^.
   SoftmaxFunction    p = softmax(logits) over the last dimension (at most 1024
                      wide); caches the `keep_ppm` largest probabilities of every
                      row with uint16 columns; backward is the derivative of
@@ -60,15 +64,23 @@ class GeluFunction(torch.autograd.Function):
 class LayerNormFunction(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float = 1e-5,
-                frozen: bool = False, keep_ppm: int = 100000):
+                frozen: bool = False, keep_ppm: int = 100000, quant_bits: int = 0, block: int = 64):
         H = x.shape[-1]
         x2 = x.contiguous().view(-1, H)
         rows = x2.shape[0]
         y = torch.empty_like(x2)
         mean = torch.empty(rows, dtype=torch.float32, device=x.device)
         rstd = torch.empty(rows, dtype=torch.float32, device=x.device)
-        sf.layernorm_forward(x2, gamma, beta, eps, y, mean, rstd)
         ctx.frozen = frozen
+        ctx.quant = (quant_bits, block)
+        if quant_bits:
+            n = x2.numel()
+            codes = torch.empty(sf.packed_bytes(n, quant_bits), dtype=torch.uint8, device=x.device)
+            scales = torch.empty(sf.num_blocks(n, block), dtype=torch.float32, device=x.device)
+            sf.layernorm_forward_quant_pack(x2, gamma, beta, eps, quant_bits, block, y, mean, rstd, codes, scales)
+            ctx.save_for_backward(codes, scales, mean, rstd, gamma)
+            return y.view(x.shape)
+        sf.layernorm_forward(x2, gamma, beta, eps, y, mean, rstd)
         if frozen:
             n = x2.numel()
             k = sf.keep_count(n, keep_ppm)
@@ -89,17 +101,30 @@ class LayerNormFunction(torch.autograd.Function):
     def backward(ctx, grad_output: torch.Tensor):
         H = grad_output.shape[-1]
         dy = grad_output.contiguous().view(-1, H)
+        none = (None,) * 5
+        bits, block = ctx.quant
+        if bits:
+            codes, scales, mean, rstd, gamma = ctx.saved_tensors
+            dx = torch.empty_like(dy)
+            sf.layernorm_backward_dequant(codes, scales, bits, block, mean, rstd, gamma, dy, dx)
+            if ctx.frozen:
+                return (dx.view(grad_output.shape), None, None) + none
+            x_hat = torch.empty_like(dy)
+            sf.dequant_unpack(codes, scales, sf.Q_BLOCK, bits, block, 0, x_hat.view(-1))
+            dgamma, dbeta = torch.empty_like(gamma), torch.empty_like(gamma)
+            sf.layernorm_param_grads(x_hat, mean, rstd, dy, dgamma, dbeta)
+            return (dx.view(grad_output.shape), dgamma, dbeta) + none
         if ctx.frozen:
             vals, idx, row_ptr, rstd, gamma = ctx.saved_tensors
             dx = torch.empty_like(dy)
             sf.layernorm_backward_pruned(vals, idx, row_ptr, ctx.k, rstd, gamma, dy, dx)
-            return dx.view(grad_output.shape), None, None, None, None, None
+            return (dx.view(grad_output.shape), None, None) + none
         x2, mean, rstd, gamma = ctx.saved_tensors
         dgamma, dbeta = torch.empty_like(gamma), torch.empty_like(gamma)
         sf.layernorm_param_grads(x2, mean, rstd, dy, dgamma, dbeta)
         dx = torch.empty_like(dy)
         sf.layernorm_backward(x2, mean, rstd, gamma, dy, dx)
-        return dx.view(grad_output.shape), dgamma, dbeta, None, None, None
+        return (dx.view(grad_output.shape), dgamma, dbeta) + none
 
 
 class SoftmaxFunction(torch.autograd.Function):

@@ -35,7 +35,7 @@ EXPORTS = (
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_softmax_backward_pruned", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
-    "slimfit_layernorm_backward_pruned", "slimfit_layernorm_backward", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
+    "slimfit_layernorm_backward_pruned", "slimfit_layernorm_forward_quant_pack", "slimfit_layernorm_backward_dequant", "slimfit_layernorm_backward", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
     "slimfit_freeze_count", "slimfit_ils_select",
     "slimfit_ils_update", "slimfit_schedule_random", "slimfit_schedule_progressive",
 )
@@ -380,6 +380,36 @@ def layernorm_backward(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, 
     rc = lib().slimfit_layernorm_backward(_dev(x), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
                                           C.c_int64(H), _dev(dx), _stream(stream))
     _check(rc, "layernorm_backward")
+
+
+def layernorm_forward_quant_pack(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float, bits: int,
+                                 block: int, y: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor,
+                                 codes: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
+    """layernorm_forward plus, from the same read of x, the codes and scales of quant_pack(x) in BLOCK mode."""
+    _require(x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape)
+    _require(all(t.dtype == torch.float32 for t in (x, gamma, beta, y, mean, rstd, scales)) and codes.dtype == torch.uint8)
+    rows, H = x.shape
+    _require(gamma.numel() == H and beta.numel() == H and mean.numel() >= rows and rstd.numel() >= rows)
+    _require(codes.numel() >= rows * H * bits // 8 and scales.numel() >= rows * H // max(block, 1))
+    rc = lib().slimfit_layernorm_forward_quant_pack(
+        _dev(x), _dev(gamma), _dev(beta), C.c_int64(rows), C.c_int64(H), C.c_float(eps), C.c_int32(bits),
+        C.c_int32(block), _dev(y), _dev(mean), _dev(rstd), _dev(codes), _dev(scales), _stream(stream))
+    _check(rc, "layernorm_forward_quant_pack")
+
+
+def layernorm_backward_dequant(codes: torch.Tensor, scales: torch.Tensor, bits: int, block: int, mean: torch.Tensor,
+                               rstd: torch.Tensor, gamma: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
+                               stream=None) -> None:
+    """Input gradient of a LayerNorm whose input was cached by layernorm_forward_quant_pack."""
+    _require(dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape)
+    _require(all(t.dtype == torch.float32 for t in (scales, mean, rstd, gamma, dy, dx)) and codes.dtype == torch.uint8)
+    rows, H = dy.shape
+    _require(gamma.numel() == H and mean.numel() >= rows and rstd.numel() >= rows)
+    _require(codes.numel() >= rows * H * bits // 8 and scales.numel() >= rows * H // max(block, 1))
+    rc = lib().slimfit_layernorm_backward_dequant(
+        _dev(codes), _dev(scales), C.c_int32(bits), C.c_int32(block), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy),
+        C.c_int64(rows), C.c_int64(H), _dev(dx), _stream(stream))
+    _check(rc, "layernorm_backward_dequant")
 
 
 def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, dy: torch.Tensor,

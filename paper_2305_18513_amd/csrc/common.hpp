@@ -70,6 +70,51 @@ __device__ __forceinline__ float group_max_f32(float v)
     return v;
 }
 
+// the same with the group size a wave-uniform run-time value (8, 16, 32 or 64)
+__device__ __forceinline__ float group_max_f32_dyn(float v, int G)
+{
+    v = fmaxf(v, dpp_f32<kDppXor1>(v));
+    v = fmaxf(v, dpp_f32<kDppXor2>(v));
+    v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+    if (G >= 16) v = fmaxf(v, dpp_f32<kDppMirror>(v));
+    if (G >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    if (G >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+
+// Alg. 2 with one scale per block: code = clamp(round_half_even(x * mult), qmin, qmax)
+// -- one fp32 multiply -- where mult = qmax / a and the stored scale = a / qmax for a
+// block whose largest magnitude is a (two IEEE fp32 divisions); a block of zeros, or one
+// whose multiplier would overflow, gets scale 0 and codes 0.
+template <int BITS>
+__device__ __forceinline__ int quantise_one(float x, float mult)
+{
+    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+    constexpr float qmin = -(float)(1 << (BITS - 1));
+    float r = __builtin_rintf(x * mult);
+    r = fminf(fmaxf(r, qmin), qmax);
+    return (int)r;
+}
+template <int BITS>
+__device__ __forceinline__ void block_scale(float a, float &mult, float &scale)
+{
+    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+    mult = 0.0f;
+    scale = 0.0f;
+    if (a > 0.0f) {
+        mult = qmax / a;
+        if (__builtin_isinf(mult)) mult = 0.0f;
+        else scale = a / qmax;
+    }
+}
+// field i of BITS bits of a packed word, sign-extended
+template <int BITS>
+__device__ __forceinline__ int code_field(uint32_t word, int i)
+{
+    const int sh = i * BITS;
+    return (int)(word << (32 - BITS - sh)) >> (32 - BITS);
+}
+
 // Whole-wave reductions of unsigned keys; the result is wave-uniform (SGPR).
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {

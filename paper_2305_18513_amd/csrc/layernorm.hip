@@ -9,6 +9,9 @@
 //                                     formed from x and the row statistics);
 //   param_grad_*_kernel               gamma^ and beta^ of an active LayerNorm
 //                                     (column sums over all rows, two stages);
+//   layernorm_forward_quant_kernel    the forward pass that also writes the low-bit
+//                                     cache of its input (Alg. 2), one read of x;
+//   layernorm_backward_dequant_kernel the input gradient straight from that cache;
 //   layernorm_backward_pruned_kernel  the input gradient of a frozen LayerNorm,
 //                                     x^ = H g - sum g - x~ sum(g x~),
 //                                     g = gamma y^ / (H sqrt(Var + eps)), with
@@ -258,6 +261,157 @@ layernorm_backward_kernel(const float *__restrict__ x, const float *__restrict__
     }
 }
 
+// ---- LayerNorm with the low-bit cache of its input fused in ------------------------------
+// Forward: the wave that holds a row for the statistics also quantises it (Alg. 2, one
+// scale per `block` consecutive elements = G = block / 4 consecutive lanes of one of its
+// vectors, the block maximum a DPP butterfly) and stores codes and scales, so the input is
+// read once for both.  H is a multiple of block, hence every block lies inside one row
+// and the codes are those of the flat quantiser.
+// Backward: x^ = code * scale is rebuilt in registers and goes straight into the dense
+// input-gradient formula; it is never stored.
+template <int BITS>
+__device__ __forceinline__ uint32_t pack4(const f32x4 &v, float mult)
+{
+    constexpr uint32_t m = (1u << BITS) - 1u;
+    return ((uint32_t)quantise_one<BITS>(v.x, mult) & m) | (((uint32_t)quantise_one<BITS>(v.y, mult) & m) << BITS) |
+           (((uint32_t)quantise_one<BITS>(v.z, mult) & m) << (2 * BITS)) |
+           (((uint32_t)quantise_one<BITS>(v.w, mult) & m) << (3 * BITS));
+}
+
+template <int NV, int BITS>
+__global__ void __launch_bounds__(kThreads)
+layernorm_forward_quant_kernel(const float *__restrict__ x, const float *__restrict__ gamma,
+                               const float *__restrict__ beta, int64_t rows, int H, float eps, int G, int block_shift,
+                               float *__restrict__ y, float *__restrict__ mean, float *__restrict__ rstd,
+                               uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (r >= rows) return;                                   // whole waves leave: the lane exchanges below stay complete
+    const int nvec = H / 4;
+    const int64_t e0 = r * (int64_t)H;
+    f32x4 v[NV], ga[NV], be[NV];
+    load_row<NV>(x + e0, nvec, lane, v, true);
+    load_row<NV>(gamma, nvec, lane, ga, false);
+    load_row<NV>(beta, nvec, lane, be, false);
+
+    // the cache: codes and scales of this row's blocks
+    auto write_cache = [&]() {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        float a = fmaxf(fmaxf(fabsf(v[i].x), fabsf(v[i].y)), fmaxf(fabsf(v[i].z), fabsf(v[i].w)));
+        a = group_max_f32_dyn(a, G);
+        float mult, scale;
+        block_scale<BITS>(a, mult, scale);
+        if (q < nvec) {
+            const int64_t e = e0 + (int64_t)q * 4;
+            if ((lane & (G - 1)) == 0) scales[e >> block_shift] = scale;
+            const uint32_t w = pack4<BITS>(v[i], mult);
+            if (BITS == 4) __builtin_nontemporal_store((uint16_t)w, reinterpret_cast<uint16_t *>(codes + e / 2));
+            else __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(codes + e));
+        }
+    }
+    };
+    write_cache();       // before or after the y stores makes no measurable difference
+
+    float part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) part += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    const float mu = wave_sum_f32(part) / (float)H;
+    part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const bool in = i * kWave + lane < nvec;
+        const float a = v[i].x - mu, b = v[i].y - mu, c = v[i].z - mu, d = v[i].w - mu;
+        part += in ? (a * a + b * b) + (c * c + d * d) : 0.0f;
+    }
+    const float var = wave_sum_f32(part) / (float)H;
+    const float rs = 1.0f / __builtin_sqrtf(var + eps);
+    if (lane == 0) {
+        mean[r] = mu;
+        rstd[r] = rs;
+    }
+    f32x4 *dst = reinterpret_cast<f32x4 *>(y + e0);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        if (q < nvec) {
+            f32x4 o;
+            o.x = ((v[i].x - mu) * rs) * ga[i].x + be[i].x;
+            o.y = ((v[i].y - mu) * rs) * ga[i].y + be[i].y;
+            o.z = ((v[i].z - mu) * rs) * ga[i].z + be[i].z;
+            o.w = ((v[i].w - mu) * rs) * ga[i].w + be[i].w;
+            __builtin_nontemporal_store(o, dst + q);
+        }
+    }
+}
+
+template <int NV, int BITS>
+__global__ void __launch_bounds__(kThreads)
+layernorm_backward_dequant_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ scales, int block_shift,
+                                  const float *__restrict__ mean, const float *__restrict__ rstd,
+                                  const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
+                                  float *__restrict__ dx)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int nvec = H / 4;
+    const int64_t e0 = r * (int64_t)H;
+    f32x4 g[NV], ga[NV];
+    uint32_t w[NV];
+    float sc[NV];
+    load_row<NV>(dy + e0, nvec, lane, g, true);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        w[i] = 0u;
+        sc[i] = 0.0f;
+        if (q < nvec) {
+            const int64_t e = e0 + (int64_t)q * 4;
+            if (BITS == 4) w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(codes + e / 2));
+            else w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(codes + e));
+            sc[i] = scales[e >> block_shift];
+        }
+    }
+    load_row<NV>(gamma, nvec, lane, ga, false);
+    const float mu = mean[r], rs = rstd[r];
+    const float scale = rs / (float)H;
+    f32x4 xt[NV];
+    float part_g = 0.0f, part_gx = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const bool in = i * kWave + lane < nvec;
+        xt[i].x = in ? ((float)code_field<BITS>(w[i], 0) * sc[i] - mu) * rs : 0.0f;
+        xt[i].y = in ? ((float)code_field<BITS>(w[i], 1) * sc[i] - mu) * rs : 0.0f;
+        xt[i].z = in ? ((float)code_field<BITS>(w[i], 2) * sc[i] - mu) * rs : 0.0f;
+        xt[i].w = in ? ((float)code_field<BITS>(w[i], 3) * sc[i] - mu) * rs : 0.0f;
+        g[i].x = (ga[i].x * g[i].x) * scale;
+        g[i].y = (ga[i].y * g[i].y) * scale;
+        g[i].z = (ga[i].z * g[i].z) * scale;
+        g[i].w = (ga[i].w * g[i].w) * scale;
+        part_g += (g[i].x + g[i].y) + (g[i].z + g[i].w);
+        part_gx += (g[i].x * xt[i].x + g[i].y * xt[i].y) + (g[i].z * xt[i].z + g[i].w * xt[i].w);
+    }
+    const float sum_g = wave_sum_f32(part_g);
+    const float sum_gx = wave_sum_f32(part_gx);
+    const float fH = (float)H;
+    f32x4 *dst = reinterpret_cast<f32x4 *>(dx + e0);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+        if (q < nvec) {
+            f32x4 o;
+            o.x = (fH * g[i].x - sum_g) - xt[i].x * sum_gx;
+            o.y = (fH * g[i].y - sum_g) - xt[i].y * sum_gx;
+            o.z = (fH * g[i].z - sum_g) - xt[i].z * sum_gx;
+            o.w = (fH * g[i].w - sum_g) - xt[i].w * sum_gx;
+            __builtin_nontemporal_store(o, dst + q);
+        }
+    }
+}
+
 // ---- parameter gradients of an active LayerNorm: column sums over all rows --------------
 // gamma^_j = sum_r x~_rj * y^_rj,  beta^_j = sum_r y^_rj.  A workgroup owns a slab of
 // kSlabRows consecutive rows and a group of 256 columns: lane l of every wave holds the
@@ -359,6 +513,14 @@ int32_t validate(int64_t rows, int64_t H)
 {
     if (rows < 0 || H < 4 || H % 4 != 0) return SLIMFIT_ERR_INVALID_ARG;
     if (H > kMaxH || rows * H > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;
+    return SLIMFIT_OK;
+}
+
+int32_t validate_quant(int64_t H, int32_t bits, int32_t block)
+{
+    if (bits != 4 && bits != 8) return SLIMFIT_ERR_UNSUPPORTED;
+    if (block != 32 && block != 64 && block != 128 && block != 256) return SLIMFIT_ERR_UNSUPPORTED;
+    if (H % block != 0) return SLIMFIT_ERR_UNSUPPORTED;        // a block must not straddle two rows
     return SLIMFIT_OK;
 }
 
@@ -503,5 +665,75 @@ extern "C" int32_t slimfit_layernorm_backward(const float *x, const float *mean,
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
     SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_kernel<NV><<<grid, kThreads, 0, s>>>(
                                              x, mean, rstd, gamma, dy, rows, (int)H, dx)));
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_layernorm_forward_quant_pack(const float *x, const float *gamma, const float *beta,
+                                                        int64_t rows, int64_t H, float eps, int32_t bits, int32_t block,
+                                                        float *y, float *mean, float *rstd, uint8_t *codes,
+                                                        float *scales, void *stream)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if ((rc = validate_quant(H, bits, block)) != SLIMFIT_OK) return rc;
+    if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
+    if (rows == 0) return SLIMFIT_OK;
+    if (!x || !gamma || !beta || !y || !mean || !rstd || !codes || !scales || x == y) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(x, 16) || !aligned_to(y, 16) || !aligned_to(gamma, 16) || !aligned_to(beta, 16) ||
+        !aligned_to(mean, 4) || !aligned_to(rstd, 4) || !aligned_to(codes, 16) || !aligned_to(scales, 16))
+        return SLIMFIT_ERR_ALIGNMENT;
+    const int64_t n = rows * H;
+    const size_t nbytes = (size_t)n * 4;
+    if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(y, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(beta, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(mean, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(codes, (size_t)(n * bits / 8))) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(scales, (size_t)(n / block) * 4)) != SLIMFIT_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
+    const int G = block / 4, shift = __builtin_ctz((unsigned)block);
+    if (bits == 4)
+        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_forward_quant_kernel<NV, 4><<<grid, kThreads, 0, s>>>(
+                                                 x, gamma, beta, rows, (int)H, eps, G, shift, y, mean, rstd, codes, scales)));
+    else
+        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_forward_quant_kernel<NV, 8><<<grid, kThreads, 0, s>>>(
+                                                 x, gamma, beta, rows, (int)H, eps, G, shift, y, mean, rstd, codes, scales)));
+    return launch_status();
+}
+
+extern "C" int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, const float *scales, int32_t bits,
+                                                      int32_t block, const float *mean, const float *rstd,
+                                                      const float *gamma, const float *dy, int64_t rows, int64_t H,
+                                                      float *dx, void *stream)
+{
+    int32_t rc = validate(rows, H);
+    if (rc != SLIMFIT_OK) return rc;
+    if ((rc = validate_quant(H, bits, block)) != SLIMFIT_OK) return rc;
+    if (rows == 0) return SLIMFIT_OK;
+    if (!codes || !scales || !mean || !rstd || !gamma || !dy || !dx || dx == dy) return SLIMFIT_ERR_INVALID_ARG;
+    if (!aligned_to(codes, 16) || !aligned_to(scales, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16) ||
+        !aligned_to(gamma, 16) || !aligned_to(mean, 4) || !aligned_to(rstd, 4))
+        return SLIMFIT_ERR_ALIGNMENT;
+    const int64_t n = rows * H;
+    const size_t nbytes = (size_t)n * 4;
+    if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dx, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(mean, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(codes, (size_t)(n * bits / 8))) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(scales, (size_t)(n / block) * 4)) != SLIMFIT_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
+    const int shift = __builtin_ctz((unsigned)block);
+    if (bits == 4)
+        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_dequant_kernel<NV, 4><<<grid, kThreads, 0, s>>>(
+                                                 codes, scales, shift, mean, rstd, gamma, dy, rows, (int)H, dx)));
+    else
+        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_dequant_kernel<NV, 8><<<grid, kThreads, 0, s>>>(
+                                                 codes, scales, shift, mean, rstd, gamma, dy, rows, (int)H, dx)));
     return launch_status();
 }

@@ -68,17 +68,6 @@ template <> struct Vec<uint16_t> {   // bf16 bit patterns
     __device__ static void store1(uint16_t *p, float v) { *p = (uint16_t)bf16_narrow(v); }
 };
 
-// code = clamp(round_half_even(x * mult), qmin, qmax) -- one fp32 multiply
-template <int BITS>
-__device__ __forceinline__ int quantise_one(float x, float mult)
-{
-    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
-    constexpr float qmin = -(float)(1 << (BITS - 1));
-    float r = __builtin_rintf(x * mult);
-    r = fminf(fmaxf(r, qmin), qmax);
-    return (int)r;
-}
-
 // Exact (erf) GELU and its derivative in fp32.
 // 1 + erf(x / sqrt 2) is built from erfc(t), t = |x| / sqrt 2:  2 - erfc(t) for
 // x >= 0 and erfc(t) itself for x < 0, which also keeps the left tail free of
@@ -127,7 +116,6 @@ __device__ __forceinline__ void quant_tile(const T *__restrict__ x, int64_t n, f
 {
     constexpr int V = Vec<T>::V;
     constexpr int OUT_BYTES = V * BITS / 8;            // packed bytes per lane-vector: 2, 4 or 8
-    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
     constexpr int kUnroll = kUnrollQ;
     const int64_t first_vec = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
 
@@ -168,13 +156,8 @@ __device__ __forceinline__ void quant_tile(const T *__restrict__ x, int64_t n, f
 #pragma unroll
             for (int i = 0; i < V; ++i) a = fmaxf(a, fabsf(f[u][i]));
             a = group_max_f32<G>(a);                   // all lanes take part (no divergence above)
-            float inv = 0.0f, scale = 0.0f;
-            if (a > 0.0f) {
-                inv = qmax / a;                        // IEEE fp32 division
-                if (__builtin_isinf(inv)) inv = 0.0f;
-                else scale = a / qmax;                 // IEEE fp32 division
-            }
-            mult = inv;
+            float scale;
+            block_scale<BITS>(a, mult, scale);
             if ((threadIdx.x & (G - 1)) == 0 && (INSIDE || e0 < n)) scales[e0 / (V * G)] = scale;
         }
         if (!INSIDE && e0 >= n) continue;

@@ -75,6 +75,45 @@ def test_layernorm_function_frozen_and_active():
     assert float(rel) < 0.5
 
 
+def test_layernorm_function_with_the_quantised_cache():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(4)
+    rows, H = 96, 768
+    x = torch.randn(4, 24, H, generator=g, device="cuda").requires_grad_(True)
+    gamma = torch.nn.Parameter(torch.rand(H, generator=g, device="cuda") + 0.5)
+    beta = torch.nn.Parameter(torch.rand(H, generator=g, device="cuda") - 0.5)
+    dy = torch.randn(4, 24, H, generator=g, device="cuda")
+    n = rows * H
+    for frozen in (True, False):
+        x.grad = gamma.grad = beta.grad = None
+        y = ag.LayerNormFunction.apply(x, gamma, beta, 1e-5, frozen, 100000, 4, 64)
+        assert _saved_bytes(y) == sf.packed_bytes(n, 4) + 4 * sf.num_blocks(n, 64) + 8 * rows
+        y.backward(dy)
+        y2 = torch.empty(rows, H, device="cuda")
+        mean, rstd = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+        codes = torch.empty(sf.packed_bytes(n, 4), dtype=torch.uint8, device="cuda")
+        scales = torch.empty(sf.num_blocks(n, 64), device="cuda")
+        sf.layernorm_forward_quant_pack(x.detach().view(rows, H), gamma.detach(), beta.detach(), 1e-5, 4, 64, y2, mean,
+                                        rstd, codes, scales)
+        dx2 = torch.empty(rows, H, device="cuda")
+        sf.layernorm_backward_dequant(codes, scales, 4, 64, mean, rstd, gamma.detach(), dy.view(rows, H), dx2)
+        assert torch.equal(y.detach().view(rows, H), y2) and torch.equal(x.grad.view(rows, H), dx2)
+        assert torch.allclose(y.detach(), torch.nn.functional.layer_norm(x.detach(), (H,), gamma, beta, 1e-5), rtol=1e-5, atol=1e-5)
+        if frozen:
+            assert gamma.grad is None and beta.grad is None
+        else:
+            xh = torch.empty(rows, H, device="cuda")
+            sf.dequant_unpack(codes, scales, sf.Q_BLOCK, 4, 64, 0, xh.view(-1))
+            dg, db = torch.empty(H, device="cuda"), torch.empty(H, device="cuda")
+            sf.layernorm_param_grads(xh, mean, rstd, dy.view(rows, H), dg, db)
+            assert torch.equal(gamma.grad, dg) and torch.equal(beta.grad, db)
+            # 4-bit cache: the gradient is close to, not equal to, the exact one
+            xe = x.detach().clone().requires_grad_(True)
+            torch.nn.functional.layer_norm(xe, (H,), gamma.detach(), beta.detach(), 1e-5).backward(dy)
+            rel = (x.grad - xe.grad).norm() / xe.grad.norm()
+            assert rel < 0.2, float(rel)
+
+
 def test_softmax_function_equals_the_fused_calls_and_caches_a_tenth():
     require_gpu()
     g = torch.Generator(device="cuda").manual_seed(3)

@@ -1,0 +1,135 @@
+"""GPU parity: LayerNorm with the low-bit cache of its input fused in (slimfit_layernorm_forward_quant_pack,
+slimfit_layernorm_backward_dequant) vs the CPU oracle.  Codes and scales are bit-identical to the oracle's flat
+quantiser on the same input; y, the statistics and the input gradient are fp32 evaluations compared with the fp64
+oracle (forward on x, backward on the oracle's own dequantised x^ and statistics) within the header's tolerances."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2305_18513_amd import binding as sf
+from paper_2305_18513_amd import synth
+from tests.gpu_util import Guarded, require_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(seed, rows, H):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    x = torch.randn(rows, H, generator=g, device="cuda") * (0.5 + 2.5 * torch.rand(rows, 1, generator=g, device="cuda"))
+    x = x + 4 * torch.rand(rows, 1, generator=g, device="cuda") - 2
+    x = torch.where(torch.rand(rows, H, generator=g, device="cuda") < 0.002, x * 30, x)      # outliers
+    if rows > 2:
+        x[1, : min(H, 64)] = 0.0                                                              # a block of zeros
+    gamma = 0.5 + torch.rand(H, generator=g, device="cuda")
+    beta = torch.rand(H, generator=g, device="cuda") - 0.5
+    dy = torch.randn(rows, H, generator=g, device="cuda")
+    return x, gamma, beta, dy
+
+
+def _run_both(x, gamma, beta, dy, bits, block, eps=1e-5):
+    rows, H = x.shape
+    n = rows * H
+    y = Guarded(n, torch.float32)
+    mean, rstd = Guarded(rows, torch.float32), Guarded(rows, torch.float32)
+    codes = Guarded(n * bits // 8, torch.uint8)
+    scales = Guarded(n // block, torch.float32)
+    before = x.clone()
+    sf.layernorm_forward_quant_pack(x, gamma, beta, eps, bits, block, y.t.view(rows, H), mean.t, rstd.t, codes.t, scales.t)
+    torch.cuda.synchronize()
+    for b in (y, mean, rstd, codes, scales):
+        b.check()
+    assert torch.equal(x, before)
+
+    xh, gh, bh, dyh = to_np(x), to_np(gamma), to_np(beta), to_np(dy)
+    # the cache: bit for bit the flat quantiser's
+    oc, osc = ref.quant_pack(xh.reshape(-1), mode=sf.Q_BLOCK, bits=bits, block=block, frac_bits=0, threads=4)
+    np.testing.assert_array_equal(to_np(codes.t), oc)
+    np.testing.assert_array_equal(to_np(scales.t).view(np.uint32), osc.view(np.uint32))
+    # y and the statistics
+    oy, om, orr = ref.layernorm_forward(xh, gh, bh, eps=eps, threads=4)
+    xd = xh.astype(np.float64)
+    xmax = np.abs(xd).max(axis=1)
+    mu = xd.mean(1)
+    rs = 1.0 / np.sqrt(xd.var(1) + eps)
+    assert np.all(np.abs(to_np(mean.t).astype(np.float64) - mu) <= 1e-6 * xmax + 1e-30)
+    assert np.all(np.abs(to_np(rstd.t).astype(np.float64) - rs) <= 2e-6 * rs)
+    xt = (xd - mu[:, None]) * rs[:, None]
+    tol = np.abs(gh)[None, :] * (4e-6 * np.abs(xt) + 2e-6 * (xmax * rs)[:, None]) + 1e-6 * np.abs(oy.astype(np.float64))
+    gy = to_np(y.t).reshape(rows, H).astype(np.float64)
+    want = xt * gh.astype(np.float64) + bh.astype(np.float64)
+    assert np.all(np.abs(gy - want) <= tol), "y: worst ratio %.3g" % float((np.abs(gy - want) / tol).max())
+
+    # backward: both sides start from the oracle's cache and statistics
+    xhat = ref.dequant_unpack(oc, osc, n, mode=sf.Q_BLOCK, bits=bits, block=block, frac_bits=0, out_dtype=np.float32,
+                              threads=4).reshape(rows, H)
+    d_codes, d_scales = torch.from_numpy(oc).cuda(), torch.from_numpy(osc).cuda()
+    d_mean, d_rstd = torch.from_numpy(om).cuda(), torch.from_numpy(orr).cuda()
+    dx = Guarded(n, torch.float32)
+    sf.layernorm_backward_dequant(d_codes, d_scales, bits, block, d_mean, d_rstd, gamma, dy, dx.t.view(rows, H))
+    torch.cuda.synchronize()
+    dx.check()
+    want_dx = ref.layernorm_backward(xhat, om, orr, gh, dyh).astype(np.float64)
+    xt64 = (xhat.astype(np.float64) - om.astype(np.float64)[:, None]) * orr.astype(np.float64)[:, None]
+    g64 = gh.astype(np.float64) * dyh.astype(np.float64) * orr.astype(np.float64)[:, None] / H
+    tol = 4e-6 * (H * np.abs(g64) + np.abs(g64).sum(1, keepdims=True)
+                  + np.abs(xt64) * np.abs(g64 * xt64).sum(1, keepdims=True)) + 1e-30
+    got = to_np(dx.t).reshape(rows, H).astype(np.float64)
+    assert np.all(np.abs(got - want_dx) <= tol), "dx: worst ratio %.3g" % float((np.abs(got - want_dx) / tol).max())
+
+
+SHAPES = [(1, 256), (3, 512), (7, 768), (33, 1024), (5, 1280), (4, 2048), (3, 4096), (130, 256), (1025, 512)]
+
+
+@pytest.mark.parametrize("bits,block", [(4, 64), (4, 32), (8, 128), (8, 256), (4, 256)])
+@pytest.mark.parametrize("rows,H", SHAPES)
+def test_fused_pair(rows, H, bits, block):
+    require_gpu()
+    x, gamma, beta, dy = _inputs(rows * 5 + H + bits, rows, H)
+    _run_both(x, gamma, beta, dy, bits, block)
+
+
+def test_narrow_rows_with_small_blocks():
+    require_gpu()
+    for rows, H, block in [(9, 32, 32), (70, 64, 32), (70, 64, 64), (11, 96, 32), (5, 192, 64), (1000, 128, 128)]:
+        x, gamma, beta, dy = _inputs(rows + H, rows, H)
+        _run_both(x, gamma, beta, dy, 4, block)
+        _run_both(x, gamma, beta, dy, 8, block)
+
+
+def test_argument_errors():
+    require_gpu()
+    x = torch.randn(8, 96, device="cuda")
+    y = torch.empty_like(x)
+    ga = torch.ones(96, device="cuda")
+    m, r = torch.empty(8, device="cuda"), torch.empty(8, device="cuda")
+    codes = torch.empty(8 * 96, dtype=torch.uint8, device="cuda")
+    scales = torch.empty(8 * 96 // 32, device="cuda")
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.layernorm_forward_quant_pack(x, ga, ga, 1e-5, 4, 64, y, m, r, codes, scales)       # 96 % 64 != 0
+    assert e.value.status == sf.ERR_UNSUPPORTED
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.layernorm_forward_quant_pack(x, ga, ga, 1e-5, 5, 32, y, m, r, codes, scales)
+    assert e.value.status == sf.ERR_UNSUPPORTED
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.layernorm_forward_quant_pack(x, ga, ga, 1e-5, 4, 32, x, m, r, codes, scales)       # in place
+    assert e.value.status == sf.ERR_INVALID_ARG
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.layernorm_backward_dequant(codes, scales, 4, 32, m, r, ga, y, y)
+    assert e.value.status == sf.ERR_INVALID_ARG
+    with pytest.raises(sf.SlimfitError) as e:
+        sf.layernorm_backward_dequant(codes[1:], scales, 4, 32, m, r, ga, x, y)
+    assert e.value.status == sf.ERR_ALIGNMENT
+
+
+@pytest.mark.parametrize("ci", [1, 3])
+def test_layernorm_input_at_full_size(ci):
+    require_gpu()
+    cfg = synth.CONFIGS[ci]
+    x = synth.activation(cfg, "ln_in", device="cuda").reshape(-1, cfg.hidden).float()
+    rows, H = x.shape
+    g = torch.Generator(device="cuda").manual_seed(ci)
+    gamma = 0.5 + torch.rand(H, generator=g, device="cuda")
+    beta = torch.rand(H, generator=g, device="cuda") - 0.5
+    dy = torch.randn(rows, H, generator=g, device="cuda")
+    _run_both(x, gamma, beta, dy, cfg.quant_bits[-1], cfg.quant_block)
