@@ -46,7 +46,7 @@ def lib():
         if _lib is None:
             _lib = C.CDLL(build())
             for name in ("layer_delta", "quant_pack", "dequant_unpack",
-                         "prune_scores", "restore_scores", "ils_select",
+                         "prune_scores", "restore_scores", "ils_select", "ils_select_blocks",
                          "ils_update", "freeze_count", "keep_count",
                          "prune_global", "restore_global", "gelu", "gelu_backward", "softmax_prune", "softmax_backward_pruned",
                          "layernorm_forward", "standardize", "layernorm_backward_pruned", "layernorm_param_grads", "layernorm_backward",
@@ -341,6 +341,18 @@ def ils_select(d, n_freeze):
     rc = lib().slimfit_ref_ils_select(_ptr(d), C.c_int(L), C.c_int(n_freeze),
                                       _ptr(frozen), _ptr(mask))
     _check(rc, "ils_select")
+    return frozen, mask
+
+
+def ils_select_blocks(d, group, n_freeze):
+    """ILS over blocks of `group` consecutive layers.  Returns (frozen_blocks int32[n_freeze], layer mask uint8[L])."""
+    d = np.ascontiguousarray(d, dtype=np.float32)
+    L = d.size
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(L, dtype=np.uint8)
+    rc = lib().slimfit_ref_ils_select_blocks(_ptr(d), C.c_int(L), C.c_int(group), C.c_int(n_freeze),
+                                             _ptr(frozen), _ptr(mask))
+    _check(rc, "ils_select_blocks")
     return frozen, mask
 
 

@@ -873,6 +873,67 @@ int slimfit_ref_ils_select(const float *d, int L, int n_freeze,
     return REF_OK;
 }
 
+/* ILS at the granularity of blocks of consecutive layers (e.g. the tensors   */
+/* of one encoder block): a block's distance is the mean of its layers'       */
+/* distances (Eq. 1 values), summed in layer order in double; the n_freeze    */
+/* blocks with the smallest means are frozen whole.  Same order as above:     */
+/* equal means by lower block index, a block holding a NaN after all others.  */
+/* With group = 1 this is slimfit_ref_ils_select.                             */
+int slimfit_ref_ils_select_blocks(const float *d, int L, int group, int n_freeze,
+                                  int32_t *frozen_blocks, uint8_t *mask)
+{
+    if (L < 0 || group < 1 || n_freeze < 0)
+        return REF_BAD;
+    const int nb = (L + group - 1) / group;
+    if (n_freeze > nb || (L > 0 && !d) || (n_freeze > 0 && !frozen_blocks))
+        return REF_BAD;
+    double *mean = (double *)malloc(sizeof(double) * (size_t)(nb > 0 ? nb : 1));
+    char *taken = (char *)calloc((size_t)(nb > 0 ? nb : 1), 1);
+    if (!mean || !taken) {
+        free(mean);
+        free(taken);
+        return REF_BAD;
+    }
+    for (int b = 0; b < nb; ++b) {
+        const int lo = b * group, hi = lo + group < L ? lo + group : L;
+        double sum = 0.0;
+        for (int i = lo; i < hi; ++i)
+            sum += (double)d[i];
+        mean[b] = sum / (double)(hi - lo);
+    }
+    if (mask)
+        memset(mask, 0, (size_t)L);
+    /* selection by repeated minimum: obviously the n_freeze smallest, in order */
+    for (int s = 0; s < n_freeze; ++s) {
+        int best = -1;
+        for (int b = 0; b < nb; ++b) {
+            if (taken[b])
+                continue;
+            if (best < 0) {
+                best = b;
+                continue;
+            }
+            const int nan_b = mean[b] != mean[b], nan_best = mean[best] != mean[best];
+            if (nan_b != nan_best) {
+                if (nan_best)
+                    best = b;
+            } else if (!nan_b && mean[b] < mean[best]) {
+                best = b;
+            }
+        }
+        taken[best] = 1;
+        frozen_blocks[s] = best;
+        if (mask) {
+            const int lo = best * group, hi = lo + group < L ? lo + group : L;
+            for (int i = lo; i < hi; ++i)
+                mask[i] = 1;
+        }
+    }
+    free(mean);
+    free(taken);
+    return REF_OK;
+}
+
 int slimfit_ref_ils_update(float *d, const float *new_scores,
                            const uint8_t *frozen_mask, int L)
 {

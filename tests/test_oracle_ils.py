@@ -122,3 +122,55 @@ def test_bad_arguments_rejected():
         ref.ils_select(d, -1)
     with pytest.raises(ValueError):
         ref.freeze_count(4, 1.5)
+
+
+# ---- block granularity ------------------------------------------------------------------------------------------
+
+def test_blocks_of_one_layer_are_plain_ils(golden_dir):
+    for d, frozen in _read_fig4(golden_dir):
+        fb, mb = ref.ils_select_blocks(d, 1, len(frozen))
+        f1, m1 = ref.ils_select(d, len(frozen))
+        np.testing.assert_array_equal(fb, f1)
+        np.testing.assert_array_equal(mb, m1)
+        assert sorted(fb.tolist()) == frozen
+
+
+def test_blocks_match_numpy_means_and_stable_argsort():
+    rng = np.random.default_rng(0)
+    for L, group in ((8, 2), (74, 6), (198, 8), (25, 8), (7, 10), (64, 64), (65, 64)):
+        d = (10.0 ** rng.uniform(-6, -2, L)).astype(np.float32)
+        nb = -(-L // group)
+        means = np.array([d[b * group:(b + 1) * group].astype(np.float64).mean() for b in range(nb)])
+        order = np.argsort(means, kind="stable")
+        for n in (0, 1, nb // 2, nb):
+            fb, mask = ref.ils_select_blocks(d, group, n)
+            np.testing.assert_array_equal(fb, order[:n])
+            want = np.zeros(L, np.uint8)
+            for b in order[:n]:
+                want[b * group:(b + 1) * group] = 1
+            np.testing.assert_array_equal(mask, want)
+
+
+def test_blocks_worked_example_ties_short_last_block_and_nan():
+    # blocks of 3: means 2, 2, 1, (9+1)/2 = 5 -> order: block 2, then the tie 0 before 1, then the short block 3
+    d = np.array([1, 2, 3, 3, 2, 1, 1, 1, 1, 9, 1], np.float32)
+    fb, mask = ref.ils_select_blocks(d, 3, 4)
+    assert fb.tolist() == [2, 0, 1, 3]
+    fb, mask = ref.ils_select_blocks(d, 3, 2)
+    assert fb.tolist() == [2, 0] and mask.tolist() == [1, 1, 1, 0, 0, 0, 1, 1, 1, 0, 0]
+    # the short block is judged by its mean, not by its sum: (4+4)/2 = 4 loses against (3+3+3)/3 = 3
+    fb, _ = ref.ils_select_blocks(np.array([3, 3, 3, 5, 5, 5, 4, 4], np.float32), 3, 2)
+    assert fb.tolist() == [0, 2]
+    # a NaN anywhere in a block sends the block behind every other, +inf included
+    d = np.array([np.nan, 0, 0, np.inf, np.inf, np.inf, 5, 5, 5], np.float32)
+    fb, _ = ref.ils_select_blocks(d, 3, 3)
+    assert fb.tolist() == [2, 1, 0]
+
+
+def test_blocks_bad_arguments_rejected():
+    d = np.ones(10, np.float32)
+    for group, n in ((0, 1), (-1, 1), (3, 5), (3, -1)):
+        with pytest.raises(ValueError):
+            ref.ils_select_blocks(d, group, n)
+    fb, mask = ref.ils_select_blocks(np.zeros(0, np.float32), 4, 0)
+    assert fb.size == 0 and mask.size == 0
