@@ -413,11 +413,23 @@ int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, const float *sc
  *                         lower index; NaN orders after +inf.  mask (uint8[L]
  *                         or NULL) gets 1 for frozen, 0 for active.
  *  slimfit_ils_update   : d[i] = new_scores[i] where frozen_mask[i] == 0.
+ *  slimfit_ils_select_blocks : the same selection at the granularity of blocks of
+ *                         `group` consecutive layers (the tensors of one encoder
+ *                         block; the last block may be shorter): a block's
+ *                         distance is the mean of its layers' d, summed in layer
+ *                         order in double; frozen_blocks[0..n_freeze) = the blocks
+ *                         with the smallest means, same ordering rules; mask
+ *                         (uint8[L] or NULL) gets 1 for every layer of a frozen
+ *                         block.  n_freeze <= ceil(L / group).  group = 1 is
+ *                         slimfit_ils_select.
  * ---------------------------------------------------------------------- */
 int32_t slimfit_freeze_count(int32_t L, double F);
 
 int32_t slimfit_ils_select(const float *d, int32_t L, int32_t n_freeze,
                            int32_t *frozen_idx, uint8_t *mask);
+
+int32_t slimfit_ils_select_blocks(const float *d, int32_t L, int32_t group, int32_t n_freeze,
+                                  int32_t *frozen_blocks, uint8_t *mask);
 
 int32_t slimfit_ils_update(float *d, const float *new_scores,
                            const uint8_t *frozen_mask, int32_t L);

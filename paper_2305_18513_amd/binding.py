@@ -36,7 +36,7 @@ EXPORTS = (
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_softmax_backward_pruned", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
     "slimfit_restore_global", "slimfit_layernorm_forward", "slimfit_prune_global_standardized",
     "slimfit_layernorm_backward_pruned", "slimfit_layernorm_forward_quant_pack", "slimfit_layernorm_backward_dequant", "slimfit_layernorm_backward", "slimfit_layernorm_param_grads_workspace", "slimfit_layernorm_param_grads",
-    "slimfit_freeze_count", "slimfit_ils_select",
+    "slimfit_freeze_count", "slimfit_ils_select", "slimfit_ils_select_blocks",
     "slimfit_ils_update", "slimfit_schedule_random", "slimfit_schedule_progressive",
 )
 
@@ -459,6 +459,18 @@ def ils_select(d: np.ndarray, n_freeze: int):
     rc = lib().slimfit_ils_select(C.c_void_p(d.ctypes.data), C.c_int32(d.size), C.c_int32(n_freeze),
                                   C.c_void_p(frozen.ctypes.data), C.c_void_p(mask.ctypes.data))
     _check(rc, "ils_select")
+    return frozen, mask
+
+
+def ils_select_blocks(d: np.ndarray, group: int, n_freeze: int):
+    """ILS over blocks of ``group`` consecutive layers.  Returns (frozen_blocks int32[n_freeze], layer mask uint8[L])."""
+    d = np.ascontiguousarray(d, dtype=np.float32)
+    frozen = np.zeros(max(n_freeze, 0), dtype=np.int32)
+    mask = np.zeros(d.size, dtype=np.uint8)
+    rc = lib().slimfit_ils_select_blocks(C.c_void_p(d.ctypes.data), C.c_int32(d.size), C.c_int32(group),
+                                         C.c_int32(n_freeze), C.c_void_p(frozen.ctypes.data),
+                                         C.c_void_p(mask.ctypes.data))
+    _check(rc, "ils_select_blocks")
     return frozen, mask
 
 

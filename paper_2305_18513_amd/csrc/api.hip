@@ -95,6 +95,41 @@ extern "C" int32_t slimfit_ils_select(const float *d, int32_t L, int32_t n_freez
     return SLIMFIT_OK;
 }
 
+extern "C" int32_t slimfit_ils_select_blocks(const float *d, int32_t L, int32_t group, int32_t n_freeze,
+                                             int32_t *frozen_blocks, uint8_t *mask)
+{
+    if (L < 0 || group < 1 || n_freeze < 0) return SLIMFIT_ERR_INVALID_ARG;
+    const int32_t nb = (int32_t)(((int64_t)L + group - 1) / group);
+    if (n_freeze > nb || (L > 0 && !d) || (n_freeze > 0 && !frozen_blocks)) return SLIMFIT_ERR_INVALID_ARG;
+    if (mask) std::fill(mask, mask + L, (uint8_t)0);
+    if (n_freeze == 0) return SLIMFIT_OK;
+    auto first_layer = [group](int32_t b) { return (int64_t)b * group; };
+    auto end_layer = [group, L](int32_t b) { return std::min<int64_t>((int64_t)b * group + group, L); };
+    std::vector<double> mean((size_t)nb);
+    for (int32_t b = 0; b < nb; ++b) {
+        double sum = 0.0;                                    // layer order, double
+        for (int64_t i = first_layer(b); i < end_layer(b); ++i) sum += (double)d[i];
+        mean[(size_t)b] = sum / (double)(end_layer(b) - first_layer(b));
+    }
+    std::vector<int32_t> order((size_t)nb);
+    std::iota(order.begin(), order.end(), 0);
+    auto before = [&mean](int32_t a, int32_t b) {
+        const double ma = mean[(size_t)a], mb = mean[(size_t)b];
+        const bool na = std::isnan(ma), nb_ = std::isnan(mb);
+        if (na != nb_) return nb_;
+        if (!na && ma != mb) return ma < mb;
+        return a < b;
+    };
+    std::partial_sort(order.begin(), order.begin() + n_freeze, order.end(), before);
+    for (int32_t s = 0; s < n_freeze; ++s) {
+        const int32_t b = order[(size_t)s];
+        frozen_blocks[s] = b;
+        if (mask)
+            for (int64_t i = first_layer(b); i < end_layer(b); ++i) mask[i] = 1;
+    }
+    return SLIMFIT_OK;
+}
+
 extern "C" int32_t slimfit_ils_update(float *d, const float *new_scores, const uint8_t *frozen_mask, int32_t L)
 {
     if (L < 0) return SLIMFIT_ERR_INVALID_ARG;

@@ -207,3 +207,25 @@ def test_schedule_variants_match_the_oracle():
             sf.schedule_random(bad[0], bad[1], 0, 0)
         with pytest.raises(sf.SlimfitError):
             sf.schedule_progressive(*bad)
+
+
+def test_block_ils_matches_the_oracle():
+    """ILS over blocks of consecutive layers (host code): the library against the oracle."""
+    rng = np.random.default_rng(3)
+    for L, group in ((1, 1), (8, 2), (74, 6), (198, 8), (25, 8), (7, 10), (192, 8)):
+        for trial in range(3):
+            d = (10.0 ** rng.uniform(-6, -2, L)).astype(np.float32)
+            if trial == 1:
+                d = np.round(d * 1e4).astype(np.float32)                 # many ties
+            if trial == 2 and L > 3:
+                d[rng.integers(0, L)] = np.nan
+                d[rng.integers(0, L)] = np.inf
+            nb = -(-L // group)
+            for n in sorted({0, 1, nb // 2, nb}):
+                gi, gm = sf.ils_select_blocks(d, group, n)
+                oi, om = ref.ils_select_blocks(d, group, n)
+                np.testing.assert_array_equal(gi, oi)
+                np.testing.assert_array_equal(gm, om)
+    for group, n in ((0, 1), (3, 5), (3, -1)):
+        with pytest.raises(sf.SlimfitError):
+            sf.ils_select_blocks(np.ones(10, np.float32), group, n)
