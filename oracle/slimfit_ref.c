@@ -17,7 +17,9 @@
  * Return value: 0 on success, a negative number for an argument the
  * definition does not cover.
  *
- * Pins (tests/, -m "not gpu"): Fig. 4 replay for the ILS pair; closed forms,
+ * Pins (tests/, -m "not gpu"): Fig. 4 replay for the ILS pair (and, with
+ * blocks of one layer, for its block-granularity variant, which is further
+ * pinned by NumPy means with a stable argsort and a worked example); closed forms,
  * scaling/sign/permutation invariants and a NumPy float64 one-liner for
  * Eq. 1; exhaustive grid against Alg. 2 in double, half-step bound,
  * idempotence and pack/unpack identity for the quantiser; brute-force
