@@ -98,6 +98,28 @@ def layer_delta(w_prev, w_cur, cur_is_delta=False, eps=0.0, threads=1):
     return out
 
 
+def apply_update_layer_delta(w, delta, eps=0.0, threads=1):
+    """Eq. 1 from (W^{t-1}, update) while the update is applied.  Returns (d float32[L], list of new weights);
+    the inputs are left untouched."""
+    L = len(w)
+    assert len(delta) == L
+    w = [np.array(a, copy=True).reshape(-1) for a in w]
+    delta = [np.ascontiguousarray(a).reshape(-1) for a in delta]
+    out = np.zeros(L, dtype=np.float32)
+    if L == 0:
+        return out, w
+    wdt, ddt = _dt(w[0]), _dt(delta[0])
+    for a, b in zip(w, delta):
+        assert _dt(a) == wdt and _dt(b) == ddt and a.size == b.size
+    numel = np.array([a.size for a in w], dtype=np.int64)
+    pw = (C.c_void_p * L)(*[a.ctypes.data for a in w])
+    pd = (C.c_void_p * L)(*[a.ctypes.data for a in delta])
+    rc = lib().slimfit_ref_apply_update_layer_delta(
+        pw, C.c_int(wdt), pd, C.c_int(ddt), _ptr(numel), C.c_int(L), C.c_float(eps), _ptr(out), C.c_int(threads))
+    _check(rc, "apply_update_layer_delta")
+    return out, w
+
+
 def packed_bytes(n, bits):
     return (n * bits + 7) // 8
 

@@ -144,6 +144,39 @@ int slimfit_ref_layer_delta(const void *const *w_prev, int prev_dt,
     return REF_OK;
 }
 
+/* Eq. 1 measured while the optimizer's update is applied: the caller   */
+/* hands over W^{t-1} and the update delta = W^t - W^{t-1}; the score is */
+/* that of the function above with cur_is_delta, and the weights become  */
+/* W^t = W^{t-1} + delta -- one fp32 addition on the widened operands,   */
+/* rounded once more to bf16 for bf16 weights.  No copy of W^{t-1} has   */
+/* to be kept for the score.                                             */
+int slimfit_ref_apply_update_layer_delta(void *const *w, int w_dt,
+                                         const void *const *delta, int delta_dt,
+                                         const int64_t *numel, int L, float eps,
+                                         float *d_out, int threads)
+{
+    if (L < 0 || !dtype_ok(w_dt) || !dtype_ok(delta_dt) || !(eps >= 0.0f))
+        return REF_BAD;
+    if (L == 0)
+        return REF_OK;
+    if (!w || !delta || !numel || !d_out)
+        return REF_BAD;
+    for (int i = 0; i < L; ++i)
+        if (numel[i] < 0 || (numel[i] > 0 && (!w[i] || !delta[i])))
+            return REF_BAD;
+    if (threads < 1)
+        threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+    for (int i = 0; i < L; ++i) {
+        d_out[i] = layer_distance(w[i], w_dt, delta[i], delta_dt, 1, numel[i], eps);
+        for (int64_t j = 0; j < numel[i]; ++j) {
+            volatile float sum = load_elem(w[i], w_dt, j) + load_elem(delta[i], delta_dt, j);
+            store_elem(w[i], w_dt, j, sum);
+        }
+    }
+    return REF_OK;
+}
+
 /* ------------------------------------------------------------------ */
 /* Alg. 2 -- fixed-point conversion, plus the per-block-scale variant   */
 /*   quantise:   y = clamp(round(x * 2^fb), -2^(b-1), 2^(b-1)-1)        */

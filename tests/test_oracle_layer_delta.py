@@ -130,3 +130,50 @@ def test_negative_eps_rejected():
     w = _f32([1.0])
     with pytest.raises(ValueError):
         ref.layer_delta([w], [w], eps=-1.0)
+
+
+# ---- the score measured while the update is applied ---------------------------------------------------------------
+
+def test_apply_update_new_weights_are_one_fp32_addition():
+    rng = np.random.default_rng(21)
+    ws = [_f32(rng.standard_normal(n) * 0.02) for n in (1, 7, 4099)]
+    ds = [_f32(rng.standard_normal(w.size) * 1e-4) for w in ws]
+    d, new = ref.apply_update_layer_delta(ws, ds)
+    for w, dl, nw in zip(ws, ds, new):
+        np.testing.assert_array_equal(nw.view(np.uint32), (w + dl).view(np.uint32))        # NumPy float32 addition
+    np.testing.assert_array_equal(d, ref.layer_delta(ws, ds, cur_is_delta=True))
+    # hand value: |0.5/2| and |-1/4| -> mean 0.25; new weights 2.5 and 3
+    d, new = ref.apply_update_layer_delta([_f32([2.0, 4.0])], [_f32([0.5, -1.0])])
+    assert d[0] == np.float32(0.25) and new[0].tolist() == [2.5, 3.0]
+
+
+def test_apply_update_agrees_with_the_two_tensor_form_when_the_addition_is_exact():
+    rng = np.random.default_rng(22)
+    w = _f32(rng.integers(1, 1000, 5000)) / np.float32(64)          # few mantissa bits: w + delta is exact
+    dl = _f32(rng.integers(-50, 50, 5000)) / np.float32(64)
+    d, new = ref.apply_update_layer_delta([w], [dl])
+    assert np.all(new[0].astype(np.float64) == w.astype(np.float64) + dl.astype(np.float64))
+    assert d[0] == ref.layer_delta([w], [new[0]])[0]
+
+
+def test_apply_update_bf16_weights_round_once_more():
+    rng = np.random.default_rng(23)
+    w32 = _f32(rng.standard_normal(3000) * 0.02)
+    wb = torch.from_numpy(w32).to(torch.bfloat16)
+    dl = _f32(rng.standard_normal(3000) * 1e-3)
+    wbits = wb.view(torch.int16).numpy().view(np.uint16)
+    d, new = ref.apply_update_layer_delta([wbits], [dl])
+    want = (wb.float() + torch.from_numpy(dl)).to(torch.bfloat16)                           # library rounding
+    np.testing.assert_array_equal(new[0], want.view(torch.int16).numpy().view(np.uint16))
+    np.testing.assert_array_equal(d, ref.layer_delta([wbits], [dl], cur_is_delta=True))
+    # inputs untouched
+    np.testing.assert_array_equal(wbits, wb.view(torch.int16).numpy().view(np.uint16))
+
+
+def test_apply_update_bad_arguments_and_empty():
+    d, new = ref.apply_update_layer_delta([], [])
+    assert d.size == 0 and new == []
+    d, new = ref.apply_update_layer_delta([_f32([])], [_f32([])])
+    assert new[0].size == 0
+    with pytest.raises(ValueError):
+        ref.apply_update_layer_delta([_f32([1.0])], [_f32([1.0])], eps=-1.0)
