@@ -419,6 +419,30 @@ def main() -> int:
                                 "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
             del lny, mu, rs, pv, pi, rp, lws
 
+        # Eq. 1 taken while the update is applied (weights read, update read, weights written: one pass instead of
+        # the optimizer's own apply pass, a kept copy of the old weights and the scoring pass); on copies, so that
+        # the step's own tensors stay as generated
+        w_tmp = [p.clone() for p in prev]
+        upd = [c.clone() for c in cur] if cfg.delta_given else [c - p.float() for p, c in zip(prev, cur)]
+        ws_apply = torch.empty_like(ws)
+        d_apply = torch.empty_like(d_dev)
+        sf.layer_delta_plan(w_tmp, upd, ws_apply)
+        for _ in range(2):
+            sf.layer_delta_apply_run(numel, pdt, sf.F32, 0.0, d_apply, ws_apply)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(8)]
+        for a, b in ev:
+            a.record()
+            sf.layer_delta_apply_run(numel, pdt, sf.F32, 0.0, d_apply, ws_apply)
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+        nb = sum(numel) * (2 * esize(cfg.w_dtype) + 4) + 4 * L
+        extras["apply_update_layer_delta[all weight tensors]"] = {
+            "median_ms": round(ms, 5), "bytes_per_launch": nb, "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del w_tmp, upd, ws_apply, d_apply
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)

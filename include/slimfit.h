@@ -121,6 +121,38 @@ int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_dt,
                             void *stream);
 
 /* ------------------------------------------------------------------------
+ * (a') Eq. 1 measured while the optimizer's update is applied.  The paper's
+ *     formulation compares W^t with a kept copy of W^{t-1}; when the optimizer
+ *     hands over its update delta_i = W_i^t - W_i^{t-1} instead of applying it,
+ *     one pass can do both: take the terms |delta| / |W^{t-1}| and overwrite
+ *     W^{t-1} with W^t = W^{t-1} + delta.  No copy of the previous weights is
+ *     kept and the update costs no pass of its own.
+ *
+ *  w     : HOST array of L DEVICE pointers to the weights (numel[i] elements of
+ *          w_dt, 16-byte aligned); on return of the kernels they hold W^t: one
+ *          fp32 addition per element on the widened operands, bf16 weights
+ *          rounded to nearest even once more.
+ *  delta : HOST array of L DEVICE pointers to the updates (delta_dt), read only;
+ *          must not alias w.
+ *  d_out, eps, workspace, numel, arithmetic of the score: as in (a) with
+ *          cur_is_delta != 0.
+ *
+ *  slimfit_apply_update_layer_delta = plan + run.  slimfit_layer_delta_apply_run
+ *  runs on a plan written by slimfit_layer_delta_plan(w as w_prev, delta as
+ *  w_cur): it WRITES through the planned w_prev pointers.  Without a matching
+ *  plan d_out is NaN and no weight is touched.
+ * ---------------------------------------------------------------------- */
+int32_t slimfit_layer_delta_apply_run(const int64_t *numel, int32_t L, int32_t w_dt, int32_t delta_dt,
+                                      float eps, float *d_out,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+int32_t slimfit_apply_update_layer_delta(void *const *w, int32_t w_dt,
+                                         const void *const *delta, int32_t delta_dt,
+                                         const int64_t *numel, int32_t L, float eps,
+                                         float *d_out, void *workspace, size_t workspace_bytes,
+                                         void *stream);
+
+/* ------------------------------------------------------------------------
  * (b) Low-bit caching of saved activations -- Alg. 2 (appendix on the
  *     conversion between fixed point and fp32), Sec. 4 (8 bits = 4 integer +
  *     4 fractional for the imbalanced layer) and Sec. 5 (4 bits for GELU, two

@@ -30,7 +30,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_HIP, ERR
 EXPORTS = (
     "slimfit_status_string", "slimfit_version", "slimfit_set_pointer_checks",
     "slimfit_layer_delta_workspace", "slimfit_layer_delta_plan",
-    "slimfit_layer_delta_run", "slimfit_layer_delta",
+    "slimfit_layer_delta_run", "slimfit_layer_delta", "slimfit_layer_delta_apply_run", "slimfit_apply_update_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_softmax_backward_pruned", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
@@ -186,6 +186,35 @@ def layer_delta(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor], c
         C.c_float(eps), _dev(d_out), _dev(workspace),
         C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
     _check(rc, "layer_delta")
+
+
+def layer_delta_apply_run(numel: Sequence[int], w_dt: int, delta_dt: int, eps: float, d_out: torch.Tensor,
+                          workspace: torch.Tensor, stream=None) -> None:
+    """Score + apply on a plan made by layer_delta_plan(weights, updates); overwrites the planned weights."""
+    n = _numel_array(numel)
+    _require(d_out.dtype == torch.float32 and d_out.numel() >= n.size)
+    rc = lib().slimfit_layer_delta_apply_run(
+        C.c_void_p(n.ctypes.data), C.c_int32(n.size), C.c_int32(w_dt), C.c_int32(delta_dt), C.c_float(eps),
+        _dev(d_out), _dev(workspace), C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(rc, "layer_delta_apply_run")
+
+
+def apply_update_layer_delta(w: Sequence[torch.Tensor], delta: Sequence[torch.Tensor], eps: float,
+                             d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """d_out[i] = mean |delta_i / w_i| and w_i += delta_i, one pass over both."""
+    L = len(w)
+    _require(len(delta) == L)
+    for a, b in zip(w, delta):
+        _require(a.numel() == b.numel())
+    numel = _numel_array([t.numel() for t in w])
+    wdt = _dt(w[0]) if L else F32
+    ddt = _dt(delta[0]) if L else F32
+    _require(d_out.dtype == torch.float32 and d_out.numel() >= L)
+    rc = lib().slimfit_apply_update_layer_delta(
+        _ptr_array(w), C.c_int32(wdt), _ptr_array(delta), C.c_int32(ddt), C.c_void_p(numel.ctypes.data),
+        C.c_int32(L), C.c_float(eps), _dev(d_out), _dev(workspace),
+        C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(rc, "apply_update_layer_delta")
 
 
 # ---------------------------------------------------------------- (b) Alg. 2

@@ -28,6 +28,14 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kChunk = SLIMFIT_DELTA_CHUNK;  // elements per workgroup
 constexpr bool kNT = SLIMFIT_DELTA_NT != 0;
+#ifndef SLIMFIT_DELTA_APPLY_NT
+#define SLIMFIT_DELTA_APPLY_NT 1             // the new weights are not read again before the caches have turned over
+#endif
+constexpr bool kApplyNT = SLIMFIT_DELTA_APPLY_NT != 0;
+#ifndef SLIMFIT_DELTA_APPLY_SPLIT
+#define SLIMFIT_DELTA_APPLY_SPLIT 1         // 2 or 4 parts per chunk: no faster
+#endif
+constexpr int kApplySplit = SLIMFIT_DELTA_APPLY_SPLIT;
 constexpr int kVecPerThread = kChunk / 4 / kThreads;
 constexpr uint32_t kMagic = 0x534C4644u;     // "SLFD"
 constexpr int kPlanBatch = 32;
@@ -81,6 +89,24 @@ template <> struct Load4<uint16_t> {
     __device__ static float one(const uint16_t *p) { return bf16_widen(*p); }
 };
 
+// W^t = W^{t-1} + delta written back over W^{t-1}: one fp32 addition, bf16 weights rounded once more
+template <typename T> struct Store4;
+template <> struct Store4<float> {
+    __device__ static void vec(float *p, const float (&f)[4])
+    {
+        store_global<kApplyNT>(reinterpret_cast<f32x4 *>(p), f32x4{f[0], f[1], f[2], f[3]});
+    }
+    __device__ static void one(float *p, float v) { *p = v; }
+};
+template <> struct Store4<uint16_t> {
+    __device__ static void vec(uint16_t *p, const float (&f)[4])
+    {
+        store_global<kApplyNT>(reinterpret_cast<u32x2 *>(p), u32x2{bf16_narrow(f[0]) | (bf16_narrow(f[1]) << 16),
+                                                                   bf16_narrow(f[2]) | (bf16_narrow(f[3]) << 16)});
+    }
+    __device__ static void one(uint16_t *p, float v) { *p = (uint16_t)bf16_narrow(v); }
+};
+
 template <bool IS_DELTA>
 __device__ __forceinline__ float term(float wp, float c, float eps)
 {
@@ -104,7 +130,9 @@ __device__ __forceinline__ double block_sum(double v, double *lds)
     return s;
 }
 
-template <typename TP, typename TC, bool IS_DELTA>
+// APPLY (with IS_DELTA): the chunk of W^{t-1} is overwritten with W^{t-1} + delta after its terms are taken,
+// so the score needs no copy of the previous weights and the update costs no pass of its own.
+template <typename TP, typename TC, bool IS_DELTA, bool APPLY = false>
 __global__ __launch_bounds__(kThreads) void layer_delta_partials_kernel(const char *__restrict__ ws, int32_t L,
                                                                         int64_t total_chunks, float eps,
                                                                         double *__restrict__ partials)
@@ -133,20 +161,41 @@ __global__ __launch_bounds__(kThreads) void layer_delta_partials_kernel(const ch
 
     double acc = 0.0;
     if (len == kChunk) {
-        float p[kVecPerThread][4], c[kVecPerThread][4];
+        // APPLY: the chunk goes in kApplySplit parts, and each part's new weights leave before its
+        // terms (a division and an fp64 addition each) are worked out
+        constexpr int kParts = APPLY ? kApplySplit : 1;
+        constexpr int kPer = kVecPerThread / kParts;
 #pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-            const int v = (i * kThreads + threadIdx.x) * 4;
-            Load4<TP>::vec(wp + v, p[i]);
-            Load4<TC>::vec(wc + v, c[i]);
+        for (int part = 0; part < kParts; ++part) {
+            float p[kPer][4], c[kPer][4];
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int v = ((part * kPer + i) * kThreads + threadIdx.x) * 4;
+                Load4<TP>::vec(wp + v, p[i]);
+                Load4<TC>::vec(wc + v, c[i]);
+            }
+            if (APPLY) {
+                TP *wn = const_cast<TP *>(wp);
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) {
+                    const int v = ((part * kPer + i) * kThreads + threadIdx.x) * 4;
+                    float n4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) n4[j] = p[i][j] + c[i][j];
+                    Store4<TP>::vec(wn + v, n4);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kPer; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc += (double)term<IS_DELTA>(p[i][j], c[i][j], eps);
         }
-#pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc += (double)term<IS_DELTA>(p[i][j], c[i][j], eps);
     } else {
-        for (int64_t j = threadIdx.x; j < len; j += kThreads)
-            acc += (double)term<IS_DELTA>(Load4<TP>::one(wp + j), Load4<TC>::one(wc + j), eps);
+        for (int64_t j = threadIdx.x; j < len; j += kThreads) {
+            const float a = Load4<TP>::one(wp + j), b = Load4<TC>::one(wc + j);
+            acc += (double)term<IS_DELTA>(a, b, eps);
+            if (APPLY) Store4<TP>::one(const_cast<TP *>(wp) + j, a + b);
+        }
     }
     const double s = block_sum(acc, lds);
     if (threadIdx.x == 0) partials[chunk] = s;
@@ -204,10 +253,12 @@ int32_t check_workspace(const Layout &lay, const void *ws, size_t ws_bytes)
 }
 
 template <typename TP, typename TC>
-void launch_partials(bool is_delta, unsigned grid, hipStream_t st, const char *ws, int32_t L, int64_t chunks, float eps,
-                     double *partials)
+void launch_partials(bool is_delta, bool apply, unsigned grid, hipStream_t st, const char *ws, int32_t L, int64_t chunks,
+                     float eps, double *partials)
 {
-    if (is_delta)
+    if (apply)
+        layer_delta_partials_kernel<TP, TC, true, true><<<grid, kThreads, 0, st>>>(ws, L, chunks, eps, partials);
+    else if (is_delta)
         layer_delta_partials_kernel<TP, TC, true><<<grid, kThreads, 0, st>>>(ws, L, chunks, eps, partials);
     else
         layer_delta_partials_kernel<TP, TC, false><<<grid, kThreads, 0, st>>>(ws, L, chunks, eps, partials);
@@ -273,9 +324,8 @@ extern "C" int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t p
     return launch_status();
 }
 
-extern "C" int32_t slimfit_layer_delta_run(const int64_t *numel, int32_t L, int32_t prev_dt, int32_t cur_dt,
-                                           int32_t cur_is_delta, float eps, float *d_out, void *workspace,
-                                           size_t workspace_bytes, void *stream)
+static int32_t run_entry(const int64_t *numel, int32_t L, int32_t prev_dt, int32_t cur_dt, int32_t cur_is_delta, bool apply,
+                         float eps, float *d_out, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(prev_dt) || !dtype_ok(cur_dt) || !(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     Layout lay;
@@ -294,16 +344,29 @@ extern "C" int32_t slimfit_layer_delta_run(const int64_t *numel, int32_t L, int3
     const bool is_delta = cur_is_delta != 0;
     if (grid > 0) {
         if (prev_dt == SLIMFIT_F32 && cur_dt == SLIMFIT_F32)
-            launch_partials<float, float>(is_delta, grid, st, ws, L, lay.total_chunks, eps, partials);
+            launch_partials<float, float>(is_delta, apply, grid, st, ws, L, lay.total_chunks, eps, partials);
         else if (prev_dt == SLIMFIT_BF16 && cur_dt == SLIMFIT_F32)
-            launch_partials<uint16_t, float>(is_delta, grid, st, ws, L, lay.total_chunks, eps, partials);
+            launch_partials<uint16_t, float>(is_delta, apply, grid, st, ws, L, lay.total_chunks, eps, partials);
         else if (prev_dt == SLIMFIT_F32 && cur_dt == SLIMFIT_BF16)
-            launch_partials<float, uint16_t>(is_delta, grid, st, ws, L, lay.total_chunks, eps, partials);
+            launch_partials<float, uint16_t>(is_delta, apply, grid, st, ws, L, lay.total_chunks, eps, partials);
         else
-            launch_partials<uint16_t, uint16_t>(is_delta, grid, st, ws, L, lay.total_chunks, eps, partials);
+            launch_partials<uint16_t, uint16_t>(is_delta, apply, grid, st, ws, L, lay.total_chunks, eps, partials);
     }
     layer_delta_finish_kernel<<<(unsigned)L, kWave, 0, st>>>(ws, L, lay.total_chunks, prev_dt, cur_dt, partials, d_out);
     return launch_status();
+}
+
+extern "C" int32_t slimfit_layer_delta_run(const int64_t *numel, int32_t L, int32_t prev_dt, int32_t cur_dt,
+                                           int32_t cur_is_delta, float eps, float *d_out, void *workspace,
+                                           size_t workspace_bytes, void *stream)
+{
+    return run_entry(numel, L, prev_dt, cur_dt, cur_is_delta, false, eps, d_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t slimfit_layer_delta_apply_run(const int64_t *numel, int32_t L, int32_t w_dt, int32_t delta_dt, float eps,
+                                                 float *d_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_entry(numel, L, w_dt, delta_dt, 1, true, eps, d_out, workspace, workspace_bytes, stream);
 }
 
 extern "C" int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_dt, const void *const *w_cur,
@@ -319,4 +382,20 @@ extern "C" int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_d
     if (rc != SLIMFIT_OK) return rc;
     return slimfit_layer_delta_run(numel, L, prev_dt, cur_dt, cur_is_delta, eps, d_out, workspace, workspace_bytes,
                                    stream);
+}
+
+extern "C" int32_t slimfit_apply_update_layer_delta(void *const *w, int32_t w_dt, const void *const *delta,
+                                                    int32_t delta_dt, const int64_t *numel, int32_t L, float eps,
+                                                    float *d_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
+    if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
+    if (L > 0 && !aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;
+    if (L > 0 && check_device_range(d_out, sizeof(float) * (size_t)L) != SLIMFIT_OK) return SLIMFIT_ERR_POINTER;
+    if (L > 0 && w && delta && numel)
+        for (int32_t i = 0; i < L; ++i)
+            if (numel[i] > 0 && w[i] == delta[i]) return SLIMFIT_ERR_INVALID_ARG;      // the update must not alias the weights
+    int32_t rc = slimfit_layer_delta_plan(w, w_dt, delta, delta_dt, numel, L, workspace, workspace_bytes, stream);
+    if (rc != SLIMFIT_OK) return rc;
+    return slimfit_layer_delta_apply_run(numel, L, w_dt, delta_dt, eps, d_out, workspace, workspace_bytes, stream);
 }
