@@ -371,53 +371,57 @@ def main() -> int:
                             "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                             "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del probs
-        # LayerNorm around the pruned cache (fp32 tensors only): forward with row statistics, 10 % of the
-        # standardised input kept without storing it, input gradient of the frozen layer from the kept pairs
-        if cfg.act_dtype == torch.float32:
-            H = cfg.hidden
-            lnx = [s.ln[0].view(-1, H) for s in sets]
-            rows_l = lnx[0].shape[0]
-            n_l = rows_l * H
-            k_l = sf.keep_count(n_l, 100000)
-            gam = torch.rand(H, device="cuda") + 0.5
-            bet = torch.rand(H, device="cuda") - 0.5
-            lny = [torch.empty_like(x) for x in lnx]
-            mu = [torch.empty(rows_l, device="cuda") for _ in sets]
-            rs = [torch.empty(rows_l, device="cuda") for _ in sets]
-            pv = [torch.empty(k_l, device="cuda") for _ in sets]
-            pi = [torch.empty(k_l, dtype=torch.int32, device="cuda") for _ in sets]
-            rp = [torch.empty(rows_l + 1, dtype=torch.int32, device="cuda") for _ in sets]
-            lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
-            nb_lq = 8 * n_l + sf.packed_bytes(n_l, bits) + 4 * sf.num_blocks(n_l, block) + 8 * rows_l
-            ln_runs = {
-                "layernorm_forward[ln_in]": (8 * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
-                    lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
-                "prune_global_standardized[ln_in, 10%]": (4 * n_l + 8 * k_l + 12 * rows_l, lambda i:
-                    sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
-                "layernorm_backward_pruned[ln_in]": (8 * n_l + 8 * k_l + 8 * rows_l, lambda i:
-                    sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
-                # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
-                # reads the input anyway, and the input gradient straight from that cache
-                "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
-                    lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
-                "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
-                    sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
-            }
-            for name, (nb, fn) in ln_runs.items():
-                for i in range(len(sets)):
-                    fn(i)
-                torch.cuda.synchronize()
-                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-                for i, (a, b) in enumerate(ev):
-                    a.record()
-                    fn(i % n_sets)
-                    b.record()
-                torch.cuda.synchronize()
-                ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-            del lny, mu, rs, pv, pi, rp, lws
+        # LayerNorm around its caches: forward with row statistics; the pruned cache (fp32 tensors only: 10 % of the
+        # standardised input kept without storing it, input gradient of the frozen layer from the kept pairs); the
+        # quantised cache fused into the forward and backward kernels (fp32 or bf16 tensors)
+        fp32_acts = cfg.act_dtype == torch.float32
+        H = cfg.hidden
+        lnx = [s.ln[0].view(-1, H) for s in sets]
+        rows_l = lnx[0].shape[0]
+        n_l = rows_l * H
+        k_l = sf.keep_count(n_l, 100000)
+        gam = torch.rand(H, device="cuda") + 0.5
+        bet = torch.rand(H, device="cuda") - 0.5
+        lny = [torch.empty_like(x) for x in lnx]
+        mu = [torch.empty(rows_l, device="cuda") for _ in sets]
+        rs = [torch.empty(rows_l, device="cuda") for _ in sets]
+        pv = [torch.empty(k_l, device="cuda") for _ in sets]
+        pi = [torch.empty(k_l, dtype=torch.int32, device="cuda") for _ in sets]
+        rp = [torch.empty(rows_l + 1, dtype=torch.int32, device="cuda") for _ in sets]
+        lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
+        nb_lq = 2 * in_sz * n_l + sf.packed_bytes(n_l, bits) + 4 * sf.num_blocks(n_l, block) + 8 * rows_l
+        ln_runs = {
+            "layernorm_forward[ln_in]": (2 * in_sz * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
+                lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
+        }
+        if fp32_acts:
+            ln_runs["prune_global_standardized[ln_in, 10%]"] = (4 * n_l + 8 * k_l + 12 * rows_l, lambda i:
+                sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws))
+            ln_runs["layernorm_backward_pruned[ln_in]"] = (8 * n_l + 8 * k_l + 8 * rows_l, lambda i:
+                sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i]))
+        ln_runs.update({
+            # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
+            # reads the input anyway, and the input gradient straight from that cache
+            "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
+                lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
+            "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
+                sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
+        })
+        for name, (nb, fn) in ln_runs.items():
+            for i in range(len(sets)):
+                fn(i)
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for i, (a, b) in enumerate(ev):
+                a.record()
+                fn(i % n_sets)
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+            extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                            "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del lny, mu, rs, pv, pi, rp, lws
 
         # Eq. 1 taken while the update is applied (weights read, update read, weights written: one pass instead of
         # the optimizer's own apply pass, a kept copy of the old weights and the scoring pass); on copies, so that

@@ -357,8 +357,14 @@ int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32
  *     largest 10 % of x~ (Alg. 5) and computes its input gradient as
  *        g = gamma * y^ / (H * sqrt(Var x + eps)),
  *        x^ = H * g - sum_H g - x~ * sum_H (g * x~),
- *     every pruned x~ counting as 0.  All tensors fp32, fp32 arithmetic with
- *     fixed-order sums.
+ *     every pruned x~ counting as 0.  fp32 arithmetic with fixed-order sums.
+ *     gamma, beta, the statistics and the parameter gradients are always fp32;
+ *     the entry points that take dt accept x / y / dy / dx as fp32 or bf16 (bf16
+ *     inputs are widened exactly, bf16 outputs are the fp32 results rounded to
+ *     nearest even: one further bf16 rounding on top of the tolerances below).
+ *     The two entry points of the pruned cache itself
+ *     (slimfit_prune_global_standardized, slimfit_layernorm_backward_pruned) take
+ *     fp32 tensors only.
  *
  *  slimfit_layernorm_forward : y, and per row mean = E x and
  *        rstd = 1 / sqrt(Var x + eps).  Against the fp64 values: mean within
@@ -377,12 +383,14 @@ int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32
  *        rstd, gamma and y^ (dy); a pair whose index does not fall in the row
  *        the pointers file it under is skipped.
  *        |d x^| <= 4e-6 * (H * |g| + sum_H |g| + |x~| * sum_H |g * x~|).
- *  x, y, dy, dx : DEVICE float[rows * H], 16-byte aligned, outputs distinct from
- *  inputs; gamma, beta : DEVICE float[H], 16-byte aligned.
- *  4 <= H <= 4096, H % 4 == 0, rows * H < 2^31 (else INVALID_ARG / UNSUPPORTED).
+ *  x, y, dy, dx : DEVICE, rows * H elements of dt, 16-byte aligned, outputs
+ *  distinct from inputs; gamma, beta : DEVICE float[H], 16-byte aligned.
+ *  H <= 4096, a multiple of 4 (fp32) or 8 (bf16), rows * H < 2^31 (else
+ *  INVALID_ARG / UNSUPPORTED).
  * ---------------------------------------------------------------------- */
-int32_t slimfit_layernorm_forward(const float *x, const float *gamma, const float *beta, int64_t rows, int64_t H,
-                                  float eps, float *y, float *mean, float *rstd, void *stream);
+int32_t slimfit_layernorm_forward(const void *x, int32_t dt, const float *gamma, const float *beta,
+                                  int64_t rows, int64_t H, float eps, void *y, float *mean, float *rstd,
+                                  void *stream);
 
 int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, int64_t H,
                                           const float *mean, const float *rstd, int64_t k, int32_t by_magnitude,
@@ -392,8 +400,9 @@ int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, int64_t n, 
 /* Input gradient of an active (not frozen) LayerNorm, Sec. 4: the formula above with every
  * x~ present, x~ = (x - mean[r]) * rstd[r] from the statistics slimfit_layernorm_forward
  * returned; same tolerance as slimfit_layernorm_backward_pruned.  dx must be neither x nor dy. */
-int32_t slimfit_layernorm_backward(const float *x, const float *mean, const float *rstd, const float *gamma,
-                                   const float *dy, int64_t rows, int64_t H, float *dx, void *stream);
+int32_t slimfit_layernorm_backward(const void *x, int32_t dt, const float *mean, const float *rstd,
+                                   const float *gamma, const void *dy, int64_t rows, int64_t H, void *dx,
+                                   void *stream);
 
 /* Parameter gradients of an active (not frozen) LayerNorm, Sec. 4:
  *   gamma^_j = sum over rows of x~_rj * y^_rj,   beta^_j = sum over rows of y^_rj,
@@ -404,8 +413,8 @@ int32_t slimfit_layernorm_backward(const float *x, const float *mean, const floa
  * slimfit_layernorm_param_grads_workspace(rows, H) bytes; contents overwritten. */
 int32_t slimfit_layernorm_param_grads_workspace(int64_t rows, int64_t H, size_t *bytes);
 
-int32_t slimfit_layernorm_param_grads(const float *x, const float *mean, const float *rstd, const float *dy,
-                                      int64_t rows, int64_t H, float *dgamma, float *dbeta,
+int32_t slimfit_layernorm_param_grads(const void *x, int32_t dt, const float *mean, const float *rstd,
+                                      const void *dy, int64_t rows, int64_t H, float *dgamma, float *dbeta,
                                       void *workspace, size_t workspace_bytes, void *stream);
 
 int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *row_ptr, int64_t k,
@@ -414,7 +423,7 @@ int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx,
 
 /* LayerNorm with the low-bit cache of its input (Alg. 2, one scale per block; Sec. 4 and 5) fused in.
  *   slimfit_layernorm_forward_quant_pack : slimfit_layernorm_forward and, from the same read of x,
- *        the codes and scales slimfit_quant_pack(x, F32, rows*H, BLOCK, bits, block) produces --
+ *        the codes and scales slimfit_quant_pack(x, dt, rows*H, BLOCK, bits, block) produces --
  *        bit for bit -- so the input is read once instead of twice.
  *   slimfit_layernorm_backward_dequant   : slimfit_layernorm_backward on x^ = code * scale (one fp32
  *        multiplication, the value slimfit_dequant_unpack would store) without storing x^:
@@ -423,14 +432,15 @@ int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx,
  * bits 4 | 8; block 32 | 64 | 128 | 256 and H % block == 0, so that no block straddles two rows (else
  * UNSUPPORTED).  codes: DEVICE uint8[rows*H*bits/8]; scales: DEVICE float[rows*H/block]; both 16-byte
  * aligned.  Everything else as slimfit_layernorm_forward / slimfit_layernorm_backward. */
-int32_t slimfit_layernorm_forward_quant_pack(const float *x, const float *gamma, const float *beta,
+int32_t slimfit_layernorm_forward_quant_pack(const void *x, int32_t dt, const float *gamma, const float *beta,
                                              int64_t rows, int64_t H, float eps, int32_t bits, int32_t block,
-                                             float *y, float *mean, float *rstd, uint8_t *codes, float *scales,
+                                             void *y, float *mean, float *rstd, uint8_t *codes, float *scales,
                                              void *stream);
 
 int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, const float *scales, int32_t bits, int32_t block,
                                            const float *mean, const float *rstd, const float *gamma,
-                                           const float *dy, int64_t rows, int64_t H, float *dx, void *stream);
+                                           const void *dy, int32_t dt, int64_t rows, int64_t H, void *dx,
+                                           void *stream);
 
 /* ------------------------------------------------------------------------
  * (d) Inter-layer scheduling on the host -- Alg. 1 and Sec. 3.2 / Fig. 4:

@@ -368,12 +368,13 @@ def restore_global(vals: torch.Tensor, idx: torch.Tensor, k: int, out: torch.Ten
 
 def layernorm_forward(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float, y: torch.Tensor,
                       mean: torch.Tensor, rstd: torch.Tensor, stream=None) -> None:
-    _require(x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape)
-    _require(all(t.dtype == torch.float32 for t in (x, gamma, beta, y, mean, rstd)))
+    _require(x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape and y.dtype == x.dtype)
+    _require(all(t.dtype == torch.float32 for t in (gamma, beta, mean, rstd)))
     rows, H = x.shape
     _require(gamma.numel() == H and beta.numel() == H and mean.numel() >= rows and rstd.numel() >= rows)
-    rc = lib().slimfit_layernorm_forward(_dev(x), _dev(gamma), _dev(beta), C.c_int64(rows), C.c_int64(H),
-                                         C.c_float(eps), _dev(y), _dev(mean), _dev(rstd), _stream(stream))
+    rc = lib().slimfit_layernorm_forward(_dev(x), C.c_int32(_dt(x)), _dev(gamma), _dev(beta), C.c_int64(rows),
+                                         C.c_int64(H), C.c_float(eps), _dev(y), _dev(mean), _dev(rstd),
+                                         _stream(stream))
     _check(rc, "layernorm_forward")
 
 
@@ -402,12 +403,12 @@ def layernorm_backward(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tensor, 
                        dy: torch.Tensor, dx: torch.Tensor, stream=None) -> None:
     """Input gradient of an active LayerNorm (every standardised input present)."""
     _require(x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dx.is_contiguous())
-    _require(dy.shape == x.shape and dx.shape == x.shape)
-    _require(all(t.dtype == torch.float32 for t in (x, mean, rstd, gamma, dy, dx)))
+    _require(dy.shape == x.shape and dx.shape == x.shape and dy.dtype == x.dtype and dx.dtype == x.dtype)
+    _require(all(t.dtype == torch.float32 for t in (mean, rstd, gamma)))
     rows, H = x.shape
     _require(mean.numel() >= rows and rstd.numel() >= rows and gamma.numel() == H)
-    rc = lib().slimfit_layernorm_backward(_dev(x), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
-                                          C.c_int64(H), _dev(dx), _stream(stream))
+    rc = lib().slimfit_layernorm_backward(_dev(x), C.c_int32(_dt(x)), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy),
+                                          C.c_int64(rows), C.c_int64(H), _dev(dx), _stream(stream))
     _check(rc, "layernorm_backward")
 
 
@@ -416,12 +417,13 @@ def layernorm_forward_quant_pack(x: torch.Tensor, gamma: torch.Tensor, beta: tor
                                  codes: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
     """layernorm_forward plus, from the same read of x, the codes and scales of quant_pack(x) in BLOCK mode."""
     _require(x.dim() == 2 and x.is_contiguous() and y.is_contiguous() and y.shape == x.shape)
-    _require(all(t.dtype == torch.float32 for t in (x, gamma, beta, y, mean, rstd, scales)) and codes.dtype == torch.uint8)
+    _require(all(t.dtype == torch.float32 for t in (gamma, beta, mean, rstd, scales)) and codes.dtype == torch.uint8)
+    _require(y.dtype == x.dtype)
     rows, H = x.shape
     _require(gamma.numel() == H and beta.numel() == H and mean.numel() >= rows and rstd.numel() >= rows)
     _require(codes.numel() >= rows * H * bits // 8 and scales.numel() >= rows * H // max(block, 1))
     rc = lib().slimfit_layernorm_forward_quant_pack(
-        _dev(x), _dev(gamma), _dev(beta), C.c_int64(rows), C.c_int64(H), C.c_float(eps), C.c_int32(bits),
+        _dev(x), C.c_int32(_dt(x)), _dev(gamma), _dev(beta), C.c_int64(rows), C.c_int64(H), C.c_float(eps), C.c_int32(bits),
         C.c_int32(block), _dev(y), _dev(mean), _dev(rstd), _dev(codes), _dev(scales), _stream(stream))
     _check(rc, "layernorm_forward_quant_pack")
 
@@ -431,13 +433,14 @@ def layernorm_backward_dequant(codes: torch.Tensor, scales: torch.Tensor, bits: 
                                stream=None) -> None:
     """Input gradient of a LayerNorm whose input was cached by layernorm_forward_quant_pack."""
     _require(dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape)
-    _require(all(t.dtype == torch.float32 for t in (scales, mean, rstd, gamma, dy, dx)) and codes.dtype == torch.uint8)
+    _require(all(t.dtype == torch.float32 for t in (scales, mean, rstd, gamma)) and codes.dtype == torch.uint8)
+    _require(dx.dtype == dy.dtype)
     rows, H = dy.shape
     _require(gamma.numel() == H and mean.numel() >= rows and rstd.numel() >= rows)
     _require(codes.numel() >= rows * H * bits // 8 and scales.numel() >= rows * H // max(block, 1))
     rc = lib().slimfit_layernorm_backward_dequant(
         _dev(codes), _dev(scales), C.c_int32(bits), C.c_int32(block), _dev(mean), _dev(rstd), _dev(gamma), _dev(dy),
-        C.c_int64(rows), C.c_int64(H), _dev(dx), _stream(stream))
+        C.c_int32(_dt(dy)), C.c_int64(rows), C.c_int64(H), _dev(dx), _stream(stream))
     _check(rc, "layernorm_backward_dequant")
 
 
@@ -445,8 +448,8 @@ def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tenso
                           dgamma: torch.Tensor, dbeta: torch.Tensor, workspace: Optional[torch.Tensor] = None,
                           stream=None) -> None:
     """gamma^ and beta^ of an active LayerNorm: column sums over the rows of ``x`` / ``dy`` (rows, H)."""
-    _require(x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dy.shape == x.shape)
-    _require(all(t.dtype == torch.float32 for t in (x, mean, rstd, dy, dgamma, dbeta)))
+    _require(x.dim() == 2 and x.is_contiguous() and dy.is_contiguous() and dy.shape == x.shape and dy.dtype == x.dtype)
+    _require(all(t.dtype == torch.float32 for t in (mean, rstd, dgamma, dbeta)))
     rows, H = x.shape
     _require(mean.numel() >= rows and rstd.numel() >= rows and dgamma.numel() == H and dbeta.numel() == H)
     need = C.c_size_t(0)
@@ -455,7 +458,8 @@ def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tenso
     if workspace is None:
         workspace = torch.empty(int(need.value), dtype=torch.uint8, device=x.device)
     rc = lib().slimfit_layernorm_param_grads(
-        _dev(x), _dev(mean), _dev(rstd), _dev(dy), C.c_int64(rows), C.c_int64(H), _dev(dgamma), _dev(dbeta),
+        _dev(x), C.c_int32(_dt(x)), _dev(mean), _dev(rstd), _dev(dy), C.c_int64(rows), C.c_int64(H), _dev(dgamma),
+        _dev(dbeta),
         _dev(workspace), C.c_size_t(workspace.numel()), _stream(stream))
     _check(rc, "layernorm_param_grads")
 

@@ -70,12 +70,12 @@ __device__ __forceinline__ float group_max_f32(float v)
     return v;
 }
 
-// the same with the group size a wave-uniform run-time value (8, 16, 32 or 64)
+// the same with the group size a wave-uniform run-time value (4, 8, 16, 32 or 64)
 __device__ __forceinline__ float group_max_f32_dyn(float v, int G)
 {
     v = fmaxf(v, dpp_f32<kDppXor1>(v));
     v = fmaxf(v, dpp_f32<kDppXor2>(v));
-    v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+    if (G >= 8) v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
     if (G >= 16) v = fmaxf(v, dpp_f32<kDppMirror>(v));
     if (G >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
     if (G >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));

@@ -68,51 +68,148 @@ __device__ __forceinline__ void load_row(const float *__restrict__ row, int nvec
     }
 }
 
-template <int NV>
-__global__ void __launch_bounds__(kThreads)
-layernorm_forward_kernel(const float *__restrict__ x, const float *__restrict__ gamma, const float *__restrict__ beta,
-                         int64_t rows, int H, float eps, float *__restrict__ y, float *__restrict__ mean,
-                         float *__restrict__ rstd)
+// A 16-byte vector of a row as E floats: 4 fp32 elements, or 8 bf16 elements widened (exactly) on the
+// way in and rounded to nearest even on the way out.  gamma / beta / statistics are always fp32.
+template <typename T> struct RowIO;
+template <> struct RowIO<float> {
+    static constexpr int E = 4;
+    __device__ static void load(const float *row, int q, float (&f)[4])
+    {
+        const f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(row) + q);
+        f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
+    }
+    __device__ static void store(float *row, int q, const float (&f)[4])
+    {
+        __builtin_nontemporal_store(f32x4{f[0], f[1], f[2], f[3]}, reinterpret_cast<f32x4 *>(row) + q);
+    }
+};
+template <> struct RowIO<uint16_t> {
+    static constexpr int E = 8;
+    __device__ static void load(const uint16_t *row, int q, float (&f)[8])
+    {
+        const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + q);
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+            f[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static void store(uint16_t *row, int q, const float (&f)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = bf16_narrow(f[2 * i]) | (bf16_narrow(f[2 * i + 1]) << 16);
+        __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4 *>(row) + q);
+    }
+};
+// the fp32 parameters (or any fp32 row) that go with vector q of E elements
+template <int E>
+__device__ __forceinline__ void load_f32(const float *g, int q, float (&f)[E])
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
-    if (r >= rows) return;
-    const int nvec = H / 4;
-    f32x4 v[NV], ga[NV], be[NV];
-    load_row<NV>(x + r * (int64_t)H, nvec, lane, v, true);
-    load_row<NV>(gamma, nvec, lane, ga, false);
-    load_row<NV>(beta, nvec, lane, be, false);
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c) {
+        const f32x4 r = reinterpret_cast<const f32x4 *>(g)[q * (E / 4) + c];
+        f[4 * c] = r.x; f[4 * c + 1] = r.y; f[4 * c + 2] = r.z; f[4 * c + 3] = r.w;
+    }
+}
+// lane's vectors of a row (vectors past the row's end hold zeros)
+template <typename T, int NV>
+__device__ __forceinline__ void load_row_t(const T *row, int nvec, int lane, float (&v)[NV][RowIO<T>::E])
+{
+    constexpr int E = RowIO<T>::E;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[i][e] = 0.0f;
+        if (q < nvec) RowIO<T>::load(row, q, v[i]);
+    }
+}
+template <int E, int NV>
+__device__ __forceinline__ void load_params(const float *g, int nvec, int lane, float (&v)[NV][E])
+{
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = i * kWave + lane;
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[i][e] = 0.0f;
+        if (q < nvec) load_f32<E>(g, q, v[i]);
+    }
+}
+// pairwise sum of a vector's E values, the same tree for every vector
+template <int E>
+__device__ __forceinline__ float sum_vec(const float (&f)[E])
+{
+    float s = (f[0] + f[1]) + (f[2] + f[3]);
+    if constexpr (E == 8) s += (f[4] + f[5]) + (f[6] + f[7]);
+    return s;
+}
 
+// Shared front end of the two forward kernels: statistics of the row held in v.
+template <int E, int NV>
+__device__ __forceinline__ void row_statistics(const float (&v)[NV][E], int nvec, int lane, int H, float eps, float &mu,
+                                               float &rs)
+{
     float part = 0.0f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) part += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    const float mu = wave_sum_f32(part) / (float)H;
+    for (int i = 0; i < NV; ++i) part += sum_vec<E>(v[i]);
+    mu = wave_sum_f32(part) / (float)H;
     part = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const bool in = i * kWave + lane < nvec;             // padding vectors must not add mu^2
-        const float a = v[i].x - mu, b = v[i].y - mu, c = v[i].z - mu, d = v[i].w - mu;
-        part += in ? (a * a + b * b) + (c * c + d * d) : 0.0f;
+        float sq[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const float d = v[i][e] - mu;
+            sq[e] = d * d;
+        }
+        part += in ? sum_vec<E>(sq) : 0.0f;
     }
     const float var = wave_sum_f32(part) / (float)H;
-    const float rs = 1.0f / __builtin_sqrtf(var + eps);
-    if (lane == 0) {
-        mean[r] = mu;
-        rstd[r] = rs;
-    }
-    f32x4 *dst = reinterpret_cast<f32x4 *>(y + r * (int64_t)H);
+    rs = 1.0f / __builtin_sqrtf(var + eps);
+}
+template <typename T, int NV>
+__device__ __forceinline__ void store_normalised(T *yrow, const float (&v)[NV][RowIO<T>::E],
+                                                 const float (&ga)[NV][RowIO<T>::E], const float (&be)[NV][RowIO<T>::E],
+                                                 int nvec, int lane, float mu, float rs)
+{
+    constexpr int E = RowIO<T>::E;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
         if (q < nvec) {
-            f32x4 o;
-            o.x = ((v[i].x - mu) * rs) * ga[i].x + be[i].x;
-            o.y = ((v[i].y - mu) * rs) * ga[i].y + be[i].y;
-            o.z = ((v[i].z - mu) * rs) * ga[i].z + be[i].z;
-            o.w = ((v[i].w - mu) * rs) * ga[i].w + be[i].w;
-            __builtin_nontemporal_store(o, dst + q);
+            float o[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[e] = ((v[i][e] - mu) * rs) * ga[i][e] + be[i][e];
+            RowIO<T>::store(yrow, q, o);
         }
     }
+}
+
+template <typename T, int NV>
+__global__ void __launch_bounds__(kThreads)
+layernorm_forward_kernel(const T *__restrict__ x, const float *__restrict__ gamma, const float *__restrict__ beta,
+                         int64_t rows, int H, float eps, T *__restrict__ y, float *__restrict__ mean,
+                         float *__restrict__ rstd)
+{
+    constexpr int E = RowIO<T>::E;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int nvec = H / E;
+    float v[NV][E], ga[NV][E], be[NV][E];
+    load_row_t<T, NV>(x + r * (int64_t)H, nvec, lane, v);
+    load_params<E, NV>(gamma, nvec, lane, ga);
+    load_params<E, NV>(beta, nvec, lane, be);
+    float mu, rs;
+    row_statistics<E, NV>(v, nvec, lane, H, eps, mu, rs);
+    if (lane == 0) {
+        mean[r] = mu;
+        rstd[r] = rs;
+    }
+    store_normalised<T, NV>(y + r * (int64_t)H, v, ga, be, nvec, lane, mu, rs);
 }
 
 template <int NV>
@@ -212,53 +309,64 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
 }
 
 // ---- input gradient of an active LayerNorm: the row formula with every x~ present ----------
-template <int NV>
-__global__ void __launch_bounds__(kThreads)
-layernorm_backward_kernel(const float *__restrict__ x, const float *__restrict__ mean, const float *__restrict__ rstd,
-                          const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
-                          float *__restrict__ dx)
+// Shared back end of the two dense backward kernels: xt holds x~ (zeros in padding vectors), g holds y^.
+template <typename T, int NV>
+__device__ __forceinline__ void backward_from_xt(float (&xt)[NV][RowIO<T>::E], float (&g)[NV][RowIO<T>::E],
+                                                 const float (&ga)[NV][RowIO<T>::E], int nvec, int lane, int H, float rs,
+                                                 T *dxrow)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
-    if (r >= rows) return;
-    const int nvec = H / 4;
-    f32x4 xt[NV], g[NV], ga[NV];
-    load_row<NV>(x + r * (int64_t)H, nvec, lane, xt, true);
-    load_row<NV>(dy + r * (int64_t)H, nvec, lane, g, true);
-    load_row<NV>(gamma, nvec, lane, ga, false);
-    const float mu = mean[r], rs = rstd[r];
+    constexpr int E = RowIO<T>::E;
     const float scale = rs / (float)H;
     float part_g = 0.0f, part_gx = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const bool in = i * kWave + lane < nvec;                 // padding vectors hold zeros: x~ must be 0 there too
-        xt[i].x = in ? (xt[i].x - mu) * rs : 0.0f;
-        xt[i].y = in ? (xt[i].y - mu) * rs : 0.0f;
-        xt[i].z = in ? (xt[i].z - mu) * rs : 0.0f;
-        xt[i].w = in ? (xt[i].w - mu) * rs : 0.0f;
-        g[i].x = (ga[i].x * g[i].x) * scale;
-        g[i].y = (ga[i].y * g[i].y) * scale;
-        g[i].z = (ga[i].z * g[i].z) * scale;
-        g[i].w = (ga[i].w * g[i].w) * scale;
-        part_g += (g[i].x + g[i].y) + (g[i].z + g[i].w);
-        part_gx += (g[i].x * xt[i].x + g[i].y * xt[i].y) + (g[i].z * xt[i].z + g[i].w * xt[i].w);
+        float gx[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            g[i][e] = (ga[i][e] * g[i][e]) * scale;
+            gx[e] = g[i][e] * xt[i][e];
+        }
+        part_g += sum_vec<E>(g[i]);
+        part_gx += sum_vec<E>(gx);
     }
     const float sum_g = wave_sum_f32(part_g);
     const float sum_gx = wave_sum_f32(part_gx);
     const float fH = (float)H;
-    f32x4 *dst = reinterpret_cast<f32x4 *>(dx + r * (int64_t)H);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
         if (q < nvec) {
-            f32x4 o;
-            o.x = (fH * g[i].x - sum_g) - xt[i].x * sum_gx;
-            o.y = (fH * g[i].y - sum_g) - xt[i].y * sum_gx;
-            o.z = (fH * g[i].z - sum_g) - xt[i].z * sum_gx;
-            o.w = (fH * g[i].w - sum_g) - xt[i].w * sum_gx;
-            __builtin_nontemporal_store(o, dst + q);
+            float o[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[e] = (fH * g[i][e] - sum_g) - xt[i][e] * sum_gx;
+            RowIO<T>::store(dxrow, q, o);
         }
     }
+}
+
+template <typename T, int NV>
+__global__ void __launch_bounds__(kThreads)
+layernorm_backward_kernel(const T *__restrict__ x, const float *__restrict__ mean, const float *__restrict__ rstd,
+                          const float *__restrict__ gamma, const T *__restrict__ dy, int64_t rows, int H,
+                          T *__restrict__ dx)
+{
+    constexpr int E = RowIO<T>::E;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int nvec = H / E;
+    float xt[NV][E], g[NV][E], ga[NV][E];
+    load_row_t<T, NV>(x + r * (int64_t)H, nvec, lane, xt);
+    load_row_t<T, NV>(dy + r * (int64_t)H, nvec, lane, g);
+    load_params<E, NV>(gamma, nvec, lane, ga);
+    const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const bool in = i * kWave + lane < nvec;                 // padding vectors hold zeros: x~ must be 0 there too
+#pragma unroll
+        for (int e = 0; e < E; ++e) xt[i][e] = in ? (xt[i][e] - mu) * rs : 0.0f;
+    }
+    backward_from_xt<T, NV>(xt, g, ga, nvec, lane, H, rs, dx + r * (int64_t)H);
 }
 
 // ---- LayerNorm with the low-bit cache of its input fused in ------------------------------
@@ -269,147 +377,116 @@ layernorm_backward_kernel(const float *__restrict__ x, const float *__restrict__
 // and the codes are those of the flat quantiser.
 // Backward: x^ = code * scale is rebuilt in registers and goes straight into the dense
 // input-gradient formula; it is never stored.
-template <int BITS>
-__device__ __forceinline__ uint32_t pack4(const f32x4 &v, float mult)
+// the E codes of a vector, element i in bits [i*BITS, (i+1)*BITS) of the 64-bit result (two words)
+template <int BITS, int E>
+__device__ __forceinline__ void pack_codes(const float (&f)[E], float mult, uint32_t (&w)[2])
 {
-    constexpr uint32_t m = (1u << BITS) - 1u;
-    return ((uint32_t)quantise_one<BITS>(v.x, mult) & m) | (((uint32_t)quantise_one<BITS>(v.y, mult) & m) << BITS) |
-           (((uint32_t)quantise_one<BITS>(v.z, mult) & m) << (2 * BITS)) |
-           (((uint32_t)quantise_one<BITS>(v.w, mult) & m) << (3 * BITS));
+    w[0] = w[1] = 0u;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+        const uint32_t c = (uint32_t)quantise_one<BITS>(f[i], mult) & ((1u << BITS) - 1u);
+        w[(i * BITS) / 32] |= c << ((i * BITS) % 32);
+    }
 }
 
-template <int NV, int BITS>
+template <typename T, int NV, int BITS>
 __global__ void __launch_bounds__(kThreads)
-layernorm_forward_quant_kernel(const float *__restrict__ x, const float *__restrict__ gamma,
+layernorm_forward_quant_kernel(const T *__restrict__ x, const float *__restrict__ gamma,
                                const float *__restrict__ beta, int64_t rows, int H, float eps, int G, int block_shift,
-                               float *__restrict__ y, float *__restrict__ mean, float *__restrict__ rstd,
+                               T *__restrict__ y, float *__restrict__ mean, float *__restrict__ rstd,
                                uint8_t *__restrict__ codes, float *__restrict__ scales)
 {
+    constexpr int E = RowIO<T>::E;
+    constexpr int OUT_BYTES = E * BITS / 8;                  // 2, 4 or 8
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     if (r >= rows) return;                                   // whole waves leave: the lane exchanges below stay complete
-    const int nvec = H / 4;
+    const int nvec = H / E;
     const int64_t e0 = r * (int64_t)H;
-    f32x4 v[NV], ga[NV], be[NV];
-    load_row<NV>(x + e0, nvec, lane, v, true);
-    load_row<NV>(gamma, nvec, lane, ga, false);
-    load_row<NV>(beta, nvec, lane, be, false);
+    float v[NV][E], ga[NV][E], be[NV][E];
+    load_row_t<T, NV>(x + e0, nvec, lane, v);
+    load_params<E, NV>(gamma, nvec, lane, ga);
+    load_params<E, NV>(beta, nvec, lane, be);
 
-    // the cache: codes and scales of this row's blocks
-    auto write_cache = [&]() {
+    // the cache: codes and scales of this row's blocks (writing it after y instead makes no measurable difference)
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
-        float a = fmaxf(fmaxf(fabsf(v[i].x), fabsf(v[i].y)), fmaxf(fabsf(v[i].z), fabsf(v[i].w)));
+        float a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) a = fmaxf(a, fabsf(v[i][e]));
         a = group_max_f32_dyn(a, G);
         float mult, scale;
         block_scale<BITS>(a, mult, scale);
         if (q < nvec) {
-            const int64_t e = e0 + (int64_t)q * 4;
-            if ((lane & (G - 1)) == 0) scales[e >> block_shift] = scale;
-            const uint32_t w = pack4<BITS>(v[i], mult);
-            if (BITS == 4) __builtin_nontemporal_store((uint16_t)w, reinterpret_cast<uint16_t *>(codes + e / 2));
-            else __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(codes + e));
+            const int64_t el = e0 + (int64_t)q * E;
+            if ((lane & (G - 1)) == 0) scales[el >> block_shift] = scale;
+            uint32_t w[2];
+            pack_codes<BITS, E>(v[i], mult, w);
+            uint8_t *dst = codes + (el * BITS) / 8;
+            if (OUT_BYTES == 2) __builtin_nontemporal_store((uint16_t)w[0], reinterpret_cast<uint16_t *>(dst));
+            else if (OUT_BYTES == 4) __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(dst));
+            else __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2 *>(dst));
         }
     }
-    };
-    write_cache();       // before or after the y stores makes no measurable difference
 
-    float part = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) part += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    const float mu = wave_sum_f32(part) / (float)H;
-    part = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const bool in = i * kWave + lane < nvec;
-        const float a = v[i].x - mu, b = v[i].y - mu, c = v[i].z - mu, d = v[i].w - mu;
-        part += in ? (a * a + b * b) + (c * c + d * d) : 0.0f;
-    }
-    const float var = wave_sum_f32(part) / (float)H;
-    const float rs = 1.0f / __builtin_sqrtf(var + eps);
+    float mu, rs;
+    row_statistics<E, NV>(v, nvec, lane, H, eps, mu, rs);
     if (lane == 0) {
         mean[r] = mu;
         rstd[r] = rs;
     }
-    f32x4 *dst = reinterpret_cast<f32x4 *>(y + e0);
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int q = i * kWave + lane;
-        if (q < nvec) {
-            f32x4 o;
-            o.x = ((v[i].x - mu) * rs) * ga[i].x + be[i].x;
-            o.y = ((v[i].y - mu) * rs) * ga[i].y + be[i].y;
-            o.z = ((v[i].z - mu) * rs) * ga[i].z + be[i].z;
-            o.w = ((v[i].w - mu) * rs) * ga[i].w + be[i].w;
-            __builtin_nontemporal_store(o, dst + q);
-        }
-    }
+    store_normalised<T, NV>(y + e0, v, ga, be, nvec, lane, mu, rs);
 }
 
-template <int NV, int BITS>
+template <typename T, int NV, int BITS>
 __global__ void __launch_bounds__(kThreads)
 layernorm_backward_dequant_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ scales, int block_shift,
                                   const float *__restrict__ mean, const float *__restrict__ rstd,
-                                  const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
-                                  float *__restrict__ dx)
+                                  const float *__restrict__ gamma, const T *__restrict__ dy, int64_t rows, int H,
+                                  T *__restrict__ dx)
 {
+    constexpr int E = RowIO<T>::E;
+    constexpr int IN_BYTES = E * BITS / 8;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t r = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     if (r >= rows) return;
-    const int nvec = H / 4;
+    const int nvec = H / E;
     const int64_t e0 = r * (int64_t)H;
-    f32x4 g[NV], ga[NV];
-    uint32_t w[NV];
+    float g[NV][E], ga[NV][E], xt[NV][E];
+    uint32_t w[NV][2];
     float sc[NV];
-    load_row<NV>(dy + e0, nvec, lane, g, true);
+    load_row_t<T, NV>(dy + e0, nvec, lane, g);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
-        w[i] = 0u;
+        w[i][0] = w[i][1] = 0u;
         sc[i] = 0.0f;
         if (q < nvec) {
-            const int64_t e = e0 + (int64_t)q * 4;
-            if (BITS == 4) w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(codes + e / 2));
-            else w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(codes + e));
-            sc[i] = scales[e >> block_shift];
+            const int64_t el = e0 + (int64_t)q * E;
+            const uint8_t *src = codes + (el * BITS) / 8;
+            if (IN_BYTES == 2) w[i][0] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(src));
+            else if (IN_BYTES == 4) w[i][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src));
+            else {
+                const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src));
+                w[i][0] = t.x;
+                w[i][1] = t.y;
+            }
+            sc[i] = scales[el >> block_shift];
         }
     }
-    load_row<NV>(gamma, nvec, lane, ga, false);
+    load_params<E, NV>(gamma, nvec, lane, ga);
     const float mu = mean[r], rs = rstd[r];
-    const float scale = rs / (float)H;
-    f32x4 xt[NV];
-    float part_g = 0.0f, part_gx = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const bool in = i * kWave + lane < nvec;
-        xt[i].x = in ? ((float)code_field<BITS>(w[i], 0) * sc[i] - mu) * rs : 0.0f;
-        xt[i].y = in ? ((float)code_field<BITS>(w[i], 1) * sc[i] - mu) * rs : 0.0f;
-        xt[i].z = in ? ((float)code_field<BITS>(w[i], 2) * sc[i] - mu) * rs : 0.0f;
-        xt[i].w = in ? ((float)code_field<BITS>(w[i], 3) * sc[i] - mu) * rs : 0.0f;
-        g[i].x = (ga[i].x * g[i].x) * scale;
-        g[i].y = (ga[i].y * g[i].y) * scale;
-        g[i].z = (ga[i].z * g[i].z) * scale;
-        g[i].w = (ga[i].w * g[i].w) * scale;
-        part_g += (g[i].x + g[i].y) + (g[i].z + g[i].w);
-        part_gx += (g[i].x * xt[i].x + g[i].y * xt[i].y) + (g[i].z * xt[i].z + g[i].w * xt[i].w);
-    }
-    const float sum_g = wave_sum_f32(part_g);
-    const float sum_gx = wave_sum_f32(part_gx);
-    const float fH = (float)H;
-    f32x4 *dst = reinterpret_cast<f32x4 *>(dx + e0);
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int q = i * kWave + lane;
-        if (q < nvec) {
-            f32x4 o;
-            o.x = (fH * g[i].x - sum_g) - xt[i].x * sum_gx;
-            o.y = (fH * g[i].y - sum_g) - xt[i].y * sum_gx;
-            o.z = (fH * g[i].z - sum_g) - xt[i].z * sum_gx;
-            o.w = (fH * g[i].w - sum_g) - xt[i].w * sum_gx;
-            __builtin_nontemporal_store(o, dst + q);
+        for (int e = 0; e < E; ++e) {
+            const float xh = (float)code_field<BITS>(w[i][(e * BITS) / 32], e % (32 / BITS)) * sc[i];   // one fp32 multiply
+            xt[i][e] = in ? (xh - mu) * rs : 0.0f;
         }
     }
+    backward_from_xt<T, NV>(xt, g, ga, nvec, lane, H, rs, dx + e0);
 }
 
 // ---- parameter gradients of an active LayerNorm: column sums over all rows --------------
@@ -422,65 +499,74 @@ layernorm_backward_dequant_kernel(const uint8_t *__restrict__ codes, const float
 // scheduling.  (Smaller slabs fill the chip better but leave more partials to the second
 // kernel, which then dominates: 64-row slabs of whole rows took 0.093 ms, 16-row ones 0.185.)
 constexpr int kSlabRows = 256;
-constexpr int kGroupVecs = kWave;           // column vectors per workgroup: 256 columns
+constexpr int kGroupVecs = kWave;           // column vectors per workgroup: 256 columns (fp32), 512 (bf16)
 
+template <typename T>
 __global__ void __launch_bounds__(kThreads)
-param_grad_partials_kernel(const float *__restrict__ x, const float *__restrict__ mean, const float *__restrict__ rstd,
-                           const float *__restrict__ dy, int64_t rows, int H, int groups, float *__restrict__ partials)
+param_grad_partials_kernel(const T *__restrict__ x, const float *__restrict__ mean, const float *__restrict__ rstd,
+                           const T *__restrict__ dy, int64_t rows, int H, int groups, float *__restrict__ partials)
 {
-    __shared__ f32x4 red_g[kWaves][kWave], red_b[kWaves][kWave];
+    constexpr int E = RowIO<T>::E;
+    __shared__ float red_g[kWaves][kWave][E], red_b[kWaves][kWave][E];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nvec = H / 4;
+    const int nvec = H / E;
     const int64_t slab = blockIdx.x / groups;
     const int group = blockIdx.x % groups;
     const int q = group * kGroupVecs + lane;                   // this lane's column vector
     const bool mine = q < nvec;
     const int64_t r0 = slab * kSlabRows;
     const int n_rows = (int)min((int64_t)kSlabRows, rows - r0);
-    f32x4 sg = {0.0f, 0.0f, 0.0f, 0.0f}, sb = {0.0f, 0.0f, 0.0f, 0.0f};
+    float sg[E], sb[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) sg[e] = sb[e] = 0.0f;
     constexpr int kRowsInFlight = 4;
     for (int i0 = wave; i0 < n_rows; i0 += kWaves * kRowsInFlight) {          // wave-uniform
-        f32x4 xv[kRowsInFlight], gv[kRowsInFlight];
+        float xv[kRowsInFlight][E], gv[kRowsInFlight][E];
         float mu[kRowsInFlight], rs[kRowsInFlight];
 #pragma unroll
         for (int u = 0; u < kRowsInFlight; ++u) {
             const int64_t r = min(r0 + i0 + u * kWaves, rows - 1);            // a row past the slab is re-read, not used
             mu[u] = mean[r];                                                  // uniform: scalar loads
             rs[u] = rstd[r];
-            xv[u] = gv[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int e = 0; e < E; ++e) xv[u][e] = gv[u][e] = 0.0f;
             if (mine) {
-                xv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x + r * (int64_t)H) + q);
-                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(dy + r * (int64_t)H) + q);
+                RowIO<T>::load(x + r * (int64_t)H, q, xv[u]);
+                RowIO<T>::load(dy + r * (int64_t)H, q, gv[u]);
             }
         }
 #pragma unroll
         for (int u = 0; u < kRowsInFlight; ++u) {
             if (i0 + u * kWaves < n_rows) {                                   // wave-uniform; rows add in order
-                sg.x += ((xv[u].x - mu[u]) * rs[u]) * gv[u].x;
-                sg.y += ((xv[u].y - mu[u]) * rs[u]) * gv[u].y;
-                sg.z += ((xv[u].z - mu[u]) * rs[u]) * gv[u].z;
-                sg.w += ((xv[u].w - mu[u]) * rs[u]) * gv[u].w;
-                sb.x += gv[u].x;
-                sb.y += gv[u].y;
-                sb.z += gv[u].z;
-                sb.w += gv[u].w;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    sg[e] += ((xv[u][e] - mu[u]) * rs[u]) * gv[u][e];
+                    sb[e] += gv[u][e];
+                }
             }
         }
     }
-    red_g[wave][lane] = sg;
-    red_b[wave][lane] = sb;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        red_g[wave][lane][e] = sg[e];
+        red_b[wave][lane][e] = sb[e];
+    }
     __syncthreads();
     if (wave == 0 && mine) {
-        f32x4 tg = red_g[0][lane], tb = red_b[0][lane];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) {
-            tg += red_g[w][lane];
-            tb += red_b[w][lane];
-        }
         // partials: [slab][2][H]
-        reinterpret_cast<f32x4 *>(partials + slab * 2 * H)[q] = tg;
-        reinterpret_cast<f32x4 *>(partials + slab * 2 * H + H)[q] = tb;
+        float *pg = partials + slab * 2 * H + (int64_t)q * E, *pb = pg + H;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float tg = red_g[0][lane][e], tb = red_b[0][lane][e];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) {
+                tg += red_g[w][lane][e];
+                tb += red_b[w][lane][e];
+            }
+            pg[e] = tg;
+            pb[e] = tb;
+        }
     }
 }
 
@@ -509,9 +595,11 @@ param_grad_finish_kernel(const float *__restrict__ partials, int64_t slabs, int 
     }
 }
 
-int32_t validate(int64_t rows, int64_t H)
+int32_t validate(int64_t rows, int64_t H, int32_t dt = SLIMFIT_F32)
 {
-    if (rows < 0 || H < 4 || H % 4 != 0) return SLIMFIT_ERR_INVALID_ARG;
+    if (!dtype_ok(dt)) return SLIMFIT_ERR_INVALID_ARG;
+    const int64_t epv = dt == SLIMFIT_F32 ? 4 : 8;             // elements per 16-byte vector
+    if (rows < 0 || H < epv || H % epv != 0) return SLIMFIT_ERR_INVALID_ARG;
     if (H > kMaxH || rows * H > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;
     return SLIMFIT_OK;
 }
@@ -525,7 +613,11 @@ int32_t validate_quant(int64_t H, int32_t bits, int32_t block)
 }
 
 // vectors a lane has to hold for rows of H elements
-int lane_vectors(int64_t H) { return (int)((H / 4 + kWave - 1) / kWave); }
+int lane_vectors(int64_t H, int32_t dt = SLIMFIT_F32)
+{
+    const int64_t epv = dt == SLIMFIT_F32 ? 4 : 8;
+    return (int)((H / epv + kWave - 1) / kWave);
+}
 
 }  // namespace
 }  // namespace slimfit
@@ -542,11 +634,18 @@ using namespace slimfit;
         else if (nv_ <= 8) { constexpr int NV = 8; CALL; }   \
         else { constexpr int NV = 16; CALL; }                \
     } while (0)
+// the same over the element type: CALL sees the type TT and NV (a bf16 row of 4096 elements is 8 vectors a lane)
+#define SLIMFIT_LN_DISPATCH_T(DT, H, CALL)                                        \
+    do {                                                                          \
+        if ((DT) == SLIMFIT_F32) { using TT = float; SLIMFIT_LN_DISPATCH(lane_vectors(H, DT), CALL); }         \
+        else { using TT = uint16_t; SLIMFIT_LN_DISPATCH(lane_vectors(H, DT), CALL); }                          \
+    } while (0)
 
-extern "C" int32_t slimfit_layernorm_forward(const float *x, const float *gamma, const float *beta, int64_t rows,
-                                             int64_t H, float eps, float *y, float *mean, float *rstd, void *stream)
+extern "C" int32_t slimfit_layernorm_forward(const void *x, int32_t dt, const float *gamma, const float *beta,
+                                             int64_t rows, int64_t H, float eps, void *y, float *mean, float *rstd,
+                                             void *stream)
 {
-    int32_t rc = validate(rows, H);
+    int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     if (rows == 0) return SLIMFIT_OK;
@@ -554,7 +653,7 @@ extern "C" int32_t slimfit_layernorm_forward(const float *x, const float *gamma,
     if (!aligned_to(x, 16) || !aligned_to(y, 16) || !aligned_to(gamma, 16) || !aligned_to(beta, 16) ||
         !aligned_to(mean, 4) || !aligned_to(rstd, 4))
         return SLIMFIT_ERR_ALIGNMENT;
-    const size_t nbytes = (size_t)rows * (size_t)H * 4;
+    const size_t nbytes = (size_t)rows * (size_t)H * dtype_size(dt);
     if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(y, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
@@ -563,8 +662,9 @@ extern "C" int32_t slimfit_layernorm_forward(const float *x, const float *gamma,
     if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
-    SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_forward_kernel<NV><<<grid, kThreads, 0, s>>>(
-                                             x, gamma, beta, rows, (int)H, eps, y, mean, rstd)));
+    SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_forward_kernel<TT, NV><<<grid, kThreads, 0, s>>>(
+                                     static_cast<const TT *>(x), gamma, beta, rows, (int)H, eps, static_cast<TT *>(y), mean,
+                                     rstd)));
     return launch_status();
 }
 
@@ -609,11 +709,11 @@ extern "C" int32_t slimfit_layernorm_param_grads_workspace(int64_t rows, int64_t
     return SLIMFIT_OK;
 }
 
-extern "C" int32_t slimfit_layernorm_param_grads(const float *x, const float *mean, const float *rstd, const float *dy,
-                                                 int64_t rows, int64_t H, float *dgamma, float *dbeta, void *workspace,
-                                                 size_t workspace_bytes, void *stream)
+extern "C" int32_t slimfit_layernorm_param_grads(const void *x, int32_t dt, const float *mean, const float *rstd,
+                                                 const void *dy, int64_t rows, int64_t H, float *dgamma, float *dbeta,
+                                                 void *workspace, size_t workspace_bytes, void *stream)
 {
-    int32_t rc = validate(rows, H);
+    int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (!dgamma || !dbeta || !workspace || (rows > 0 && (!x || !mean || !rstd || !dy))) return SLIMFIT_ERR_INVALID_ARG;
     if (!aligned_to(dgamma, 4) || !aligned_to(dbeta, 4) || !aligned_to(workspace, 16) ||
@@ -626,7 +726,7 @@ extern "C" int32_t slimfit_layernorm_param_grads(const float *x, const float *me
     if ((rc = check_device_range(dbeta, (size_t)H * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(workspace, need)) != SLIMFIT_OK) return rc;
     if (rows > 0) {
-        const size_t nbytes = (size_t)rows * (size_t)H * 4;
+        const size_t nbytes = (size_t)rows * (size_t)H * dtype_size(dt);
         if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
         if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
         if ((rc = check_device_range(mean, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
@@ -635,26 +735,34 @@ extern "C" int32_t slimfit_layernorm_param_grads(const float *x, const float *me
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t slabs = (rows + kSlabRows - 1) / kSlabRows;
     float *partials = static_cast<float *>(workspace);
-    const int groups = (int)((H / 4 + kGroupVecs - 1) / kGroupVecs);
-    if (slabs > 0)
-        param_grad_partials_kernel<<<(unsigned)(slabs * groups), kThreads, 0, s>>>(x, mean, rstd, dy, rows, (int)H, groups,
-                                                                                   partials);
+    const int64_t epv = dt == SLIMFIT_F32 ? 4 : 8;
+    const int groups = (int)((H / epv + kGroupVecs - 1) / kGroupVecs);
+    if (slabs > 0) {
+        if (dt == SLIMFIT_F32)
+            param_grad_partials_kernel<float><<<(unsigned)(slabs * groups), kThreads, 0, s>>>(
+                static_cast<const float *>(x), mean, rstd, static_cast<const float *>(dy), rows, (int)H, groups, partials);
+        else
+            param_grad_partials_kernel<uint16_t><<<(unsigned)(slabs * groups), kThreads, 0, s>>>(
+                static_cast<const uint16_t *>(x), mean, rstd, static_cast<const uint16_t *>(dy), rows, (int)H, groups,
+                partials);
+    }
     const unsigned fgrid = (unsigned)((2 * H + kFinishCols - 1) / kFinishCols);
     param_grad_finish_kernel<<<fgrid, kThreads, 0, s>>>(partials, slabs, (int)H, dgamma, dbeta);
     return launch_status();
 }
 
-extern "C" int32_t slimfit_layernorm_backward(const float *x, const float *mean, const float *rstd, const float *gamma,
-                                              const float *dy, int64_t rows, int64_t H, float *dx, void *stream)
+extern "C" int32_t slimfit_layernorm_backward(const void *x, int32_t dt, const float *mean, const float *rstd,
+                                              const float *gamma, const void *dy, int64_t rows, int64_t H, void *dx,
+                                              void *stream)
 {
-    int32_t rc = validate(rows, H);
+    int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (rows == 0) return SLIMFIT_OK;
     if (!x || !mean || !rstd || !gamma || !dy || !dx || dx == x || dx == dy) return SLIMFIT_ERR_INVALID_ARG;
     if (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16) || !aligned_to(gamma, 16) ||
         !aligned_to(mean, 4) || !aligned_to(rstd, 4))
         return SLIMFIT_ERR_ALIGNMENT;
-    const size_t nbytes = (size_t)rows * (size_t)H * 4;
+    const size_t nbytes = (size_t)rows * (size_t)H * dtype_size(dt);
     if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(dx, nbytes)) != SLIMFIT_OK) return rc;
@@ -663,17 +771,18 @@ extern "C" int32_t slimfit_layernorm_backward(const float *x, const float *mean,
     if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
-    SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_kernel<NV><<<grid, kThreads, 0, s>>>(
-                                             x, mean, rstd, gamma, dy, rows, (int)H, dx)));
+    SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_backward_kernel<TT, NV><<<grid, kThreads, 0, s>>>(
+                                     static_cast<const TT *>(x), mean, rstd, gamma, static_cast<const TT *>(dy), rows, (int)H,
+                                     static_cast<TT *>(dx))));
     return launch_status();
 }
 
-extern "C" int32_t slimfit_layernorm_forward_quant_pack(const float *x, const float *gamma, const float *beta,
-                                                        int64_t rows, int64_t H, float eps, int32_t bits, int32_t block,
-                                                        float *y, float *mean, float *rstd, uint8_t *codes,
-                                                        float *scales, void *stream)
+extern "C" int32_t slimfit_layernorm_forward_quant_pack(const void *x, int32_t dt, const float *gamma,
+                                                        const float *beta, int64_t rows, int64_t H, float eps,
+                                                        int32_t bits, int32_t block, void *y, float *mean, float *rstd,
+                                                        uint8_t *codes, float *scales, void *stream)
 {
-    int32_t rc = validate(rows, H);
+    int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if ((rc = validate_quant(H, bits, block)) != SLIMFIT_OK) return rc;
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
@@ -683,7 +792,7 @@ extern "C" int32_t slimfit_layernorm_forward_quant_pack(const float *x, const fl
         !aligned_to(mean, 4) || !aligned_to(rstd, 4) || !aligned_to(codes, 16) || !aligned_to(scales, 16))
         return SLIMFIT_ERR_ALIGNMENT;
     const int64_t n = rows * H;
-    const size_t nbytes = (size_t)n * 4;
+    const size_t nbytes = (size_t)n * dtype_size(dt);
     if ((rc = check_device_range(x, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(y, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
@@ -694,22 +803,24 @@ extern "C" int32_t slimfit_layernorm_forward_quant_pack(const float *x, const fl
     if ((rc = check_device_range(scales, (size_t)(n / block) * 4)) != SLIMFIT_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
-    const int G = block / 4, shift = __builtin_ctz((unsigned)block);
+    const int G = block / (dt == SLIMFIT_F32 ? 4 : 8), shift = __builtin_ctz((unsigned)block);
     if (bits == 4)
-        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_forward_quant_kernel<NV, 4><<<grid, kThreads, 0, s>>>(
-                                                 x, gamma, beta, rows, (int)H, eps, G, shift, y, mean, rstd, codes, scales)));
+        SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_forward_quant_kernel<TT, NV, 4><<<grid, kThreads, 0, s>>>(
+                                         static_cast<const TT *>(x), gamma, beta, rows, (int)H, eps, G, shift,
+                                         static_cast<TT *>(y), mean, rstd, codes, scales)));
     else
-        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_forward_quant_kernel<NV, 8><<<grid, kThreads, 0, s>>>(
-                                                 x, gamma, beta, rows, (int)H, eps, G, shift, y, mean, rstd, codes, scales)));
+        SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_forward_quant_kernel<TT, NV, 8><<<grid, kThreads, 0, s>>>(
+                                         static_cast<const TT *>(x), gamma, beta, rows, (int)H, eps, G, shift,
+                                         static_cast<TT *>(y), mean, rstd, codes, scales)));
     return launch_status();
 }
 
 extern "C" int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, const float *scales, int32_t bits,
                                                       int32_t block, const float *mean, const float *rstd,
-                                                      const float *gamma, const float *dy, int64_t rows, int64_t H,
-                                                      float *dx, void *stream)
+                                                      const float *gamma, const void *dy, int32_t dt, int64_t rows,
+                                                      int64_t H, void *dx, void *stream)
 {
-    int32_t rc = validate(rows, H);
+    int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if ((rc = validate_quant(H, bits, block)) != SLIMFIT_OK) return rc;
     if (rows == 0) return SLIMFIT_OK;
@@ -718,7 +829,7 @@ extern "C" int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, cons
         !aligned_to(gamma, 16) || !aligned_to(mean, 4) || !aligned_to(rstd, 4))
         return SLIMFIT_ERR_ALIGNMENT;
     const int64_t n = rows * H;
-    const size_t nbytes = (size_t)n * 4;
+    const size_t nbytes = (size_t)n * dtype_size(dt);
     if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(dx, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
@@ -730,10 +841,12 @@ extern "C" int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, cons
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
     const int shift = __builtin_ctz((unsigned)block);
     if (bits == 4)
-        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_dequant_kernel<NV, 4><<<grid, kThreads, 0, s>>>(
-                                                 codes, scales, shift, mean, rstd, gamma, dy, rows, (int)H, dx)));
+        SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_backward_dequant_kernel<TT, NV, 4><<<grid, kThreads, 0, s>>>(
+                                         codes, scales, shift, mean, rstd, gamma, static_cast<const TT *>(dy), rows, (int)H,
+                                         static_cast<TT *>(dx))));
     else
-        SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_dequant_kernel<NV, 8><<<grid, kThreads, 0, s>>>(
-                                                 codes, scales, shift, mean, rstd, gamma, dy, rows, (int)H, dx)));
+        SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_backward_dequant_kernel<TT, NV, 8><<<grid, kThreads, 0, s>>>(
+                                         codes, scales, shift, mean, rstd, gamma, static_cast<const TT *>(dy), rows, (int)H,
+                                         static_cast<TT *>(dx))));
     return launch_status();
 }

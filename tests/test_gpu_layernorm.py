@@ -24,15 +24,21 @@ def _inputs(seed, rows, H):
     return x, gamma, beta, dy
 
 
+def _f32(t):
+    """Device tensor (fp32 or bf16) -> host float32 array; the widening of bf16 is exact."""
+    return t.detach().float().cpu().numpy()
+
+
 def _forward_both(x, gamma, beta, eps=1e-5):
     rows, H = x.shape
-    y = Guarded(rows * H, torch.float32)
+    bf16 = x.dtype == torch.bfloat16
+    y = Guarded(rows * H, x.dtype)
     mean = Guarded(rows, torch.float32)
     rstd = Guarded(rows, torch.float32)
     sf.layernorm_forward(x, gamma, beta, eps, y.t.view(rows, H), mean.t, rstd.t)
     torch.cuda.synchronize()
     y.check(); mean.check(); rstd.check()
-    xh, gh, bh = to_np(x), to_np(gamma), to_np(beta)
+    xh, gh, bh = _f32(x), to_np(gamma), to_np(beta)
     oy, om, orr = ref.layernorm_forward(xh, gh, bh, eps=eps, threads=4)
     xd = xh.astype(np.float64)
     xmax = np.abs(xd).max(axis=1)
@@ -43,8 +49,10 @@ def _forward_both(x, gamma, beta, eps=1e-5):
     assert np.all(np.abs(gr - rs) <= 2e-6 * rs)
     xt = (xd - mu[:, None]) * rs[:, None]
     tol = np.abs(gh)[None, :] * (4e-6 * np.abs(xt) + 2e-6 * (xmax * rs)[:, None]) + 1e-6 * np.abs(oy.astype(np.float64))
-    gy = to_np(y.t).reshape(rows, H).astype(np.float64)
+    gy = _f32(y.t).reshape(rows, H).astype(np.float64)
     want = xt * gh.astype(np.float64) + bh.astype(np.float64)
+    if bf16:
+        tol = tol + np.abs(want) * 2.0 ** -8                                   # the output's own rounding
     bad = np.abs(gy - want) > tol
     assert not bad.any(), "y: %d outside tolerance, worst ratio %.3g" % (int(bad.sum()), float((np.abs(gy - want) / tol).max()))
     # the later stages are fed with the oracle's statistics (fp64 results rounded to fp32), not with the kernel's
@@ -106,18 +114,30 @@ def test_forward_prune_backward_chain(rows, H):
     _prune_both(x, mean, rstd, max(1, n // 10), by_mag=False)
 
 
-@pytest.mark.parametrize("rows,H", [(1, 4), (63, 64), (64, 252), (65, 768), (1000, 1024), (130, 4096), (257, 20)])
-def test_active_layer_gradients(rows, H):
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("rows,H", [(1, 4), (1, 8), (63, 64), (64, 252), (64, 248), (65, 768), (1000, 1024), (130, 4096),
+                                    (257, 20), (257, 24)])
+def test_active_layer_gradients(rows, H, dtype):
     require_gpu()
+    bf16 = dtype == torch.bfloat16
     x, gamma, beta, dy = _inputs(rows * 3 + H, rows, H)
-    xh, dyh = to_np(x), to_np(dy)
+    x, dy = x.to(dtype), dy.to(dtype)
+    if bf16 and H % 8:                                                          # a bf16 row must be whole 16-byte vectors
+        with pytest.raises(sf.SlimfitError) as e:
+            sf.layernorm_backward(x, torch.zeros(rows, device="cuda"), torch.ones(rows, device="cuda"), gamma, dy,
+                                  torch.empty_like(x))
+        assert e.value.status == sf.ERR_INVALID_ARG
+        return
+    if bf16:
+        _forward_both(x, gamma, beta)                                           # bf16 rows through the forward kernel too
+    xh, dyh = _f32(x), _f32(dy)
     _, om, orr = ref.layernorm_forward(xh, to_np(gamma), to_np(beta), eps=1e-5, threads=4)
     mean, rstd = torch.from_numpy(om).cuda(), torch.from_numpy(orr).cuda()
     dg, db = Guarded(H, torch.float32), Guarded(H, torch.float32)
     sf.layernorm_param_grads(x, mean, rstd, dy, dg.t, db.t)
     torch.cuda.synchronize()
     dg.check(); db.check()
-    dx = Guarded(rows * H, torch.float32)
+    dx = Guarded(rows * H, dtype)
     sf.layernorm_backward(x, mean, rstd, gamma, dy, dx.t.view(rows, H))
     torch.cuda.synchronize()
     dx.check()
@@ -125,7 +145,9 @@ def test_active_layer_gradients(rows, H):
     xt64 = (xh.astype(np.float64) - om.astype(np.float64)[:, None]) * orr.astype(np.float64)[:, None]
     g64 = to_np(gamma).astype(np.float64) * dyh.astype(np.float64) * orr.astype(np.float64)[:, None] / H
     tol = 4e-6 * (H * np.abs(g64) + np.abs(g64).sum(1, keepdims=True) + np.abs(xt64) * np.abs(g64 * xt64).sum(1, keepdims=True)) + 1e-30
-    got = to_np(dx.t).reshape(rows, H).astype(np.float64)
+    if bf16:
+        tol = tol + np.abs(want) * 2.0 ** -8
+    got = _f32(dx.t).reshape(rows, H).astype(np.float64)
     assert np.all(np.abs(got - want) <= tol), "dense dx: worst ratio %.3g" % float((np.abs(got - want) / tol).max())
     wg, wb = ref.layernorm_param_grads(xh, om, orr, dyh)
     xt = (xh.astype(np.float64) - om.astype(np.float64)[:, None]) * orr.astype(np.float64)[:, None]

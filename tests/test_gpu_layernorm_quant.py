@@ -27,10 +27,16 @@ def _inputs(seed, rows, H):
     return x, gamma, beta, dy
 
 
+def _f32(t):
+    """Device tensor (fp32 or bf16) -> host float32 array; the widening of bf16 is exact."""
+    return t.detach().float().cpu().numpy()
+
+
 def _run_both(x, gamma, beta, dy, bits, block, eps=1e-5):
     rows, H = x.shape
     n = rows * H
-    y = Guarded(n, torch.float32)
+    bf16 = x.dtype == torch.bfloat16
+    y = Guarded(n, x.dtype)
     mean, rstd = Guarded(rows, torch.float32), Guarded(rows, torch.float32)
     codes = Guarded(n * bits // 8, torch.uint8)
     scales = Guarded(n // block, torch.float32)
@@ -41,9 +47,9 @@ def _run_both(x, gamma, beta, dy, bits, block, eps=1e-5):
         b.check()
     assert torch.equal(x, before)
 
-    xh, gh, bh, dyh = to_np(x), to_np(gamma), to_np(beta), to_np(dy)
-    # the cache: bit for bit the flat quantiser's
-    oc, osc = ref.quant_pack(xh.reshape(-1), mode=sf.Q_BLOCK, bits=bits, block=block, frac_bits=0, threads=4)
+    xh, gh, bh, dyh = _f32(x), to_np(gamma), to_np(beta), _f32(dy)
+    # the cache: bit for bit the flat quantiser's (on the tensor in its own dtype)
+    oc, osc = ref.quant_pack(to_np(x).reshape(-1), mode=sf.Q_BLOCK, bits=bits, block=block, frac_bits=0, threads=4)
     np.testing.assert_array_equal(to_np(codes.t), oc)
     np.testing.assert_array_equal(to_np(scales.t).view(np.uint32), osc.view(np.uint32))
     # y and the statistics
@@ -56,8 +62,10 @@ def _run_both(x, gamma, beta, dy, bits, block, eps=1e-5):
     assert np.all(np.abs(to_np(rstd.t).astype(np.float64) - rs) <= 2e-6 * rs)
     xt = (xd - mu[:, None]) * rs[:, None]
     tol = np.abs(gh)[None, :] * (4e-6 * np.abs(xt) + 2e-6 * (xmax * rs)[:, None]) + 1e-6 * np.abs(oy.astype(np.float64))
-    gy = to_np(y.t).reshape(rows, H).astype(np.float64)
+    gy = _f32(y.t).reshape(rows, H).astype(np.float64)
     want = xt * gh.astype(np.float64) + bh.astype(np.float64)
+    if bf16:
+        tol = tol + np.abs(want) * 2.0 ** -8
     assert np.all(np.abs(gy - want) <= tol), "y: worst ratio %.3g" % float((np.abs(gy - want) / tol).max())
 
     # backward: both sides start from the oracle's cache and statistics
@@ -65,7 +73,7 @@ def _run_both(x, gamma, beta, dy, bits, block, eps=1e-5):
                               threads=4).reshape(rows, H)
     d_codes, d_scales = torch.from_numpy(oc).cuda(), torch.from_numpy(osc).cuda()
     d_mean, d_rstd = torch.from_numpy(om).cuda(), torch.from_numpy(orr).cuda()
-    dx = Guarded(n, torch.float32)
+    dx = Guarded(n, x.dtype)
     sf.layernorm_backward_dequant(d_codes, d_scales, bits, block, d_mean, d_rstd, gamma, dy, dx.t.view(rows, H))
     torch.cuda.synchronize()
     dx.check()
@@ -74,19 +82,22 @@ def _run_both(x, gamma, beta, dy, bits, block, eps=1e-5):
     g64 = gh.astype(np.float64) * dyh.astype(np.float64) * orr.astype(np.float64)[:, None] / H
     tol = 4e-6 * (H * np.abs(g64) + np.abs(g64).sum(1, keepdims=True)
                   + np.abs(xt64) * np.abs(g64 * xt64).sum(1, keepdims=True)) + 1e-30
-    got = to_np(dx.t).reshape(rows, H).astype(np.float64)
+    if bf16:
+        tol = tol + np.abs(want_dx) * 2.0 ** -8
+    got = _f32(dx.t).reshape(rows, H).astype(np.float64)
     assert np.all(np.abs(got - want_dx) <= tol), "dx: worst ratio %.3g" % float((np.abs(got - want_dx) / tol).max())
 
 
 SHAPES = [(1, 256), (3, 512), (7, 768), (33, 1024), (5, 1280), (4, 2048), (3, 4096), (130, 256), (1025, 512)]
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("bits,block", [(4, 64), (4, 32), (8, 128), (8, 256), (4, 256)])
 @pytest.mark.parametrize("rows,H", SHAPES)
-def test_fused_pair(rows, H, bits, block):
+def test_fused_pair(rows, H, bits, block, dtype):
     require_gpu()
     x, gamma, beta, dy = _inputs(rows * 5 + H + bits, rows, H)
-    _run_both(x, gamma, beta, dy, bits, block)
+    _run_both(x.to(dtype), gamma, beta, dy.to(dtype), bits, block)
 
 
 def test_narrow_rows_with_small_blocks():
@@ -95,6 +106,8 @@ def test_narrow_rows_with_small_blocks():
         x, gamma, beta, dy = _inputs(rows + H, rows, H)
         _run_both(x, gamma, beta, dy, 4, block)
         _run_both(x, gamma, beta, dy, 8, block)
+        _run_both(x.bfloat16(), gamma, beta, dy.bfloat16(), 4, block)
+        _run_both(x.bfloat16(), gamma, beta, dy.bfloat16(), 8, block)
 
 
 def test_argument_errors():
@@ -122,14 +135,14 @@ def test_argument_errors():
     assert e.value.status == sf.ERR_ALIGNMENT
 
 
-@pytest.mark.parametrize("ci", [1, 3])
+@pytest.mark.parametrize("ci", [1, 3, 4])
 def test_layernorm_input_at_full_size(ci):
     require_gpu()
     cfg = synth.CONFIGS[ci]
-    x = synth.activation(cfg, "ln_in", device="cuda").reshape(-1, cfg.hidden).float()
+    x = synth.activation(cfg, "ln_in", device="cuda").reshape(-1, cfg.hidden)
     rows, H = x.shape
     g = torch.Generator(device="cuda").manual_seed(ci)
     gamma = 0.5 + torch.rand(H, generator=g, device="cuda")
     beta = torch.rand(H, generator=g, device="cuda") - 0.5
-    dy = torch.randn(rows, H, generator=g, device="cuda")
+    dy = torch.randn(rows, H, generator=g, device="cuda").to(x.dtype)
     _run_both(x, gamma, beta, dy, cfg.quant_bits[-1], cfg.quant_block)
