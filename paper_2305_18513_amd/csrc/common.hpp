@@ -147,12 +147,33 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 // ---- bf16 -----------------------------------------------------------------------
 __device__ __forceinline__ float bf16_widen(uint32_t h) { return __builtin_bit_cast(float, h << 16); }
 
-// fp32 -> bf16, round to nearest even (finite inputs; NaN keeps a NaN pattern)
+// fp32 -> bf16, round to nearest even, denormals kept, NaN stays NaN.  gfx950 has the conversion in
+// hardware (one instruction for a pair); the integer form is kept for comparison.
+#ifndef SLIMFIT_HW_BF16_CVT
+#define SLIMFIT_HW_BF16_CVT 1
+#endif
 __device__ __forceinline__ uint32_t bf16_narrow(float f)
 {
+#if SLIMFIT_HW_BF16_CVT
+    return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
+#else
     uint32_t u = __builtin_bit_cast(uint32_t, f);
     uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
     return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : r;
+#endif
+}
+
+// two at once, a in the low half
+__device__ __forceinline__ uint32_t bf16_narrow2(float a, float b)
+{
+#if SLIMFIT_HW_BF16_CVT
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const bf16x2_t h = __builtin_convertvector(f32x2_t{a, b}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
+#else
+    return bf16_narrow(a) | (bf16_narrow(b) << 16);
+#endif
 }
 
 // Order-preserving map float -> uint32 (larger float <=> larger key) and back.

@@ -101,8 +101,7 @@ template <> struct Store4<float> {
 template <> struct Store4<uint16_t> {
     __device__ static void vec(uint16_t *p, const float (&f)[4])
     {
-        store_global<kApplyNT>(reinterpret_cast<u32x2 *>(p), u32x2{bf16_narrow(f[0]) | (bf16_narrow(f[1]) << 16),
-                                                                   bf16_narrow(f[2]) | (bf16_narrow(f[3]) << 16)});
+        store_global<kApplyNT>(reinterpret_cast<u32x2 *>(p), u32x2{bf16_narrow2(f[0], f[1]), bf16_narrow2(f[2], f[3])});
     }
     __device__ static void one(uint16_t *p, float v) { *p = (uint16_t)bf16_narrow(v); }
 };

@@ -99,7 +99,7 @@ template <> struct RowIO<uint16_t> {
     {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = bf16_narrow(f[2 * i]) | (bf16_narrow(f[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = bf16_narrow2(f[2 * i], f[2 * i + 1]);
         __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4 *>(row) + q);
     }
 };

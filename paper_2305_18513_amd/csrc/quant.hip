@@ -61,7 +61,7 @@ template <> struct Vec<uint16_t> {   // bf16 bit patterns
     {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = bf16_narrow(f[2 * i]) | (bf16_narrow(f[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = bf16_narrow2(f[2 * i], f[2 * i + 1]);
         return raw{w[0], w[1], w[2], w[3]};
     }
     __device__ static float load1(const uint16_t *p) { return bf16_widen(*p); }

@@ -85,6 +85,29 @@ def test_degenerate_blocks_and_denormals():
     _run_both(x.cuda(), sf.Q_FIXED, 8, 64, 4)
 
 
+def test_bf16_output_rounding_on_hand_made_scales():
+    """The fp32 -> bf16 conversion of the output path against the oracle's: ties both ways, the largest finite
+    value and overflow to infinity, denormal results, signed zeros (scales are the caller's, so any value goes)."""
+    require_gpu()
+    block, bits = 32, 8
+    scale_bits = np.array([0x3F808000, 0x3F818000, 0x3F800001, 0x3F80FFFF, 0x7F7FFFFF, 0x7F000000, 0x00000001,
+                           0x00008000, 0x00018000, 0x007FFFFF, 0x00800000, 0x3B808000, 0x00000000, 0x80000000,
+                           0x7F800000, 0x3F7F8000], dtype=np.uint32)
+    scales = scale_bits.view(np.float32)
+    n = scales.size * block
+    codes = np.tile(np.array([1, -1, 2, 3, 127, -128, 0, 5] * 4, dtype=np.int8).view(np.uint8), scales.size)
+    want = ref.dequant_unpack(codes, scales, n, mode=sf.Q_BLOCK, bits=bits, block=block, out_dtype=np.uint16)
+    y = Guarded(n, torch.bfloat16)
+    sf.dequant_unpack(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(), sf.Q_BLOCK, bits, block, 0, y.t)
+    torch.cuda.synchronize()
+    y.check()
+    got = to_np(y.t)
+    is_nan = (want & 0x7FFF) > 0x7F80                                   # inf * 0: NaN on both sides, payload free
+    np.testing.assert_array_equal((got & 0x7FFF) > 0x7F80, is_nan)
+    np.testing.assert_array_equal(got[~is_nan], want[~is_nan])
+    assert is_nan.any() and (want == 0x7F80).any() and ((want & 0x7F80) == 0).any()     # the cases are really there
+
+
 @pytest.mark.parametrize("ci", [0])
 def test_config0_tensors(ci):
     require_gpu()
