@@ -216,7 +216,7 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // uniform: rows and pointers stay scalar
     uint32_t *hist = s_hist[wave];
     StageRec *rec = s_stage[STAGED ? wave : 0].rec;
-    const float ninf = -__builtin_inff(), pinf = __builtin_inff();
+    const float ninf = -__builtin_inff(), pinf = __builtin_inff(), qnan = __builtin_nanf("");
 
     // a unit is kRowsPerUnit consecutive rows owned by one wave; a workgroup owns
     // kRowWaves consecutive units, so its output is one contiguous run
@@ -246,9 +246,12 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
         int my_count = 0;                                                    // lane i keeps row i's count
         for (int i = 0; i < n_here; ++i) {
             const int64_t row = row0 + i;
+            // absent columns hold NaN from here on: every ordered comparison with them is false and
+            // fmaxf / fminf pass them over, so the predicates below need no validity term (a ballot of a
+            // compound predicate costs two extra vector instructions per slot)
             float f[M];
 #pragma unroll
-            for (int j = 0; j < M; ++j) f[j] = nxt[j];
+            for (int j = 0; j < M; ++j) f[j] = (FULL || valid[j]) ? nxt[j] : qnan;
             {   // the next row's loads fly during this row's work
                 const bool last = i + 1 >= n_here;
                 const int64_t next = last ? (unit + unit_stride) * kRowsPerUnit : row + 1;
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
             if constexpr (SOFTMAX) {
                 float lm = ninf;
 #pragma unroll
-                for (int j = 0; j < M; ++j) lm = fmaxf(lm, (FULL || valid[j]) ? f[j] : ninf);
+                for (int j = 0; j < M; ++j) lm = fmaxf(lm, f[j]);
                 const float row_max = key_to_float(wave_umax(float_to_key(lm)));
                 float part = 0.0f;
 #pragma unroll
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
             auto count_ge = [&](float t) {
                 int c = 0;
 #pragma unroll
-                for (int j = 0; j < M; ++j) c += popc64(__builtin_amdgcn_ballot_w64(valid[j] && f[j] >= t));
+                for (int j = 0; j < M; ++j) c += popc64(__builtin_amdgcn_ballot_w64(f[j] >= t));
                 return c;
             };
 
@@ -305,8 +308,8 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
                 float lmax = ninf, lmin = pinf;
 #pragma unroll
                 for (int j = 0; j < M; ++j) {
-                    lmax = fmaxf(lmax, valid[j] ? f[j] : ninf);
-                    lmin = fminf(lmin, valid[j] ? f[j] : pinf);
+                    lmax = fmaxf(lmax, f[j]);
+                    lmin = fminf(lmin, f[j]);
                 }
                 uint32_t hi = wave_umax(float_to_key(lmax));
                 uint32_t lo = ~wave_umax(~float_to_key(lmin));
@@ -385,23 +388,23 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
             uint16_t *oi = idx + row * (int64_t)k;
             const uint32_t first = STAGED ? (uint32_t)(i * k) : 0u;
             if (c_ge == kk) {
-                emit_row<T, M, STAGED>([&](int j) { return valid[j] && f[j] >= T_cut; }, kept_value, lane, k, kk, ov, oi, rec,
+                emit_row<T, M, STAGED>([&](int j) { return f[j] >= T_cut; }, kept_value, lane, k, kk, ov, oi, rec,
                                        first);
             } else {
                 // more than kk entries reach the cut value: all above it, then the
                 // equal ones by ascending column until kk are taken
                 int c_gt = 0;
 #pragma unroll
-                for (int j = 0; j < M; ++j) c_gt += popc64(__builtin_amdgcn_ballot_w64(valid[j] && f[j] > T_exact));
+                for (int j = 0; j < M; ++j) c_gt += popc64(__builtin_amdgcn_ballot_w64(f[j] > T_exact));
                 const int need = kk - c_gt;
                 bool sel[M];
                 int seen = 0;
 #pragma unroll
                 for (int j = 0; j < M; ++j) {
-                    const bool eq = valid[j] && f[j] == T_exact;
+                    const bool eq = f[j] == T_exact;
                     const uint64_t eqm = __builtin_amdgcn_ballot_w64(eq);
                     const int rank = seen + (int)lanes_below(eqm);
-                    sel[j] = valid[j] && (f[j] > T_exact || (eq && rank < need));
+                    sel[j] = f[j] > T_exact || (eq && rank < need);
                     seen += popc64(eqm);
                 }
                 emit_row<T, M, STAGED>([&](int j) { return sel[j]; }, kept_value, lane, k, kk, ov, oi, rec, first);
