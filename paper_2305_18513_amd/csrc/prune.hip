@@ -224,26 +224,30 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
     const int64_t unit0 = (int64_t)blockIdx.x * kRowWaves + wave;
     const int64_t unit_stride = (int64_t)gridDim.x * kRowWaves;
 
+    // byte offsets of this lane's columns inside a row: 32 bits, so that a load is a scalar row
+    // address plus a vector offset and no 64-bit address is formed per element
     bool valid[M];
-    uint32_t ccol[M];
+    uint32_t coff[M];
 #pragma unroll
     for (int j = 0; j < M; ++j) {
         const int col = j * kWave + lane;
         valid[j] = FULL || col < cols;
-        ccol[j] = (uint32_t)(valid[j] ? col : cols - 1);   // absent columns re-read the last one
+        coff[j] = (uint32_t)(valid[j] ? col : cols - 1) * (uint32_t)sizeof(T);   // absent columns re-read the last one
     }
+    auto load_col = [&](const T *row, int j) {
+        return load_elem_stream<T>(reinterpret_cast<const T *>(reinterpret_cast<const char *>(row) + coff[j]));
+    };
 
     float nxt[M];
-    const T *next_src = p + unit0 * kRowsPerUnit * (int64_t)cols;     // row whose loads are in flight
-    if (unit0 < n_units) {
-#pragma unroll
-        for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(next_src + ccol[j]);
-    }
-
     for (int64_t unit = unit0; unit < n_units; unit += unit_stride) {        // wave-uniform trip counts
         const int64_t row0 = unit * kRowsPerUnit;
         const int n_here = (int)min((int64_t)kRowsPerUnit, rows - row0);
         int my_count = 0;                                                    // lane i keeps row i's count
+        // the launch gives every wave one unit (the loop only runs on for row counts beyond the grid
+        // limit), so rows are prefetched inside a unit only
+        const T *next_src = p + row0 * (int64_t)cols;                        // row whose loads are in flight
+#pragma unroll
+        for (int j = 0; j < M; ++j) nxt[j] = load_col(next_src, j);
         for (int i = 0; i < n_here; ++i) {
             const int64_t row = row0 + i;
             // absent columns hold NaN from here on: every ordered comparison with them is false and
@@ -252,14 +256,10 @@ __global__ __launch_bounds__(kRowThreads) void prune_rows_kernel(const T *__rest
             float f[M];
 #pragma unroll
             for (int j = 0; j < M; ++j) f[j] = (FULL || valid[j]) ? nxt[j] : qnan;
-            {   // the next row's loads fly during this row's work
-                const bool last = i + 1 >= n_here;
-                const int64_t next = last ? (unit + unit_stride) * kRowsPerUnit : row + 1;
-                next_src = last ? p + next * (int64_t)cols : next_src + cols;
-                if (next < rows) {
+            if (i + 1 < n_here) {        // the next row's loads fly during this row's work
+                next_src += cols;
 #pragma unroll
-                    for (int j = 0; j < M; ++j) nxt[j] = load_elem_stream<T>(next_src + ccol[j]);
-                }
+                for (int j = 0; j < M; ++j) nxt[j] = load_col(next_src, j);
             }
 
             float pv[M];                 // SOFTMAX: the row's probabilities, in the output dtype's values
