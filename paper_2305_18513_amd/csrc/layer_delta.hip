@@ -390,10 +390,10 @@ extern "C" int32_t slimfit_apply_update_layer_delta(void *const *w, int32_t w_dt
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;
-    if (L > 0 && check_device_range(d_out, sizeof(float) * (size_t)L) != SLIMFIT_OK) return SLIMFIT_ERR_POINTER;
     if (L > 0 && w && delta && numel)
         for (int32_t i = 0; i < L; ++i)
             if (numel[i] > 0 && w[i] == delta[i]) return SLIMFIT_ERR_INVALID_ARG;      // the update must not alias the weights
+    if (L > 0 && check_device_range(d_out, sizeof(float) * (size_t)L) != SLIMFIT_OK) return SLIMFIT_ERR_POINTER;
     int32_t rc = slimfit_layer_delta_plan(w, w_dt, delta, delta_dt, numel, L, workspace, workspace_bytes, stream);
     if (rc != SLIMFIT_OK) return rc;
     return slimfit_layer_delta_apply_run(numel, L, w_dt, delta_dt, eps, d_out, workspace, workspace_bytes, stream);

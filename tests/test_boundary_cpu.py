@@ -229,3 +229,67 @@ def test_block_ils_matches_the_oracle():
     for group, n in ((0, 1), (3, 5), (3, -1)):
         with pytest.raises(sf.SlimfitError):
             sf.ils_select_blocks(np.ones(10, np.float32), group, n)
+
+
+def test_fused_and_layernorm_argument_errors_return_before_any_launch(lib):
+    """The later entry points reject bad sizes, dtypes, null and misaligned pointers on the host (no GPU needed)."""
+    P = C.c_void_p
+    # softmax backward from the pairs: (vals, idx, counts, dp, dt, rows, cols, k, ds, stream)
+    def smb(vals=16, idx=16, dp=16, dt=0, rows=4, cols=64, k=6, ds=32):
+        return lib.slimfit_softmax_backward_pruned(P(vals), P(idx), P(0), P(dp), C.c_int32(dt), C.c_int64(rows),
+                                                   C.c_int32(cols), C.c_int32(k), P(ds), P(0))
+    assert smb(rows=0) == sf.OK
+    assert smb(k=65) == sf.ERR_INVALID_ARG
+    assert smb(dt=2) == sf.ERR_INVALID_ARG
+    assert smb(vals=0) == sf.ERR_INVALID_ARG
+    assert smb(dp=32) == sf.ERR_INVALID_ARG                      # ds must not be dp
+    assert smb(ds=40) == sf.ERR_ALIGNMENT                        # ds needs 16-byte alignment
+    assert smb(cols=70000, k=6) == sf.ERR_UNSUPPORTED
+
+    # LayerNorm forward: (x, dt, gamma, beta, rows, H, eps, y, mean, rstd, stream)
+    def lnf(x=16, dt=0, rows=4, H=64, eps=1e-5, y=32, gamma=16):
+        return lib.slimfit_layernorm_forward(P(x), C.c_int32(dt), P(gamma), P(16), C.c_int64(rows), C.c_int64(H),
+                                             C.c_float(eps), P(y), P(16), P(16), P(0))
+    assert lnf(rows=0) == sf.OK
+    assert lnf(H=6) == sf.ERR_INVALID_ARG                        # fp32 rows are whole 16-byte vectors
+    assert lnf(dt=1, H=12) == sf.ERR_INVALID_ARG                 # bf16 rows too: multiples of 8
+    assert lnf(dt=1, H=16, rows=0) == sf.OK
+    assert lnf(H=4100) == sf.ERR_UNSUPPORTED
+    assert lnf(eps=-1.0) == sf.ERR_INVALID_ARG
+    assert lnf(y=16) == sf.ERR_INVALID_ARG                       # in place
+    assert lnf(gamma=20) == sf.ERR_ALIGNMENT
+    assert lnf(dt=7) == sf.ERR_INVALID_ARG
+
+    # LayerNorm forward + quantiser: (x, dt, gamma, beta, rows, H, eps, bits, block, y, mean, rstd, codes, scales, stream)
+    def lnq(H=64, bits=4, block=64, codes=16):
+        return lib.slimfit_layernorm_forward_quant_pack(P(16), C.c_int32(0), P(16), P(16), C.c_int64(4), C.c_int64(H),
+                                                        C.c_float(1e-5), C.c_int32(bits), C.c_int32(block), P(32), P(16),
+                                                        P(16), P(codes), P(16), P(0))
+    assert lnq(bits=5) == sf.ERR_UNSUPPORTED
+    assert lnq(block=48) == sf.ERR_UNSUPPORTED
+    assert lnq(H=96) == sf.ERR_UNSUPPORTED                       # a block would straddle two rows
+    assert lnq(codes=0) == sf.ERR_INVALID_ARG
+    assert lnq(codes=24) == sf.ERR_ALIGNMENT
+
+    # score while applying the update: (w, w_dt, delta, delta_dt, numel, L, eps, d_out, workspace, bytes, stream)
+    numel = np.array([100, 5000], dtype=np.int64)
+    w = (C.c_void_p * 2)(256, 512)
+    dl = (C.c_void_p * 2)(1024, 2048)
+    def app(w=w, dl=dl, eps=0.0, d_out=256, ws=256, ws_bytes=1 << 20, L=2):      # (sizes are checked after d_out's range)
+        return lib.slimfit_apply_update_layer_delta(w, C.c_int32(0), dl, C.c_int32(0), P(numel.ctypes.data), C.c_int32(L),
+                                                    C.c_float(eps), P(d_out), P(ws), C.c_size_t(ws_bytes), P(0))
+    assert app(L=0) == sf.OK
+    assert app(eps=-1.0) == sf.ERR_INVALID_ARG
+    assert app(d_out=0) == sf.ERR_INVALID_ARG
+    assert app(d_out=258) == sf.ERR_ALIGNMENT
+    assert app(dl=w) == sf.ERR_INVALID_ARG                       # the update aliases the weights
+
+    # block-granularity ILS needs a positive group and at most ceil(L / group) blocks
+    d = np.ones(10, np.float32)
+    out = np.zeros(4, np.int32)
+    assert lib.slimfit_ils_select_blocks(P(d.ctypes.data), C.c_int32(10), C.c_int32(0), C.c_int32(1), P(out.ctypes.data),
+                                         P(0)) == sf.ERR_INVALID_ARG
+    assert lib.slimfit_ils_select_blocks(P(d.ctypes.data), C.c_int32(10), C.c_int32(3), C.c_int32(5), P(out.ctypes.data),
+                                         P(0)) == sf.ERR_INVALID_ARG
+    assert lib.slimfit_ils_select_blocks(P(d.ctypes.data), C.c_int32(10), C.c_int32(3), C.c_int32(4), P(out.ctypes.data),
+                                         P(0)) == sf.OK
