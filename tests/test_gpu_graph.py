@@ -51,8 +51,19 @@ def test_captured_calls_replay_to_the_eager_results():
         "dgamma": torch.empty(H, device="cuda"),
         "dbeta": torch.empty(H, device="cuda"),
         "d": torch.empty(3, device="cuda"),
+        "sm_ds": torch.empty(rows, cols, device="cuda"),
+        "lq_y": torch.empty(640, H, device="cuda"),
+        "lq_codes": torch.empty(640 * H // 2, dtype=torch.uint8, device="cuda"),
+        "lq_scales": torch.empty(640 * H // 64, device="cuda"),
+        "lq_dx": torch.empty(640, H, device="cuda"),
+        "d_apply": torch.empty(3, device="cuda"),
+        "w0": torch.empty_like(w_prev[0]), "w1": torch.empty_like(w_prev[1]), "w2": torch.empty_like(w_prev[2]),
     }
+    w_apply = [out["w0"], out["w1"], out["w2"]]
+    upd = [c - q for q, c in zip(w_prev, w_cur)]
     ws_delta = torch.empty(sf.layer_delta_workspace(numel), dtype=torch.uint8, device="cuda")
+    ws_apply = torch.empty_like(ws_delta)
+    sf.layer_delta_plan(w_apply, upd, ws_apply)
     ws_pg = torch.empty(sf.prune_global_workspace(n), dtype=torch.uint8, device="cuda")
     ws_ln = torch.empty(sf.prune_global_workspace(640 * H), dtype=torch.uint8, device="cuda")
     ws_par = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
@@ -76,6 +87,13 @@ def test_captured_calls_replay_to_the_eager_results():
         sf.layernorm_backward(lnx, o["mean"], o["rstd"], gamma, dy, o["ln_dx_dense"])
         sf.layernorm_param_grads(lnx, o["mean"], o["rstd"], dy, o["dgamma"], o["dbeta"], ws_par)
         sf.layer_delta_run(numel, sf.F32, sf.F32, False, 0.0, o["d"], ws_delta)
+        sf.softmax_backward_pruned(o["vals"], o["idx"], None, p, o["sm_ds"])
+        sf.layernorm_forward_quant_pack(lnx, gamma, beta, 1e-5, 4, 64, o["lq_y"], o["mean"], o["rstd"], o["lq_codes"],
+                                        o["lq_scales"])
+        sf.layernorm_backward_dequant(o["lq_codes"], o["lq_scales"], 4, 64, o["mean"], o["rstd"], gamma, dy, o["lq_dx"])
+        for dst, src in zip(w_apply, w_prev):                      # the update is applied to a fresh copy every time
+            dst.copy_(src)
+        sf.layer_delta_apply_run(numel, sf.F32, sf.F32, 0.0, o["d_apply"], ws_apply)
 
     calls()
     torch.cuda.synchronize()
