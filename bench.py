@@ -371,10 +371,9 @@ def main() -> int:
                             "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                             "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del probs
-        # LayerNorm around its caches: forward with row statistics; the pruned cache (fp32 tensors only: 10 % of the
-        # standardised input kept without storing it, input gradient of the frozen layer from the kept pairs); the
-        # quantised cache fused into the forward and backward kernels (fp32 or bf16 tensors)
-        fp32_acts = cfg.act_dtype == torch.float32
+        # LayerNorm around its caches: forward with row statistics; the pruned cache (10 % of the standardised input
+        # kept without storing it, input gradient of the frozen layer from the kept pairs); the quantised cache fused
+        # into the forward and backward kernels
         H = cfg.hidden
         lnx = [s.ln[0].view(-1, H) for s in sets]
         rows_l = lnx[0].shape[0]
@@ -393,20 +392,17 @@ def main() -> int:
         ln_runs = {
             "layernorm_forward[ln_in]": (2 * in_sz * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
                 lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
-        }
-        if fp32_acts:
-            ln_runs["prune_global_standardized[ln_in, 10%]"] = (4 * n_l + 8 * k_l + 12 * rows_l, lambda i:
-                sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws))
-            ln_runs["layernorm_backward_pruned[ln_in]"] = (8 * n_l + 8 * k_l + 8 * rows_l, lambda i:
-                sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i]))
-        ln_runs.update({
+            "prune_global_standardized[ln_in, 10%]": (in_sz * n_l + 8 * k_l + 12 * rows_l, lambda i:
+                sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
+            "layernorm_backward_pruned[ln_in]": (2 * in_sz * n_l + 8 * k_l + 8 * rows_l, lambda i:
+                sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
             # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
             # reads the input anyway, and the input gradient straight from that cache
             "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
                 lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
             "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
                 sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
-        })
+        }
         for name, (nb, fn) in ln_runs.items():
             for i in range(len(sets)):
                 fn(i)

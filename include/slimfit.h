@@ -362,9 +362,9 @@ int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32
  *     the entry points that take dt accept x / y / dy / dx as fp32 or bf16 (bf16
  *     inputs are widened exactly, bf16 outputs are the fp32 results rounded to
  *     nearest even: one further bf16 rounding on top of the tolerances below).
- *     The two entry points of the pruned cache itself
- *     (slimfit_prune_global_standardized, slimfit_layernorm_backward_pruned) take
- *     fp32 tensors only.
+ *     The standardised values are fp32 numbers whatever the input's type, so
+ *     the kept values (vals of slimfit_prune_global_standardized and of
+ *     slimfit_layernorm_backward_pruned) are always fp32.
  *
  *  slimfit_layernorm_forward : y, and per row mean = E x and
  *        rstd = 1 / sqrt(Var x + eps).  Against the fp64 values: mean within
@@ -373,8 +373,9 @@ int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32
  *  slimfit_prune_global_standardized : slimfit_prune_global applied to x~
  *        without storing it: element j of row r enters as
  *        fl(fl(x_j - mean[r]) * rstd[r]) (two fp32 operations), vals receive
- *        those values.  n = rows * H; H a multiple of 4, >= 4; fp32 only
- *        (bf16: UNSUPPORTED).  mean, rstd: DEVICE float[n / H].
+ *        those values as fp32 (x itself fp32 or bf16, widened exactly).
+ *        n = rows * H; H a multiple of 4 (fp32) or 8 (bf16).
+ *        mean, rstd: DEVICE float[n / H].
  *        row_ptr: DEVICE int32[n / H + 1] or NULL; row_ptr[r] = number of
  *        survivors with index below r * H, the last entry = k (the pairs of row
  *        r are [row_ptr[r], row_ptr[r+1]) of the list).
@@ -418,8 +419,8 @@ int32_t slimfit_layernorm_param_grads(const void *x, int32_t dt, const float *me
                                       void *workspace, size_t workspace_bytes, void *stream);
 
 int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *row_ptr, int64_t k,
-                                          const float *rstd, const float *gamma, const float *dy,
-                                          int64_t rows, int64_t H, float *dx, void *stream);
+                                          const float *rstd, const float *gamma, const void *dy, int32_t dt,
+                                          int64_t rows, int64_t H, void *dx, void *stream);
 
 /* LayerNorm with the low-bit cache of its input (Alg. 2, one scale per block; Sec. 4 and 5) fused in.
  *   slimfit_layernorm_forward_quant_pack : slimfit_layernorm_forward and, from the same read of x,

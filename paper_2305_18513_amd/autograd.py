@@ -25,8 +25,8 @@ computes; the dense matrix products of the linear layer are torch's.
                      layer caches nothing but the weight and returns
                      grad_weight = None.
 
-All tensors are CUDA tensors (fp32 or bf16 activations; the pruned LayerNorm
-cache fp32 only; gamma / beta fp32); the kernels run on torch's current stream.
+All tensors are CUDA tensors (fp32 or bf16 activations; gamma / beta and the
+kept standardised values fp32); the kernels run on torch's current stream.
 """
 from __future__ import annotations
 

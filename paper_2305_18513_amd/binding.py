@@ -383,7 +383,7 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
                               row_ptr: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                               stream=None) -> None:
     """prune_global of the standardised rows of ``x`` (rows, H), formed on the fly from mean / rstd."""
-    _require(x.dim() == 2 and x.is_contiguous() and vals.dtype == x.dtype and idx.dtype == torch.int32)
+    _require(x.dim() == 2 and x.is_contiguous() and vals.dtype == torch.float32 and idx.dtype == torch.int32)
     _require(mean.dtype == torch.float32 and rstd.dtype == torch.float32)
     rows, H = x.shape
     n = x.numel()
@@ -468,13 +468,13 @@ def layernorm_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, row_ptr: to
                               rstd: torch.Tensor, gamma: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
                               stream=None) -> None:
     _require(dy.dim() == 2 and dy.is_contiguous() and dx.is_contiguous() and dx.shape == dy.shape)
-    _require(all(t.dtype == torch.float32 for t in (vals, rstd, gamma, dy, dx)))
+    _require(all(t.dtype == torch.float32 for t in (vals, rstd, gamma)) and dx.dtype == dy.dtype)
     _require(idx.dtype == torch.int32 and row_ptr.dtype == torch.int32)
     rows, H = dy.shape
     _require(row_ptr.numel() >= rows + 1)
     rc = lib().slimfit_layernorm_backward_pruned(
-        _dev(vals), _dev(idx), _dev(row_ptr), C.c_int64(k), _dev(rstd), _dev(gamma), _dev(dy), C.c_int64(rows),
-        C.c_int64(H), _dev(dx), _stream(stream))
+        _dev(vals), _dev(idx), _dev(row_ptr), C.c_int64(k), _dev(rstd), _dev(gamma), _dev(dy), C.c_int32(_dt(dy)),
+        C.c_int64(rows), C.c_int64(H), _dev(dx), _stream(stream))
     _check(rc, "layernorm_backward_pruned")
 
 

@@ -212,25 +212,26 @@ layernorm_forward_kernel(const T *__restrict__ x, const float *__restrict__ gamm
     store_normalised<T, NV>(y + r * (int64_t)H, v, ga, be, nvec, lane, mu, rs);
 }
 
-template <int NV>
+template <typename T, int NV>
 __global__ void __launch_bounds__(kThreads)
 layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *__restrict__ idx,
                                  const int32_t *__restrict__ row_ptr, int64_t k, const float *__restrict__ rstd,
-                                 const float *__restrict__ gamma, const float *__restrict__ dy, int64_t rows, int H,
-                                 float *__restrict__ dx)
+                                 const float *__restrict__ gamma, const T *__restrict__ dy, int64_t rows, int H,
+                                 T *__restrict__ dx)
 {
+    constexpr int E = RowIO<T>::E;
     extern __shared__ __align__(16) float lds[];             // kWaves rows of H floats
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r = (int64_t)blockIdx.x * kWaves + wave;
     if (r >= rows) return;
     float *buf = lds + (size_t)wave * H;
-    const int nvec = H / 4;
+    const int nvec = H / E;
     const int64_t e0 = r * (int64_t)H;
 
-    f32x4 g[NV], ga[NV];
-    load_row<NV>(dy + e0, nvec, lane, g, true);
-    load_row<NV>(gamma, nvec, lane, ga, false);
+    float g[NV][E], ga[NV][E];
+    load_row_t<T, NV>(dy + e0, nvec, lane, g);
+    load_params<E, NV>(gamma, nvec, lane, ga);
 
     // the row's pairs: [row_ptr[r], row_ptr[r + 1]) of the index-ordered list
     int64_t p0 = min(max((int64_t)row_ptr[r], (int64_t)0), k);
@@ -240,13 +241,15 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
     float part = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        g[i].x = (ga[i].x * g[i].x) * scale;
-        g[i].y = (ga[i].y * g[i].y) * scale;
-        g[i].z = (ga[i].z * g[i].z) * scale;
-        g[i].w = (ga[i].w * g[i].w) * scale;
-        part += (g[i].x + g[i].y) + (g[i].z + g[i].w);
+#pragma unroll
+        for (int e = 0; e < E; ++e) g[i][e] = (ga[i][e] * g[i][e]) * scale;
+        part += sum_vec<E>(g[i]);
         const int q = i * kWave + lane;
-        if (q < nvec) reinterpret_cast<f32x4 *>(buf)[q] = g[i];
+        if (q < nvec) {
+#pragma unroll
+            for (int c = 0; c < E / 4; ++c)
+                reinterpret_cast<f32x4 *>(buf)[q * (E / 4) + c] = f32x4{g[i][4 * c], g[i][4 * c + 1], g[i][4 * c + 2], g[i][4 * c + 3]};
+        }
     }
     const float sum_g = wave_sum_f32(part);
     __builtin_amdgcn_wave_barrier();                          // LDS serves a wave's accesses in order
@@ -282,12 +285,11 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
         if (q < nvec) {
-            f32x4 o;
-            o.x = fH * g[i].x - sum_g;
-            o.y = fH * g[i].y - sum_g;
-            o.z = fH * g[i].z - sum_g;
-            o.w = fH * g[i].w - sum_g;
-            reinterpret_cast<f32x4 *>(buf)[q] = o;
+#pragma unroll
+            for (int c = 0; c < E / 4; ++c)
+                reinterpret_cast<f32x4 *>(buf)[q * (E / 4) + c] =
+                    f32x4{fH * g[i][4 * c] - sum_g, fH * g[i][4 * c + 1] - sum_g, fH * g[i][4 * c + 2] - sum_g,
+                          fH * g[i][4 * c + 3] - sum_g};
         }
     }
     __builtin_amdgcn_wave_barrier();
@@ -300,15 +302,17 @@ layernorm_backward_pruned_kernel(const float *__restrict__ vals, const int32_t *
         if (c >= 0 && c < H) buf[c] -= vals[s] * sum_gx;
     }
     __builtin_amdgcn_wave_barrier();
-    f32x4 *dst = reinterpret_cast<f32x4 *>(dx + e0);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int q = i * kWave + lane;
-        if (q < nvec) __builtin_nontemporal_store(reinterpret_cast<const f32x4 *>(buf)[q], dst + q);
+        if (q < nvec) {
+            float o[E];
+            load_f32<E>(buf, q, o);
+            RowIO<T>::store(dx + e0, q, o);
+        }
     }
 }
 
-// ---- input gradient of an active LayerNorm: the row formula with every x~ present ----------
 // Shared back end of the two dense backward kernels: xt holds x~ (zeros in padding vectors), g holds y^.
 template <typename T, int NV>
 __device__ __forceinline__ void backward_from_xt(float (&xt)[NV][RowIO<T>::E], float (&g)[NV][RowIO<T>::E],
@@ -669,10 +673,10 @@ extern "C" int32_t slimfit_layernorm_forward(const void *x, int32_t dt, const fl
 }
 
 extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const int32_t *idx, const int32_t *row_ptr,
-                                                     int64_t k, const float *rstd, const float *gamma, const float *dy,
-                                                     int64_t rows, int64_t H, float *dx, void *stream)
+                                                     int64_t k, const float *rstd, const float *gamma, const void *dy,
+                                                     int32_t dt, int64_t rows, int64_t H, void *dx, void *stream)
 {
-    int32_t rc = validate(rows, H);
+    int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (k < 0 || k > rows * H) return SLIMFIT_ERR_INVALID_ARG;
     if (rows == 0) return SLIMFIT_OK;
@@ -682,8 +686,9 @@ extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const in
         !aligned_to(row_ptr, 4) || (k > 0 && (!aligned_to(vals, 4) || !aligned_to(idx, 4))))
         return SLIMFIT_ERR_ALIGNMENT;
     const int64_t n = rows * H;
-    if ((rc = check_device_range(dy, (size_t)n * 4)) != SLIMFIT_OK) return rc;
-    if ((rc = check_device_range(dx, (size_t)n * 4)) != SLIMFIT_OK) return rc;
+    const size_t nbytes = (size_t)n * dtype_size(dt);
+    if ((rc = check_device_range(dy, nbytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(dx, nbytes)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(gamma, (size_t)H * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(rstd, (size_t)rows * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(row_ptr, (size_t)(rows + 1) * 4)) != SLIMFIT_OK) return rc;
@@ -694,8 +699,9 @@ extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const in
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = (unsigned)((rows + kWaves - 1) / kWaves);
     const size_t lds_bytes = (size_t)kWaves * (size_t)H * 4;              // at most 64 KB
-    SLIMFIT_LN_DISPATCH(lane_vectors(H), (layernorm_backward_pruned_kernel<NV><<<grid, kThreads, lds_bytes, s>>>(
-                                             vals, idx, row_ptr, k, rstd, gamma, dy, rows, (int)H, dx)));
+    SLIMFIT_LN_DISPATCH_T(dt, H, (layernorm_backward_pruned_kernel<TT, NV><<<grid, kThreads, lds_bytes, s>>>(
+                                     vals, idx, row_ptr, k, rstd, gamma, static_cast<const TT *>(dy), rows, (int)H,
+                                     static_cast<TT *>(dx))));
     return launch_status();
 }
 

@@ -76,14 +76,32 @@ struct State {                             // first 64 bytes of the workspace
 constexpr int kListShare = 16;             // a tile's key list holds 1/16 of the tile's element count
 __device__ __forceinline__ bool use_list(const State *st) { return st->route != 0u && st->overflow == 0u; }
 
+// bf16 elements that enter the selection widened to fp32: the rows of a bf16 tensor that is standardised
+// on the way in (the standardised values are fp32, and so are the kept values)
+struct Bf16Row {
+    uint16_t h;
+};
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static constexpr int EPV = 4;          // elements per 16-byte vector
     static constexpr int KEYBITS = 32;
+    static constexpr bool WIDEN = false;
+    using Out = float;                     // type of the kept values
+    using Key = float;                     // type whose key / digit plan applies
 };
 template <> struct Elem<uint16_t> {
     static constexpr int EPV = 8;
     static constexpr int KEYBITS = 16;
+    static constexpr bool WIDEN = false;
+    using Out = uint16_t;
+    using Key = uint16_t;
+};
+template <> struct Elem<Bf16Row> {
+    static constexpr int EPV = 8;
+    static constexpr int KEYBITS = 32;
+    static constexpr bool WIDEN = true;    // raw bits are the fp32 pattern of the widened element
+    using Out = float;
+    using Key = float;
 };
 
 // raw element bits -> key (larger key <=> earlier in the descending order)
@@ -100,9 +118,23 @@ template <> __device__ __forceinline__ uint32_t make_key<uint16_t, false>(uint32
     h = (h == 0x8000u) ? 0u : h;
     return h ^ ((h & 0x8000u) ? 0xFFFFu : 0x8000u);
 }
+template <> __device__ __forceinline__ uint32_t make_key<Bf16Row, true>(uint32_t b) { return make_key<float, true>(b); }
+template <> __device__ __forceinline__ uint32_t make_key<Bf16Row, false>(uint32_t b) { return make_key<float, false>(b); }
 
 __device__ __forceinline__ uint32_t raw_bits(const float *p) { return __builtin_bit_cast(uint32_t, *p); }
 __device__ __forceinline__ uint32_t raw_bits(const uint16_t *p) { return *p; }
+__device__ __forceinline__ uint32_t raw_bits(const Bf16Row *p) { return (uint32_t)p->h << 16; }
+// the eight halves of a 16-byte vector, as they are or widened to fp32 bit patterns
+template <bool WIDEN>
+__device__ __forceinline__ void split_halves(const u32x4 &w, uint32_t (&bits)[8])
+{
+    const uint32_t q[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bits[2 * i] = WIDEN ? q[i] << 16 : q[i] & 0xFFFFu;
+        bits[2 * i + 1] = WIDEN ? q[i] & 0xFFFF0000u : q[i] >> 16;
+    }
+}
 
 // The EPV raw elements of vector `v` (element offset v*EPV); returns how many of
 // them lie inside [0, n).  A vector that straddles n is read element by element.
@@ -116,10 +148,7 @@ __device__ __forceinline__ int load_vec(const T *x, int64_t n, int64_t v, uint32
         if constexpr (EPV == 4) {
             bits[0] = w.x; bits[1] = w.y; bits[2] = w.z; bits[3] = w.w;
         } else {
-            bits[0] = w.x & 0xFFFFu; bits[1] = w.x >> 16;
-            bits[2] = w.y & 0xFFFFu; bits[3] = w.y >> 16;
-            bits[4] = w.z & 0xFFFFu; bits[5] = w.z >> 16;
-            bits[6] = w.w & 0xFFFFu; bits[7] = w.w >> 16;
+            split_halves<Elem<T>::WIDEN>(w, bits);
         }
         return EPV;
     }
@@ -148,10 +177,7 @@ __device__ __forceinline__ int load_tile_vec(const T *x, int64_t n, int64_t nvec
         if constexpr (EPV == 4) {
             bits[0] = w.x; bits[1] = w.y; bits[2] = w.z; bits[3] = w.w;
         } else {
-            bits[0] = w.x & 0xFFFFu; bits[1] = w.x >> 16;
-            bits[2] = w.y & 0xFFFFu; bits[3] = w.y >> 16;
-            bits[4] = w.z & 0xFFFFu; bits[5] = w.z >> 16;
-            bits[6] = w.w & 0xFFFFu; bits[7] = w.w >> 16;
+            split_halves<Elem<T>::WIDEN>(w, bits);
         }
         return EPV;
     } else {
@@ -638,7 +664,8 @@ template <> __device__ __forceinline__ void store_raw<uint16_t>(uint16_t *p, uin
 template <typename T, bool MAG, bool STD, bool INSIDE>
 __device__ __forceinline__ void
 write_tile(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
-             T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k, Std sd)
+             typename Elem<T>::Out *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k,
+             Std sd)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int NW = kTileThreads / kWave;
@@ -718,7 +745,7 @@ write_tile(const T *__restrict__ x, int64_t n, const State *__restrict__ st, con
                 if (above || (tie && my_eq < budget)) {
                     const uint32_t pos = out_base + my_gt + min(my_eq, budget);
                     if (pos < k) {                          // always true for consistent counts; guards the stores
-                        store_raw<T>(vals + pos, bits[j][e]);
+                        store_raw<typename Elem<T>::Out>(vals + pos, bits[j][e]);
                         idx[pos] = (int32_t)(e0 + e);
                     }
                 }
@@ -735,7 +762,8 @@ write_tile(const T *__restrict__ x, int64_t n, const State *__restrict__ st, con
 template <typename T, bool MAG, bool STD>
 __global__ void __launch_bounds__(kTileThreads)
 write_kernel(const T *__restrict__ x, int64_t n, const State *__restrict__ st, const u32x2 *__restrict__ tile_base,
-             T *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k, Std sd)
+             typename Elem<T>::Out *__restrict__ vals, int32_t *__restrict__ idx, int32_t *__restrict__ tile_ptr, uint32_t k,
+             Std sd)
 {
     // workgroup-uniform: the whole tile lies below n
     constexpr int64_t kTileElems = (int64_t)kTileThreads * kVecPerThread * Elem<T>::EPV;
@@ -871,9 +899,10 @@ template <> struct Digits<uint16_t> {
 };
 
 template <typename T, bool MAG, bool STD>
-void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int32_t *tile_ptr, const Workspace &w,
-                   const Std &sd, hipStream_t s)
+void launch_select(const T *x, int64_t n, uint32_t k, typename Elem<T>::Out *vals, int32_t *idx, int32_t *tile_ptr,
+                   const Workspace &w, const Std &sd, hipStream_t s)
 {
+    using DigitPlan = Digits<typename Elem<T>::Key>;
     constexpr int EPV = Elem<T>::EPV;
     const int64_t nvec = (n + EPV - 1) / EPV;
     const int64_t chunk = (int64_t)kHistThreads * kVecPerThread;
@@ -884,10 +913,10 @@ void launch_select(const T *x, int64_t n, uint32_t k, T *vals, int32_t *idx, int
 
     init_kernel<<<1, kSelectThreads, 0, s>>>(w.st, w.hist, k);
     int hi = Elem<T>::KEYBITS;
-    for (int d = 0; d < Digits<T>::N; ++d) {
-        const int bits = Digits<T>::bits[d];
+    for (int d = 0; d < DigitPlan::N; ++d) {
+        const int bits = DigitPlan::bits[d];
         const int shift = hi - bits;
-        const bool first = d == 0, last = d == Digits<T>::N - 1;
+        const bool first = d == 0, last = d == DigitPlan::N - 1;
         if (first)
             hist_kernel<T, MAG, STD, true><<<hist_grid, kHistThreads, 0, s>>>(x, n, w.st, w.hist, w.tile_cnt, w.lists,
                                                                              ntiles, shift, 1 << bits, sd);
@@ -935,14 +964,13 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
     if (!dtype_ok(dt) || n < 0 || k < 0 || k > n) return SLIMFIT_ERR_INVALID_ARG;
     if (n > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;                 // indices are int32
     const bool standardised = H != 0;
-    if (standardised) {
-        if (H < 4 || H % 4 != 0 || n % H != 0) return SLIMFIT_ERR_INVALID_ARG;
-        if (dt != SLIMFIT_F32) return SLIMFIT_ERR_UNSUPPORTED;
-    }
+    const int64_t epv = dt == SLIMFIT_F32 ? 4 : 8;            // a row has to be whole 16-byte vectors
+    if (standardised && (H < epv || H % epv != 0 || n % H != 0)) return SLIMFIT_ERR_INVALID_ARG;
     if (k == 0) return SLIMFIT_OK;
     if (!x || !vals || !idx || !workspace || (standardised && (!mean || !rstd))) return SLIMFIT_ERR_INVALID_ARG;
     const size_t esz = dtype_size(dt);
-    if (!aligned_to(x, 16) || !aligned_to(vals, esz) || !aligned_to(idx, 4) || !aligned_to(workspace, 16) ||
+    const size_t vsz = standardised ? 4 : esz;                // standardised values are fp32 whatever the input
+    if (!aligned_to(x, 16) || !aligned_to(vals, vsz) || !aligned_to(idx, 4) || !aligned_to(workspace, 16) ||
         (tile_ptr && !aligned_to(tile_ptr, 4)) || (row_ptr && !aligned_to(row_ptr, 4)) ||
         (standardised && (!aligned_to(mean, 4) || !aligned_to(rstd, 4))))
         return SLIMFIT_ERR_ALIGNMENT;
@@ -950,7 +978,7 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
     if (workspace_bytes < w.bytes) return SLIMFIT_ERR_WORKSPACE;
     int32_t rc;
     if ((rc = check_device_range(x, (size_t)n * esz)) != SLIMFIT_OK) return rc;
-    if ((rc = check_device_range(vals, (size_t)k * esz)) != SLIMFIT_OK) return rc;
+    if ((rc = check_device_range(vals, (size_t)k * vsz)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(idx, (size_t)k * 4)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(workspace, w.bytes)) != SLIMFIT_OK) return rc;
     if (tile_ptr && (rc = check_device_range(tile_ptr, (size_t)slimfit_global_tile_ptr_len(n) * 4)) != SLIMFIT_OK)
@@ -968,7 +996,7 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
         sd.rstd = rstd;
         sd.magic = (uint32_t)((pow + (uint64_t)H - 1) / (uint64_t)H);   // < 2^32 because H > 2^(l-1)
         sd.shift = (uint32_t)(l - 1);
-        sd.wave_uniform = (H % (kWave * 4) == 0) ? 1u : 0u;             // fp32: 4 elements a vector
+        sd.wave_uniform = (H % (kWave * epv) == 0) ? 1u : 0u;           // the 64 vectors a wave loads together share a row
         sd.last_row = (uint32_t)(rows - 1);
         sd.H = (uint32_t)H;
         sd.row_ptr = row_ptr;
@@ -986,6 +1014,11 @@ int32_t prune_global_entry(const void *x, int32_t dt, int64_t n, int64_t H, cons
             if (by_magnitude) launch_select<float, true, false>(xf, n, kk, vf, idx, tile_ptr, w, sd, s);
             else launch_select<float, false, false>(xf, n, kk, vf, idx, tile_ptr, w, sd, s);
         }
+    } else if (standardised) {
+        const Bf16Row *xr = static_cast<const Bf16Row *>(x);
+        float *vf = static_cast<float *>(vals);
+        if (by_magnitude) launch_select<Bf16Row, true, true>(xr, n, kk, vf, idx, tile_ptr, w, sd, s);
+        else launch_select<Bf16Row, false, true>(xr, n, kk, vf, idx, tile_ptr, w, sd, s);
     } else {
         const uint16_t *xh = static_cast<const uint16_t *>(x);
         uint16_t *vh = static_cast<uint16_t *>(vals);
