@@ -75,6 +75,40 @@ def test_layernorm_function_frozen_and_active():
     assert float(rel) < 0.5
 
 
+def test_layernorm_function_on_bf16_activations():
+    """bf16 rows, fp32 parameters: the frozen layer keeps fp32 standardised values, the active one returns fp32
+    parameter gradients; both equal the same C-ABI calls made by hand."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(6)
+    rows, H = 64, 512
+    x = torch.randn(rows, H, generator=g, device="cuda").bfloat16().requires_grad_(True)
+    gamma = torch.nn.Parameter(torch.rand(H, generator=g, device="cuda") + 0.5)
+    beta = torch.nn.Parameter(torch.rand(H, generator=g, device="cuda") - 0.5)
+    dy = torch.randn(rows, H, generator=g, device="cuda").bfloat16()
+    k = sf.keep_count(rows * H, 100000)
+    y = ag.LayerNormFunction.apply(x, gamma, beta, 1e-5, True, 100000)
+    assert y.dtype == torch.bfloat16 and _saved_bytes(y) == 8 * k + 4 * (rows + 1) + 4 * rows
+    y.backward(dy)
+    assert gamma.grad is None and x.grad.dtype == torch.bfloat16
+    y2 = torch.empty_like(x.detach())
+    mean, rstd = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    sf.layernorm_forward(x.detach(), gamma.detach(), beta.detach(), 1e-5, y2, mean, rstd)
+    vals, idx = torch.empty(k, device="cuda"), torch.empty(k, dtype=torch.int32, device="cuda")
+    rp = torch.empty(rows + 1, dtype=torch.int32, device="cuda")
+    sf.prune_global_standardized(x.detach(), mean, rstd, k, vals, idx, True, None, rp)
+    dx2 = torch.empty_like(dy)
+    sf.layernorm_backward_pruned(vals, idx, rp, k, rstd, gamma.detach(), dy, dx2)
+    assert torch.equal(y.detach(), y2) and torch.equal(x.grad, dx2)
+    x.grad = None
+    ag.LayerNormFunction.apply(x, gamma, beta, 1e-5, False, 100000).backward(dy)
+    xr = x.detach().float().requires_grad_(True)
+    gr, br = gamma.detach().clone().requires_grad_(True), beta.detach().clone().requires_grad_(True)
+    torch.nn.functional.layer_norm(xr, (H,), gr, br, 1e-5).backward(dy.float())
+    assert torch.allclose(x.grad.float(), xr.grad, rtol=2e-2, atol=2e-2)
+    assert gamma.grad.dtype == torch.float32
+    assert torch.allclose(gamma.grad, gr.grad, rtol=1e-3, atol=1e-3) and torch.allclose(beta.grad, br.grad, rtol=1e-3, atol=1e-3)
+
+
 def test_layernorm_function_with_the_quantised_cache():
     require_gpu()
     g = torch.Generator(device="cuda").manual_seed(4)
