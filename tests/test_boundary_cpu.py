@@ -293,3 +293,14 @@ def test_fused_and_layernorm_argument_errors_return_before_any_launch(lib):
                                          P(0)) == sf.ERR_INVALID_ARG
     assert lib.slimfit_ils_select_blocks(P(d.ctypes.data), C.c_int32(10), C.c_int32(3), C.c_int32(4), P(out.ctypes.data),
                                          P(0)) == sf.OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is single-GPU by design: --gpus above 1 ends with a message and a non-zero status, before any GPU use."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "single-GPU" in (r.stdout + r.stderr)
