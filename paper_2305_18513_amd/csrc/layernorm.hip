@@ -31,7 +31,10 @@
 namespace slimfit {
 namespace {
 
-constexpr int kThreads = 256;
+#ifndef SLIMFIT_LN_THREADS
+#define SLIMFIT_LN_THREADS 256
+#endif
+constexpr int kThreads = SLIMFIT_LN_THREADS;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kMaxH = 4096;                 // NV <= 16 vectors of 4 per lane
 
