@@ -81,6 +81,50 @@ def test_prune_and_restore_rows_past_two_to_the_32_elements():
     assert bool((nz.sum(1) == k).all()) and bool(((out == p) | ~nz).all())
 
 
+def test_softmax_backward_rows_past_two_to_the_32_elements():
+    """Both kernels of slimfit_softmax_backward_pruned (a wave per row at k = 38, spread records at k = 9) on a gradient
+    tensor of more than 2^32 bf16 elements: sampled rows against the oracle, and the zero pattern everywhere."""
+    _need(40)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    for cols, k in ((384, 38), (197, 9)):
+        rows = ((1 << 32) + (1 << 22)) // cols
+        dp = torch.empty(rows, cols, dtype=torch.bfloat16, device="cuda")
+        step = 1_000_000
+        for s in range(0, rows, step):
+            dp[s:s + step] = torch.randn(min(step, rows - s), cols, generator=g, device="cuda").bfloat16()
+        # pairs: k distinct columns per row in ascending order, values in (0, 1)
+        cols_sorted = torch.empty(rows, k, dtype=torch.int16, device="cuda")
+        for s in range(0, rows, step):
+            m = min(step, rows - s)
+            perm = torch.rand(m, cols, generator=g, device="cuda").argsort(dim=1)[:, :k]
+            cols_sorted[s:s + m] = perm.sort(dim=1).values.to(torch.int16)
+        idx = cols_sorted.view(torch.uint16)
+        vals = torch.rand(rows, k, generator=g, device="cuda").bfloat16()
+        ds = torch.empty_like(dp)
+        sf.softmax_backward_pruned(vals, idx, None, dp, ds)
+        torch.cuda.synchronize()
+        first_past = (1 << 32) // cols
+        rng = np.random.default_rng(cols)
+        picks = sorted(set([0, rows - 1, first_past - 1, first_past, first_past + 1, (1 << 31) // cols]
+                           + rng.integers(0, rows, 300).tolist()))
+        sel = torch.tensor(picks, device="cuda")
+        v32 = vals[sel].float().cpu().numpy()
+        d32 = dp[sel].float().cpu().numpy()
+        ih = to_np(idx.view(torch.int16)[sel]).view(np.uint16)
+        want = ref.softmax_backward_pruned(v32, ih, None, d32).astype(np.float64)
+        got = ds[sel].float().cpu().numpy().astype(np.float64)
+        absdot = np.abs(np.take_along_axis(d32, ih.astype(np.int64), 1).astype(np.float64) * v32).sum(1, keepdims=True)
+        tol = 2e-6 * absdot + np.abs(want) * 2.0 ** -8 + 1e-30
+        assert np.all(np.abs(got - want) <= tol)
+        # every row holds at most k non-zero entries (a product may round to zero), all at kept columns
+        nz = ds != 0
+        assert bool((nz.sum(1) <= k).all())
+        kept = torch.zeros(len(picks), cols, dtype=torch.bool, device="cuda")
+        kept.scatter_(1, cols_sorted[sel].long(), True)
+        assert bool((~nz[sel] | kept).all())
+        del dp, ds, nz, vals, idx, cols_sorted
+
+
 def test_layer_delta_closed_form_past_two_to_the_32_elements():
     _need(40)
     n = (1 << 32) + 16384 * 3 + 5
