@@ -91,7 +91,10 @@ def test_scores_equal_layer_delta_with_the_update_given_and_eps():
         d0 = torch.empty(3, device="cuda")
         sf.layer_delta(w, dl, True, eps, d0, ws)
         got, _ = _run_both(w, dl, eps=eps)
-        np.testing.assert_array_equal(got.view(np.uint32), to_np(d0).view(np.uint32))   # same kernel arithmetic
+        # same terms, fp64 sums in a different order (other workgroup shape): equal up to the final fp32 rounding
+        fin = np.isfinite(got)
+        np.testing.assert_allclose(got[fin], to_np(d0)[fin], rtol=1.2e-7, atol=0)
+        np.testing.assert_array_equal(got[~fin], to_np(d0)[~fin])
     assert np.isinf(_run_both(w, dl, eps=0.0)[0][1])
 
 
