@@ -31,7 +31,14 @@ namespace {
 #define SLIMFIT_QUANT_NT 1
 #endif
 
-constexpr int kThreads = 256;
+#ifndef SLIMFIT_QUANT_THREADS
+#define SLIMFIT_QUANT_THREADS 256
+#endif
+#ifndef SLIMFIT_DEQUANT_THREADS
+#define SLIMFIT_DEQUANT_THREADS 512
+#endif
+constexpr int kThreads = SLIMFIT_QUANT_THREADS;      // quantiser workgroup
+constexpr int kThreadsD = SLIMFIT_DEQUANT_THREADS;   // dequantiser workgroup
 constexpr int kUnrollQ = SLIMFIT_QUANT_UNROLL;
 constexpr int kUnrollD = SLIMFIT_DEQUANT_UNROLL;
 constexpr bool kNT = SLIMFIT_QUANT_NT != 0;
@@ -201,14 +208,14 @@ __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, 
     constexpr int V = Vec<T>::V;
     constexpr int IN_BYTES = V * BITS / 8;
     constexpr int kUnroll = kUnrollD;
-    const int64_t first_vec = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    const int64_t first_vec = (int64_t)blockIdx.x * (kThreadsD * kUnroll) + threadIdx.x;
 
     uint32_t w[kUnroll][2];
     float s[kUnroll];
     float grad[GELU ? kUnroll : 1][V];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+        const int64_t e0 = (first_vec + (int64_t)u * kThreadsD) * V;
         w[u][0] = w[u][1] = 0u;
         s[u] = fixed_step;
         if (!INSIDE && e0 >= n) continue;
@@ -235,7 +242,7 @@ __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, 
 
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        const int64_t e0 = (first_vec + (int64_t)u * kThreads) * V;
+        const int64_t e0 = (first_vec + (int64_t)u * kThreadsD) * V;
         if (!INSIDE && e0 >= n) continue;
         float f[V];
 #pragma unroll
@@ -255,21 +262,21 @@ __device__ __forceinline__ void dequant_tile(const uint8_t *__restrict__ codes, 
 }
 
 template <typename T, int BITS, bool BLOCKED, bool GELU>
-__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
+__global__ __launch_bounds__(kThreadsD) void dequant_unpack_kernel(const uint8_t *__restrict__ codes,
                                                                   const float *__restrict__ scales, int64_t n,
                                                                   int block_shift, float fixed_step,
                                                                   T *__restrict__ y, const T *__restrict__ dy)
 {
-    constexpr int64_t TILE = (int64_t)kThreads * kUnrollD * Vec<T>::V;
+    constexpr int64_t TILE = (int64_t)kThreadsD * kUnrollD * Vec<T>::V;
     if (((int64_t)blockIdx.x + 1) * TILE <= n)         // workgroup-uniform
         dequant_tile<T, BITS, BLOCKED, true, GELU>(codes, scales, n, block_shift, fixed_step, y, dy);
     else
         dequant_tile<T, BITS, BLOCKED, false, GELU>(codes, scales, n, block_shift, fixed_step, y, dy);
 }
 
-inline unsigned grid_for(int64_t n, int V, int unroll)
+inline unsigned grid_for(int64_t n, int V, int unroll, int threads)
 {
-    const int64_t per_block = (int64_t)kThreads * unroll * V;
+    const int64_t per_block = (int64_t)threads * unroll * V;
     return (unsigned)((n + per_block - 1) / per_block);
 }
 
@@ -278,7 +285,7 @@ void launch_quant(const void *x, int64_t n, int mode, int block, int frac_bits, 
                   hipStream_t st)
 {
     constexpr int V = Vec<T>::V;
-    const dim3 grid(grid_for(n, V, kUnrollQ)), tb(kThreads);
+    const dim3 grid(grid_for(n, V, kUnrollQ, kThreads)), tb(kThreads);
     const T *xp = static_cast<const T *>(x);
     T *yp = static_cast<T *>(y);
     if (mode == SLIMFIT_Q_FIXED) {
@@ -300,7 +307,7 @@ void launch_dequant(const uint8_t *codes, const float *scales, int64_t n, int mo
                     const void *dy, hipStream_t st)
 {
     constexpr int V = Vec<T>::V;
-    const dim3 grid(grid_for(n, V, kUnrollD)), tb(kThreads);
+    const dim3 grid(grid_for(n, V, kUnrollD, kThreadsD)), tb(kThreadsD);
     T *yp = static_cast<T *>(y);
     const T *gp = static_cast<const T *>(dy);
     if (mode == SLIMFIT_Q_FIXED)
