@@ -25,7 +25,10 @@ namespace {
 #ifndef SLIMFIT_DELTA_NT
 #define SLIMFIT_DELTA_NT 1                   // both tensors are streamed once
 #endif
-constexpr int kThreads = 256;
+#ifndef SLIMFIT_DELTA_THREADS
+#define SLIMFIT_DELTA_THREADS 256
+#endif
+constexpr int kThreads = SLIMFIT_DELTA_THREADS;
 constexpr int kChunk = SLIMFIT_DELTA_CHUNK;  // elements per workgroup
 constexpr bool kNT = SLIMFIT_DELTA_NT != 0;
 #ifndef SLIMFIT_DELTA_APPLY_NT
