@@ -272,7 +272,7 @@ int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int3
  *     bf16 rounding.
  *
  *  logits, probs : DEVICE, rows*cols elements of dt, distinct buffers.
- *  vals, idx     : as in (c).   1 <= k <= cols <= 1024 (wider rows: UNSUPPORTED).
+ *  vals, idx     : as in (c).   1 <= k <= cols <= 2048 (wider rows: UNSUPPORTED).
  * ---------------------------------------------------------------------- */
 int32_t slimfit_softmax_prune(const void *logits, int32_t dt, int64_t rows, int32_t cols, int32_t k,
                               void *probs, void *vals, uint16_t *idx, void *stream);

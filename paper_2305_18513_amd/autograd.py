@@ -16,7 +16,7 @@ computes; the dense matrix products of the linear layer are torch's.
                      forward kernel itself (plus mean and rstd); backward rebuilds
                      x^ in registers, and an active layer's gamma / beta gradients
                      use the dequantised x^.
-  SoftmaxFunction    p = softmax(logits) over the last dimension (at most 1024
+  SoftmaxFunction    p = softmax(logits) over the last dimension (at most 2048
                      wide); caches the `keep_ppm` largest probabilities of every
                      row with uint16 columns; backward is the derivative of
                      softmax with the restored (sparse) row in place of p.

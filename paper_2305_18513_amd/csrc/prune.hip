@@ -6,8 +6,10 @@
 // column order, where T is the k-th largest value of the row.  Three kernels:
 //   prune_rows_kernel       rows of up to 1024 columns, one wavefront per row,
 //                           the row held in registers (lane l: columns l, l+64, ...)
-//   prune_rows_wide_kernel  wider rows, one workgroup per row, the row re-read
-//                           from cache for every probe
+//   prune_rows_block_kernel rows of up to 16384 columns, one workgroup per row,
+//                           the row held in the workgroup's registers
+//   prune_rows_wide_kernel  wider rows still, one workgroup per row, the row
+//                           re-read from cache for every probe
 //   restore_tile_kernel     the restoring process: zeros + scatter in one pass
 //   softmax_backward_tile_kernel  the Softmax input gradient from the kept pairs
 #include "common.hpp"
@@ -25,7 +27,10 @@ constexpr int kWavesPerBlock = kThreads / kWave;
 #endif
 constexpr int kRowWaves = SLIMFIT_PRUNE_WAVES;          // waves per workgroup of the register-path kernel
 constexpr int kRowThreads = kRowWaves * kWave;
-constexpr int kMaxRegSlots = 16;             // register path: cols <= 64 * 16
+#ifndef SLIMFIT_PRUNE_WAVE_SLOTS
+#define SLIMFIT_PRUNE_WAVE_SLOTS 32
+#endif
+constexpr int kMaxRegSlots = SLIMFIT_PRUNE_WAVE_SLOTS;   // one-wave path: cols <= 64 * this (16, 32 or 64)
 #ifndef SLIMFIT_PRUNE_BLOCKS
 #define SLIMFIT_PRUNE_BLOCKS (1 << 30)
 #endif
@@ -437,8 +442,7 @@ struct BlockScratch {
 
 __device__ __forceinline__ int block_sum_int(int v, BlockScratch &s)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    v = __builtin_amdgcn_readlane(wave_scan_i32(v), kWave - 1);          // the wave's sum, by DPP
     __syncthreads();                         // previous use of the scratch is over
     if ((threadIdx.x & 63) == 0) s.i[threadIdx.x >> 6] = v;
     __syncthreads();
@@ -477,6 +481,191 @@ __device__ __forceinline__ int block_prefix(bool flag, int *total, BlockScratch 
     }
     *total = all;
     return before + (int)lanes_below(m);
+}
+
+// ---------------------------------------------------------------------------
+// rows of 1025 .. 16384 columns: one workgroup per row, the row held in registers
+// ---------------------------------------------------------------------------
+// The algorithm of the one-wave kernel with workgroup-wide steps: thread t holds columns t, t + 256, ...
+// (S slots), the 256-bin histogram lives in LDS with one bin per thread, counts and extrema go through
+// LDS between the four waves, and the survivors' positions come from a table of per-(slot, wave)
+// counts that is prefix-summed once.  The row is read from memory once.  Every branch around a
+// barrier depends on workgroup-wide results only.
+__device__ __forceinline__ int block_inclusive_scan_i32(int v, BlockScratch &s)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    int incl = wave_scan_i32(v);
+    __syncthreads();                         // previous use of the scratch is over
+    if (lane == kWave - 1) s.i[wave] = incl;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) incl += (w < wave) ? s.i[w] : 0;
+    return incl;
+}
+// table[0 .. n) (n <= kThreads) -> its exclusive prefix sums, in place
+__device__ __forceinline__ void block_scan_table(int *table, int n, BlockScratch &s)
+{
+    __syncthreads();                         // the table is complete
+    const int v = (int)threadIdx.x < n ? table[threadIdx.x] : 0;
+    const int incl = block_inclusive_scan_i32(v, s);
+    if ((int)threadIdx.x < n) table[threadIdx.x] = incl - v;
+    __syncthreads();
+}
+
+template <typename T, int S>
+__global__ __launch_bounds__(kThreads) void prune_rows_block_kernel(const T *__restrict__ p, int64_t rows, int cols,
+                                                                    int k, int mode, float tau, T *__restrict__ vals,
+                                                                    uint16_t *__restrict__ idx,
+                                                                    int32_t *__restrict__ counts)
+{
+    static_assert(S <= 64 && S * kWavesPerBlock <= kThreads, "slots");
+    constexpr int KEY_SHIFT = sizeof(T) == 2 ? 16 : 0;
+    constexpr uint32_t UNIT = 1u << KEY_SHIFT;
+    constexpr uint32_t KEY_MASK = ~(UNIT - 1u);
+    __shared__ BlockScratch scratch;
+    __shared__ uint32_t hist[kBins];
+    __shared__ int table[S * kWavesPerBlock];                  // entry s * 4 + wave
+    __shared__ int found[2];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const float ninf = -__builtin_inff(), pinf = __builtin_inff(), qnan = __builtin_nanf("");
+
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {        // workgroup-uniform
+        const T *src = p + row * (int64_t)cols;
+        float f[S];                                                        // absent columns hold NaN
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const int col = s * kThreads + tid;
+            f[s] = col < cols ? load_elem_stream<T>(src + col) : qnan;
+        }
+        auto count_ge = [&](float t) {
+            int c = 0;
+#pragma unroll
+            for (int s = 0; s < S; ++s) c += f[s] >= t ? 1 : 0;
+            return block_sum_int(c, scratch);
+        };
+
+        int kk = k;
+        float T_cut = 0.0f, T_exact = 0.0f;
+        int c_ge = 0;
+        bool have_cut = false;
+        if (mode == SLIMFIT_PRUNE_THRESHOLD) {
+            const int c_tau = count_ge(tau);
+            if (c_tau <= k) { kk = c_tau; T_cut = T_exact = tau; c_ge = c_tau; have_cut = true; }
+        }
+        if (!have_cut) {
+            float lmax = ninf, lmin = pinf;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                lmax = fmaxf(lmax, f[s]);
+                lmin = fminf(lmin, f[s]);
+            }
+            uint32_t hi = block_max_u32(float_to_key(lmax), scratch);
+            uint32_t lo = ~block_max_u32(~float_to_key(lmin), scratch);
+            if (hi == 0x7FFFFFFFu) hi = 0x80000000u;                       // -0 is folded onto +0
+            if (lo == 0x7FFFFFFFu) lo = 0x80000000u;
+            hi &= KEY_MASK;
+            lo &= KEY_MASK;
+            const uint32_t range = (hi - lo) >> KEY_SHIFT;
+            const int width_bits = 32 - __builtin_clz(range | 1u);
+            const int sh = KEY_SHIFT + (width_bits > 8 ? width_bits - 8 : 0);   // bin = (hi - key) >> sh < 256
+
+            hist[tid] = 0u;                                                // kBins == kThreads
+            if (tid == 0) {
+                found[0] = kBins - 1;
+                found[1] = cols;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                if (s * kThreads + tid < cols) {
+                    const uint32_t b = ((hi - (float_to_key(f[s] + 0.0f) & KEY_MASK)) >> sh) & (kBins - 1);
+                    atomicAdd(&hist[b], 1u);
+                }
+            }
+            __syncthreads();
+            const int h = (int)hist[tid];
+            const int incl = block_inclusive_scan_i32(h, scratch);         // entries in bins 0 .. tid
+            if (incl >= kk && incl - h < kk) {                             // the bin holding the kk-th largest entry
+                found[0] = tid;
+                found[1] = incl;
+            }
+            __syncthreads();
+            const int B = found[0];
+            c_ge = found[1];
+            const uint64_t span = (uint64_t)(B + 1) << sh;
+            uint32_t blo = span > (uint64_t)(hi - lo) ? lo : (uint32_t)(hi - (uint32_t)span + UNIT);
+            uint32_t bhi = hi - ((uint32_t)B << sh) + UNIT;               // exclusive
+            if (c_ge != kk) {
+                while (bhi - blo > UNIT) {                                 // workgroup-uniform: c is a workgroup sum
+                    const uint32_t mid = blo + (((bhi - blo) >> (KEY_SHIFT + 1)) << KEY_SHIFT);
+                    const int c = count_ge(key_to_float(mid));
+                    if (c >= kk) {
+                        blo = mid;
+                        c_ge = c;
+                        if (c == kk) break;
+                    } else {
+                        bhi = mid;
+                    }
+                }
+            }
+            T_cut = key_to_float(blo);
+            T_exact = key_to_float((blo & 0x80000000u) ? blo : (blo | (UNIT - 1u)));
+        }
+
+        // which slots of this thread are kept (bit s)
+        uint64_t keep = 0;
+        if (c_ge == kk) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) keep |= (uint64_t)(f[s] >= T_cut ? 1 : 0) << s;
+        } else {
+            // more than kk entries reach the cut value: all above it, then the equal ones by ascending
+            // column until kk are taken
+            int c = 0;
+#pragma unroll
+            for (int s = 0; s < S; ++s) c += f[s] > T_exact ? 1 : 0;
+            const int need = kk - block_sum_int(c, scratch);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const uint64_t eqm = __builtin_amdgcn_ballot_w64(f[s] == T_exact);
+                if (lane == 0) table[s * kWavesPerBlock + wave] = popc64(eqm);
+            }
+            block_scan_table(table, S * kWavesPerBlock, scratch);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const bool eq = f[s] == T_exact;
+                const uint64_t eqm = __builtin_amdgcn_ballot_w64(eq);
+                const int rank = table[s * kWavesPerBlock + wave] + (int)lanes_below(eqm);
+                keep |= (uint64_t)((f[s] > T_exact || (eq && rank < need)) ? 1 : 0) << s;
+            }
+            __syncthreads();                                               // the table is reused below
+        }
+
+        // positions in ascending column order: slot-major, then wave, then lane
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const uint64_t m = __builtin_amdgcn_ballot_w64(((keep >> s) & 1u) != 0);
+            if (lane == 0) table[s * kWavesPerBlock + wave] = popc64(m);
+        }
+        block_scan_table(table, S * kWavesPerBlock, scratch);
+        T *ov = vals + row * (int64_t)k;
+        uint16_t *oi = idx + row * (int64_t)k;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const bool sel = ((keep >> s) & 1u) != 0;
+            const uint64_t m = __builtin_amdgcn_ballot_w64(sel);
+            const int pos = table[s * kWavesPerBlock + wave] + (int)lanes_below(m);
+            if (sel && pos < k) {
+                ov[pos] = Elem<T>::raw(f[s]);
+                oi[pos] = (uint16_t)(s * kThreads + tid);
+            }
+        }
+        for (int s = kk + tid; s < k; s += kThreads) {                     // THRESHOLD: unused slots
+            ov[s] = Elem<T>::zero();
+            oi[s] = 0xFFFFu;
+        }
+        if (counts && tid == 0) counts[row] = kk;
+        __syncthreads();                                                   // LDS is reused by the next row
+    }
 }
 
 template <typename T>
@@ -878,8 +1067,16 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
     T *pr = static_cast<T *>(probs);
     const int slots = (cols + kWave - 1) / kWave;
     if (slots > kMaxRegSlots) {                       // never with SOFTMAX: the entry point rejects such rows
-        const unsigned grid = (unsigned)(rows < 16384 ? rows : 16384);
-        prune_rows_wide_kernel<T><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
+        const int bslots = (cols + kThreads - 1) / kThreads;              // slots per thread of a whole workgroup
+        const unsigned bgrid = (unsigned)(rows < (1 << 20) ? rows : (1 << 20));
+        if (bslots <= 8) prune_rows_block_kernel<T, 8><<<bgrid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
+        else if (bslots <= 16) prune_rows_block_kernel<T, 16><<<bgrid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
+        else if (bslots <= 32) prune_rows_block_kernel<T, 32><<<bgrid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
+        else if (bslots <= 64) prune_rows_block_kernel<T, 64><<<bgrid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
+        else {
+            const unsigned grid = (unsigned)(rows < 16384 ? rows : 16384);
+            prune_rows_wide_kernel<T><<<grid, kThreads, 0, st>>>(pp, rows, cols, k, mode, tau, vv, idx, counts);
+        }
         return;
     }
     const int64_t rows_per_block = (int64_t)kRowWaves * kRowsPerUnit;
@@ -902,7 +1099,15 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
     else if (slots <= 6) SLIMFIT_PRUNE_CASE(6);
     else if (slots <= 8) SLIMFIT_PRUNE_CASE(8);
     else if (slots <= 12) SLIMFIT_PRUNE_CASE(12);
-    else SLIMFIT_PRUNE_CASE(16);
+    else if (slots <= 16) SLIMFIT_PRUNE_CASE(16);
+#if SLIMFIT_PRUNE_WAVE_SLOTS >= 32
+    else if (slots <= 24) SLIMFIT_PRUNE_LAUNCH(24, false, false);       // wide rows: no staging, ragged or not
+    else if (slots <= 32) SLIMFIT_PRUNE_LAUNCH(32, false, false);
+#endif
+#if SLIMFIT_PRUNE_WAVE_SLOTS >= 64
+    else if (slots <= 48) SLIMFIT_PRUNE_LAUNCH(48, false, false);
+    else if (slots <= 64) SLIMFIT_PRUNE_LAUNCH(64, false, false);
+#endif
 #undef SLIMFIT_PRUNE_CASE
 #undef SLIMFIT_PRUNE_LAUNCH
 }

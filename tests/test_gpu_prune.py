@@ -60,6 +60,34 @@ def test_topk_random_and_ties(rows, cols, k):
     _run_both(p, k)
 
 
+# rows of 1025 .. 16384 columns take the workgroup-per-row kernel (8, 16, 32 or 64 slots a thread); wider ones
+# the re-reading kernel
+WIDE = [(1025, 1), (1025, 102), (1536, 153), (2047, 2047), (2048, 204), (2049, 64), (3000, 300), (4096, 409),
+        (4097, 65), (8192, 819), (8193, 3), (12000, 1200), (16384, 1638), (16385, 1638)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("cols,k", WIDE)
+def test_wide_rows_topk_threshold_and_ties(cols, k, dtype):
+    require_gpu()
+    rows = 23
+    g = torch.Generator(device="cuda").manual_seed(cols + k)
+    p = torch.randn(rows, cols, generator=g, device="cuda")
+    p[1] = 0.25                                                   # all equal
+    p[2] = torch.randint(0, 3, (cols,), generator=g, device="cuda").float()   # ties across the cut
+    p[3, ::2] = p[3, -1]
+    p[4] = -p[4].abs()                                            # all negative
+    p[5] = torch.softmax(p[5] * 3, dim=0)                         # probabilities over many binades
+    p[6] = p[6] * 1e-30
+    p[7, : cols // 2] = -0.0
+    p[7, cols // 2:] = 0.0
+    p[8] = (p[8] * 8).round() / 8
+    p = p.to(dtype)
+    _run_both(p, k)
+    _run_both(p, k, mode=sf.PRUNE_THRESHOLD, tau=0.5)
+    _run_both(p, k, mode=sf.PRUNE_THRESHOLD, tau=-1e9)            # every entry passes: falls back to the k largest
+
+
 @pytest.mark.parametrize("cols,k", [(64, 6), (197, 9), (384, 38), (300, 64), (1024, 33), (2000, 70)])
 def test_bf16_signed_rows_with_ties_at_the_cut(cols, k):
     # bf16 keys of negative values are not multiples of 2^16 in the integer image of

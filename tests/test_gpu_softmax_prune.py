@@ -55,7 +55,8 @@ def _run_both(l: torch.Tensor, k: int):
 
 
 SHAPES = [(1, 1, 1), (7, 5, 2), (7, 5, 5), (33, 64, 6), (65, 70, 69), (130, 128, 12), (257, 197, 9),
-          (101, 384, 38), (40, 577, 57), (19, 1024, 102), (1001, 256, 32), (37, 208, 20), (130, 16, 3), (9, 17, 17)]
+          (101, 384, 38), (40, 577, 57), (19, 1024, 102), (1001, 256, 32), (37, 208, 20), (130, 16, 3), (9, 17, 17),
+          (11, 1025, 102), (9, 1536, 153), (7, 2000, 64), (5, 2048, 204), (3, 2048, 2048)]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -75,7 +76,7 @@ def test_random_rows_ties_and_ranges(rows, cols, k, dtype):
 
 def test_argument_errors():
     require_gpu()
-    l = torch.randn(8, 1025, device="cuda")
+    l = torch.randn(8, 2049, device="cuda")
     p = torch.empty_like(l)
     v = torch.empty(8, 4, device="cuda")
     i = torch.empty(8, 4, dtype=torch.uint16, device="cuda")
