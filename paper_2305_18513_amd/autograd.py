@@ -20,6 +20,11 @@ computes; the dense matrix products of the linear layer are torch's.
                      wide); caches the `keep_ppm` largest probabilities of every
                      row with uint16 columns; backward is the derivative of
                      softmax with the restored (sparse) row in place of p.
+  SoftmaxMatmulFunction  out = softmax(logits) @ V with the probabilities shared
+                     between the two ops as the paper has it: only the kept
+                     pairs and V are cached.  Backward: dP = dO @ V^T (dense
+                     product, torch's), dV = P^^T @ dO with P^ restored from the
+                     pairs, dlogits from the pairs as in SoftmaxFunction.
   LinearFunction     Alg. 4: an active layer caches its input in `bits` bits and
                      computes grad_weight from the dequantised input; a frozen
                      layer caches nothing but the weight and returns
@@ -150,6 +155,38 @@ class SoftmaxFunction(torch.autograd.Function):
         ds = torch.empty_like(dp)
         sf.softmax_backward_pruned(vals, idx, None, dp, ds)
         return ds.view(grad_output.shape), None
+
+
+class SoftmaxMatmulFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, logits: torch.Tensor, v: torch.Tensor, keep_ppm: int = 100000):
+        # logits (..., Tq, Tk), v (..., Tk, D)
+        cols = logits.shape[-1]
+        l2 = logits.contiguous().view(-1, cols)
+        rows = l2.shape[0]
+        k = max(1, sf.keep_count(cols, keep_ppm))
+        probs = torch.empty_like(l2)
+        vals = torch.empty(rows, k, dtype=l2.dtype, device=l2.device)
+        idx = torch.empty(rows, k, dtype=torch.uint16, device=l2.device)
+        sf.softmax_prune(l2, k, probs, vals, idx)
+        out = torch.matmul(probs.view(logits.shape), v)
+        ctx.save_for_backward(vals, idx, v)
+        ctx.shape = logits.shape
+        return out
+
+    @staticmethod
+    def backward(ctx, grad_output: torch.Tensor):
+        vals, idx, v = ctx.saved_tensors
+        shape = ctx.shape
+        cols = shape[-1]
+        rows = vals.shape[0]
+        dp = torch.matmul(grad_output, v.transpose(-1, -2)).contiguous().view(rows, cols)
+        p_hat = torch.empty(rows, cols, dtype=vals.dtype, device=vals.device)
+        sf.restore_scores(vals, idx, None, p_hat)
+        dv = torch.matmul(p_hat.view(shape).transpose(-1, -2), grad_output)
+        ds = torch.empty_like(dp)
+        sf.softmax_backward_pruned(vals, idx, None, dp, ds)
+        return ds.view(shape), dv, None
 
 
 class LinearFunction(torch.autograd.Function):

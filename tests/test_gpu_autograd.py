@@ -240,3 +240,86 @@ def test_feed_forward_block_keeps_less_memory_when_wrapped():
 
     kept_plain, kept_wrapped = held(plain), held(wrapped)
     assert kept_wrapped < 0.25 * kept_plain, (kept_plain, kept_wrapped)
+
+
+def test_softmax_matmul_function_shares_the_pruned_probabilities():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(8)
+    B, h, T, D = 2, 4, 197, 64
+    logits = (torch.randn(B, h, T, T, generator=g, device="cuda") * 2).requires_grad_(True)
+    v = torch.randn(B, h, T, D, generator=g, device="cuda").requires_grad_(True)
+    do = torch.randn(B, h, T, D, generator=g, device="cuda")
+    rows, k = B * h * T, sf.keep_count(T, 100000)
+    out = ag.SoftmaxMatmulFunction.apply(logits, v, 100000)
+    assert _saved_bytes(out) == rows * k * 6 + v.numel() * 4            # the pairs and V, not the T x T probabilities
+    out.backward(do)
+    # forward is exact; with every column kept both gradients are the dense ones
+    assert torch.allclose(out.detach(), torch.softmax(logits.detach(), -1) @ v.detach(), rtol=1e-4, atol=1e-5)
+    l2, v2 = logits.detach().clone().requires_grad_(True), v.detach().clone().requires_grad_(True)
+    ag.SoftmaxMatmulFunction.apply(l2, v2, 1000000).backward(do)
+    l3, v3 = logits.detach().clone().requires_grad_(True), v.detach().clone().requires_grad_(True)
+    (torch.softmax(l3, -1) @ v3).backward(do)
+    assert torch.allclose(l2.grad, l3.grad, rtol=1e-3, atol=1e-5) and torch.allclose(v2.grad, v3.grad, rtol=1e-3, atol=1e-4)
+    # pruned: the gradients are those of the same library calls made by hand
+    p = torch.empty(rows, T, device="cuda")
+    vals, idx = torch.empty(rows, k, device="cuda"), torch.empty(rows, k, dtype=torch.uint16, device="cuda")
+    sf.softmax_prune(logits.detach().view(rows, T), k, p, vals, idx)
+    p_hat = torch.empty(rows, T, device="cuda")
+    sf.restore_scores(vals, idx, None, p_hat)
+    dp = (do @ v.detach().transpose(-1, -2)).contiguous().view(rows, T)
+    ds = torch.empty(rows, T, device="cuda")
+    sf.softmax_backward_pruned(vals, idx, None, dp, ds)
+    assert torch.equal(logits.grad.view(rows, T), ds)
+    assert torch.equal(v.grad, p_hat.view(B, h, T, T).transpose(-1, -2) @ do)
+
+
+def test_encoder_block_keeps_less_memory_when_wrapped():
+    """A whole frozen encoder block (LayerNorm, QKV, attention with shared pruned probabilities, projection,
+    LayerNorm, feed-forward with GELU): activation bytes held between forward and backward, wrapped vs plain torch."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(9)
+    B, T, H, heads = 8, 256, 512, 8
+    D = H // heads
+    x = torch.randn(B, T, H, generator=g, device="cuda").requires_grad_(True)
+    def par(*shape):
+        return torch.nn.Parameter(torch.randn(*shape, generator=g, device="cuda") * 0.03)
+    wqkv, wo, w1, w2 = par(3 * H, H), par(H, H), par(4 * H, H), par(H, 4 * H)
+    g1, b1 = torch.nn.Parameter(torch.ones(H, device="cuda")), torch.nn.Parameter(torch.zeros(H, device="cuda"))
+    g2, b2 = torch.nn.Parameter(torch.ones(H, device="cuda")), torch.nn.Parameter(torch.zeros(H, device="cuda"))
+
+    def held(fn):
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        before = torch.cuda.memory_allocated()
+        out = fn()
+        torch.cuda.synchronize()
+        kept = torch.cuda.memory_allocated() - before - out.numel() * out.element_size()
+        out.sum().backward()
+        return kept
+
+    def split_heads(t):
+        return t.view(B, T, heads, D).transpose(1, 2)
+
+    def plain():
+        h = torch.nn.functional.layer_norm(x, (H,), g1, b1, 1e-5)
+        q, k_, v = torch.nn.functional.linear(h, wqkv).chunk(3, dim=-1)
+        s = split_heads(q) @ split_heads(k_).transpose(-1, -2) / D ** 0.5
+        a = (torch.softmax(s, -1) @ split_heads(v)).transpose(1, 2).reshape(B, T, H)
+        y = x + torch.nn.functional.linear(a, wo)
+        h = torch.nn.functional.layer_norm(y, (H,), g2, b2, 1e-5)
+        h = torch.nn.functional.linear(torch.nn.functional.gelu(torch.nn.functional.linear(h, w1)), w2)
+        return y + h
+
+    def wrapped():
+        h = ag.LayerNormFunction.apply(x, g1, b1, 1e-5, True, 100000)
+        q, k_, v = ag.LinearFunction.apply(h, wqkv, None, False, 8, 64).chunk(3, dim=-1)
+        s = split_heads(q) @ split_heads(k_).transpose(-1, -2) / D ** 0.5
+        a = ag.SoftmaxMatmulFunction.apply(s, split_heads(v).contiguous(), 100000).transpose(1, 2).reshape(B, T, H)
+        y = x + ag.LinearFunction.apply(a, wo, None, False, 8, 64)
+        h = ag.LayerNormFunction.apply(y, g2, b2, 1e-5, True, 100000)
+        h = ag.LinearFunction.apply(ag.GeluFunction.apply(ag.LinearFunction.apply(h, w1, None, False, 8, 64), 4, 64), w2,
+                                    None, False, 8, 64)
+        return y + h
+
+    kept_plain, kept_wrapped = held(plain), held(wrapped)
+    assert kept_wrapped < 0.5 * kept_plain, (kept_plain, kept_wrapped)
