@@ -443,6 +443,25 @@ def main() -> int:
             "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del w_tmp, upd, ws_apply, d_apply
 
+        # one frozen encoder block of this configuration through the autograd wrappers: activation bytes held between
+        # forward and backward, against the same block in plain torch ops (the paper's figures are for whole models
+        # on its own hardware: context, not a target)
+        from paper_2305_18513_amd import autograd as ag
+        blk_b = min(cfg.batch, 32)
+        xb = torch.randn(blk_b, cfg.tokens, cfg.hidden, device="cuda").to(cfg.act_dtype).requires_grad_(True)
+        blk = ag.encoder_block_params(cfg.hidden, seed=cfg.seed, dtype=cfg.act_dtype)
+        keep = cfg.keep_ppm
+        for wrapped in (False, True):                       # untimed first pass of each
+            ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, wrapped, keep, bits, block))
+        kept_p, ms_p = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, False))
+        kept_w, ms_w = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, True, keep, bits, block))
+        extras["encoder_block_autograd"] = {
+            "shape": {"batch": blk_b, "tokens": cfg.tokens, "hidden": cfg.hidden, "heads": cfg.heads},
+            "held_MB_plain_torch": round(kept_p / 1e6, 1), "held_MB_wrapped": round(kept_w / 1e6, 1),
+            "reduction": round(kept_p / max(kept_w, 1), 2),
+            "fwd_bwd_ms_plain_torch": round(ms_p, 3), "fwd_bwd_ms_wrapped": round(ms_w, 3)}
+        del xb, blk
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)

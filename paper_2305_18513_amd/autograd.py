@@ -224,3 +224,66 @@ class LinearFunction(torch.autograd.Function):
             grad_bias = None
         grad_input = grad_output.matmul(weight)
         return grad_input, grad_weight, grad_bias, None, None, None
+
+
+def encoder_block_params(hidden: int, device="cuda", seed: int = 0, dtype=torch.float32):
+    """Random weights of one encoder block (QKV, projection, two feed-forward matrices, two LayerNorms)."""
+    g = torch.Generator(device=device).manual_seed(seed)
+
+    def mat(rows, cols):
+        return torch.nn.Parameter((torch.randn(rows, cols, generator=g, device=device) * 0.03).to(dtype))
+
+    def vec(value):
+        return torch.nn.Parameter(torch.full((hidden,), value, device=device))
+
+    return {"wqkv": mat(3 * hidden, hidden), "wo": mat(hidden, hidden), "w1": mat(4 * hidden, hidden),
+            "w2": mat(hidden, 4 * hidden), "g1": vec(1.0), "b1": vec(0.0), "g2": vec(1.0), "b2": vec(0.0)}
+
+
+def frozen_encoder_block(x: torch.Tensor, p: dict, heads: int, wrapped: bool, keep_ppm: int = 100000,
+                         gelu_bits: int = 4, block: int = 64) -> torch.Tensor:
+    """One pre-LN encoder block whose layers are all frozen: with ``wrapped`` the activations kept
+    for the backward pass are the compressed ones (pruned LayerNorm input, pruned attention probabilities shared by
+    Softmax and MatMul, 4-bit GELU input, nothing for the frozen linear layers); without, plain torch ops."""
+    B, T, H = x.shape
+    D = H // heads
+    F = torch.nn.functional
+
+    def split(t):
+        return t.reshape(B, T, heads, D).transpose(1, 2)
+
+    if wrapped:
+        h = LayerNormFunction.apply(x, p["g1"], p["b1"], 1e-5, True, keep_ppm)
+        q, k_, v = LinearFunction.apply(h, p["wqkv"], None, False, 8, block).chunk(3, dim=-1)
+        s = torch.matmul(split(q), split(k_).transpose(-1, -2)) / D ** 0.5
+        a = SoftmaxMatmulFunction.apply(s, split(v).contiguous(), keep_ppm).transpose(1, 2).reshape(B, T, H)
+        y = x + LinearFunction.apply(a, p["wo"], None, False, 8, block)
+        h = LayerNormFunction.apply(y, p["g2"], p["b2"], 1e-5, True, keep_ppm)
+        h = LinearFunction.apply(h, p["w1"], None, False, 8, block)
+        h = LinearFunction.apply(GeluFunction.apply(h, gelu_bits, block), p["w2"], None, False, 8, block)
+        return y + h
+    h = F.layer_norm(x, (H,), p["g1"].to(x.dtype), p["b1"].to(x.dtype), 1e-5)
+    q, k_, v = F.linear(h, p["wqkv"]).chunk(3, dim=-1)
+    s = torch.matmul(split(q), split(k_).transpose(-1, -2)) / D ** 0.5
+    a = torch.matmul(torch.softmax(s, -1), split(v)).transpose(1, 2).reshape(B, T, H)
+    y = x + F.linear(a, p["wo"])
+    h = F.layer_norm(y, (H,), p["g2"].to(x.dtype), p["b2"].to(x.dtype), 1e-5)
+    h = F.linear(F.gelu(F.linear(h, p["w1"])), p["w2"])
+    return y + h
+
+
+def held_activation_bytes(fn) -> tuple:
+    """(bytes that stay allocated between the forward pass of ``fn`` and its backward pass, apart from the output;
+    milliseconds of forward + backward)."""
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    before = torch.cuda.memory_allocated()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    out = fn()
+    torch.cuda.synchronize()
+    kept = torch.cuda.memory_allocated() - before - out.numel() * out.element_size()
+    out.sum().backward()
+    t1.record()
+    torch.cuda.synchronize()
+    return kept, t0.elapsed_time(t1)
