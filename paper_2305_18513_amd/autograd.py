@@ -25,6 +25,8 @@ computes; the dense matrix products of the linear layer are torch's.
                      pairs and V are cached.  Backward: dP = dO @ V^T (dense
                      product, torch's), dV = P^^T @ dO with P^ restored from the
                      pairs, dlogits from the pairs as in SoftmaxFunction.
+  MatmulFunction     out = a @ b with both operands cached in 8 bits (the paper's
+                     placement for MatMul's activations).
   LinearFunction     Alg. 4: an active layer caches its input in `bits` bits and
                      computes grad_weight from the dequantised input; a frozen
                      layer caches nothing but the weight and returns
@@ -42,6 +44,47 @@ from . import binding as sf
 
 def _flat(t: torch.Tensor) -> torch.Tensor:
     return t.contiguous().view(-1)
+
+
+def _quantise(t: torch.Tensor, bits: int, block: int):
+    """(codes, scales) of the flattened tensor, block-scaled."""
+    f = _flat(t)
+    n = f.numel()
+    codes = torch.empty(sf.packed_bytes(n, bits), dtype=torch.uint8, device=t.device)
+    scales = torch.empty(sf.num_blocks(n, block), dtype=torch.float32, device=t.device)
+    sf.quant_pack(f, sf.Q_BLOCK, bits, block, 0, codes, scales)
+    return codes, scales
+
+
+def _dequantise(codes, scales, bits: int, block: int, shape, dtype) -> torch.Tensor:
+    out = torch.empty(shape, dtype=dtype, device=codes.device)
+    sf.dequant_unpack(codes, scales, sf.Q_BLOCK, bits, block, 0, out.view(-1))
+    return out
+
+
+class MatmulFunction(torch.autograd.Function):
+    """out = a @ b with both operands cached in `bits` bits (the paper keeps MatMul's activations in 8 bits);
+    backward multiplies the incoming gradient with the dequantised operands."""
+
+    @staticmethod
+    def forward(ctx, a: torch.Tensor, b: torch.Tensor, bits: int = 8, block: int = 64):
+        out = torch.matmul(a, b)
+        ca, sa = _quantise(a, bits, block)
+        cb, sb = _quantise(b, bits, block)
+        ctx.save_for_backward(ca, sa, cb, sb)
+        ctx.meta = (bits, block, a.shape, b.shape, a.dtype)
+        return out
+
+    @staticmethod
+    def backward(ctx, grad_output: torch.Tensor):
+        ca, sa, cb, sb = ctx.saved_tensors
+        bits, block, sha, shb, dtype = ctx.meta
+        b_hat = _dequantise(cb, sb, bits, block, shb, dtype)
+        da = torch.matmul(grad_output, b_hat.transpose(-1, -2))
+        del b_hat
+        a_hat = _dequantise(ca, sa, bits, block, sha, dtype)
+        db = torch.matmul(a_hat.transpose(-1, -2), grad_output)
+        return da, db, None, None
 
 
 class GeluFunction(torch.autograd.Function):
@@ -159,8 +202,8 @@ class SoftmaxFunction(torch.autograd.Function):
 
 class SoftmaxMatmulFunction(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, logits: torch.Tensor, v: torch.Tensor, keep_ppm: int = 100000):
-        # logits (..., Tq, Tk), v (..., Tk, D)
+    def forward(ctx, logits: torch.Tensor, v: torch.Tensor, keep_ppm: int = 100000, v_bits: int = 0, block: int = 64):
+        # logits (..., Tq, Tk), v (..., Tk, D); v_bits != 0 caches V quantised as well
         cols = logits.shape[-1]
         l2 = logits.contiguous().view(-1, cols)
         rows = l2.shape[0]
@@ -170,14 +213,22 @@ class SoftmaxMatmulFunction(torch.autograd.Function):
         idx = torch.empty(rows, k, dtype=torch.uint16, device=l2.device)
         sf.softmax_prune(l2, k, probs, vals, idx)
         out = torch.matmul(probs.view(logits.shape), v)
-        ctx.save_for_backward(vals, idx, v)
-        ctx.shape = logits.shape
+        if v_bits:
+            cv, sv = _quantise(v, v_bits, block)
+            ctx.save_for_backward(vals, idx, cv, sv)
+        else:
+            ctx.save_for_backward(vals, idx, v)
+        ctx.meta = (logits.shape, v.shape, v.dtype, v_bits, block)
         return out
 
     @staticmethod
     def backward(ctx, grad_output: torch.Tensor):
-        vals, idx, v = ctx.saved_tensors
-        shape = ctx.shape
+        shape, v_shape, v_dtype, v_bits, block = ctx.meta
+        if v_bits:
+            vals, idx, cv, sv = ctx.saved_tensors
+            v = _dequantise(cv, sv, v_bits, block, v_shape, v_dtype)
+        else:
+            vals, idx, v = ctx.saved_tensors
         cols = shape[-1]
         rows = vals.shape[0]
         dp = torch.matmul(grad_output, v.transpose(-1, -2)).contiguous().view(rows, cols)
@@ -186,7 +237,7 @@ class SoftmaxMatmulFunction(torch.autograd.Function):
         dv = torch.matmul(p_hat.view(shape).transpose(-1, -2), grad_output)
         ds = torch.empty_like(dp)
         sf.softmax_backward_pruned(vals, idx, None, dp, ds)
-        return ds.view(shape), dv, None
+        return ds.view(shape), dv, None, None, None
 
 
 class LinearFunction(torch.autograd.Function):
@@ -255,8 +306,8 @@ def frozen_encoder_block(x: torch.Tensor, p: dict, heads: int, wrapped: bool, ke
     if wrapped:
         h = LayerNormFunction.apply(x, p["g1"], p["b1"], 1e-5, True, keep_ppm)
         q, k_, v = LinearFunction.apply(h, p["wqkv"], None, False, 8, block).chunk(3, dim=-1)
-        s = torch.matmul(split(q), split(k_).transpose(-1, -2)) / D ** 0.5
-        a = SoftmaxMatmulFunction.apply(s, split(v).contiguous(), keep_ppm).transpose(1, 2).reshape(B, T, H)
+        s = MatmulFunction.apply(split(q).contiguous(), split(k_).transpose(-1, -2).contiguous(), 8, block) / D ** 0.5
+        a = SoftmaxMatmulFunction.apply(s, split(v).contiguous(), keep_ppm, 8, block).transpose(1, 2).reshape(B, T, H)
         y = x + LinearFunction.apply(a, p["wo"], None, False, 8, block)
         h = LayerNormFunction.apply(y, p["g2"], p["b2"], 1e-5, True, keep_ppm)
         h = LinearFunction.apply(h, p["w1"], None, False, 8, block)

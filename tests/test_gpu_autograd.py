@@ -273,6 +273,28 @@ def test_softmax_matmul_function_shares_the_pruned_probabilities():
     assert torch.equal(v.grad, p_hat.view(B, h, T, T).transpose(-1, -2) @ do)
 
 
+def test_matmul_function_caches_both_operands_in_eight_bits():
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(10)
+    a = torch.randn(3, 4, 50, 64, generator=g, device="cuda").requires_grad_(True)
+    b = torch.randn(3, 4, 64, 70, generator=g, device="cuda").requires_grad_(True)
+    do = torch.randn(3, 4, 50, 70, generator=g, device="cuda")
+    out = ag.MatmulFunction.apply(a, b, 8, 64)
+    na, nb = a.numel(), b.numel()
+    assert _saved_bytes(out) == na + nb + 4 * (sf.num_blocks(na, 64) + sf.num_blocks(nb, 64))
+    assert torch.equal(out.detach(), a.detach() @ b.detach())
+    out.backward(do)
+    a2, b2 = a.detach().clone().requires_grad_(True), b.detach().clone().requires_grad_(True)
+    (a2 @ b2).backward(do)
+    assert (a.grad - a2.grad).norm() / a2.grad.norm() < 0.02 and (b.grad - b2.grad).norm() / b2.grad.norm() < 0.02
+    # exactly the products with the dequantised operands
+    ca = torch.empty(na, dtype=torch.uint8, device="cuda"); sa = torch.empty(sf.num_blocks(na, 64), device="cuda")
+    sf.quant_pack(a.detach().view(-1), sf.Q_BLOCK, 8, 64, 0, ca, sa)
+    ah = torch.empty_like(a.detach())
+    sf.dequant_unpack(ca, sa, sf.Q_BLOCK, 8, 64, 0, ah.view(-1))
+    assert torch.equal(b.grad, ah.transpose(-1, -2) @ do)
+
+
 def test_encoder_block_keeps_less_memory_when_wrapped():
     """A whole frozen encoder block (LayerNorm, QKV, attention with shared pruned probabilities, projection,
     LayerNorm, feed-forward with GELU): activation bytes held between forward and backward, wrapped vs plain torch,
@@ -288,7 +310,7 @@ def test_encoder_block_keeps_less_memory_when_wrapped():
     for q in params.values():
         q.grad = None
     kept_wrapped, _ = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(x, params, heads, wrapped=True))
-    assert kept_wrapped < 0.5 * kept_plain, (kept_plain, kept_wrapped)
+    assert kept_wrapped < 0.25 * kept_plain, (kept_plain, kept_wrapped)
     with torch.no_grad():
         y0 = ag.frozen_encoder_block(x, params, heads, wrapped=False)
         y1 = ag.frozen_encoder_block(x, params, heads, wrapped=True)
