@@ -209,258 +209,264 @@ def main() -> int:
 
     extras = {}
     if not args.no_extras:
-        # the same step with its 169 launches captured in one HIP graph (the library allocates nothing and
-        # never synchronises, so the calls capture as they are); replays are checked against the eager results
-        eager_d = d_dev.clone()
-        eager_codes = sets[0].codes[0].clone()
-        eager_vals = sets[0].vals.clone()
+        try:
+            # the same step with its 169 launches captured in one HIP graph (the library allocates nothing and
+            # never synchronises, so the calls capture as they are); replays are checked against the eager results
+            eager_d = d_dev.clone()
+            eager_codes = sets[0].codes[0].clone()
+            eager_vals = sets[0].vals.clone()
 
-        def kernels_only():
-            for b in range(cfg.n_blocks):
-                s = sets[b % n_sets]
-                for i, a in enumerate(s.acts):
-                    sf.quant_pack(a, sf.Q_BLOCK, bits, block, 0, s.codes[i], s.scales[i])
-                sf.prune_scores(s.scores, cfg.keep_k, mode, tau, s.vals, s.idx, s.counts)
-            for b in reversed(range(cfg.n_blocks)):
-                s = sets[b % n_sets]
-                for i in reversed(range(3)):
-                    sf.dequant_unpack(s.codes[i], s.scales[i], sf.Q_BLOCK, bits, block, 0, s.deq[i])
-            sf.layer_delta_run(numel, pdt, sf.F32, cfg.delta_given, 0.0, d_dev, ws)
+            def kernels_only():
+                for b in range(cfg.n_blocks):
+                    s = sets[b % n_sets]
+                    for i, a in enumerate(s.acts):
+                        sf.quant_pack(a, sf.Q_BLOCK, bits, block, 0, s.codes[i], s.scales[i])
+                    sf.prune_scores(s.scores, cfg.keep_k, mode, tau, s.vals, s.idx, s.counts)
+                for b in reversed(range(cfg.n_blocks)):
+                    s = sets[b % n_sets]
+                    for i in reversed(range(3)):
+                        sf.dequant_unpack(s.codes[i], s.scales[i], sf.Q_BLOCK, bits, block, 0, s.deq[i])
+                sf.layer_delta_run(numel, pdt, sf.F32, cfg.delta_given, 0.0, d_dev, ws)
 
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            kernels_only()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        was_on = sf.set_pointer_checks(False)             # pointer queries have no place inside a capture
-        with torch.cuda.graph(graph, stream=side):
-            kernels_only()
-        sf.set_pointer_checks(was_on)
-
-        def graph_step():
-            nonlocal mask
-            graph.replay()
-            d_host_pinned.copy_(d_dev, non_blocking=True)
-            torch.cuda.current_stream().synchronize()
-            sf.ils_update(d_vec, d_host_pinned.numpy(), mask)
-            _, mask = sf.ils_select(d_vec, n_freeze)
-
-        same = True
-        for _ in range(max(args.warmup, 2)):
-            d_dev.zero_()
-            sets[0].codes[0].zero_()
-            sets[0].vals.zero_()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                kernels_only()
+            torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
-            graph_step()
-            same = same and torch.equal(d_dev, eager_d) and torch.equal(sets[0].codes[0], eager_codes) \
-                and torch.equal(sets[0].vals.view(torch.uint8), eager_vals.view(torch.uint8))
-        torch.cuda.synchronize()
-        tg = time.perf_counter()
-        for _ in range(args.steps):
-            graph_step()
-        torch.cuda.synchronize()
-        g_ms = (time.perf_counter() - tg) * 1e3 / args.steps
-        extras["step_as_hip_graph"] = {"ms_per_step": round(g_ms, 4), "GBps": round(step_bytes / (g_ms * 1e-3) / 1e9, 1),
-                                       "frac_hbm_peak": round(step_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                                       "replays_match_eager": bool(same)}
-        del graph, eager_codes, eager_vals
+            graph = torch.cuda.CUDAGraph()
+            was_on = sf.set_pointer_checks(False)             # pointer queries have no place inside a capture
+            with torch.cuda.graph(graph, stream=side):
+                kernels_only()
+            sf.set_pointer_checks(was_on)
+
+            def graph_step():
+                nonlocal mask
+                graph.replay()
+                d_host_pinned.copy_(d_dev, non_blocking=True)
+                torch.cuda.current_stream().synchronize()
+                sf.ils_update(d_vec, d_host_pinned.numpy(), mask)
+                _, mask = sf.ils_select(d_vec, n_freeze)
+
+            same = True
+            for _ in range(max(args.warmup, 2)):
+                d_dev.zero_()
+                sets[0].codes[0].zero_()
+                sets[0].vals.zero_()
+                torch.cuda.synchronize()
+                graph_step()
+                same = same and torch.equal(d_dev, eager_d) and torch.equal(sets[0].codes[0], eager_codes) \
+                    and torch.equal(sets[0].vals.view(torch.uint8), eager_vals.view(torch.uint8))
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            for _ in range(args.steps):
+                graph_step()
+            torch.cuda.synchronize()
+            g_ms = (time.perf_counter() - tg) * 1e3 / args.steps
+            extras["step_as_hip_graph"] = {"ms_per_step": round(g_ms, 4), "GBps": round(step_bytes / (g_ms * 1e-3) / 1e9, 1),
+                                           "frac_hbm_peak": round(step_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                           "replays_match_eager": bool(same)}
+            del graph, eager_codes, eager_vals
+        except Exception as exc:       # an extra must not cost the step its result line
+            extras.setdefault("errors", []).append(repr(exc))
 
     # next rows of the scope table, outside the timed step: the backward half of pruning
     if not args.no_extras:
-        dense = [torch.empty_like(s.scores) for s in sets]
-        for i in range(len(sets)):
-            sf.restore_scores(sets[i].vals, sets[i].idx, sets[i].counts, dense[i])
-        torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-        for i, (a, b) in enumerate(ev):
-            s = sets[i % n_sets]
-            a.record()
-            sf.restore_scores(s.vals, s.idx, s.counts, dense[i % n_sets])
-            b.record()
-        torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-        nb = b_prune + 4 * cfg.score_rows
-        extras["restore_scores"] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                    "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                    "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del dense
-        # the paper's own placement for the same tensor: 8-bit fixed point, 4 integer + 4 fractional bits
-        sc = [s.scores.reshape(-1) for s in sets]
-        n_sc = sc[0].numel()
-        c8 = [torch.empty(n_sc, dtype=torch.uint8, device="cuda") for _ in sets]
-        for i in range(len(sets)):
-            sf.quant_pack(sc[i], sf.Q_FIXED, 8, 64, 4, c8[i], None)
-        torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-        for i, (a, b) in enumerate(ev):
-            a.record()
-            sf.quant_pack(sc[i % n_sets], sf.Q_FIXED, 8, 64, 4, c8[i % n_sets], None)
-            b.record()
-        torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-        nb = n_sc * (in_sz + 1)
-        extras["quant_pack[scores, fixed 4.4]"] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                                   "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                                   "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del c8, sc
-        # Alg. 5 as printed: the flattened LayerNorm input, int(numel * 0.1) survivors by magnitude, and its restore
-        lns = [s.ln[0] for s in sets]
-        n_ln = lns[0].numel()
-        k_ln = sf.keep_count(n_ln, 100000)
-        gv = [torch.empty(k_ln, dtype=lns[0].dtype, device="cuda") for _ in sets]
-        gi = [torch.empty(k_ln, dtype=torch.int32, device="cuda") for _ in sets]
-        gp = [torch.empty(sf.global_tile_ptr_len(n_ln), dtype=torch.int32, device="cuda") for _ in sets]
-        gws = torch.empty(sf.prune_global_workspace(n_ln), dtype=torch.uint8, device="cuda")
-        gout = [torch.empty_like(x) for x in lns]
-        nb = n_ln * in_sz + k_ln * (in_sz + 4)
-        runs = {
-            "prune_global[ln_in, 10%]": lambda i: sf.prune_global(lns[i], k_ln, gv[i], gi[i], True, gp[i], gws),
-            "restore_global[ln_in, tile pointers]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i], gp[i]),
-            "restore_global[ln_in, zeros+scatter]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i]),
-        }
-        for name, fn in runs.items():
+        try:
+            dense = [torch.empty_like(s.scores) for s in sets]
             for i in range(len(sets)):
-                fn(i)
+                sf.restore_scores(sets[i].vals, sets[i].idx, sets[i].counts, dense[i])
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for i, (a, b) in enumerate(ev):
+                s = sets[i % n_sets]
+                a.record()
+                sf.restore_scores(s.vals, s.idx, s.counts, dense[i % n_sets])
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+            nb = b_prune + 4 * cfg.score_rows
+            extras["restore_scores"] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                                        "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                                        "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del dense
+            # the paper's own placement for the same tensor: 8-bit fixed point, 4 integer + 4 fractional bits
+            sc = [s.scores.reshape(-1) for s in sets]
+            n_sc = sc[0].numel()
+            c8 = [torch.empty(n_sc, dtype=torch.uint8, device="cuda") for _ in sets]
+            for i in range(len(sets)):
+                sf.quant_pack(sc[i], sf.Q_FIXED, 8, 64, 4, c8[i], None)
             torch.cuda.synchronize()
             ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
             for i, (a, b) in enumerate(ev):
                 a.record()
-                fn(i % n_sets)
+                sf.quant_pack(sc[i % n_sets], sf.Q_FIXED, 8, 64, 4, c8[i % n_sets], None)
                 b.record()
             torch.cuda.synchronize()
             ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-            extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb, "numel": n_ln, "k": k_ln,
-                            "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del gv, gi, gp, gws, gout
-        # the caches fused into their producer / consumer (x read once; the dequantised values never stored;
-        # softmax and pruning in one pass over the logits)
-        n_g = sets[0].gelu.numel()
-        nb_g = 2 * n_g * in_sz + sf.packed_bytes(n_g, bits) + 4 * sf.num_blocks(n_g, block)
-        rows_s, cols_s = sets[0].scores.shape
-        nb_s = 2 * rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (in_sz + 2)
-        probs = [torch.empty_like(s.scores) for s in sets]
-        fused = {
-            "gelu_quant_pack[gelu_in]": (nb_g, lambda i: sf.gelu_quant_pack(
-                sets[i].gelu, sf.Q_BLOCK, bits, block, 0, sets[i].deq[0], sets[i].codes[0], sets[i].scales[0])),
-            "gelu_backward_dequant[gelu_in]": (nb_g, lambda i: sf.gelu_backward_dequant(
-                sets[i].codes[0], sets[i].scales[0], sf.Q_BLOCK, bits, block, 0, sets[i].gelu, sets[i].deq[0])),
-            "softmax_prune[scores as logits]": (nb_s, lambda i: sf.softmax_prune(
-                sets[i].scores, cfg.keep_k, probs[i], sets[i].vals, sets[i].idx)),
-            # consumes the pairs the line above left; the score tensor stands in for the incoming gradient
-            # (only its kept columns are read: k elements per row are the algorithmic bytes, although at
-            # 10 % kept nearly every 128-byte line of it is touched)
-            "softmax_backward_pruned[scores]": (
-                rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (2 * in_sz + 2),
-                lambda i: sf.softmax_backward_pruned(sets[i].vals, sets[i].idx, None, sets[i].scores, probs[i])),
-        }
-        for name, (nb, fn) in fused.items():
-            for i in range(len(sets)):
-                fn(i)
-            torch.cuda.synchronize()
-            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-            for i, (a, b) in enumerate(ev):
-                a.record()
-                fn(i % n_sets)
-                b.record()
-            torch.cuda.synchronize()
-            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-            extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                            "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del probs
-        # LayerNorm around its caches: forward with row statistics; the pruned cache (10 % of the standardised input
-        # kept without storing it, input gradient of the frozen layer from the kept pairs); the quantised cache fused
-        # into the forward and backward kernels
-        H = cfg.hidden
-        lnx = [s.ln[0].view(-1, H) for s in sets]
-        rows_l = lnx[0].shape[0]
-        n_l = rows_l * H
-        k_l = sf.keep_count(n_l, 100000)
-        gam = torch.rand(H, device="cuda") + 0.5
-        bet = torch.rand(H, device="cuda") - 0.5
-        lny = [torch.empty_like(x) for x in lnx]
-        mu = [torch.empty(rows_l, device="cuda") for _ in sets]
-        rs = [torch.empty(rows_l, device="cuda") for _ in sets]
-        pv = [torch.empty(k_l, device="cuda") for _ in sets]
-        pi = [torch.empty(k_l, dtype=torch.int32, device="cuda") for _ in sets]
-        rp = [torch.empty(rows_l + 1, dtype=torch.int32, device="cuda") for _ in sets]
-        lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
-        nb_lq = 2 * in_sz * n_l + sf.packed_bytes(n_l, bits) + 4 * sf.num_blocks(n_l, block) + 8 * rows_l
-        ln_runs = {
-            "layernorm_forward[ln_in]": (2 * in_sz * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
-                lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
-            "prune_global_standardized[ln_in, 10%]": (in_sz * n_l + 8 * k_l + 12 * rows_l, lambda i:
-                sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
-            "layernorm_backward_pruned[ln_in]": (2 * in_sz * n_l + 8 * k_l + 8 * rows_l, lambda i:
-                sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
-            # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
-            # reads the input anyway, and the input gradient straight from that cache
-            "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
-                lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
-            "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
-                sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
-        }
-        for name, (nb, fn) in ln_runs.items():
-            for i in range(len(sets)):
-                fn(i)
-            torch.cuda.synchronize()
-            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-            for i, (a, b) in enumerate(ev):
-                a.record()
-                fn(i % n_sets)
-                b.record()
-            torch.cuda.synchronize()
-            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-            extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                            "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del lny, mu, rs, pv, pi, rp, lws
+            nb = n_sc * (in_sz + 1)
+            extras["quant_pack[scores, fixed 4.4]"] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                                                       "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                                                       "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del c8, sc
+            # Alg. 5 as printed: the flattened LayerNorm input, int(numel * 0.1) survivors by magnitude, and its restore
+            lns = [s.ln[0] for s in sets]
+            n_ln = lns[0].numel()
+            k_ln = sf.keep_count(n_ln, 100000)
+            gv = [torch.empty(k_ln, dtype=lns[0].dtype, device="cuda") for _ in sets]
+            gi = [torch.empty(k_ln, dtype=torch.int32, device="cuda") for _ in sets]
+            gp = [torch.empty(sf.global_tile_ptr_len(n_ln), dtype=torch.int32, device="cuda") for _ in sets]
+            gws = torch.empty(sf.prune_global_workspace(n_ln), dtype=torch.uint8, device="cuda")
+            gout = [torch.empty_like(x) for x in lns]
+            nb = n_ln * in_sz + k_ln * (in_sz + 4)
+            runs = {
+                "prune_global[ln_in, 10%]": lambda i: sf.prune_global(lns[i], k_ln, gv[i], gi[i], True, gp[i], gws),
+                "restore_global[ln_in, tile pointers]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i], gp[i]),
+                "restore_global[ln_in, zeros+scatter]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i]),
+            }
+            for name, fn in runs.items():
+                for i in range(len(sets)):
+                    fn(i)
+                torch.cuda.synchronize()
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+                for i, (a, b) in enumerate(ev):
+                    a.record()
+                    fn(i % n_sets)
+                    b.record()
+                torch.cuda.synchronize()
+                ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb, "numel": n_ln, "k": k_ln,
+                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del gv, gi, gp, gws, gout
+            # the caches fused into their producer / consumer (x read once; the dequantised values never stored;
+            # softmax and pruning in one pass over the logits)
+            n_g = sets[0].gelu.numel()
+            nb_g = 2 * n_g * in_sz + sf.packed_bytes(n_g, bits) + 4 * sf.num_blocks(n_g, block)
+            rows_s, cols_s = sets[0].scores.shape
+            nb_s = 2 * rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (in_sz + 2)
+            probs = [torch.empty_like(s.scores) for s in sets]
+            fused = {
+                "gelu_quant_pack[gelu_in]": (nb_g, lambda i: sf.gelu_quant_pack(
+                    sets[i].gelu, sf.Q_BLOCK, bits, block, 0, sets[i].deq[0], sets[i].codes[0], sets[i].scales[0])),
+                "gelu_backward_dequant[gelu_in]": (nb_g, lambda i: sf.gelu_backward_dequant(
+                    sets[i].codes[0], sets[i].scales[0], sf.Q_BLOCK, bits, block, 0, sets[i].gelu, sets[i].deq[0])),
+                "softmax_prune[scores as logits]": (nb_s, lambda i: sf.softmax_prune(
+                    sets[i].scores, cfg.keep_k, probs[i], sets[i].vals, sets[i].idx)),
+                # consumes the pairs the line above left; the score tensor stands in for the incoming gradient
+                # (only its kept columns are read: k elements per row are the algorithmic bytes, although at
+                # 10 % kept nearly every 128-byte line of it is touched)
+                "softmax_backward_pruned[scores]": (
+                    rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (2 * in_sz + 2),
+                    lambda i: sf.softmax_backward_pruned(sets[i].vals, sets[i].idx, None, sets[i].scores, probs[i])),
+            }
+            for name, (nb, fn) in fused.items():
+                for i in range(len(sets)):
+                    fn(i)
+                torch.cuda.synchronize()
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+                for i, (a, b) in enumerate(ev):
+                    a.record()
+                    fn(i % n_sets)
+                    b.record()
+                torch.cuda.synchronize()
+                ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del probs
+            # LayerNorm around its caches: forward with row statistics; the pruned cache (10 % of the standardised input
+            # kept without storing it, input gradient of the frozen layer from the kept pairs); the quantised cache fused
+            # into the forward and backward kernels
+            H = cfg.hidden
+            lnx = [s.ln[0].view(-1, H) for s in sets]
+            rows_l = lnx[0].shape[0]
+            n_l = rows_l * H
+            k_l = sf.keep_count(n_l, 100000)
+            gam = torch.rand(H, device="cuda") + 0.5
+            bet = torch.rand(H, device="cuda") - 0.5
+            lny = [torch.empty_like(x) for x in lnx]
+            mu = [torch.empty(rows_l, device="cuda") for _ in sets]
+            rs = [torch.empty(rows_l, device="cuda") for _ in sets]
+            pv = [torch.empty(k_l, device="cuda") for _ in sets]
+            pi = [torch.empty(k_l, dtype=torch.int32, device="cuda") for _ in sets]
+            rp = [torch.empty(rows_l + 1, dtype=torch.int32, device="cuda") for _ in sets]
+            lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
+            nb_lq = 2 * in_sz * n_l + sf.packed_bytes(n_l, bits) + 4 * sf.num_blocks(n_l, block) + 8 * rows_l
+            ln_runs = {
+                "layernorm_forward[ln_in]": (2 * in_sz * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
+                    lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
+                "prune_global_standardized[ln_in, 10%]": (in_sz * n_l + 8 * k_l + 12 * rows_l, lambda i:
+                    sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
+                "layernorm_backward_pruned[ln_in]": (2 * in_sz * n_l + 8 * k_l + 8 * rows_l, lambda i:
+                    sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
+                # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
+                # reads the input anyway, and the input gradient straight from that cache
+                "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
+                    lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
+                "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
+                    sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
+            }
+            for name, (nb, fn) in ln_runs.items():
+                for i in range(len(sets)):
+                    fn(i)
+                torch.cuda.synchronize()
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+                for i, (a, b) in enumerate(ev):
+                    a.record()
+                    fn(i % n_sets)
+                    b.record()
+                torch.cuda.synchronize()
+                ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
+                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del lny, mu, rs, pv, pi, rp, lws
 
-        # Eq. 1 taken while the update is applied (weights read, update read, weights written: one pass instead of
-        # the optimizer's own apply pass, a kept copy of the old weights and the scoring pass); on copies, so that
-        # the step's own tensors stay as generated
-        w_tmp = [p.clone() for p in prev]
-        upd = [c.clone() for c in cur] if cfg.delta_given else [c - p.float() for p, c in zip(prev, cur)]
-        ws_apply = torch.empty_like(ws)
-        d_apply = torch.empty_like(d_dev)
-        sf.layer_delta_plan(w_tmp, upd, ws_apply)
-        for _ in range(2):
-            sf.layer_delta_apply_run(numel, pdt, sf.F32, 0.0, d_apply, ws_apply)
-        torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(8)]
-        for a, b in ev:
-            a.record()
-            sf.layer_delta_apply_run(numel, pdt, sf.F32, 0.0, d_apply, ws_apply)
-            b.record()
-        torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-        nb = sum(numel) * (2 * esize(cfg.w_dtype) + 4) + 4 * L
-        extras["apply_update_layer_delta[all weight tensors]"] = {
-            "median_ms": round(ms, 5), "bytes_per_launch": nb, "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-            "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del w_tmp, upd, ws_apply, d_apply
+            # Eq. 1 taken while the update is applied (weights read, update read, weights written: one pass instead of
+            # the optimizer's own apply pass, a kept copy of the old weights and the scoring pass); on copies, so that
+            # the step's own tensors stay as generated
+            w_tmp = [p.clone() for p in prev]
+            upd = [c.clone() for c in cur] if cfg.delta_given else [c - p.float() for p, c in zip(prev, cur)]
+            ws_apply = torch.empty_like(ws)
+            d_apply = torch.empty_like(d_dev)
+            sf.layer_delta_plan(w_tmp, upd, ws_apply)
+            for _ in range(2):
+                sf.layer_delta_apply_run(numel, pdt, sf.F32, 0.0, d_apply, ws_apply)
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(8)]
+            for a, b in ev:
+                a.record()
+                sf.layer_delta_apply_run(numel, pdt, sf.F32, 0.0, d_apply, ws_apply)
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+            nb = sum(numel) * (2 * esize(cfg.w_dtype) + 4) + 4 * L
+            extras["apply_update_layer_delta[all weight tensors]"] = {
+                "median_ms": round(ms, 5), "bytes_per_launch": nb, "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del w_tmp, upd, ws_apply, d_apply
 
-        # one frozen encoder block of this configuration through the autograd wrappers: activation bytes held between
-        # forward and backward, against the same block in plain torch ops (the paper's figures are for whole models
-        # on its own hardware: context, not a target)
-        from paper_2305_18513_amd import autograd as ag
-        blk_b = min(cfg.batch, 32)
-        xb = torch.randn(blk_b, cfg.tokens, cfg.hidden, device="cuda").to(cfg.act_dtype).requires_grad_(True)
-        blk = ag.encoder_block_params(cfg.hidden, seed=cfg.seed, dtype=cfg.act_dtype)
-        keep = cfg.keep_ppm
-        for wrapped in (False, True):                       # untimed first pass of each
-            ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, wrapped, keep, bits, block))
-        kept_p, ms_p = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, False))
-        kept_w, ms_w = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, True, keep, bits, block))
-        extras["encoder_block_autograd"] = {
-            "shape": {"batch": blk_b, "tokens": cfg.tokens, "hidden": cfg.hidden, "heads": cfg.heads},
-            "held_MB_plain_torch": round(kept_p / 1e6, 1), "held_MB_wrapped": round(kept_w / 1e6, 1),
-            "reduction": round(kept_p / max(kept_w, 1), 2),
-            "fwd_bwd_ms_plain_torch": round(ms_p, 3), "fwd_bwd_ms_wrapped": round(ms_w, 3)}
-        del xb, blk
+            # one frozen encoder block of this configuration through the autograd wrappers: activation bytes held between
+            # forward and backward, against the same block in plain torch ops (the paper's figures are for whole models
+            # on its own hardware: context, not a target)
+            from paper_2305_18513_amd import autograd as ag
+            blk_b = min(cfg.batch, 32)
+            xb = torch.randn(blk_b, cfg.tokens, cfg.hidden, device="cuda").to(cfg.act_dtype).requires_grad_(True)
+            blk = ag.encoder_block_params(cfg.hidden, seed=cfg.seed, dtype=cfg.act_dtype)
+            keep = cfg.keep_ppm
+            for wrapped in (False, True):                       # untimed first pass of each
+                ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, wrapped, keep, bits, block))
+            kept_p, ms_p = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, False))
+            kept_w, ms_w = ag.held_activation_bytes(lambda: ag.frozen_encoder_block(xb, blk, cfg.heads, True, keep, bits, block))
+            extras["encoder_block_autograd"] = {
+                "shape": {"batch": blk_b, "tokens": cfg.tokens, "hidden": cfg.hidden, "heads": cfg.heads},
+                "held_MB_plain_torch": round(kept_p / 1e6, 1), "held_MB_wrapped": round(kept_w / 1e6, 1),
+                "reduction": round(kept_p / max(kept_w, 1), 2),
+                "fwd_bwd_ms_plain_torch": round(ms_p, 3), "fwd_bwd_ms_wrapped": round(ms_w, 3)}
+            del xb, blk
+        except Exception as exc:       # an extra must not cost the step its result line
+            extras.setdefault("errors", []).append(repr(exc))
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
