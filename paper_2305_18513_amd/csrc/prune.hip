@@ -559,8 +559,27 @@ __global__ __launch_bounds__(kThreads) void prune_rows_block_kernel(const T *__r
                 lmax = fmaxf(lmax, f[s]);
                 lmin = fminf(lmin, f[s]);
             }
-            uint32_t hi = block_max_u32(float_to_key(lmax), scratch);
-            uint32_t lo = ~block_max_u32(~float_to_key(lmin), scratch);
+            // both extrema through LDS in one exchange (the minimum as a maximum of complements); the histogram
+            // and the search result are cleared in the same step
+            const uint32_t wmax = wave_max_u32(float_to_key(lmax)), wmin = wave_max_u32(~float_to_key(lmin));
+            __syncthreads();                                               // previous use of the scratch is over
+            if (lane == 0) {
+                scratch.u[wave] = wmax;
+                scratch.i[wave] = (int)wmin;
+            }
+            hist[tid] = 0u;                                                // kBins == kThreads
+            if (tid == 0) {
+                found[0] = kBins - 1;
+                found[1] = cols;
+            }
+            __syncthreads();
+            uint32_t hi = 0u, lo = 0u;
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock; ++w) {
+                hi = max(hi, scratch.u[w]);
+                lo = max(lo, (uint32_t)scratch.i[w]);
+            }
+            lo = ~lo;
             if (hi == 0x7FFFFFFFu) hi = 0x80000000u;                       // -0 is folded onto +0
             if (lo == 0x7FFFFFFFu) lo = 0x80000000u;
             hi &= KEY_MASK;
@@ -568,13 +587,6 @@ __global__ __launch_bounds__(kThreads) void prune_rows_block_kernel(const T *__r
             const uint32_t range = (hi - lo) >> KEY_SHIFT;
             const int width_bits = 32 - __builtin_clz(range | 1u);
             const int sh = KEY_SHIFT + (width_bits > 8 ? width_bits - 8 : 0);   // bin = (hi - key) >> sh < 256
-
-            hist[tid] = 0u;                                                // kBins == kThreads
-            if (tid == 0) {
-                found[0] = kBins - 1;
-                found[1] = cols;
-            }
-            __syncthreads();
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 if (s * kThreads + tid < cols) {
