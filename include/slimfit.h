@@ -16,7 +16,8 @@
  *    tensor); "host pointer" = ordinary process memory.  Each argument says
  *    which one it is.  The caller owns every buffer and keeps it alive until
  *    the stream has passed the call.  Inputs are never written; outputs are
- *    fully overwritten for the sizes given.
+ *    fully overwritten for the sizes given (the one argument that is both, the
+ *    weights of slimfit_apply_update_layer_delta, is marked as such).
  *  - Device pointers must be 16-byte aligned (SLIMFIT_ERR_ALIGNMENT), except
  *    where a narrower alignment is stated.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
