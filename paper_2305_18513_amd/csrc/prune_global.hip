@@ -85,7 +85,6 @@ template <typename T> struct Elem;
 template <> struct Elem<float> {
     static constexpr int EPV = 4;          // elements per 16-byte vector
     static constexpr int KEYBITS = 32;
-    static constexpr bool WIDEN = false;
     using Out = float;                     // type of the kept values
     using Key = float;                     // type whose key / digit plan applies
 };
