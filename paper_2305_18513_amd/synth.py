@@ -16,7 +16,7 @@ Hx4H, one 4HxH and two LayerNorm weight vectors of length H.
 from __future__ import annotations
 
 import math
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import List, Tuple
 
 import torch

@@ -1,8 +1,5 @@
 """Pins for the oracle's GELU and its derivative (the activation whose input Sec. 4 caches in 4 bits) -- CPU only."""
-import math
-
 import numpy as np
-import pytest
 from scipy import stats
 
 from oracle import ref
