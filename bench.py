@@ -492,6 +492,36 @@ def main() -> int:
     copy_gbs = 2 * csrc.numel() * 4 / (copy_ms * 1e-3) / 1e9
     del csrc, cdst
 
+    # what a kernel that only streams reaches with the dominant kernel's own read : write mix and size
+    probe = None
+    try:
+        reads = {"prune_scores": cfg.score_rows * cfg.score_cols * in_sz}
+        for nm, a in zip(names_q, sets[0].acts):
+            reads[nm] = a.numel() * in_sz
+        dom_read = reads.get(dom, 0)
+        dom_write = timers.bytes[dom] - dom_read if dom_read else 0
+        if dom_read and dom_write > 0 and dom_read >= dom_write:
+            ratio = max(1, min(16, int(round(dom_read / dom_write))))
+            out_vecs = max(256, dom_write // 16 // 256 * 256)
+            pdst = torch.empty(out_vecs * 4, dtype=torch.float32, device="cuda")
+            psrc = torch.empty(out_vecs * 4 * ratio, dtype=torch.float32, device="cuda").normal_()
+            for _ in range(3):
+                sf.stream_probe(psrc, pdst, ratio)
+            torch.cuda.synchronize()
+            pev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for a, b in pev:
+                a.record()
+                sf.stream_probe(psrc, pdst, ratio)
+                b.record()
+            torch.cuda.synchronize()
+            probe_ms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
+            probe_bytes = out_vecs * 16 * (ratio + 1)
+            probe = {"read_write_ratio": ratio, "bytes": probe_bytes, "ms": round(probe_ms, 5),
+                     "GBps": round(probe_bytes / (probe_ms * 1e-3) / 1e9, 1)}
+            del psrc, pdst
+    except Exception as exc:  # the yardstick is context: it never costs the result its line
+        probe = {"error": repr(exc)}
+
     # host side of the step alone: ils_update + ils_select over the L scores
     lat = []
     probe_d, probe_new = d_vec.copy(), d_host_pinned.numpy().copy()
@@ -531,6 +561,11 @@ def main() -> int:
                 "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index, {}).get(dom),
                 "algorithmic_bytes": kernels[dom]["bytes_per_launch"], "avg_ms": kernels[dom]["avg_ms"],
                 "measured_copy_GBps": round(copy_gbs, 1), "frac_of_measured_copy": round(kernels[dom]["GBps"] / copy_gbs, 4)}
+    if probe is not None:
+        # a streaming kernel of the same read : write mix and size, timed the same way on this machine
+        roofline["stream_probe"] = probe
+        if probe.get("GBps"):
+            roofline["frac_of_stream_probe"] = round(kernels[dom]["GBps"] / probe["GBps"], 4)
 
     out = {
         "metric": "activation-compression + freeze-score GB/s per fine-tune step; % of HBM peak",

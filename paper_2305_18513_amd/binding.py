@@ -28,7 +28,7 @@ GLOBAL_TILE = 4096                 # SLIMFIT_GLOBAL_TILE: granularity of prune_g
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_HIP, ERR_POINTER = range(7)
 
 EXPORTS = (
-    "slimfit_status_string", "slimfit_version", "slimfit_set_pointer_checks",
+    "slimfit_status_string", "slimfit_version", "slimfit_set_pointer_checks", "slimfit_stream_probe",
     "slimfit_layer_delta_workspace", "slimfit_layer_delta_plan",
     "slimfit_layer_delta_run", "slimfit_layer_delta", "slimfit_layer_delta_apply_run", "slimfit_apply_update_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
@@ -215,6 +215,15 @@ def apply_update_layer_delta(w: Sequence[torch.Tensor], delta: Sequence[torch.Te
         C.c_int32(L), C.c_float(eps), _dev(d_out), _dev(workspace),
         C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
     _check(rc, "apply_update_layer_delta")
+
+
+def stream_probe(src: torch.Tensor, dst: torch.Tensor, ratio: int, stream=None) -> None:
+    """Diagnostic streaming kernel: dst (16-byte vectors) = sums of ``ratio`` vectors of src each."""
+    out_vecs = dst.numel() * dst.element_size() // 16
+    blocks = (out_vecs + 255) // 256
+    _require(src.numel() * src.element_size() >= blocks * 256 * ratio * 16)
+    rc = lib().slimfit_stream_probe(_dev(src), _dev(dst), C.c_int64(out_vecs), C.c_int32(ratio), _stream(stream))
+    _check(rc, "stream_probe")
 
 
 # ---------------------------------------------------------------- (b) Alg. 2

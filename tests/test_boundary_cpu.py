@@ -295,6 +295,21 @@ def test_fused_and_layernorm_argument_errors_return_before_any_launch(lib):
                                          P(0)) == sf.OK
 
 
+def test_stream_probe_argument_errors(lib):
+    """The diagnostic streaming kernel checks its arguments like every other entry point."""
+    P = C.c_void_p
+
+    def probe(src=16, dst=64, out_vecs=256, ratio=6):
+        return lib.slimfit_stream_probe(P(src), P(dst), C.c_int64(out_vecs), C.c_int32(ratio), P(0))
+    assert probe(out_vecs=0) == sf.OK
+    assert probe(out_vecs=-1) == sf.ERR_INVALID_ARG
+    assert probe(ratio=0) == sf.ERR_INVALID_ARG
+    assert probe(ratio=17) == sf.ERR_INVALID_ARG
+    assert probe(src=0) == sf.ERR_INVALID_ARG
+    assert probe(dst=16) == sf.ERR_INVALID_ARG                   # in place
+    assert probe(dst=72) == sf.ERR_ALIGNMENT
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py is single-GPU by design: --gpus above 1 ends with a message and a non-zero status, before any GPU use."""
     import subprocess
