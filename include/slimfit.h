@@ -70,7 +70,9 @@ int32_t slimfit_set_pointer_checks(int32_t on);
 
 /* Diagnostic, not part of the method: a plain streaming kernel with a chosen read : write ratio, the
  * yardstick for what a perfect kernel of a given traffic mix could reach on this GPU.  Every thread reads
- * `ratio` 16-byte vectors (non-temporal, coalesced), adds them and writes one.
+ * `ratio` 16-byte vectors (non-temporal, coalesced), adds them and writes one: as four fp32 lanes each,
+ * output vector o = 256*b + t is the sum, for r = 0 .. ratio-1 in that order, of source vectors
+ * 256*ratio*b + 256*r + t.
  *  src : DEVICE, at least ceil(out_vecs / 256) * 256 * ratio * 16 bytes, 16-byte aligned, read only.
  *  dst : DEVICE, out_vecs * 16 bytes, 16-byte aligned, not src.     1 <= ratio <= 16. */
 int32_t slimfit_stream_probe(const void *src, void *dst, int64_t out_vecs, int32_t ratio, void *stream);
