@@ -39,8 +39,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same counters' reading of
 # a 1 GiB device copy; see profiles/bench_config3_bert_large.txt), for the default workload only.
 MEASURED_TRAFFIC_BYTES = {
-    3: {"quant_pack[gelu_in]": 918.6e6, "dequant_unpack[gelu_in]": 918.7e6,
-        "prune_scores": 1398.6e6, "layer_delta": 2417.1e6},
+    3: {"quant_pack[gelu_in]": 918.6e6, "dequant_unpack[gelu_in]": 918.8e6,
+        "prune_scores": 1399.1e6, "layer_delta": 2417.3e6},
 }
 
 
