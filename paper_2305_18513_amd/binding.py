@@ -110,9 +110,18 @@ def _dev(t: Optional[torch.Tensor]):
     return C.c_void_p(t.data_ptr())
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream(stream) -> C.c_void_p:
+    """The hipStream_t to launch on: the caller's, else torch's current stream on the current device."""
     if stream is None:
-        stream = torch.cuda.current_stream().cuda_stream
+        # the raw handle straight from torch (0.3 us) where this torch has the call; building a Stream object
+        # to read its handle costs 3 us, a third of a whole call
+        if _raw_stream is not None:
+            stream = _raw_stream(torch.cuda.current_device())
+        else:
+            stream = torch.cuda.current_stream().cuda_stream
     return C.c_void_p(int(stream))
 
 
