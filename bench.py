@@ -20,6 +20,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -501,10 +502,11 @@ def main() -> int:
         dom_read = reads.get(dom, 0)
         dom_write = timers.bytes[dom] - dom_read if dom_read else 0
         if dom_read and dom_write > 0 and dom_read >= dom_write:
-            ratio = max(1, min(16, int(round(dom_read / dom_write))))
-            out_vecs = max(256, dom_write // 16 // 256 * 256)
-            pdst = torch.empty(out_vecs * 4, dtype=torch.float32, device="cuda")
-            psrc = torch.empty(out_vecs * 4 * ratio, dtype=torch.float32, device="cuda").normal_()
+            # the probe writes 16 / ratio bytes per 16 bytes read, ratio a power of two: the one nearest the kernel's
+            ratio = min((1, 2, 4, 8, 16), key=lambda r: abs(math.log2(r) - math.log2(dom_read / dom_write)))
+            in_vecs = max(1024, dom_read // 16 // 1024 * 1024)
+            psrc = torch.empty(in_vecs * 4, dtype=torch.float32, device="cuda").normal_()
+            pdst = torch.empty(in_vecs * (16 // ratio), dtype=torch.uint8, device="cuda")
             for _ in range(3):
                 sf.stream_probe(psrc, pdst, ratio)
             torch.cuda.synchronize()
@@ -515,8 +517,9 @@ def main() -> int:
                 b.record()
             torch.cuda.synchronize()
             probe_ms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
-            probe_bytes = out_vecs * 16 * (ratio + 1)
-            probe = {"read_write_ratio": ratio, "bytes": probe_bytes, "ms": round(probe_ms, 5),
+            probe_bytes = in_vecs * 16 + in_vecs * (16 // ratio)
+            probe = {"read_write_ratio": ratio, "kernel_read_write_ratio": round(dom_read / dom_write, 2),
+                     "bytes": probe_bytes, "ms": round(probe_ms, 5),
                      "GBps": round(probe_bytes / (probe_ms * 1e-3) / 1e9, 1)}
             del psrc, pdst
     except Exception as exc:  # the yardstick is context: it never costs the result its line

@@ -69,13 +69,14 @@ int32_t slimfit_version(void);
 int32_t slimfit_set_pointer_checks(int32_t on);
 
 /* Diagnostic, not part of the method: a plain streaming kernel with a chosen read : write ratio, the
- * yardstick for what a perfect kernel of a given traffic mix could reach on this GPU.  Every thread reads
- * `ratio` 16-byte vectors (non-temporal, coalesced), adds them and writes one: as four fp32 lanes each,
- * output vector o = 256*b + t is the sum, for r = 0 .. ratio-1 in that order, of source vectors
- * 256*ratio*b + 256*r + t.
- *  src : DEVICE, at least ceil(out_vecs / 256) * 256 * ratio * 16 bytes, 16-byte aligned, read only.
- *  dst : DEVICE, out_vecs * 16 bytes, 16-byte aligned, not src.     1 <= ratio <= 16. */
-int32_t slimfit_stream_probe(const void *src, void *dst, int64_t out_vecs, int32_t ratio, void *stream);
+ * yardstick for what a perfect kernel of a given traffic mix could reach on this GPU.  Every thread keeps
+ * four 16-byte loads in flight (non-temporal, coalesced) and writes 16 / ratio bytes for every vector it
+ * read, next to its neighbours'.  With source vector i = (x, y, z, w) as fp32 and s = ((x + y) + z) + w,
+ * output element i is: ratio 1 the vector itself; 2 the pair (x + y, z + w); 4 s; 8 the upper 16 bits of
+ * s; 16 the upper 8 bits of s.
+ *  src : DEVICE, in_vecs * 16 bytes, 16-byte aligned, read only.
+ *  dst : DEVICE, in_vecs * 16 / ratio bytes, 16-byte aligned, not src.     ratio in {1, 2, 4, 8, 16}. */
+int32_t slimfit_stream_probe(const void *src, void *dst, int64_t in_vecs, int32_t ratio, void *stream);
 
 /* ------------------------------------------------------------------------
  * (a) Training-dynamics freeze score -- Eq. 1 (Sec. 3.1):

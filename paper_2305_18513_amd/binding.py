@@ -227,11 +227,10 @@ def apply_update_layer_delta(w: Sequence[torch.Tensor], delta: Sequence[torch.Te
 
 
 def stream_probe(src: torch.Tensor, dst: torch.Tensor, ratio: int, stream=None) -> None:
-    """Diagnostic streaming kernel: dst (16-byte vectors) = sums of ``ratio`` vectors of src each."""
-    out_vecs = dst.numel() * dst.element_size() // 16
-    blocks = (out_vecs + 255) // 256
-    _require(src.numel() * src.element_size() >= blocks * 256 * ratio * 16)
-    rc = lib().slimfit_stream_probe(_dev(src), _dev(dst), C.c_int64(out_vecs), C.c_int32(ratio), _stream(stream))
+    """Diagnostic streaming kernel: every 16-byte vector of src becomes 16 / ratio bytes of dst."""
+    in_vecs = src.numel() * src.element_size() // 16
+    _require(ratio in (1, 2, 4, 8, 16) and dst.numel() * dst.element_size() >= in_vecs * (16 // ratio))
+    rc = lib().slimfit_stream_probe(_dev(src), _dev(dst), C.c_int64(in_vecs), C.c_int32(ratio), _stream(stream))
     _check(rc, "stream_probe")
 
 

@@ -299,12 +299,12 @@ def test_stream_probe_argument_errors(lib):
     """The diagnostic streaming kernel checks its arguments like every other entry point."""
     P = C.c_void_p
 
-    def probe(src=16, dst=64, out_vecs=256, ratio=6):
-        return lib.slimfit_stream_probe(P(src), P(dst), C.c_int64(out_vecs), C.c_int32(ratio), P(0))
-    assert probe(out_vecs=0) == sf.OK
-    assert probe(out_vecs=-1) == sf.ERR_INVALID_ARG
-    assert probe(ratio=0) == sf.ERR_INVALID_ARG
-    assert probe(ratio=17) == sf.ERR_INVALID_ARG
+    def probe(src=16, dst=64, in_vecs=1024, ratio=8):
+        return lib.slimfit_stream_probe(P(src), P(dst), C.c_int64(in_vecs), C.c_int32(ratio), P(0))
+    assert probe(in_vecs=0) == sf.OK
+    assert probe(in_vecs=-1) == sf.ERR_INVALID_ARG
+    for ratio in (0, 3, 7, 32):                                  # powers of two up to 16 only
+        assert probe(ratio=ratio) == sf.ERR_INVALID_ARG
     assert probe(src=0) == sf.ERR_INVALID_ARG
     assert probe(dst=16) == sf.ERR_INVALID_ARG                   # in place
     assert probe(dst=72) == sf.ERR_ALIGNMENT

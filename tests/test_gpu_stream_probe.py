@@ -1,6 +1,7 @@
-"""GPU check of the diagnostic streaming kernel: every output vector is the sum, in order, of its ``ratio`` source
-vectors (the layout the header states), for full and ragged sizes.  It computes nothing of the method; the expected
-values are plain torch additions in the same order, so the comparison is bit for bit."""
+"""GPU check of the diagnostic streaming kernel: every output element is what the header states for its source
+vector (the vector, pair sums, the sum, or the sum's upper bits), for full workgroups and ragged tails.  It computes
+nothing of the method; the expected values are plain torch additions in the same order, so the comparison is bit for
+bit."""
 import pytest
 import torch
 
@@ -10,28 +11,37 @@ from tests.gpu_util import Guarded, require_gpu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("ratio", [1, 2, 6, 16])
-@pytest.mark.parametrize("out_vecs", [1, 255, 256, 1000, 256 * 37 + 3])
-def test_sums_of_ratio_vectors(ratio, out_vecs):
+def _expected(src, ratio):
+    v = src.view(-1, 4)
+    if ratio == 1:
+        return v.reshape(-1).view(torch.uint8)
+    if ratio == 2:
+        return torch.stack([v[:, 0] + v[:, 1], v[:, 2] + v[:, 3]], dim=1).reshape(-1).view(torch.uint8)
+    s = ((v[:, 0] + v[:, 1]) + v[:, 2]) + v[:, 3]
+    if ratio == 4:
+        return s.contiguous().view(torch.uint8)
+    bits = s.contiguous().view(torch.int32)
+    if ratio == 8:
+        return (bits >> 16).to(torch.int16).view(torch.uint8)
+    return (bits >> 24).to(torch.int8).view(torch.uint8)
+
+
+@pytest.mark.parametrize("ratio", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("in_vecs", [1, 255, 1024, 1000, 1024 * 37 + 3])
+def test_every_vector_becomes_its_share_of_bytes(ratio, in_vecs):
     require_gpu()
-    blocks = (out_vecs + 255) // 256
-    g = torch.Generator(device="cuda").manual_seed(ratio * 1000 + out_vecs)
-    src = torch.randn(blocks * 256 * ratio * 4, device="cuda", generator=g)
-    dst = Guarded(out_vecs * 4, torch.float32)
+    g = torch.Generator(device="cuda").manual_seed(ratio * 1000 + in_vecs)
+    src = torch.randn(in_vecs * 4, device="cuda", generator=g)
+    dst = Guarded(in_vecs * (16 // ratio), torch.uint8)
     sf.stream_probe(src, dst.t, ratio)
     torch.cuda.synchronize()
-    v = src.view(blocks, ratio, 256, 4)
-    want = v[:, 0].clone()
-    for r in range(1, ratio):
-        want += v[:, r]
-    want = want.reshape(-1)[: out_vecs * 4]
-    assert torch.equal(dst.t, want)
+    assert torch.equal(dst.t, _expected(src, ratio))
     dst.check()
 
 
-def test_source_too_short_is_refused():
+def test_destination_too_short_is_refused():
     require_gpu()
-    src = torch.zeros(256 * 4 * 5, device="cuda")
-    dst = torch.zeros(256 * 4, device="cuda")
+    src = torch.zeros(1024 * 4, device="cuda")
+    dst = torch.zeros(1024 * 2 - 1, dtype=torch.uint8, device="cuda")
     with pytest.raises(ValueError):
-        sf.stream_probe(src, dst, 6)
+        sf.stream_probe(src, dst, 8)
