@@ -21,7 +21,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libslimfit.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ("api.hip", "quant.hip", "layer_delta.hip", "prune.hip", "prune_global.hip", "layernorm.hip", "probe.hip")
+SOURCES = ("api.hip", "quant.hip", "layer_delta.hip", "prune.hip", "prune_short.hip", "prune_global.hip", "layernorm.hip", "probe.hip")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -14,6 +14,14 @@ constexpr int kWave = 64;
 int32_t check_device_range(const void *p, size_t bytes);   // pointer checks, see slimfit.h
 int32_t launch_status();                                    // hipGetLastError -> status
 
+// short rows that keep few entries have a kernel of their own (prune_short.hip)
+constexpr int kShortPruneMaxCols = 256;
+constexpr int kShortPruneMaxK = 16;                     // bf16 rows
+constexpr int kShortPruneMaxKF32 = 9;                   // fp32 rows
+bool prune_short_eligible(const void *p, int32_t dt, int64_t rows, int cols, int k);
+void launch_prune_short(const void *p, int32_t dt, int64_t rows, int cols, int k, int mode, float tau, void *vals,
+                        uint16_t *idx, int32_t *counts, hipStream_t st);
+
 inline bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline bool dtype_ok(int32_t dt) { return dt == SLIMFIT_F32 || dt == SLIMFIT_BF16; }
 inline size_t dtype_size(int32_t dt) { return dt == SLIMFIT_F32 ? 4 : 2; }

@@ -134,6 +134,9 @@ __device__ __forceinline__ float wave_sum_f32(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+#ifndef SLIMFIT_PRUNE_SHORT
+#define SLIMFIT_PRUNE_SHORT 1          // rows of <= 256 columns keeping <= 16 entries take the short-row kernel
+#endif
 #ifndef SLIMFIT_PRUNE_NT
 #define SLIMFIT_PRUNE_NT 1             // row loads are streamed once
 #endif
@@ -1077,6 +1080,11 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
     const T *pp = static_cast<const T *>(p);
     T *vv = static_cast<T *>(vals);
     T *pr = static_cast<T *>(probs);
+    constexpr int32_t dt = sizeof(T) == 4 ? SLIMFIT_F32 : SLIMFIT_BF16;
+    if (!SOFTMAX && SLIMFIT_PRUNE_SHORT && prune_short_eligible(p, dt, rows, cols, k)) {
+        launch_prune_short(p, dt, rows, cols, k, mode, tau, vals, idx, counts, st);
+        return;
+    }
     const int slots = (cols + kWave - 1) / kWave;
     if (slots > kMaxRegSlots) {                       // never with SOFTMAX: the entry point rejects such rows
         const int bslots = (cols + kThreads - 1) / kThreads;              // slots per thread of a whole workgroup
