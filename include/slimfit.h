@@ -132,6 +132,33 @@ int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_dt,
                             void *stream);
 
 /* ------------------------------------------------------------------------
+ * slimfit_layer_delta for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, arithmetic and results as slimfit_layer_delta,
+ * minus the workspace: the layer table and the per-chunk partial sums live in
+ * a fixed device array of SLIMFIT_LAYER_DELTA_STATIC_BYTES inside the library
+ * (one copy per GPU, held until the process ends).  The call allocates
+ * nothing and frees nothing.
+ *
+ *  - The device that is current when the call is made must be the stream's
+ *    device; its copy of the array is used.
+ *  - Limit: slimfit_layer_delta_workspace(L, numel) must not exceed
+ *    SLIMFIT_LAYER_DELTA_STATIC_BYTES (about 2 * 10^9 weights in a few
+ *    hundred layers); beyond it the call returns SLIMFIT_ERR_WORKSPACE and
+ *    enqueues nothing.
+ *  - Every call on a GPU uses that GPU's one array: calls whose kernels may
+ *    overlap on the same GPU (different streams, or a captured graph replayed
+ *    next to eager calls) race.  Nothing has to be cleared between calls: a
+ *    call rewrites the table and every partial sum it later reads.
+ * ---------------------------------------------------------------------- */
+#define SLIMFIT_LAYER_DELTA_STATIC_BYTES (1u << 20)
+
+int32_t slimfit_layer_delta_static(const void *const *w_prev, int32_t prev_dt,
+                                   const void *const *w_cur, int32_t cur_dt, int32_t cur_is_delta,
+                                   const int64_t *numel, int32_t L, float eps,
+                                   float *d_out, void *stream);
+
+/* ------------------------------------------------------------------------
  * (a') Eq. 1 measured while the optimizer's update is applied.  The paper's
  *     formulation compares W^t with a kept copy of W^{t-1}; when the optimizer
  *     hands over its update delta_i = W_i^t - W_i^{t-1} instead of applying it,

@@ -30,7 +30,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_HIP, ERR
 EXPORTS = (
     "slimfit_status_string", "slimfit_version", "slimfit_set_pointer_checks", "slimfit_stream_probe",
     "slimfit_layer_delta_workspace", "slimfit_layer_delta_plan",
-    "slimfit_layer_delta_run", "slimfit_layer_delta", "slimfit_layer_delta_apply_run", "slimfit_apply_update_layer_delta",
+    "slimfit_layer_delta_run", "slimfit_layer_delta", "slimfit_layer_delta_static", "slimfit_layer_delta_apply_run", "slimfit_apply_update_layer_delta",
     "slimfit_packed_bytes", "slimfit_num_blocks", "slimfit_quant_pack",
     "slimfit_dequant_unpack", "slimfit_gelu_quant_pack", "slimfit_gelu_backward_dequant", "slimfit_keep_count", "slimfit_prune_scores",
     "slimfit_restore_scores", "slimfit_softmax_prune", "slimfit_softmax_backward_pruned", "slimfit_prune_global_workspace", "slimfit_global_tile_ptr_len", "slimfit_prune_global",
@@ -195,6 +195,25 @@ def layer_delta(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor], c
         C.c_float(eps), _dev(d_out), _dev(workspace),
         C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
     _check(rc, "layer_delta")
+
+
+LAYER_DELTA_STATIC_BYTES = 1 << 20     # SLIMFIT_LAYER_DELTA_STATIC_BYTES
+
+
+def layer_delta_static(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor], cur_is_delta: bool,
+                       eps: float, d_out: torch.Tensor, stream=None) -> None:
+    """layer_delta on the library's own fixed scratch array: no workspace, no allocation."""
+    L = len(w_prev)
+    _require(len(w_cur) == L)
+    numel = _numel_array([t.numel() for t in w_prev])
+    pdt = _dt(w_prev[0]) if L else F32
+    cdt = _dt(w_cur[0]) if L else F32
+    _require(d_out.dtype == torch.float32 and d_out.numel() >= L)
+    rc = lib().slimfit_layer_delta_static(
+        _ptr_array(w_prev), C.c_int32(pdt), _ptr_array(w_cur), C.c_int32(cdt),
+        C.c_int32(int(bool(cur_is_delta))), C.c_void_p(numel.ctypes.data), C.c_int32(L),
+        C.c_float(eps), _dev(d_out), _stream(stream))
+    _check(rc, "layer_delta_static")
 
 
 def layer_delta_apply_run(numel: Sequence[int], w_dt: int, delta_dt: int, eps: float, d_out: torch.Tensor,

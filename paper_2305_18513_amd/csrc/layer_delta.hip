@@ -14,6 +14,7 @@
 // host staging memory.
 #include "common.hpp"
 
+#include <mutex>
 #include <vector>
 
 namespace slimfit {
@@ -252,11 +253,43 @@ int32_t layout_of(int32_t L, const int64_t *numel, Layout *out)
     return SLIMFIT_OK;
 }
 
-int32_t check_workspace(const Layout &lay, const void *ws, size_t ws_bytes)
+// own_scratch: the workspace is the library's own device array (no allocation to look up)
+int32_t check_workspace(const Layout &lay, const void *ws, size_t ws_bytes, bool own_scratch = false)
 {
     if (!ws || ws_bytes < lay.bytes) return SLIMFIT_ERR_WORKSPACE;
     if (!aligned_to(ws, 256)) return SLIMFIT_ERR_ALIGNMENT;
-    return check_device_range(ws, lay.bytes);
+    return own_scratch ? SLIMFIT_OK : check_device_range(ws, lay.bytes);
+}
+
+// ---- the workspace of slimfit_layer_delta_static ---------------------------------------------------------
+// A fixed device array, one copy per GPU the library's code is loaded on, alive until the process ends.  Its
+// name is a host-side handle, not a device address: the address on the current device is looked up once per
+// device with hipGetSymbolAddress and kept; kernels and checks only ever see that address.
+constexpr size_t kStaticScratchBytes = SLIMFIT_LAYER_DELTA_STATIC_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];            // guarded by g_scratch_mutex
+
+int32_t static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return SLIMFIT_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return SLIMFIT_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return SLIMFIT_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SLIMFIT_OK;
 }
 
 template <typename TP, typename TC>
@@ -286,9 +319,9 @@ extern "C" int32_t slimfit_layer_delta_workspace(int32_t L, const int64_t *numel
     return SLIMFIT_OK;
 }
 
-extern "C" int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t prev_dt, const void *const *w_cur,
-                                            int32_t cur_dt, const int64_t *numel, int32_t L, void *workspace,
-                                            size_t workspace_bytes, void *stream)
+static int32_t plan_entry(const void *const *w_prev, int32_t prev_dt, const void *const *w_cur, int32_t cur_dt,
+                          const int64_t *numel, int32_t L, void *workspace, size_t workspace_bytes, void *stream,
+                          bool own_scratch)
 {
     if (!dtype_ok(prev_dt) || !dtype_ok(cur_dt)) return SLIMFIT_ERR_INVALID_ARG;
     Layout lay;
@@ -301,7 +334,7 @@ extern "C" int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t p
         if (!w_prev[i] || !w_cur[i]) return SLIMFIT_ERR_INVALID_ARG;
         if (!aligned_to(w_prev[i], 16) || !aligned_to(w_cur[i], 16)) return SLIMFIT_ERR_ALIGNMENT;
     }
-    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes, own_scratch)) != SLIMFIT_OK) return rc;
     for (int32_t i = 0; i < L; ++i) {
         if ((rc = check_device_range(w_prev[i], (size_t)numel[i] * dtype_size(prev_dt))) != SLIMFIT_OK) return rc;
         if ((rc = check_device_range(w_cur[i], (size_t)numel[i] * dtype_size(cur_dt))) != SLIMFIT_OK) return rc;
@@ -331,8 +364,16 @@ extern "C" int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t p
     return launch_status();
 }
 
+extern "C" int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t prev_dt, const void *const *w_cur,
+                                            int32_t cur_dt, const int64_t *numel, int32_t L, void *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    return plan_entry(w_prev, prev_dt, w_cur, cur_dt, numel, L, workspace, workspace_bytes, stream, false);
+}
+
 static int32_t run_entry(const int64_t *numel, int32_t L, int32_t prev_dt, int32_t cur_dt, int32_t cur_is_delta, bool apply,
-                         float eps, float *d_out, void *workspace, size_t workspace_bytes, void *stream)
+                         float eps, float *d_out, void *workspace, size_t workspace_bytes, void *stream,
+                         bool own_scratch = false)
 {
     if (!dtype_ok(prev_dt) || !dtype_ok(cur_dt) || !(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     Layout lay;
@@ -341,7 +382,7 @@ static int32_t run_entry(const int64_t *numel, int32_t L, int32_t prev_dt, int32
     if (L == 0) return SLIMFIT_OK;
     if (!d_out) return SLIMFIT_ERR_INVALID_ARG;
     if (!aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;
-    if ((rc = check_workspace(lay, workspace, workspace_bytes)) != SLIMFIT_OK) return rc;
+    if ((rc = check_workspace(lay, workspace, workspace_bytes, own_scratch)) != SLIMFIT_OK) return rc;
     if ((rc = check_device_range(d_out, sizeof(float) * (size_t)L)) != SLIMFIT_OK) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -389,6 +430,27 @@ extern "C" int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_d
     if (rc != SLIMFIT_OK) return rc;
     return slimfit_layer_delta_run(numel, L, prev_dt, cur_dt, cur_is_delta, eps, d_out, workspace, workspace_bytes,
                                    stream);
+}
+
+extern "C" int32_t slimfit_layer_delta_static(const void *const *w_prev, int32_t prev_dt, const void *const *w_cur,
+                                              int32_t cur_dt, int32_t cur_is_delta, const int64_t *numel, int32_t L,
+                                              float eps, float *d_out, void *stream)
+{
+    if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
+    if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
+    if (L > 0 && !aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;
+    Layout lay;
+    int32_t rc = layout_of(L, numel, &lay);
+    if (rc != SLIMFIT_OK) return rc;
+    if (lay.bytes > kStaticScratchBytes) return SLIMFIT_ERR_WORKSPACE;     // beyond the fixed array: use slimfit_layer_delta
+    if (L == 0) return SLIMFIT_OK;
+    if (check_device_range(d_out, sizeof(float) * (size_t)L) != SLIMFIT_OK) return SLIMFIT_ERR_POINTER;
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != SLIMFIT_OK) return rc;
+    // the table and every partial the finishing kernel reads are rewritten by this call: nothing has to be cleared
+    rc = plan_entry(w_prev, prev_dt, w_cur, cur_dt, numel, L, ws, kStaticScratchBytes, stream, true);
+    if (rc != SLIMFIT_OK) return rc;
+    return run_entry(numel, L, prev_dt, cur_dt, cur_is_delta, false, eps, d_out, ws, kStaticScratchBytes, stream, true);
 }
 
 extern "C" int32_t slimfit_apply_update_layer_delta(void *const *w, int32_t w_dt, const void *const *delta,
