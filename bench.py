@@ -236,10 +236,8 @@ def main() -> int:
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
             graph = torch.cuda.CUDAGraph()
-            was_on = sf.set_pointer_checks(False)             # pointer queries have no place inside a capture
-            with torch.cuda.graph(graph, stream=side):
+            with torch.cuda.graph(graph, stream=side):        # (the library skips its pointer look-ups on a capturing stream)
                 kernels_only()
-            sf.set_pointer_checks(was_on)
 
             def graph_step():
                 nonlocal mask

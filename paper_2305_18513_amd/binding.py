@@ -48,7 +48,10 @@ class SlimfitError(RuntimeError):
 
 
 def _require(ok: bool) -> None:
-    """Shape / dtype agreement of the tensors handed to a wrapper (the C side checks sizes and pointers)."""
+    """Shape, size and dtype agreement of the tensors handed to a wrapper.
+
+    The C side can only check a pointer against its enclosing allocation, which under torch's caching allocator
+    is a segment shared by many tensors: an output tensor that is too small has to be caught here."""
     if not ok:
         raise ValueError("tensor arguments do not agree in shape or dtype with what the call expects")
 
@@ -147,6 +150,16 @@ def layer_delta_workspace(numel: Sequence[int]) -> int:
     return int(out.value)
 
 
+def _same_dtype(tensors: Sequence[torch.Tensor]) -> bool:
+    """The C ABI applies one dtype to every layer of a list."""
+    return all(t.dtype == tensors[0].dtype for t in tensors)
+
+
+def _layer_lists_ok(a: Sequence[torch.Tensor], b: Sequence[torch.Tensor]) -> bool:
+    return (len(a) == len(b) and (not a or (_same_dtype(a) and _same_dtype(b)))
+            and all(x.numel() == y.numel() for x, y in zip(a, b)))
+
+
 def _ptr_array(tensors: Sequence[torch.Tensor]):
     for t in tensors:
         if not t.is_contiguous():
@@ -157,10 +170,8 @@ def _ptr_array(tensors: Sequence[torch.Tensor]):
 def layer_delta_plan(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor],
                      workspace: torch.Tensor, stream=None) -> None:
     L = len(w_prev)
-    _require(len(w_cur) == L)
+    _require(_layer_lists_ok(w_prev, w_cur))
     numel = _numel_array([t.numel() for t in w_prev])
-    for a, b in zip(w_prev, w_cur):
-        _require(a.numel() == b.numel())
     pdt = _dt(w_prev[0]) if L else F32
     cdt = _dt(w_cur[0]) if L else F32
     rc = lib().slimfit_layer_delta_plan(
@@ -184,7 +195,7 @@ def layer_delta_run(numel: Sequence[int], prev_dt: int, cur_dt: int, cur_is_delt
 def layer_delta(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Tensor], cur_is_delta: bool,
                 eps: float, d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
     L = len(w_prev)
-    _require(len(w_cur) == L)
+    _require(_layer_lists_ok(w_prev, w_cur))
     numel = _numel_array([t.numel() for t in w_prev])
     pdt = _dt(w_prev[0]) if L else F32
     cdt = _dt(w_cur[0]) if L else F32
@@ -204,7 +215,7 @@ def layer_delta_static(w_prev: Sequence[torch.Tensor], w_cur: Sequence[torch.Ten
                        eps: float, d_out: torch.Tensor, stream=None) -> None:
     """layer_delta on the library's own fixed scratch array: no workspace, no allocation."""
     L = len(w_prev)
-    _require(len(w_cur) == L)
+    _require(_layer_lists_ok(w_prev, w_cur))
     numel = _numel_array([t.numel() for t in w_prev])
     pdt = _dt(w_prev[0]) if L else F32
     cdt = _dt(w_cur[0]) if L else F32
@@ -231,9 +242,7 @@ def apply_update_layer_delta(w: Sequence[torch.Tensor], delta: Sequence[torch.Te
                              d_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
     """d_out[i] = mean |delta_i / w_i| and w_i += delta_i, one pass over both."""
     L = len(w)
-    _require(len(delta) == L)
-    for a, b in zip(w, delta):
-        _require(a.numel() == b.numel())
+    _require(_layer_lists_ok(w, delta))
     numel = _numel_array([t.numel() for t in w])
     wdt = _dt(w[0]) if L else F32
     ddt = _dt(delta[0]) if L else F32
@@ -263,9 +272,20 @@ def num_blocks(n: int, block: int) -> int:
     return int(lib().slimfit_num_blocks(C.c_int64(n), C.c_int32(block)))
 
 
+def _cache_fits(n: int, mode: int, bits: int, block: int, codes: torch.Tensor, scales: Optional[torch.Tensor]) -> bool:
+    """codes / scales hold what Alg. 2 writes for n elements (the C side rejects bad bits / block values)."""
+    if codes.dtype != torch.uint8 or (scales is not None and scales.dtype != torch.float32):
+        return False
+    if bits in (4, 8) and codes.numel() < (n * bits + 7) // 8:
+        return False
+    if mode == Q_BLOCK and block in (32, 64, 128, 256) and (scales is None or scales.numel() < (n + block - 1) // block):
+        return False
+    return True
+
+
 def quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int,
                codes: torch.Tensor, scales: Optional[torch.Tensor], stream=None) -> None:
-    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
+    _require(_cache_fits(x.numel(), mode, bits, block, codes, scales))
     rc = lib().slimfit_quant_pack(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(x.numel()), C.c_int32(mode), C.c_int32(bits),
         C.c_int32(block), C.c_int32(frac_bits), _dev(codes), _dev(scales), _stream(stream))
@@ -274,7 +294,7 @@ def quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits: int
 
 def dequant_unpack(codes: torch.Tensor, scales: Optional[torch.Tensor], mode: int, bits: int,
                    block: int, frac_bits: int, y: torch.Tensor, stream=None) -> None:
-    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
+    _require(_cache_fits(y.numel(), mode, bits, block, codes, scales))
     rc = lib().slimfit_dequant_unpack(
         _dev(codes), _dev(scales), C.c_int64(y.numel()), C.c_int32(mode), C.c_int32(bits),
         C.c_int32(block), C.c_int32(frac_bits), _dev(y), C.c_int32(_dt(y)), _stream(stream))
@@ -287,7 +307,7 @@ def gelu_quant_pack(x: torch.Tensor, mode: int, bits: int, block: int, frac_bits
                     codes: torch.Tensor, scales: Optional[torch.Tensor], stream=None) -> None:
     """y = GELU(x) and (codes, scales) = quant_pack(x) in one pass over x."""
     _require(x.is_contiguous() and y.is_contiguous() and y.dtype == x.dtype and y.numel() == x.numel())
-    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
+    _require(_cache_fits(x.numel(), mode, bits, block, codes, scales))
     rc = lib().slimfit_gelu_quant_pack(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(x.numel()), C.c_int32(mode), C.c_int32(bits), C.c_int32(block),
         C.c_int32(frac_bits), _dev(y), _dev(codes), _dev(scales), _stream(stream))
@@ -298,7 +318,7 @@ def gelu_backward_dequant(codes: torch.Tensor, scales: Optional[torch.Tensor], m
                           frac_bits: int, dy: torch.Tensor, dx: torch.Tensor, stream=None) -> None:
     """dx = dy * GELU'(dequantised cache); the dequantised values stay in registers."""
     _require(dy.is_contiguous() and dx.is_contiguous() and dx.dtype == dy.dtype and dx.numel() == dy.numel())
-    _require(codes.dtype == torch.uint8 and (scales is None or scales.dtype == torch.float32))
+    _require(_cache_fits(dx.numel(), mode, bits, block, codes, scales))
     rc = lib().slimfit_gelu_backward_dequant(
         _dev(codes), _dev(scales), C.c_int64(dx.numel()), C.c_int32(mode), C.c_int32(bits), C.c_int32(block),
         C.c_int32(frac_bits), _dev(dy), _dev(dx), C.c_int32(_dt(dx)), _stream(stream))
@@ -314,8 +334,9 @@ def keep_count(cols: int, keep_ppm: int) -> int:
 def prune_scores(p: torch.Tensor, k: int, mode: int, tau: float, vals: torch.Tensor,
                  idx: torch.Tensor, counts: Optional[torch.Tensor], stream=None) -> None:
     _require(p.dim() == 2 and vals.dtype == p.dtype and idx.dtype == torch.uint16)
-    _require(counts is None or counts.dtype == torch.int32)
     rows, cols = p.shape
+    _require(k >= 0 and vals.numel() >= rows * k and idx.numel() >= rows * k)
+    _require(counts is None or (counts.dtype == torch.int32 and counts.numel() >= rows))
     rc = lib().slimfit_prune_scores(
         _dev(p), C.c_int32(_dt(p)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
         C.c_int32(mode), C.c_float(tau), _dev(vals), _dev(idx), _dev(counts), _stream(stream))
@@ -324,9 +345,11 @@ def prune_scores(p: torch.Tensor, k: int, mode: int, tau: float, vals: torch.Ten
 
 def restore_scores(vals: torch.Tensor, idx: torch.Tensor, counts: Optional[torch.Tensor],
                    out: torch.Tensor, stream=None) -> None:
-    _require(out.dim() == 2 and vals.dtype == out.dtype and idx.dtype == torch.uint16)
+    _require(out.dim() == 2 and vals.dim() == 2 and vals.dtype == out.dtype and idx.dtype == torch.uint16)
     rows, cols = out.shape
     k = vals.shape[1]
+    _require(vals.shape[0] >= rows and idx.numel() >= rows * k)
+    _require(counts is None or (counts.dtype == torch.int32 and counts.numel() >= rows))
     rc = lib().slimfit_restore_scores(
         _dev(vals), _dev(idx), _dev(counts), C.c_int32(_dt(out)), C.c_int64(rows),
         C.c_int32(cols), C.c_int32(k), _dev(out), _stream(stream))
@@ -340,6 +363,7 @@ def softmax_prune(logits: torch.Tensor, k: int, probs: torch.Tensor, vals: torch
     _require(probs.shape == logits.shape and probs.dtype == logits.dtype)
     _require(vals.dtype == logits.dtype and idx.dtype == torch.uint16)
     rows, cols = logits.shape
+    _require(k >= 0 and vals.numel() >= rows * k and idx.numel() >= rows * k)
     rc = lib().slimfit_softmax_prune(
         _dev(logits), C.c_int32(_dt(logits)), C.c_int64(rows), C.c_int32(cols), C.c_int32(k),
         _dev(probs), _dev(vals), _dev(idx), _stream(stream))
@@ -351,9 +375,10 @@ def softmax_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, counts: Optio
     """ds = p^ * (dp - sum(p^ * dp)) per row, p^ being the rows that restore_scores would rebuild."""
     _require(dp.dim() == 2 and dp.is_contiguous() and ds.is_contiguous())
     _require(ds.shape == dp.shape and ds.dtype == dp.dtype)
-    _require(vals.dtype == dp.dtype and idx.dtype == torch.uint16 and vals.shape == idx.shape)
+    _require(vals.dim() == 2 and vals.dtype == dp.dtype and idx.dtype == torch.uint16 and vals.shape == idx.shape)
     rows, cols = dp.shape
     k = vals.shape[1]
+    _require(vals.shape[0] >= rows and (counts is None or (counts.dtype == torch.int32 and counts.numel() >= rows)))
     rc = lib().slimfit_softmax_backward_pruned(
         _dev(vals), _dev(idx), _dev(counts), _dev(dp), C.c_int32(_dt(dp)), C.c_int64(rows),
         C.c_int32(cols), C.c_int32(k), _dev(ds), _stream(stream))
@@ -361,6 +386,17 @@ def softmax_backward_pruned(vals: torch.Tensor, idx: torch.Tensor, counts: Optio
 
 
 # ---------------------------------------------------------------- (c') Alg. 5, whole tensor
+
+def _own_workspace(workspace: Optional[torch.Tensor], nbytes: int, device, stream) -> torch.Tensor:
+    """A workspace the wrapper allocates is only safe on torch's current stream (whose allocator then keeps the
+    block until the kernels are through); with an explicit stream the caller has to own it."""
+    if workspace is not None:
+        _require(workspace.dtype == torch.uint8)        # its size goes to the C side, which compares it with the need
+        return workspace
+    if stream is not None:
+        raise ValueError("pass a workspace tensor when launching on an explicit stream")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
 
 def prune_global_workspace(n: int) -> int:
     out = C.c_size_t(0)
@@ -382,8 +418,7 @@ def prune_global(x: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor,
     _require(vals.numel() >= k and idx.numel() >= k)
     n = x.numel()
     _require(tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n)))
-    if workspace is None:
-        workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
+    workspace = _own_workspace(workspace, prune_global_workspace(n), x.device, stream)
     rc = lib().slimfit_prune_global(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(n), C.c_int64(k), C.c_int32(int(bool(by_magnitude))),
         _dev(vals), _dev(idx), _dev(tile_ptr), _dev(workspace), C.c_size_t(workspace.numel()), _stream(stream))
@@ -426,8 +461,7 @@ def prune_global_standardized(x: torch.Tensor, mean: torch.Tensor, rstd: torch.T
     _require(mean.numel() >= rows and rstd.numel() >= rows and vals.numel() >= k and idx.numel() >= k)
     _require(tile_ptr is None or (tile_ptr.dtype == torch.int32 and tile_ptr.numel() >= global_tile_ptr_len(n)))
     _require(row_ptr is None or (row_ptr.dtype == torch.int32 and row_ptr.numel() >= rows + 1))
-    if workspace is None:
-        workspace = torch.empty(prune_global_workspace(n), dtype=torch.uint8, device=x.device)
+    workspace = _own_workspace(workspace, prune_global_workspace(n), x.device, stream)
     rc = lib().slimfit_prune_global_standardized(
         _dev(x), C.c_int32(_dt(x)), C.c_int64(n), C.c_int64(H), _dev(mean), _dev(rstd), C.c_int64(k),
         C.c_int32(int(bool(by_magnitude))), _dev(vals), _dev(idx), _dev(tile_ptr), _dev(row_ptr), _dev(workspace),
@@ -491,8 +525,7 @@ def layernorm_param_grads(x: torch.Tensor, mean: torch.Tensor, rstd: torch.Tenso
     need = C.c_size_t(0)
     _check(lib().slimfit_layernorm_param_grads_workspace(C.c_int64(rows), C.c_int64(H), C.byref(need)),
            "layernorm_param_grads_workspace")
-    if workspace is None:
-        workspace = torch.empty(int(need.value), dtype=torch.uint8, device=x.device)
+    workspace = _own_workspace(workspace, int(need.value), x.device, stream)
     rc = lib().slimfit_layernorm_param_grads(
         _dev(x), C.c_int32(_dt(x)), _dev(mean), _dev(rstd), _dev(dy), C.c_int64(rows), C.c_int64(H), _dev(dgamma),
         _dev(dbeta),

@@ -12,6 +12,20 @@
 namespace slimfit {
 
 static std::atomic<int32_t> g_pointer_checks{1};
+static thread_local bool t_capturing = false;      // the entry point running on this thread launches into a capture
+
+StreamScope::StreamScope(void *stream) : prev_(t_capturing)
+{
+    if (!g_pointer_checks.load(std::memory_order_relaxed)) return;
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &status) != hipSuccess) {
+        (void)hipGetLastError();                 // e.g. the legacy stream while another stream captures: not ours to judge
+        status = hipStreamCaptureStatusNone;
+    }
+    t_capturing = prev_ || status == hipStreamCaptureStatusActive;
+}
+
+StreamScope::~StreamScope() { t_capturing = prev_; }
 
 int32_t launch_status()
 {
@@ -20,7 +34,7 @@ int32_t launch_status()
 
 int32_t check_device_range(const void *p, size_t bytes)
 {
-    if (!g_pointer_checks.load(std::memory_order_relaxed) || bytes == 0) return SLIMFIT_OK;
+    if (!g_pointer_checks.load(std::memory_order_relaxed) || t_capturing || bytes == 0) return SLIMFIT_OK;
     if (!p) return SLIMFIT_ERR_INVALID_ARG;
     hipPointerAttribute_t attr;
     if (hipPointerGetAttributes(&attr, p) != hipSuccess) {

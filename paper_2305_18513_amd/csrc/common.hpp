@@ -12,6 +12,16 @@ constexpr int kWave = 64;
 
 // ---- host-side helpers (api.cpp) --------------------------------------------
 int32_t check_device_range(const void *p, size_t bytes);   // pointer checks, see slimfit.h
+// Declared at the top of every entry point that takes a stream: while that stream is being captured into a
+// graph the pointer look-ups (runtime queries a capture does not allow) are skipped for this thread's call.
+struct StreamScope {
+    explicit StreamScope(void *stream);
+    ~StreamScope();
+    StreamScope(const StreamScope &) = delete;
+    StreamScope &operator=(const StreamScope &) = delete;
+private:
+    bool prev_;
+};
 int32_t launch_status();                                    // hipGetLastError -> status
 
 // short rows that keep few entries have a kernel of their own (prune_short.hip)

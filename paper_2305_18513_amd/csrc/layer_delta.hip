@@ -368,6 +368,7 @@ extern "C" int32_t slimfit_layer_delta_plan(const void *const *w_prev, int32_t p
                                             int32_t cur_dt, const int64_t *numel, int32_t L, void *workspace,
                                             size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     return plan_entry(w_prev, prev_dt, w_cur, cur_dt, numel, L, workspace, workspace_bytes, stream, false);
 }
 
@@ -408,12 +409,14 @@ extern "C" int32_t slimfit_layer_delta_run(const int64_t *numel, int32_t L, int3
                                            int32_t cur_is_delta, float eps, float *d_out, void *workspace,
                                            size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     return run_entry(numel, L, prev_dt, cur_dt, cur_is_delta, false, eps, d_out, workspace, workspace_bytes, stream);
 }
 
 extern "C" int32_t slimfit_layer_delta_apply_run(const int64_t *numel, int32_t L, int32_t w_dt, int32_t delta_dt, float eps,
                                                  float *d_out, void *workspace, size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     return run_entry(numel, L, w_dt, delta_dt, 1, true, eps, d_out, workspace, workspace_bytes, stream);
 }
 
@@ -421,6 +424,7 @@ extern "C" int32_t slimfit_layer_delta(const void *const *w_prev, int32_t prev_d
                                        int32_t cur_dt, int32_t cur_is_delta, const int64_t *numel, int32_t L,
                                        float eps, float *d_out, void *workspace, size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     // validate the run-only arguments first so that nothing is enqueued on error
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
@@ -436,6 +440,7 @@ extern "C" int32_t slimfit_layer_delta_static(const void *const *w_prev, int32_t
                                               int32_t cur_dt, int32_t cur_is_delta, const int64_t *numel, int32_t L,
                                               float eps, float *d_out, void *stream)
 {
+    StreamScope capture_aware(stream);
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;
@@ -457,6 +462,7 @@ extern "C" int32_t slimfit_apply_update_layer_delta(void *const *w, int32_t w_dt
                                                     int32_t delta_dt, const int64_t *numel, int32_t L, float eps,
                                                     float *d_out, void *workspace, size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !d_out) return SLIMFIT_ERR_INVALID_ARG;
     if (L > 0 && !aligned_to(d_out, 4)) return SLIMFIT_ERR_ALIGNMENT;

@@ -652,6 +652,7 @@ extern "C" int32_t slimfit_layernorm_forward(const void *x, int32_t dt, const fl
                                              int64_t rows, int64_t H, float eps, void *y, float *mean, float *rstd,
                                              void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (!(eps >= 0.0f)) return SLIMFIT_ERR_INVALID_ARG;
@@ -679,6 +680,7 @@ extern "C" int32_t slimfit_layernorm_backward_pruned(const float *vals, const in
                                                      int64_t k, const float *rstd, const float *gamma, const void *dy,
                                                      int32_t dt, int64_t rows, int64_t H, void *dx, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (k < 0 || k > rows * H) return SLIMFIT_ERR_INVALID_ARG;
@@ -722,6 +724,7 @@ extern "C" int32_t slimfit_layernorm_param_grads(const void *x, int32_t dt, cons
                                                  const void *dy, int64_t rows, int64_t H, float *dgamma, float *dbeta,
                                                  void *workspace, size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (!dgamma || !dbeta || !workspace || (rows > 0 && (!x || !mean || !rstd || !dy))) return SLIMFIT_ERR_INVALID_ARG;
@@ -764,6 +767,7 @@ extern "C" int32_t slimfit_layernorm_backward(const void *x, int32_t dt, const f
                                               const float *gamma, const void *dy, int64_t rows, int64_t H, void *dx,
                                               void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if (rows == 0) return SLIMFIT_OK;
@@ -791,6 +795,7 @@ extern "C" int32_t slimfit_layernorm_forward_quant_pack(const void *x, int32_t d
                                                         int32_t bits, int32_t block, void *y, float *mean, float *rstd,
                                                         uint8_t *codes, float *scales, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if ((rc = validate_quant(H, bits, block)) != SLIMFIT_OK) return rc;
@@ -829,6 +834,7 @@ extern "C" int32_t slimfit_layernorm_backward_dequant(const uint8_t *codes, cons
                                                       const float *gamma, const void *dy, int32_t dt, int64_t rows,
                                                       int64_t H, void *dx, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(rows, H, dt);
     if (rc != SLIMFIT_OK) return rc;
     if ((rc = validate_quant(H, bits, block)) != SLIMFIT_OK) return rc;

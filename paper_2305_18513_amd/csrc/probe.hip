@@ -64,6 +64,7 @@ using namespace slimfit;
 
 extern "C" int32_t slimfit_stream_probe(const void *src, void *dst, int64_t in_vecs, int32_t ratio, void *stream)
 {
+    StreamScope capture_aware(stream);
     if (in_vecs < 0 || (ratio != 1 && ratio != 2 && ratio != 4 && ratio != 8 && ratio != 16)) return SLIMFIT_ERR_INVALID_ARG;
     if (in_vecs == 0) return SLIMFIT_OK;
     if (!src || !dst || src == dst) return SLIMFIT_ERR_INVALID_ARG;

@@ -1154,6 +1154,7 @@ extern "C" int32_t slimfit_keep_count(int32_t cols, int32_t keep_ppm)
 extern "C" int32_t slimfit_prune_scores(const void *p, int32_t dt, int64_t rows, int32_t cols, int32_t k, int32_t mode,
                                         float tau, void *vals, uint16_t *idx, int32_t *counts, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(dt, rows, cols, k);
     if (rc != SLIMFIT_OK) return rc;
     if (mode != SLIMFIT_PRUNE_TOPK && mode != SLIMFIT_PRUNE_THRESHOLD) return SLIMFIT_ERR_INVALID_ARG;
@@ -1178,6 +1179,7 @@ extern "C" int32_t slimfit_prune_scores(const void *p, int32_t dt, int64_t rows,
 extern "C" int32_t slimfit_softmax_prune(const void *logits, int32_t dt, int64_t rows, int32_t cols, int32_t k,
                                          void *probs, void *vals, uint16_t *idx, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(dt, rows, cols, k);
     if (rc != SLIMFIT_OK) return rc;
     if (cols > kMaxRegSlots * kWave) return SLIMFIT_ERR_UNSUPPORTED;      // the row has to fit one wave's registers
@@ -1201,6 +1203,7 @@ extern "C" int32_t slimfit_softmax_prune(const void *logits, int32_t dt, int64_t
 extern "C" int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int32_t *counts, int32_t dt,
                                           int64_t rows, int32_t cols, int32_t k, void *out, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(dt, rows, cols, k);
     if (rc != SLIMFIT_OK) return rc;
     if (rows == 0) return SLIMFIT_OK;
@@ -1231,6 +1234,7 @@ extern "C" int32_t slimfit_softmax_backward_pruned(const void *vals, const uint1
                                                    const void *dp, int32_t dt, int64_t rows, int32_t cols, int32_t k,
                                                    void *ds, void *stream)
 {
+    StreamScope capture_aware(stream);
     int32_t rc = validate(dt, rows, cols, k);
     if (rc != SLIMFIT_OK) return rc;
     if (rows == 0) return SLIMFIT_OK;

@@ -1033,6 +1033,7 @@ extern "C" int32_t slimfit_prune_global(const void *x, int32_t dt, int64_t n, in
                                         void *vals, int32_t *idx, int32_t *tile_ptr, void *workspace,
                                         size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     return prune_global_entry(x, dt, n, 0, nullptr, nullptr, k, by_magnitude, vals, idx, tile_ptr, nullptr, workspace,
                               workspace_bytes, stream);
 }
@@ -1043,6 +1044,7 @@ extern "C" int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, 
                                                      int32_t *tile_ptr, int32_t *row_ptr, void *workspace,
                                                      size_t workspace_bytes, void *stream)
 {
+    StreamScope capture_aware(stream);
     if (H == 0) return SLIMFIT_ERR_INVALID_ARG;
     return prune_global_entry(x, dt, n, H, mean, rstd, k, by_magnitude, vals, idx, tile_ptr, row_ptr, workspace,
                               workspace_bytes, stream);
@@ -1051,6 +1053,7 @@ extern "C" int32_t slimfit_prune_global_standardized(const void *x, int32_t dt, 
 extern "C" int32_t slimfit_restore_global(const void *vals, const int32_t *idx, const int32_t *tile_ptr, int64_t k,
                                           int32_t dt, int64_t n, void *out, void *stream)
 {
+    StreamScope capture_aware(stream);
     if (!dtype_ok(dt) || n < 0 || k < 0 || k > n) return SLIMFIT_ERR_INVALID_ARG;
     if (n > 0x7FFFFFFFLL) return SLIMFIT_ERR_UNSUPPORTED;
     if (n == 0) return SLIMFIT_OK;

@@ -411,6 +411,7 @@ int32_t dequant_entry(const uint8_t *codes, const float *scales, int64_t n, int3
 extern "C" int32_t slimfit_quant_pack(const void *x, int32_t dt, int64_t n, int32_t mode, int32_t bits, int32_t block,
                                       int32_t frac_bits, uint8_t *codes, float *scales, void *stream)
 {
+    StreamScope capture_aware(stream);
     return quant_entry<false>(x, dt, n, mode, bits, block, frac_bits, nullptr, codes, scales, stream);
 }
 
@@ -418,6 +419,7 @@ extern "C" int32_t slimfit_dequant_unpack(const uint8_t *codes, const float *sca
                                           int32_t bits, int32_t block, int32_t frac_bits, void *y, int32_t dt,
                                           void *stream)
 {
+    StreamScope capture_aware(stream);
     return dequant_entry<false>(codes, scales, n, mode, bits, block, frac_bits, nullptr, y, dt, stream);
 }
 
@@ -425,6 +427,7 @@ extern "C" int32_t slimfit_gelu_quant_pack(const void *x, int32_t dt, int64_t n,
                                            int32_t block, int32_t frac_bits, void *y, uint8_t *codes, float *scales,
                                            void *stream)
 {
+    StreamScope capture_aware(stream);
     if (x && x == y) return SLIMFIT_ERR_INVALID_ARG;                    // the kernels are compiled for distinct buffers
     return quant_entry<true>(x, dt, n, mode, bits, block, frac_bits, y, codes, scales, stream);
 }
@@ -433,6 +436,7 @@ extern "C" int32_t slimfit_gelu_backward_dequant(const uint8_t *codes, const flo
                                                  int32_t bits, int32_t block, int32_t frac_bits, const void *dy,
                                                  void *dx, int32_t dt, void *stream)
 {
+    StreamScope capture_aware(stream);
     if (dy && dy == dx) return SLIMFIT_ERR_INVALID_ARG;
     return dequant_entry<true>(codes, scales, n, mode, bits, block, frac_bits, dy, dx, dt, stream);
 }

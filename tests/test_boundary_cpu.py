@@ -319,3 +319,64 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "single-GPU" in (r.stdout + r.stderr)
+
+
+# ---- the binding's own size and dtype checks (host tensors: a bad argument is refused before any C call) ----
+
+def test_binding_rejects_outputs_that_are_too_small():
+    import torch
+    n = 1000
+    x = torch.zeros(n)
+    codes = torch.zeros(sf.packed_bytes(n, 4), dtype=torch.uint8)
+    scales = torch.zeros(sf.num_blocks(n, 64))
+    y = torch.zeros(n)
+    with pytest.raises(ValueError):
+        sf.quant_pack(x, sf.Q_BLOCK, 4, 64, 0, codes[:-1], scales)
+    with pytest.raises(ValueError):
+        sf.quant_pack(x, sf.Q_BLOCK, 4, 64, 0, codes, scales[:-1])
+    with pytest.raises(ValueError):
+        sf.dequant_unpack(codes[:-1], scales, sf.Q_BLOCK, 4, 64, 0, y)
+    with pytest.raises(ValueError):
+        sf.gelu_quant_pack(x, sf.Q_BLOCK, 4, 64, 0, y, codes[:-1], scales)
+    with pytest.raises(ValueError):
+        sf.gelu_backward_dequant(codes, scales[:-1], sf.Q_BLOCK, 4, 64, 0, y, torch.zeros(n))
+    rows, cols, k = 10, 40, 4
+    p = torch.zeros(rows, cols)
+    vals = torch.zeros(rows, k)
+    idx = torch.zeros(rows, k, dtype=torch.uint16)
+    counts = torch.zeros(rows, dtype=torch.int32)
+    with pytest.raises(ValueError):
+        sf.prune_scores(p, k, sf.PRUNE_TOPK, 0.0, vals[:-1], idx, None)
+    with pytest.raises(ValueError):
+        sf.prune_scores(p, k, sf.PRUNE_TOPK, 0.0, vals, idx[:-1], None)
+    with pytest.raises(ValueError):
+        sf.prune_scores(p, k, sf.PRUNE_THRESHOLD, 0.0, vals, idx, counts[:-1])
+    with pytest.raises(ValueError):
+        sf.softmax_prune(p, k, torch.zeros_like(p), vals[:-1], idx)
+    with pytest.raises(ValueError):
+        sf.restore_scores(vals[:-1], idx[:-1], None, p)
+    with pytest.raises(ValueError):
+        sf.softmax_backward_pruned(vals, idx, counts[:-1], p, torch.zeros_like(p))
+
+
+def test_binding_rejects_layer_lists_of_mixed_dtype_or_size():
+    import torch
+    a = [torch.zeros(64), torch.zeros(32, dtype=torch.bfloat16)]          # an fp32 vector next to a bf16 matrix
+    b = [torch.zeros(64), torch.zeros(32)]
+    d = torch.zeros(2)
+    ws = torch.zeros(4096, dtype=torch.uint8)
+    for call in (lambda: sf.layer_delta(a, b, False, 0.0, d, ws),
+                 lambda: sf.layer_delta(b, a, False, 0.0, d, ws),
+                 lambda: sf.layer_delta_plan(a, b, ws),
+                 lambda: sf.layer_delta_static(a, b, False, 0.0, d),
+                 lambda: sf.apply_update_layer_delta(a, b, 0.0, d, ws),
+                 lambda: sf.layer_delta(b, [torch.zeros(64), torch.zeros(31)], False, 0.0, d, ws)):
+        with pytest.raises(ValueError):
+            call()
+
+
+def test_binding_wants_a_workspace_with_an_explicit_stream():
+    import torch
+    x = torch.zeros(100)
+    with pytest.raises(ValueError):
+        sf.prune_global(x, 10, torch.zeros(10), torch.zeros(10, dtype=torch.int32), stream=12345)

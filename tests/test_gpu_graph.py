@@ -106,12 +106,9 @@ def test_captured_calls_replay_to_the_eager_results():
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
-    was_on = sf.set_pointer_checks(False)
-    try:
-        with torch.cuda.graph(graph, stream=side):
-            calls()
-    finally:
-        sf.set_pointer_checks(was_on)
+    # pointer checks stay on: the library sees that the call's stream is capturing and skips the look-ups itself
+    with torch.cuda.graph(graph, stream=side):
+        calls()
 
     scratch = torch.empty(1 << 22, device="cuda")
     for replay in range(4):
