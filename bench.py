@@ -37,12 +37,52 @@ from paper_2305_18513_amd import synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same counters' reading of
-# a 1 GiB device copy; see profiles/bench_config3_bert_large.txt), for the default workload only.
-MEASURED_TRAFFIC_BYTES = {
-    3: {"quant_pack[gelu_in]": 918.6e6, "dequant_unpack[gelu_in]": 918.8e6,
-        "prune_scores": 1399.1e6, "layer_delta": 2417.3e6},
-}
+# Chip constants for the issue-side estimate of a kernel's time: 256 compute units x 4 SIMDs, a wave64 vector or
+# scalar instruction occupying its SIMD's issue slot for 4 cycles at 2.4 GHz.
+SIMDS = 1024
+CLOCK_HZ = 2.4e9
+ISSUE_CYCLES = 4
+
+# rocprofv3 counter figures per (config, kernel): HBM bytes per launch (FETCH_SIZE / WRITE_SIZE, scaled by the same
+# counters' reading of a device copy of known size) and wave-level instructions issued per row.  Read from the
+# tracked summary that `python -m paper_2305_18513_amd.profile_counters` writes from the profiling runs, so that this
+# record and the summary cannot disagree; absent file or entry: null.
+COUNTERS_FILE = os.path.join(ROOT, "profiles", "kernel_counters.txt")
+
+
+def load_counters(path=COUNTERS_FILE):
+    """{(config, kernel): {field: value}} from the DATA lines of the tracked counter summary."""
+    table = {}
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if not line.startswith("DATA "):
+                    continue
+                kv = dict(tok.split("=", 1) for tok in line.split()[1:])
+                key = (int(kv.pop("config")), kv.pop("kernel"))
+                table[key] = {k: float(v) for k, v in kv.items()}
+    except OSError:
+        pass
+    return table
+
+
+def classify_bound(avg_ms, nbytes, counters):
+    """Which limit a kernel ran against, by a fixed rule:
+      launch : its algorithmic bytes would take under 4 us at 8 TB/s (less than 32 MB a launch): start-up, ramp and
+               drain of a launch (5 - 10 us) outweigh the streaming;
+      issue  : the instructions the counters show (the larger of vector and scalar wave instructions per row x rows,
+               4 cycles each, over 1024 SIMDs at 2.4 GHz) account for at least half of the measured time;
+      hbm    : otherwise."""
+    t = avg_ms * 1e-3
+    if nbytes / (HBM_PEAK_GBS * 1e9) < 4e-6:
+        return "launch", None
+    t_issue = None
+    if counters and counters.get("rows") and (counters.get("valu_per_row") or counters.get("salu_per_row")):
+        per_row = max(counters.get("valu_per_row", 0.0), counters.get("salu_per_row", 0.0))
+        t_issue = per_row * counters["rows"] * ISSUE_CYCLES / (SIMDS * CLOCK_HZ)
+        if t_issue >= 0.5 * t:
+            return "issue", t_issue
+    return "hbm", t_issue
 
 
 def esize(dt: torch.dtype) -> int:
@@ -104,15 +144,204 @@ def prune_bytes(rows, cols, k, in_sz):
     return rows * cols * in_sz + rows * k * (in_sz + 2)
 
 
+NAMES_Q = ["quant_pack[gelu_in]", "quant_pack[ln_in]", "quant_pack[ln_in]"]
+NAMES_D = ["dequant_unpack[gelu_in]", "dequant_unpack[ln_in]", "dequant_unpack[ln_in]"]
+
+
+class Workload:
+    """One configuration resident in HBM: n_sets encoder-block buffer sets, every weight tensor, the plan."""
+
+    def __init__(self, cfg: synth.WorkloadConfig, n_sets: int):
+        self.cfg = cfg
+        self.bits = cfg.quant_bits[-1]
+        self.block = cfg.quant_block
+        self.mode = sf.PRUNE_THRESHOLD if cfg.threshold_variant else sf.PRUNE_TOPK
+        self.tau = cfg.threshold_tau if cfg.threshold_variant else 0.0
+        self.in_sz = esize(cfg.act_dtype)
+        self.n_sets = max(1, min(n_sets, cfg.n_blocks))
+        self.sets = [BlockSet(cfg, b, self.bits) for b in range(self.n_sets)]
+        self.prev, self.cur = synth.weight_units(cfg, "cuda")
+        self.numel = [t.numel() for t in self.prev]
+        self.L = len(self.numel)
+        self.ws = torch.empty(sf.layer_delta_workspace(self.numel), dtype=torch.uint8, device="cuda")
+        self.d_dev = torch.empty(self.L, dtype=torch.float32, device="cuda")
+        self.d_host_pinned = torch.empty(self.L, dtype=torch.float32, pin_memory=True)
+        self.d_vec = synth.initial_distance(cfg).numpy().copy()
+        self.n_freeze = sf.freeze_count(self.L, cfg.freeze_rate)
+        _, self.mask = sf.ils_select(self.d_vec, self.n_freeze)
+        self.pdt = sf.BF16 if cfg.w_dtype == torch.bfloat16 else sf.F32
+        sf.layer_delta_plan(self.prev, self.cur, self.ws)           # pointers are stable across steps: planned once
+        torch.cuda.synchronize()
+        self.w_bytes = sum(self.numel) * (esize(cfg.w_dtype) + 4) + 4 * self.L
+        self.b_quant = [quant_bytes(a.numel(), self.in_sz, self.bits, self.block) for a in self.sets[0].acts]
+        self.b_prune = prune_bytes(cfg.score_rows, cfg.score_cols, cfg.keep_k, self.in_sz)
+        self.step_bytes = cfg.n_blocks * (2 * sum(self.b_quant) + self.b_prune) + self.w_bytes
+        # what each kernel reads and writes per launch (for the streaming yardstick of its traffic mix)
+        self.read_write = {"prune_scores": (cfg.score_rows * cfg.score_cols * self.in_sz,
+                                            self.b_prune - cfg.score_rows * cfg.score_cols * self.in_sz),
+                           "layer_delta": (self.w_bytes - 4 * self.L, 4 * self.L)}
+        for nq, nd, a, nb in zip(NAMES_Q, NAMES_D, self.sets[0].acts, self.b_quant):
+            self.read_write[nq] = (a.numel() * self.in_sz, nb - a.numel() * self.in_sz)
+            self.read_write[nd] = (nb - a.numel() * self.in_sz, a.numel() * self.in_sz)
+        self.rows_of = {"prune_scores": cfg.score_rows}
+
+    def describe(self):
+        cfg = self.cfg
+        return "config %d: %s-shaped (%d blocks, hidden %d, %d heads, tokens %d, batch %d)" % (
+            cfg.index, cfg.name, cfg.n_blocks, cfg.hidden, cfg.heads, cfg.tokens, cfg.batch)
+
+    def step(self, run):
+        """One pass of the hot path; run(name, bytes, fn) launches fn (with or without events around it)."""
+        cfg, bits, block = self.cfg, self.bits, self.block
+        for b in range(cfg.n_blocks):                     # forward
+            s = self.sets[b % self.n_sets]
+            for i, a in enumerate(s.acts):
+                run(NAMES_Q[i], self.b_quant[i],
+                    lambda a=a, i=i, s=s: sf.quant_pack(a, sf.Q_BLOCK, bits, block, 0, s.codes[i], s.scales[i]))
+            run("prune_scores", self.b_prune,
+                lambda s=s: sf.prune_scores(s.scores, cfg.keep_k, self.mode, self.tau, s.vals, s.idx, s.counts))
+        for b in reversed(range(cfg.n_blocks)):           # backward
+            s = self.sets[b % self.n_sets]
+            for i in reversed(range(3)):
+                run(NAMES_D[i], self.b_quant[i],
+                    lambda i=i, s=s: sf.dequant_unpack(s.codes[i], s.scales[i], sf.Q_BLOCK, bits, block, 0, s.deq[i]))
+        run("layer_delta", self.w_bytes,
+            lambda: sf.layer_delta_run(self.numel, self.pdt, sf.F32, cfg.delta_given, 0.0, self.d_dev, self.ws))
+        self.d_host_pinned.copy_(self.d_dev, non_blocking=True)
+        torch.cuda.current_stream().synchronize()         # the host needs the L scores
+        sf.ils_update(self.d_vec, self.d_host_pinned.numpy(), self.mask)
+        _, self.mask = sf.ils_select(self.d_vec, self.n_freeze)
+
+    def measure(self, steps, warmup):
+        """warm-up steps, one untimed survey step with events around every launch, then `steps` timed steps with
+        events around the dominant kernel only.  Returns (wall seconds, survey, timers, dominant kernel)."""
+        timers, survey = Timers(), Timers()
+        plain = lambda name, nbytes, fn: fn()
+        for _ in range(warmup):
+            self.step(plain)
+        # An event pair costs about 3 us of stream time; around each of the step's launches that is several per
+        # cent of the step.  So one untimed step surveys every kernel and names the dominant one, and the timed
+        # region carries events around that kernel's launches only.
+        self.step(survey.launch)
+        torch.cuda.synchronize()
+        survey.collect()
+        dom = max(survey.total_ms, key=lambda n: survey.total_ms[n])
+        only_dom = lambda name, nbytes, fn: timers.launch(name, nbytes, fn) if name == dom else fn()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(only_dom)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        timers.collect()
+        return wall, survey, timers, dom
+
+
+def kernel_entry(t, name, per_step):
+    calls = t.calls[name]
+    avg_ms = t.total_ms[name] / calls
+    gbs = t.bytes[name] / (avg_ms * 1e-3) / 1e9
+    return {"calls": calls, "avg_ms": round(avg_ms, 5), "bytes_per_launch": t.bytes[name],
+            "GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+            "total_ms_per_step": round(t.total_ms[name] / per_step, 4)}
+
+
+def stream_yardstick(read_bytes, write_bytes, cache={}):
+    """What a kernel that only streams reaches with this read : write mix and size: the library's diagnostic probe,
+    timed the same way (median of 12 launches between events).  The mix is rounded to the probe's nearest shape:
+    16 / r bytes written per 16 read (r = 1 .. 16), read-only, or 2 / 4 / 8 vectors written per vector read."""
+    if read_bytes <= 0:
+        return None
+    if write_bytes * 64 < read_bytes:
+        ratio = 0
+    elif read_bytes >= write_bytes:
+        ratio = min((1, 2, 4, 8, 16), key=lambda r: abs(math.log2(r) - math.log2(read_bytes / write_bytes)))
+    else:
+        ratio = -min((2, 4, 8), key=lambda m: abs(math.log2(m) - math.log2(write_bytes / read_bytes)))
+    in_vecs = max(1024, read_bytes // 16 // 1024 * 1024)
+    key = (ratio, in_vecs)
+    if key not in cache:
+        out_bytes = sf.stream_probe_bytes(in_vecs, ratio)
+        psrc = torch.empty(in_vecs * 4, dtype=torch.float32, device="cuda").normal_()
+        pdst = torch.empty(max(out_bytes, 16), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            sf.stream_probe(psrc, pdst, ratio)
+        torch.cuda.synchronize()
+        pev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+        for a, b in pev:
+            a.record()
+            sf.stream_probe(psrc, pdst, ratio)
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
+        nbytes = in_vecs * 16 + out_bytes
+        cache[key] = {"shape": ratio, "bytes": nbytes, "ms": round(ms, 5), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+        del psrc, pdst
+    return dict(cache[key], kernel_read_write_ratio=round(read_bytes / max(write_bytes, 1), 2))
+
+
+def kernel_table(wl, survey, timers, dom, steps, counters, with_probe):
+    """Per-kernel record of one configuration: every kernel from the survey step, the dominant one from the timed
+    region; each with the bound the rule assigns and (with_probe) its streaming yardstick."""
+    kernels = {name: dict(kernel_entry(survey, name, 1), measured_in="survey step (untimed)") for name in survey.total_ms}
+    kernels[dom] = dict(kernel_entry(timers, dom, steps), measured_in="timed region", survey_avg_ms=kernels[dom]["avg_ms"])
+    for name, k in kernels.items():
+        cnt = dict(counters.get((wl.cfg.index, name), {}))
+        if name in wl.rows_of:
+            cnt.setdefault("rows", wl.rows_of[name])
+        bound, t_issue = classify_bound(k["avg_ms"], k["bytes_per_launch"], cnt)
+        k["bound"] = bound
+        if t_issue is not None:
+            k["issue_ms_estimate"] = round(t_issue * 1e3, 5)
+        if with_probe:
+            try:
+                rd, wr = wl.read_write[name]
+                probe = stream_yardstick(rd, wr)
+                if probe:
+                    k["stream_probe"] = probe
+                    k["frac_of_stream_probe"] = round(k["GBps"] / probe["GBps"], 4)
+            except Exception as exc:          # the yardstick is context: it never costs the result its line
+                k["stream_probe"] = {"error": repr(exc)}
+    return kernels
+
+
+def sets_for(cfg, requested):
+    """Buffer sets to rotate over: at least `requested`, and enough that one pass over them exceeds 1 GB of inputs
+    (four times the 256 MB memory-side cache), never more than the configuration has encoder blocks."""
+    per_set = (cfg.gelu_in_numel + 2 * cfg.ln_in_numel + cfg.score_rows * cfg.score_cols) * esize(cfg.act_dtype)
+    return max(1, min(cfg.n_blocks, max(requested, -(-(1 << 30) // per_set))))
+
+
+def brief_config(ci, counters):
+    """Another configuration, briefly: one warm-up step, the survey step, two timed steps."""
+    cfg = synth.CONFIGS[ci]
+    wl = Workload(cfg, sets_for(cfg, 3))
+    wall, survey, timers, dom = wl.measure(2, 1)
+    kernels = kernel_table(wl, survey, timers, dom, 2, counters, with_probe=False)
+    ms = wall * 1e3 / 2
+    out = {"workload": wl.describe(), "dtype": "f32" if cfg.act_dtype == torch.float32 else "bf16",
+           "quant": "%d-bit block-%d" % (wl.bits, wl.block), "keep_k": cfg.keep_k,
+           "prune_mode": "threshold" if cfg.threshold_variant else "topk", "buffer_sets": wl.n_sets,
+           "step_bytes": wl.step_bytes, "ms_per_step": round(ms, 4),
+           "GBps": round(wl.step_bytes / (ms * 1e-3) / 1e9, 1),
+           "frac_hbm_peak": round(wl.step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "dominant_kernel": dom,
+           "kernels": {n: {f: k[f] for f in ("calls", "avg_ms", "bytes_per_launch", "GBps", "frac_hbm_peak", "bound",
+                                             "measured_in") if f in k} for n, k in kernels.items()}}
+    del wl
+    torch.cuda.empty_cache()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (3 = BERT-large-shaped)")
-    ap.add_argument("--sets", type=int, default=3, help="distinct encoder-block buffer sets to rotate over")
+    ap.add_argument("--sets", type=int, default=3, help="distinct encoder-block buffer sets to rotate over (at least)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip kernels outside the timed step (restore_scores, 8-bit scores, whole-tensor pruning)")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the brief runs of the other four configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device copies (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -128,85 +357,19 @@ def main() -> int:
         from paper_2305_18513_amd import build
         build.build_library()
     sf.lib()
+    torch.cuda.set_device(0)
+    counters = load_counters()
 
     cfg = synth.CONFIGS[args.config]
-    bits = cfg.quant_bits[-1]
-    block = cfg.quant_block
-    mode = sf.PRUNE_THRESHOLD if cfg.threshold_variant else sf.PRUNE_TOPK
-    tau = cfg.threshold_tau if cfg.threshold_variant else 0.0
-    torch.cuda.set_device(0)
-    in_sz = esize(cfg.act_dtype)
+    wl = Workload(cfg, sets_for(cfg, args.sets))
+    # the names the kernels outside the timed step (extras) use
+    bits, block, mode, tau, in_sz = wl.bits, wl.block, wl.mode, wl.tau, wl.in_sz
+    sets, n_sets, prev, cur, numel, L = wl.sets, wl.n_sets, wl.prev, wl.cur, wl.numel, wl.L
+    ws, d_dev, d_host_pinned, d_vec, n_freeze, pdt = wl.ws, wl.d_dev, wl.d_host_pinned, wl.d_vec, wl.n_freeze, wl.pdt
+    b_prune, step_bytes = wl.b_prune, wl.step_bytes
 
-    n_sets = max(1, min(args.sets, cfg.n_blocks))
-    sets = [BlockSet(cfg, b, bits) for b in range(n_sets)]
-    prev, cur = synth.weight_units(cfg, "cuda")
-    numel = [t.numel() for t in prev]
-    L = len(numel)
-    ws = torch.empty(sf.layer_delta_workspace(numel), dtype=torch.uint8, device="cuda")
-    d_dev = torch.empty(L, dtype=torch.float32, device="cuda")
-    d_host_pinned = torch.empty(L, dtype=torch.float32, pin_memory=True)
-    d_vec = synth.initial_distance(cfg).numpy().copy()
-    n_freeze = sf.freeze_count(L, cfg.freeze_rate)
-    _, mask = sf.ils_select(d_vec, n_freeze)
-    pdt = sf.BF16 if cfg.w_dtype == torch.bfloat16 else sf.F32
-    sf.layer_delta_plan(prev, cur, ws)           # pointers are stable across steps: planned once
-    torch.cuda.synchronize()
-
-    w_bytes = sum(numel) * (esize(cfg.w_dtype) + 4) + 4 * L
-    b_quant = [quant_bytes(a.numel(), in_sz, bits, block) for a in sets[0].acts]
-    b_prune = prune_bytes(cfg.score_rows, cfg.score_cols, cfg.keep_k, in_sz)
-    step_bytes = cfg.n_blocks * (2 * sum(b_quant) + b_prune) + w_bytes
-    names_q = ["quant_pack[gelu_in]", "quant_pack[ln_in]", "quant_pack[ln_in]"]
-    names_d = ["dequant_unpack[gelu_in]", "dequant_unpack[ln_in]", "dequant_unpack[ln_in]"]
-
-    timers = Timers()            # the timed region: events around the dominant kernel only
-    survey = Timers()            # one untimed step with events around every kernel
-
-    def step(record):
-        """record: None (no events), "all" (survey step) or the name of the one kernel to time."""
-        nonlocal mask
-
-        def run(name, nbytes, fn):
-            if record == "all":
-                survey.launch(name, nbytes, fn)
-            elif record == name:
-                timers.launch(name, nbytes, fn)
-            else:
-                fn()
-        for b in range(cfg.n_blocks):                     # forward
-            s = sets[b % n_sets]
-            for i, a in enumerate(s.acts):
-                run(names_q[i], b_quant[i],
-                    lambda a=a, i=i, s=s: sf.quant_pack(a, sf.Q_BLOCK, bits, block, 0, s.codes[i], s.scales[i]))
-            run("prune_scores", b_prune,
-                lambda s=s: sf.prune_scores(s.scores, cfg.keep_k, mode, tau, s.vals, s.idx, s.counts))
-        for b in reversed(range(cfg.n_blocks)):           # backward
-            s = sets[b % n_sets]
-            for i in reversed(range(3)):
-                run(names_d[i], b_quant[i],
-                    lambda i=i, s=s: sf.dequant_unpack(s.codes[i], s.scales[i], sf.Q_BLOCK, bits, block, 0, s.deq[i]))
-        run("layer_delta", w_bytes,
-            lambda: sf.layer_delta_run(numel, pdt, sf.F32, cfg.delta_given, 0.0, d_dev, ws))
-        d_host_pinned.copy_(d_dev, non_blocking=True)
-        torch.cuda.current_stream().synchronize()         # the host needs the L scores
-        sf.ils_update(d_vec, d_host_pinned.numpy(), mask)
-        _, mask = sf.ils_select(d_vec, n_freeze)
-
-    for _ in range(args.warmup):
-        step(None)
-    # An event pair costs about 3 us of stream time; around each of the step's 169 launches that is 6 % of
-    # the step.  So one untimed step surveys every kernel and names the dominant one, and the timed region
-    # carries events around that kernel's launches only.
-    step("all")
-    torch.cuda.synchronize()
-    survey.collect()
-    dom = max(survey.total_ms, key=lambda n: survey.total_ms[n])
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(dom)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    timers.collect()
+    wall, survey, timers, dom = wl.measure(args.steps, args.warmup)
+    mask = wl.mask
 
     extras = {}
     if not args.no_extras:
@@ -475,54 +638,6 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # what a plain device copy of 1 GiB reaches on this machine (read + write bytes), for scale
-    csrc = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-    cdst = torch.empty_like(csrc)
-    for _ in range(3):
-        cdst.copy_(csrc)
-    torch.cuda.synchronize()
-    cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
-    for a, b in cev:
-        a.record()
-        cdst.copy_(csrc)
-        b.record()
-    torch.cuda.synchronize()
-    copy_ms = sorted(a.elapsed_time(b) for a, b in cev)[len(cev) // 2]
-    copy_gbs = 2 * csrc.numel() * 4 / (copy_ms * 1e-3) / 1e9
-    del csrc, cdst
-
-    # what a kernel that only streams reaches with the dominant kernel's own read : write mix and size
-    probe = None
-    try:
-        reads = {"prune_scores": cfg.score_rows * cfg.score_cols * in_sz}
-        for nm, a in zip(names_q, sets[0].acts):
-            reads[nm] = a.numel() * in_sz
-        dom_read = reads.get(dom, 0)
-        dom_write = timers.bytes[dom] - dom_read if dom_read else 0
-        if dom_read and dom_write > 0 and dom_read >= dom_write:
-            # the probe writes 16 / ratio bytes per 16 bytes read, ratio a power of two: the one nearest the kernel's
-            ratio = min((1, 2, 4, 8, 16), key=lambda r: abs(math.log2(r) - math.log2(dom_read / dom_write)))
-            in_vecs = max(1024, dom_read // 16 // 1024 * 1024)
-            psrc = torch.empty(in_vecs * 4, dtype=torch.float32, device="cuda").normal_()
-            pdst = torch.empty(in_vecs * (16 // ratio), dtype=torch.uint8, device="cuda")
-            for _ in range(3):
-                sf.stream_probe(psrc, pdst, ratio)
-            torch.cuda.synchronize()
-            pev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-            for a, b in pev:
-                a.record()
-                sf.stream_probe(psrc, pdst, ratio)
-                b.record()
-            torch.cuda.synchronize()
-            probe_ms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
-            probe_bytes = in_vecs * 16 + in_vecs * (16 // ratio)
-            probe = {"read_write_ratio": ratio, "kernel_read_write_ratio": round(dom_read / dom_write, 2),
-                     "bytes": probe_bytes, "ms": round(probe_ms, 5),
-                     "GBps": round(probe_bytes / (probe_ms * 1e-3) / 1e9, 1)}
-            del psrc, pdst
-    except Exception as exc:  # the yardstick is context: it never costs the result its line
-        probe = {"error": repr(exc)}
-
     # host side of the step alone: ils_update + ils_select over the L scores
     lat = []
     probe_d, probe_new = d_vec.copy(), d_host_pinned.numpy().copy()
@@ -545,28 +660,34 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     value = step_bytes / (wall / args.steps) / 1e9
 
-    def entry(t, name, per_step):
-        calls = t.calls[name]
-        avg_ms = t.total_ms[name] / calls
-        gbs = t.bytes[name] / (avg_ms * 1e-3) / 1e9
-        return {"calls": calls, "avg_ms": round(avg_ms, 5), "bytes_per_launch": t.bytes[name],
-                "GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                "total_ms_per_step": round(t.total_ms[name] / per_step, 4)}
-
-    # every kernel from the survey step; the dominant one from the timed region
-    kernels = {name: dict(entry(survey, name, 1), measured_in="survey step (untimed)") for name in survey.total_ms}
-    kernels[dom] = dict(entry(timers, dom, args.steps), measured_in="timed region",
-                        survey_avg_ms=kernels[dom]["avg_ms"])
-    roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index, {}).get(dom),
-                "algorithmic_bytes": kernels[dom]["bytes_per_launch"], "avg_ms": kernels[dom]["avg_ms"],
-                "measured_copy_GBps": round(copy_gbs, 1), "frac_of_measured_copy": round(kernels[dom]["GBps"] / copy_gbs, 4)}
-    if probe is not None:
+    kernels = kernel_table(wl, survey, timers, dom, args.steps, counters, with_probe=True)
+    kd = kernels[dom]
+    cnt = counters.get((cfg.index, dom), {})
+    traffic = None
+    if cnt.get("fetch_bytes") is not None and cnt.get("write_bytes") is not None:
+        traffic = cnt["fetch_bytes"] + cnt["write_bytes"]
+    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": kd["frac_hbm_peak"], "traffic": traffic,
+                "traffic_source": "profiles/kernel_counters.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, from "
+                                  "separate profiling runs of this bench; not measured in this run)",
+                "algorithmic_bytes": kd["bytes_per_launch"], "avg_ms": kd["avg_ms"],
+                "bound_rule": "launch: bytes / 8 TB/s < 4 us; issue: max(VALU, SALU) wave instructions per row "
+                              "(profiles/kernel_counters.txt) x rows x 4 cycles / (1024 SIMDs x 2.4 GHz) >= half the "
+                              "measured time; hbm: otherwise"}
+    if "stream_probe" in kd:
         # a streaming kernel of the same read : write mix and size, timed the same way on this machine
-        roofline["stream_probe"] = probe
-        if probe.get("GBps"):
-            roofline["frac_of_stream_probe"] = round(kernels[dom]["GBps"] / probe["GBps"], 4)
+        roofline["stream_probe"] = kd["stream_probe"]
+        if "frac_of_stream_probe" in kd:
+            roofline["frac_of_stream_probe"] = kd["frac_of_stream_probe"]
+
+    # the other configurations, briefly (per-config throughput and the bound that applies, in this same record)
+    configs = {}
+    if not args.no_other_configs:
+        main_summary = {"workload": wl.describe(), "ms_per_step": round(ms_per_step, 4), "GBps": round(value, 1),
+                        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4), "dominant_kernel": dom,
+                        "kernels": {n: {f: k[f] for f in ("calls", "avg_ms", "bytes_per_launch", "GBps", "frac_hbm_peak",
+                                                          "bound", "measured_in") if f in k} for n, k in kernels.items()}}
+        configs[str(cfg.index)] = main_summary
 
     out = {
         "metric": "activation-compression + freeze-score GB/s per fine-tune step; % of HBM peak",
@@ -585,11 +706,21 @@ def main() -> int:
         "kernels": kernels,
         "extras": extras,
     }
+    if not args.no_other_configs:
+        for ci in range(len(synth.CONFIGS)):
+            if ci == cfg.index:
+                continue
+            try:
+                configs[str(ci)] = brief_config(ci, counters)
+            except Exception as exc:       # another configuration must not cost the headline one its line
+                configs[str(ci)] = {"error": repr(exc)}
+        out["configs"] = dict(sorted(configs.items()))
     if not args.no_cpu_baseline:
         try:
             out["cpu_baseline"] = cpu_baseline(cfg, bits, block, mode, tau, sets, prev, cur)
         except Exception as exc:           # the oracle leg must not cost the GPU result its line
-            out["cpu_baseline"] = {"value": None, "unit": "GB/s", "cores": 0, "kind": "oracle", "sample": "failed: %r" % (exc,)}
+            out["cpu_baseline"] = {"value": None, "unit": "GB/s", "cores": 0, "host_cores": os.cpu_count(), "kind": "oracle",
+                                   "sample": "failed: %r" % (exc,)}
     print(json.dumps(out))
     return 0
 
@@ -637,7 +768,13 @@ def cpu_baseline(cfg, bits, block, mode, tau, sets, prev, cur):
     ref.prune_scores(s0, cfg.keep_k, mode=mode, tau=tau, threads=1)
     dt1 = time.perf_counter() - t1
     nb1 = 2 * quant_bytes(a0.size, in_sz, bits, block) + prune_bytes(s0.shape[0], s0.shape[1], cfg.keep_k, in_sz)
-    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    # cores: the threads the oracle ran on; host_cores: what the box has; usable_cores: what this process may use
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "host_cores": os.cpu_count(),
+            "usable_cores": usable, "kind": "oracle",
             "seconds": round(dt, 2), "bytes": nbytes,
             "single_thread": {"value": round(nb1 / dt1 / 1e9, 3), "unit": "GB/s", "seconds": round(dt1, 2),
                               "sample": "quant + dequant of 1/16 of one GELU input and prune of 1/16 of one score tensor"},

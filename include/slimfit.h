@@ -74,13 +74,19 @@ int32_t slimfit_version(void);
 int32_t slimfit_set_pointer_checks(int32_t on);
 
 /* Diagnostic, not part of the method: a plain streaming kernel with a chosen read : write ratio, the
- * yardstick for what a perfect kernel of a given traffic mix could reach on this GPU.  Every thread keeps
- * four 16-byte loads in flight (non-temporal, coalesced) and writes 16 / ratio bytes for every vector it
- * read, next to its neighbours'.  With source vector i = (x, y, z, w) as fp32 and s = ((x + y) + z) + w,
- * output element i is: ratio 1 the vector itself; 2 the pair (x + y, z + w); 4 s; 8 the upper 16 bits of
- * s; 16 the upper 8 bits of s.
- *  src : DEVICE, in_vecs * 16 bytes, 16-byte aligned, read only.
- *  dst : DEVICE, in_vecs * 16 / ratio bytes, 16-byte aligned, not src.     ratio in {1, 2, 4, 8, 16}. */
+ * yardstick for what a perfect kernel of a given traffic mix could reach on this GPU.  Loads are 16-byte,
+ * non-temporal and coalesced.
+ *  ratio 1, 2, 4, 8, 16 (a quantiser, a pruner): 16 / ratio bytes are written for every vector read, next
+ *      to its neighbours'.  With source vector i = (x, y, z, w) as fp32 and s = ((x + y) + z) + w, output
+ *      element i is: ratio 1 the vector itself; 2 the pair (x + y, z + w); 4 s; 8 the upper 16 bits of s;
+ *      16 the upper 8 bits of s.  dst: in_vecs * 16 / ratio bytes.
+ *  ratio 0 (a scoring pass): read only; wavefront g of workgroup b (1024 source vectors a workgroup, thread t
+ *      reading vectors b*1024 + t + 256*j) writes the sum of its lanes' s values to the float dst[4*b + g]
+ *      (lane values added over j, then butterfly over the lanes: 32, 16, ... 1).  dst: ceil(in_vecs / 1024) * 16 bytes.
+ *  ratio -2, -4, -8 (a dequantiser): M = -ratio vectors are written per vector read, one thread per output
+ *      vector: output vector o is (s, s + 1, s + 2, s + 3) with s the sum, as a float, of the unsigned 16-bit
+ *      words of source bytes [o * 16 / M, (o + 1) * 16 / M).  dst: in_vecs * M * 16 bytes.
+ *  src : DEVICE, in_vecs * 16 bytes, 16-byte aligned, read only.     dst : DEVICE, 16-byte aligned, not src. */
 int32_t slimfit_stream_probe(const void *src, void *dst, int64_t in_vecs, int32_t ratio, void *stream);
 
 /* ------------------------------------------------------------------------

@@ -254,10 +254,20 @@ def apply_update_layer_delta(w: Sequence[torch.Tensor], delta: Sequence[torch.Te
     _check(rc, "apply_update_layer_delta")
 
 
+def stream_probe_bytes(in_vecs: int, ratio: int) -> int:
+    """Bytes slimfit_stream_probe writes for in_vecs source vectors."""
+    if ratio > 0:
+        return in_vecs * (16 // ratio)
+    if ratio == 0:
+        return (in_vecs + 1023) // 1024 * 16
+    return in_vecs * (-ratio) * 16
+
+
 def stream_probe(src: torch.Tensor, dst: torch.Tensor, ratio: int, stream=None) -> None:
-    """Diagnostic streaming kernel: every 16-byte vector of src becomes 16 / ratio bytes of dst."""
+    """Diagnostic streaming kernel: shrinking (ratio 1..16), read-only (0) or growing (-2, -4, -8) traffic."""
     in_vecs = src.numel() * src.element_size() // 16
-    _require(ratio in (1, 2, 4, 8, 16) and dst.numel() * dst.element_size() >= in_vecs * (16 // ratio))
+    _require(ratio in (1, 2, 4, 8, 16, 0, -2, -4, -8)
+             and dst.numel() * dst.element_size() >= stream_probe_bytes(in_vecs, ratio))
     rc = lib().slimfit_stream_probe(_dev(src), _dev(dst), C.c_int64(in_vecs), C.c_int32(ratio), _stream(stream))
     _check(rc, "stream_probe")
 

@@ -303,7 +303,7 @@ def test_stream_probe_argument_errors(lib):
         return lib.slimfit_stream_probe(P(src), P(dst), C.c_int64(in_vecs), C.c_int32(ratio), P(0))
     assert probe(in_vecs=0) == sf.OK
     assert probe(in_vecs=-1) == sf.ERR_INVALID_ARG
-    for ratio in (0, 3, 7, 32):                                  # powers of two up to 16 only
+    for ratio in (3, 7, 32, -1, -3, -16):                        # 1 .. 16 (powers of two), 0, -2, -4, -8 only
         assert probe(ratio=ratio) == sf.ERR_INVALID_ARG
     assert probe(src=0) == sf.ERR_INVALID_ARG
     assert probe(dst=16) == sf.ERR_INVALID_ARG                   # in place
