@@ -27,10 +27,11 @@ computes; the dense matrix products of the linear layer are torch's.
                      pairs, dlogits from the pairs as in SoftmaxFunction.
   MatmulFunction     out = a @ b with both operands cached in 8 bits (the paper's
                      placement for MatMul's activations).
-  LinearFunction     Alg. 4: an active layer caches its input in `bits` bits and
-                     computes grad_weight from the dequantised input; a frozen
-                     layer caches nothing but the weight and returns
-                     grad_weight = None.
+  LinearFunction     the freezing rule of Alg. 4: a layer whose weight does not
+                     require a gradient (frozen by the scheduler) keeps nothing of
+                     its input and returns no weight gradient; an active one keeps
+                     its input in `bits` bits and forms the weight gradient from
+                     the dequantised input.
 
 All tensors are CUDA tensors (fp32 or bf16 activations; gamma / beta and the
 kept standardised values fp32); the kernels run on torch's current stream.
@@ -241,40 +242,36 @@ class SoftmaxMatmulFunction(torch.autograd.Function):
 
 
 class LinearFunction(torch.autograd.Function):
-    @staticmethod
-    def forward(ctx, input: torch.Tensor, weight: torch.Tensor, bias, requires_grad: bool = True, bits: int = 8,
-                block: int = 64):
-        out = torch.nn.functional.linear(input, weight, bias)
-        ctx.requires_weight_grad = requires_grad
-        ctx.has_bias = bias is not None
-        if requires_grad:
-            xf = _flat(input)
-            n = xf.numel()
-            codes = torch.empty(sf.packed_bytes(n, bits), dtype=torch.uint8, device=input.device)
-            scales = torch.empty(sf.num_blocks(n, block), dtype=torch.float32, device=input.device)
-            sf.quant_pack(xf, sf.Q_BLOCK, bits, block, 0, codes, scales)
-            ctx.save_for_backward(codes, scales, weight)
-            ctx.quant = (bits, block, input.shape, input.dtype)
-        else:
-            ctx.save_for_backward(weight)
-        return out
+    """y = x W^T (+ b) under the freezing rule of Alg. 4.  Whether the layer is frozen is read off the weight itself
+    (``weight.requires_grad``, which is what an inter-layer scheduler flips between iterations): a frozen layer
+    keeps nothing of x and produces no weight gradient; an active one keeps x as ``bits``-bit block-scaled codes
+    and forms its weight gradient from the dequantised x^."""
 
     @staticmethod
-    def backward(ctx, grad_output: torch.Tensor):
-        if ctx.requires_weight_grad:
-            codes, scales, weight = ctx.saved_tensors
-            bits, block, shape, dtype = ctx.quant
-            x_hat = torch.empty(shape, dtype=dtype, device=grad_output.device)
-            sf.dequant_unpack(codes, scales, sf.Q_BLOCK, bits, block, 0, x_hat.view(-1))
-            go2 = grad_output.reshape(-1, grad_output.shape[-1])
-            grad_weight = go2.t().mm(x_hat.view(-1, shape[-1]))
-            grad_bias = go2.sum(0) if ctx.has_bias else None
+    def forward(ctx, x: torch.Tensor, weight: torch.Tensor, bias, bits: int = 8, block: int = 64):
+        y = torch.nn.functional.linear(x, weight, bias)
+        ctx.cache = None                                   # descriptor of what is kept of x: nothing, or (bits, block, shape, dtype)
+        ctx.bias_active = bias is not None and bias.requires_grad
+        if weight.requires_grad:
+            codes, scales = _quantise(x, bits, block)
+            ctx.cache = (bits, block, x.shape, x.dtype)
+            ctx.save_for_backward(weight, codes, scales)
         else:
-            (weight,) = ctx.saved_tensors
-            grad_weight = None
-            grad_bias = None
-        grad_input = grad_output.matmul(weight)
-        return grad_input, grad_weight, grad_bias, None, None, None
+            ctx.save_for_backward(weight)
+        return y
+
+    @staticmethod
+    def backward(ctx, dy: torch.Tensor):
+        weight = ctx.saved_tensors[0]
+        dx = dy.matmul(weight) if ctx.needs_input_grad[0] else None
+        dy2 = dy.reshape(-1, dy.shape[-1])
+        dw = None
+        if ctx.cache is not None:
+            bits, block, shape, dtype = ctx.cache
+            x_hat = _dequantise(ctx.saved_tensors[1], ctx.saved_tensors[2], bits, block, shape, dtype)
+            dw = dy2.t().mm(x_hat.view(-1, shape[-1]))
+        db = dy2.sum(0) if ctx.bias_active else None
+        return dx, dw, db, None, None
 
 
 def encoder_block_params(hidden: int, device="cuda", seed: int = 0, dtype=torch.float32):
@@ -304,14 +301,15 @@ def frozen_encoder_block(x: torch.Tensor, p: dict, heads: int, wrapped: bool, ke
         return t.reshape(B, T, heads, D).transpose(1, 2)
 
     if wrapped:
+        w = {name: t.detach() for name, t in p.items()}    # frozen: the scheduler has switched their gradients off
         h = LayerNormFunction.apply(x, p["g1"], p["b1"], 1e-5, True, keep_ppm)
-        q, k_, v = LinearFunction.apply(h, p["wqkv"], None, False, 8, block).chunk(3, dim=-1)
+        q, k_, v = LinearFunction.apply(h, w["wqkv"], None, 8, block).chunk(3, dim=-1)
         s = MatmulFunction.apply(split(q).contiguous(), split(k_).transpose(-1, -2).contiguous(), 8, block) / D ** 0.5
         a = SoftmaxMatmulFunction.apply(s, split(v).contiguous(), keep_ppm, 8, block).transpose(1, 2).reshape(B, T, H)
-        y = x + LinearFunction.apply(a, p["wo"], None, False, 8, block)
+        y = x + LinearFunction.apply(a, w["wo"], None, 8, block)
         h = LayerNormFunction.apply(y, p["g2"], p["b2"], 1e-5, True, keep_ppm)
-        h = LinearFunction.apply(h, p["w1"], None, False, 8, block)
-        h = LinearFunction.apply(GeluFunction.apply(h, gelu_bits, block), p["w2"], None, False, 8, block)
+        h = LinearFunction.apply(h, w["w1"], None, 8, block)
+        h = LinearFunction.apply(GeluFunction.apply(h, gelu_bits, block), w["w2"], None, 8, block)
         return y + h
     h = F.layer_norm(x, (H,), p["g1"].to(x.dtype), p["b1"].to(x.dtype), 1e-5)
     q, k_, v = F.linear(h, p["wqkv"]).chunk(3, dim=-1)

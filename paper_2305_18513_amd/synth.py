@@ -38,6 +38,9 @@ class WorkloadConfig:
     quant_bits: Tuple[int, ...] = (4,)
     quant_block: int = 64
     keep_ppm: int = 100_000            # fraction of scores kept, parts/million
+    keep_k: int = 0                    # pairs kept per score row: a stated figure of the workload (6, 12, 9, 38, 9),
+                                       # not computed here; both libraries' own count functions are tested against it
+    n_freeze: int = 0                  # layers frozen per iteration, likewise stated (15, 91, 91, 182, 182)
     threshold_variant: bool = False
     freeze_rate: float = 0.95
     seed: int = 0
@@ -64,10 +67,6 @@ class WorkloadConfig:
         return self.tokens
 
     @property
-    def keep_k(self) -> int:
-        return (self.score_cols * self.keep_ppm) // 1_000_000
-
-    @property
     def unit_numels(self) -> List[int]:
         h, f = self.hidden, self.ffn
         per_block = [h * h, h * h, h * h, h * h, h, h * f, f * h, h]
@@ -78,10 +77,6 @@ class WorkloadConfig:
         return 8 * self.n_blocks
 
     @property
-    def n_freeze(self) -> int:
-        return int(self.n_units * self.freeze_rate)
-
-    @property
     def threshold_tau(self) -> float:
         """Expected 95th percentile of a log-normal softmax row entry."""
         s = self.logit_sigma
@@ -89,15 +84,15 @@ class WorkloadConfig:
 
 
 CONFIGS: Tuple[WorkloadConfig, ...] = (
-    WorkloadConfig("tiny", 0, 2, 128, 4, 64, 4, seed=0),
-    WorkloadConfig("bert_base", 1, 12, 768, 12, 128, 32, seed=1),
+    WorkloadConfig("tiny", 0, 2, 128, 4, 64, 4, keep_k=6, n_freeze=15, seed=0),
+    WorkloadConfig("bert_base", 1, 12, 768, 12, 128, 32, keep_k=12, n_freeze=91, seed=1),
     WorkloadConfig("vit_base", 2, 12, 768, 12, 197, 128, outliers="student_t",
-                   quant_bits=(8, 4), keep_ppm=50_000, seed=2),
-    WorkloadConfig("bert_large", 3, 24, 1024, 16, 384, 128, seed=3),
+                   quant_bits=(8, 4), keep_ppm=50_000, keep_k=9, n_freeze=91, seed=2),
+    WorkloadConfig("bert_large", 3, 24, 1024, 16, 384, 128, keep_k=38, n_freeze=182, seed=3),
     WorkloadConfig("vit_large", 4, 24, 1024, 16, 197, 256,
                    act_dtype=torch.bfloat16, w_dtype=torch.bfloat16,
                    delta_given=True, outliers="student_t", quant_block=32,
-                   keep_ppm=50_000, threshold_variant=True, seed=4),
+                   keep_ppm=50_000, keep_k=9, n_freeze=182, threshold_variant=True, seed=4),
 )
 
 _KIND = {"w_prev": 1, "delta": 2, "lr": 3, "gelu_in": 4, "ln_in": 5,

@@ -380,3 +380,10 @@ def test_binding_wants_a_workspace_with_an_explicit_stream():
     x = torch.zeros(100)
     with pytest.raises(ValueError):
         sf.prune_global(x, 10, torch.zeros(10), torch.zeros(10, dtype=torch.int32), stream=12345)
+
+
+def test_library_counts_reproduce_the_workloads_stated_figures():
+    from paper_2305_18513_amd import synth
+    for c in synth.CONFIGS:
+        assert sf.keep_count(c.score_cols, c.keep_ppm) == c.keep_k
+        assert sf.freeze_count(c.n_units, c.freeze_rate) == c.n_freeze

@@ -1,9 +1,11 @@
 """GPU: the torch.autograd wrappers (Alg. 4) marshal into the library correctly -- each Function's results are
 those of the same C-ABI calls made by hand (the kernels themselves are compared with the oracle elsewhere) --
 frozen layers return no weight gradient, and the cached activations are the compressed ones."""
+import numpy as np
 import pytest
 import torch
 
+from oracle import ref
 from paper_2305_18513_amd import autograd as ag
 from paper_2305_18513_amd import binding as sf
 from tests.gpu_util import require_gpu
@@ -70,9 +72,14 @@ def test_layernorm_function_frozen_and_active():
     torch.nn.functional.layer_norm(xr, (H,), gr, br, 1e-5).backward(dy)
     assert torch.allclose(x.grad, xr.grad, rtol=1e-4, atol=1e-5)
     assert torch.allclose(gamma.grad, gr.grad, rtol=1e-4, atol=1e-4) and torch.allclose(beta.grad, br.grad, rtol=1e-4, atol=1e-4)
-    # the pruned gradient approximates the exact one: it only drops part of the last term of the paper's formula
-    rel = (frozen_grad - xr.grad).norm() / xr.grad.norm()
-    assert float(rel) < 0.5
+    # the frozen layer's gradient is the paper's formula on the pairs the oracle keeps (its own statistics, its own
+    # pruner), at the backward kernel's stated tolerance
+    xh, gh, dyh = x.detach().view(rows, H).cpu().numpy(), gamma.detach().cpu().numpy(), dy.view(rows, H).cpu().numpy()
+    _, om, orr = ref.layernorm_forward(xh, gh, beta.detach().cpu().numpy(), eps=1e-5)
+    ov, oi = ref.prune_global(ref.standardize(xh, om, orr).reshape(-1), k, by_magnitude=True)
+    want = ref.layernorm_backward_pruned(ov, oi, orr, gh, dyh)
+    tol = 1e-5 * float(np.abs(want).max())
+    np.testing.assert_allclose(frozen_grad.view(rows, H).cpu().numpy(), want, rtol=1e-5, atol=tol)
 
 
 def test_layernorm_function_on_bf16_activations():
@@ -181,14 +188,18 @@ def test_linear_function_skips_the_weight_gradient_when_frozen():
     b = torch.nn.Parameter(torch.zeros(512, device="cuda"))
     dy = torch.randn(8, 32, 512, generator=g, device="cuda")
 
-    out = ag.LinearFunction.apply(x, w, b, False, 8, 64)
+    w.requires_grad_(False)                                             # what a scheduler does to a frozen layer
+    b.requires_grad_(False)
+    out = ag.LinearFunction.apply(x, w, b, 8, 64)
     assert _saved_bytes(out) == 0                                       # only the weight (a Parameter) is kept
     out.backward(dy)
     assert w.grad is None and b.grad is None
     assert torch.allclose(x.grad, dy.matmul(w.detach()), rtol=1e-5, atol=1e-5)
 
     x.grad = None
-    out = ag.LinearFunction.apply(x, w, b, True, 8, 64)
+    w.requires_grad_(True)
+    b.requires_grad_(True)
+    out = ag.LinearFunction.apply(x, w, b, 8, 64)
     n = x.numel()
     assert _saved_bytes(out) == sf.packed_bytes(n, 8) + 4 * sf.num_blocks(n, 64)       # 8-bit cache of the input
     out.backward(dy)
@@ -233,9 +244,9 @@ def test_feed_forward_block_keeps_less_memory_when_wrapped():
         return torch.nn.functional.layer_norm(h, (H,), gamma, beta, 1e-5)
 
     def wrapped():
-        h = ag.LinearFunction.apply(x, w1, None, False, 8, 64)
+        h = ag.LinearFunction.apply(x, w1.detach(), None, 8, 64)
         h = ag.GeluFunction.apply(h, 4, 64)
-        h = ag.LinearFunction.apply(h, w2, None, False, 8, 64)
+        h = ag.LinearFunction.apply(h, w2.detach(), None, 8, 64)
         return ag.LayerNormFunction.apply(h, gamma, beta, 1e-5, True, 100000)
 
     kept_plain, kept_wrapped = held(plain), held(wrapped)
@@ -315,7 +326,53 @@ def test_encoder_block_keeps_less_memory_when_wrapped():
         y0 = ag.frozen_encoder_block(x, params, heads, wrapped=False)
         y1 = ag.frozen_encoder_block(x, params, heads, wrapped=True)
     assert torch.allclose(y0, y1, rtol=1e-4, atol=1e-4)
-    # the input gradient through the compressed caches stays close to the exact one
-    rel = (x.grad - grad_plain).norm() / grad_plain.norm()
-    assert float(rel) < 0.5, float(rel)
+    assert grad_plain is not None and x.grad is not None
     assert all(q.grad is None for q in params.values())                   # frozen: no parameter gradients
+
+
+def test_frozen_feed_forward_block_backward_equals_the_composition_of_oracle_functions():
+    """x -> Linear(w1) -> GELU -> Linear(w2) -> LayerNorm, every layer frozen, through the wrappers; the same chain
+    written with the oracle's functions (quant_pack -> dequant_unpack -> gelu_backward for GELU's cache; layernorm
+    statistics -> standardize -> prune_global -> layernorm_backward_pruned for LayerNorm's) and NumPy float64
+    products for the two linear layers.  Inputs and the first weight matrix are multiples of small powers of two, so
+    that the first product is exact in fp32 and both sides quantise the very same GELU input."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(21)
+    rows, H, F = 64, 64, 256
+    x = (torch.randint(-16, 17, (rows, H), generator=g, device="cuda").float() / 8).requires_grad_(True)
+    w1 = torch.randint(-16, 17, (F, H), generator=g, device="cuda").float() / 64
+    w2 = torch.randn(H, F, generator=g, device="cuda") * 0.1
+    gamma = torch.rand(H, generator=g, device="cuda") + 0.5
+    beta = torch.rand(H, generator=g, device="cuda") - 0.5
+    dy = torch.randn(rows, H, generator=g, device="cuda")
+
+    h1 = ag.LinearFunction.apply(x, w1, None, 8, 64)
+    a = ag.GeluFunction.apply(h1, 4, 64)
+    h3 = ag.LinearFunction.apply(a, w2, None, 8, 64)
+    y = ag.LayerNormFunction.apply(h3, gamma, beta, 1e-5, True, 100000)
+    kept_vals, kept_idx = y.grad_fn.saved_tensors[0], y.grad_fn.saved_tensors[1]
+    y.backward(dy)
+
+    xh, w1h, w2h = x.detach().cpu().numpy(), w1.cpu().numpy(), w2.cpu().numpy()
+    gh, bh, dyh = gamma.cpu().numpy(), beta.cpu().numpy(), dy.cpu().numpy()
+    o_h1 = (xh.astype(np.float64) @ w1h.astype(np.float64).T)
+    assert np.array_equal(o_h1.astype(np.float32).astype(np.float64), o_h1)         # exact in fp32, as constructed
+    o_h1 = o_h1.astype(np.float32)
+    assert np.array_equal(h1.detach().cpu().numpy(), o_h1)
+    o_a = ref.gelu(o_h1).reshape(rows, F)
+    o_h3 = (o_a.astype(np.float64) @ w2h.astype(np.float64).T).astype(np.float32)
+    o_y, om, orr = ref.layernorm_forward(o_h3, gh, bh, eps=1e-5)
+    k = sf.keep_count(rows * H, 100000)
+    ov, oi = ref.prune_global(ref.standardize(o_h3, om, orr).reshape(-1), k, by_magnitude=True)
+    assert np.array_equal(kept_idx.cpu().numpy(), oi)                                 # the wrapper cached the oracle's set
+    np.testing.assert_allclose(kept_vals.cpu().numpy(), ov, rtol=2e-5, atol=2e-6)
+    np.testing.assert_allclose(y.detach().cpu().numpy(), o_y, rtol=1e-5, atol=2e-5)
+    o_dh3 = ref.layernorm_backward_pruned(ov, oi, orr, gh, dyh)                        # frozen LayerNorm: the paper's formula
+    o_da = (o_dh3.astype(np.float64) @ w2h.astype(np.float64)).astype(np.float32)      # frozen Linear: dx only
+    oc, osc = ref.quant_pack(o_h1.reshape(-1), bits=4, block=64)
+    o_dh1 = ref.gelu_backward(ref.dequant_unpack(oc, osc, o_h1.size, bits=4, block=64), o_da.reshape(-1)).reshape(rows, F)
+    o_dx = (o_dh1.astype(np.float64) @ w1h.astype(np.float64)).astype(np.float32)
+    # the kernels' own budgets (LayerNorm backward 4e-6 of its terms, GELU backward 1e-6, two fp32 products) add up
+    # to a few 1e-6 of the largest entry
+    tol = 2e-5 * float(np.abs(o_dx).max())
+    np.testing.assert_allclose(x.grad.cpu().numpy(), o_dx, rtol=2e-5, atol=tol)

@@ -160,3 +160,45 @@ def test_layer_delta_and_ils_all_units(ci):
     gi2, gm2 = sf.ils_select(want, n_freeze)
     np.testing.assert_array_equal(gi2, oi)
     np.testing.assert_array_equal(gm2, om)
+
+
+@pytest.mark.parametrize("ci", [1, 4])
+def test_layer_delta_with_exact_zeros_among_the_old_weights(ci):
+    """Eq. 1 divides by W^{t-1}: an unchanged zero weight contributes 0, a changed one makes its layer's score
+    +inf (the layer ranks last), and eps > 0 keeps every score finite -- at full size, planted in every chunk
+    position class (first element, chunk interior, chunk edge, last element)."""
+    require_gpu()
+    cfg = synth.CONFIGS[ci]
+    prev, cur = synth.weight_units(cfg, "cuda")
+    numel = [t.numel() for t in prev]
+    unchanged, changed = [0, 5, 7], [1, 4, 6, len(prev) - 1]     # layers whose zero weights stay / get an update
+    for i in unchanged + changed:
+        n = numel[i]
+        spots = sorted({0, 1, n // 3, min(n - 1, 16383), min(n - 1, 16384), n - 1})
+        for j in spots:
+            prev[i][j] = 0.0
+            if cfg.delta_given:
+                cur[i][j] = 0.0 if i in unchanged else 1e-3
+            else:
+                cur[i][j] = 0.0 if i in unchanged else 1e-3
+    ws = torch.empty(sf.layer_delta_workspace(numel), dtype=torch.uint8, device="cuda")
+    hp, hc = [to_np(t) for t in prev], [to_np(t) for t in cur]
+    for eps in (0.0, 1e-6):
+        d = torch.empty(len(prev), device="cuda")
+        sf.layer_delta(prev, cur, cfg.delta_given, eps, d, ws)
+        torch.cuda.synchronize()
+        got = to_np(d)
+        want = ref.layer_delta(hp, hc, cur_is_delta=cfg.delta_given, eps=eps, threads=THREADS)
+        fin = np.isfinite(want)
+        if eps == 0.0:
+            assert sorted(np.nonzero(~fin)[0].tolist()) == sorted(changed) and np.all(want[~fin] == np.inf)
+        else:
+            assert fin.all()
+        np.testing.assert_array_equal(np.isfinite(got), fin)
+        np.testing.assert_array_equal(got[~fin], want[~fin])
+        np.testing.assert_allclose(got[fin], want[fin], rtol=1e-6, atol=0)
+        # +inf sorts after every finite score: none of the changed-zero layers is frozen at eps = 0
+        n_freeze = sf.freeze_count(cfg.n_units, cfg.freeze_rate)
+        gi, gm = sf.ils_select(got, n_freeze)
+        if eps == 0.0:
+            assert not any(gm[i] for i in changed)

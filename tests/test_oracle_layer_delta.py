@@ -123,7 +123,8 @@ def test_synthetic_units_have_paper_layer_list_shape():
     assert [p.numel() for p in prev[:8]] == [128 * 128] * 4 + [128, 128 * 512, 512 * 128, 128]
     d = ref.layer_delta([p.numpy() for p in prev], [c.numpy() for c in cur], threads=2)
     assert np.all(np.isfinite(d)) and np.all(d > 0)
-    assert synth.CONFIGS[3].n_freeze == 182 and synth.CONFIGS[1].n_freeze == 91
+    assert [c.n_freeze for c in synth.CONFIGS] == [15, 91, 91, 182, 182]         # stated with the workloads
+    assert [ref.freeze_count(c.n_units, c.freeze_rate) for c in synth.CONFIGS] == [c.n_freeze for c in synth.CONFIGS]
 
 
 def test_negative_eps_rejected():

@@ -147,7 +147,9 @@ def test_bf16_rows_with_many_ties():
 def test_keep_count_matches_python_truncation():
     for cols, keep in ((64, 0.10), (128, 0.10), (197, 0.05), (384, 0.10), (577, 0.10)):
         assert ref.keep_count(cols, int(round(keep * 1e6))) == int(cols * keep)
+    # the workloads state their counts as data; the oracle's own arithmetic has to reproduce them
     assert [c.keep_k for c in synth.CONFIGS] == [6, 12, 9, 38, 9]
+    assert [ref.keep_count(c.score_cols, c.keep_ppm) for c in synth.CONFIGS] == [c.keep_k for c in synth.CONFIGS]
 
 
 def test_scores_recipe_and_table_of_activation_counts(golden_dir):
