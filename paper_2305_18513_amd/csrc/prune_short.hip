@@ -11,7 +11,7 @@
 //
 //   stage    the wave's R consecutive rows are one contiguous, 16-byte aligned
 //            piece of the tensor: copied to LDS with 16-byte non-temporal loads
-//            (the only pass over HBM), while the sign bits are OR-ed together;
+//            (the only pass over HBM);
 //   select   each lane keeps the largest CH keys of its segment in a sorted
 //            register list: inserting a key is one v_max plus CH-1 v_med3
 //            (new s[i] = median(s[i-1], s[i], key)), no branch, no cross-lane step.
@@ -32,9 +32,11 @@
 //            a sign bit was seen, so that -0 stays -0) are re-read from the staged
 //            rows.
 //
-// Keys: non-negative inputs (every softmax output) use their bit patterns as
-// signed integers.  When any sign bit is set among the wave's rows the keys are
-// sign * magnitude instead (so -0 and +0 coincide, as float comparison has it).
+// Keys: the bit patterns themselves, read as signed integers, order positive
+// entries correctly and put zeros and negative entries below them, which is all
+// a row needs whose kept entries are positive (every softmax row).  A wave that
+// meets a row whose k-th largest entry is not positive starts over with
+// sign * magnitude keys (-0 and +0 coincide, as float comparison has it).
 #include "common.hpp"
 
 #include <climits>
@@ -199,8 +201,12 @@ struct ShortRows {
         }
     }
 
+    // NEG: keys are sign * magnitude.  Without it the bit patterns themselves serve as (signed) keys, which orders
+    // the positive entries correctly and puts everything else (zeros of either sign, negative values in reversed
+    // order) below them: enough whenever every kept entry is positive.  The plain pass notices when that fails for
+    // one of the wave's rows and returns false before it has written anything; the caller then runs the signed pass.
     template <bool NEG>
-    static __device__ void run(const ShortArgs &a, const T *rows_lds, uint32_t *oc, int lane, int n_here, int64_t row0,
+    static __device__ bool run(const ShortArgs &a, const T *rows_lds, uint32_t *oc, int lane, int n_here, int64_t row0,
                                T *__restrict__ vals, uint16_t *__restrict__ idx, int32_t *__restrict__ counts)
     {
         const int cols = a.cols, k = a.k;
@@ -234,6 +240,14 @@ struct ShortRows {
         int kk = k;
         bool exact = false;                                 // this row has to take the exact route (fp32 only)
         uint32_t c[K];                                      // kept (column << 16 | bf16 value bits), kNoPair beyond kk
+        if constexpr (!NEG) {
+            // all kept entries positive?  With k entries kept: the k-th largest is; with fewer (a threshold run): tau is.
+            int cut_value = 0;
+#pragma unroll
+            for (int i = 0; i < K; ++i) cut_value = (i == k - 1) ? m[i] >> (BF ? 16 : TAG_BITS + 2) : cut_value;
+            const bool plain_ok = cut_value > 0 || (a.mode == SLIMFIT_PRUNE_THRESHOLD && a.tau > 0.0f);
+            if (__builtin_amdgcn_ballot_w64(!plain_ok) != 0) return false;
+        }
         if constexpr (BF) {
             auto bits_of = [&](int key) -> uint32_t {
                 const int k16 = key >> 16;
@@ -394,11 +408,9 @@ struct ShortRows {
             }
         }
         if (counts && q == 0 && r < n_here) counts[row0 + r] = kk;
+        return true;
     }
 };
-
-__device__ __forceinline__ uint32_t elem_bits(float x) { return __builtin_bit_cast(uint32_t, x); }
-__device__ __forceinline__ uint32_t elem_bits(uint16_t x) { return (uint32_t)x << 16; }
 
 // NV: 16-byte vectors a lane holds while the rows are staged (the wave's rows are 64 * cols bytes: NV >= cols / 16)
 template <typename T, int G, int K, int NV>
@@ -410,7 +422,7 @@ __global__ __launch_bounds__(kWave) void prune_rows_short_kernel(const T *__rest
     extern __shared__ uint4 short_lds[];
     constexpr int R = S::R;
     constexpr int PER16 = 16 / (int)sizeof(T);
-    static_assert(R * sizeof(T) == 64, "the wave's rows are 64 * cols bytes");
+    static_assert(R * sizeof(T) % 16 == 0, "the wave's rows are a whole number of 16-byte vectors");
     const int lane = threadIdx.x;
     const int cols = a.cols, k = a.k;
     char *slab = reinterpret_cast<char *>(short_lds);
@@ -425,37 +437,39 @@ __global__ __launch_bounds__(kWave) void prune_rows_short_kernel(const T *__rest
     const int n_here = (int)min((int64_t)R, a.rows - row0);        // >= 1 by the launch size
     const int n_elem = n_here * cols;
     const int n_vec = n_elem / PER16;
-    uint32_t bits = 0;
-    if (n_vec > 0) {                                   // wave-uniform
-        const u32x4 *src_v = reinterpret_cast<const u32x4 *>(p + row0 * (int64_t)cols);
+    const u32x4 *src_v = reinterpret_cast<const u32x4 *>(p + row0 * (int64_t)cols);
+    if (n_vec > (NV - 1) * kWave) {
+        // (wave-uniform) the piece fills all NV rounds but perhaps the last: no index arithmetic on the others
+        u32x4 v[NV];
+        const int last = min((NV - 1) * kWave + lane, n_vec - 1);
+#pragma unroll
+        for (int u = 0; u < NV - 1; ++u) v[u] = load_global<SLIMFIT_SHORT_NT != 0>(src_v + u * kWave + lane);
+        v[NV - 1] = load_global<SLIMFIT_SHORT_NT != 0>(src_v + last);
+#pragma unroll
+        for (int u = 0; u < NV - 1; ++u) dst_v[u * kWave + lane] = v[u];
+        dst_v[last] = v[NV - 1];
+    } else if (n_vec > 0) {
+        // fewer rounds (narrow rows for this NV, or a short last piece): lanes past the end re-read the last vector
+        // (and store it again where it belongs), which keeps the loads free of branches
         u32x4 v[NV];
 #pragma unroll
         for (int u = 0; u < NV; ++u) v[u] = load_global<SLIMFIT_SHORT_NT != 0>(src_v + min(u * kWave + lane, n_vec - 1));
 #pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            dst_v[min(u * kWave + lane, n_vec - 1)] = v[u];
-            bits |= v[u].x | v[u].y | v[u].z | v[u].w;
-        }
+        for (int u = 0; u < NV; ++u) dst_v[min(u * kWave + lane, n_vec - 1)] = v[u];
     }
     {
-        const int ei = n_vec * PER16 + lane;           // fewer than PER16 entries are left (short last piece only)
-        if (ei < n_elem) {
-            const T x = p[row0 * (int64_t)cols + ei];
-            reinterpret_cast<T *>(slab)[ei] = x;
-            bits |= elem_bits(x);
-        }
+        const int ei = n_vec * PER16 + lane;           // fewer than PER16 entries are left over (short last piece only)
+        if (ei < n_elem) reinterpret_cast<T *>(slab)[ei] = p[row0 * (int64_t)cols + ei];
     }
     // unused output slots read as "no pair"
     for (int t = lane; t < R * k; t += kWave) oc[t] = kNoPair;
-    constexpr uint32_t SIGNS = sizeof(T) == 2 ? 0x80008000u : 0x80000000u;
-    const bool any_neg = __builtin_amdgcn_ballot_w64((bits & SIGNS) != 0u) != 0;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     const T *rows_lds = reinterpret_cast<const T *>(slab);
-    if (any_neg) S::template run<true>(a, rows_lds, oc, lane, n_here, row0, vals, idx, counts);
-    else S::template run<false>(a, rows_lds, oc, lane, n_here, row0, vals, idx, counts);
+    if (!S::template run<false>(a, rows_lds, oc, lane, n_here, row0, vals, idx, counts))
+        S::template run<true>(a, rows_lds, oc, lane, n_here, row0, vals, idx, counts);
 }
 
 template <typename T, int G, int K, int NV>
@@ -473,11 +487,13 @@ void launch_short(const T *p, const ShortArgs &a, T *vals, uint16_t *idx, int32_
 template <typename T, int G, int K>
 void launch_short_nv(const T *p, const ShortArgs &a, T *vals, uint16_t *idx, int32_t *counts, hipStream_t st)
 {
-    const int nv = (a.cols + 15) / 16;
-    if (nv <= 4) launch_short<T, G, K, 4>(p, a, vals, idx, counts, st);
-    else if (nv <= 8) launch_short<T, G, K, 8>(p, a, vals, idx, counts, st);
-    else if (nv <= 13) launch_short<T, G, K, 13>(p, a, vals, idx, counts, st);
-    else launch_short<T, G, K, 16>(p, a, vals, idx, counts, st);
+    constexpr int R = kWave / G;
+    constexpr int S = R * (int)sizeof(T) / 64;          // a piece is S * 64 * cols bytes
+    const int nv = (a.cols * S * 4 + kWave - 1) / kWave;                // rounds of 64 vectors
+    if (nv <= 4 * S) launch_short<T, G, K, 4 * S>(p, a, vals, idx, counts, st);
+    else if (nv <= 8 * S) launch_short<T, G, K, 8 * S>(p, a, vals, idx, counts, st);
+    else if (nv <= 12 * S + 1) launch_short<T, G, K, 12 * S + 1>(p, a, vals, idx, counts, st);     // 197 columns
+    else launch_short<T, G, K, 16 * S>(p, a, vals, idx, counts, st);
 }
 
 template <typename T, int G>
@@ -515,8 +531,11 @@ void launch_prune_short(const void *p, int32_t dt, int64_t rows, int cols, int k
     a.mode = mode;
     a.tau = tau;
     a.div_magic = 65536u / (uint32_t)k + 1u;
+#ifndef SLIMFIT_SHORT_G_F32
+#define SLIMFIT_SHORT_G_F32 4
+#endif
     if (dt == SLIMFIT_F32)
-        launch_short_k<float, 4>(static_cast<const float *>(p), a, static_cast<float *>(vals), idx, counts, st);
+        launch_short_k<float, SLIMFIT_SHORT_G_F32>(static_cast<const float *>(p), a, static_cast<float *>(vals), idx, counts, st);
     else
         launch_short_k<uint16_t, 2>(static_cast<const uint16_t *>(p), a, static_cast<uint16_t *>(vals), idx, counts, st);
 }
