@@ -64,6 +64,14 @@ __device__ __forceinline__ int med3_i32(int a, int b, int c)
     return d;
 }
 
+// (a & mask) | b in one instruction; mask sits in a register because the three-operand encoding takes no literal
+__device__ __forceinline__ int and_or_i32(int a, int mask, int b)
+{
+    int d;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(mask), "s"(b));
+    return d;
+}
+
 // s is sorted in descending order; afterwards it holds the CH largest of s + {key}
 template <int CH>
 __device__ __forceinline__ void chain_insert(int (&s)[CH], int key)
@@ -222,11 +230,13 @@ struct ShortRows {
         int m[CHP];
 #pragma unroll
         for (int i = 0; i < CHP; ++i) m[i] = INT_MIN;
+        int value_mask = (int)~COL_MASK;
+        asm("" : "+v"(value_mask));                        // in a register, not a literal at every use
         for_each_entry<NEG>(seg, E, len, e_all, [&](int e, int bits, bool ok) {
             // the tag is wave-uniform: the earlier entry of the segment ranks higher
             int key;
             if constexpr (BF) key = (int)(((uint32_t)(NEG ? signed_key_16(bits) : bits) << 16) | (uint32_t)(TAG_TOP - e));
-            else key = (int)(((uint32_t)(NEG ? signed_key_f32((uint32_t)bits) : bits) & ~COL_MASK) | (uint32_t)(TAG_TOP - e));
+            else key = and_or_i32(NEG ? signed_key_f32((uint32_t)bits) : bits, value_mask, TAG_TOP - e);
             chain_insert<CHP>(m, ok ? key : INT_MIN);
         });
 #pragma unroll
