@@ -256,7 +256,8 @@ def stream_yardstick(read_bytes, write_bytes, cache={}):
     elif read_bytes >= write_bytes:
         ratio = min((1, 2, 4, 8, 16), key=lambda r: abs(math.log2(r) - math.log2(read_bytes / write_bytes)))
     else:
-        ratio = -min((2, 4, 8), key=lambda m: abs(math.log2(m) - math.log2(write_bytes / read_bytes)))
+        ratio = -min((1, 2, 4, 8), key=lambda m: abs(math.log2(m) - math.log2(write_bytes / read_bytes)))
+        ratio = 1 if ratio == -1 else ratio
     in_vecs = max(1024, read_bytes // 16 // 1024 * 1024)
     key = (ratio, in_vecs)
     if key not in cache:
@@ -277,6 +278,28 @@ def stream_yardstick(read_bytes, write_bytes, cache={}):
         cache[key] = {"shape": ratio, "bytes": nbytes, "ms": round(ms, 5), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
         del psrc, pdst
     return dict(cache[key], kernel_read_write_ratio=round(read_bytes / max(write_bytes, 1), 2))
+
+
+def extra_record(name, ms, nbytes, write_bytes, counters, **more):
+    """Record of an operation timed outside the step: its algorithmic bytes against the HBM peak, against the
+    streaming probe of the same read : write mix and size, and (when the tracked counter summary has the operation)
+    against the HBM bytes its kernels really moved."""
+    rec = {"median_ms": round(ms, 5), "bytes_per_launch": nbytes}
+    rec.update(more)
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    rec["GBps"] = round(gbps, 1)
+    rec["frac_hbm_peak"] = round(gbps / HBM_PEAK_GBS, 4)
+    probe = stream_yardstick(nbytes - write_bytes, write_bytes)
+    if probe:
+        rec["stream_probe"] = probe
+        rec["frac_of_stream_probe"] = round(gbps / probe["GBps"], 4)
+    cnt = counters.get((-1, name.replace(" ", "_")))
+    if cnt and "fetch_bytes" in cnt:
+        moved = cnt["fetch_bytes"] + cnt["write_bytes"]
+        rec["traffic"] = int(moved)
+        rec["traffic_over_algorithmic"] = round(moved / nbytes, 3)
+        rec["frac_hbm_peak_on_traffic"] = round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    return rec
 
 
 def kernel_table(wl, survey, timers, dom, steps, counters, with_probe):
@@ -448,9 +471,7 @@ def main() -> int:
             torch.cuda.synchronize()
             ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
             nb = b_prune + 4 * cfg.score_rows
-            extras["restore_scores"] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                        "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                        "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            extras["restore_scores"] = extra_record("restore_scores", ms, nb, cfg.score_rows * cfg.score_cols * in_sz, counters)
             del dense
             # the paper's own placement for the same tensor: 8-bit fixed point, 4 integer + 4 fractional bits
             sc = [s.scores.reshape(-1) for s in sets]
@@ -467,9 +488,7 @@ def main() -> int:
             torch.cuda.synchronize()
             ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
             nb = n_sc * (in_sz + 1)
-            extras["quant_pack[scores, fixed 4.4]"] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                                       "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                                       "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            extras["quant_pack[scores, fixed 4.4]"] = extra_record("quant_pack[scores, fixed 4.4]", ms, nb, n_sc, counters)
             del c8, sc
             # Alg. 5 as printed: the flattened LayerNorm input, int(numel * 0.1) survivors by magnitude, and its restore
             lns = [s.ln[0] for s in sets]
@@ -482,11 +501,11 @@ def main() -> int:
             gout = [torch.empty_like(x) for x in lns]
             nb = n_ln * in_sz + k_ln * (in_sz + 4)
             runs = {
-                "prune_global[ln_in, 10%]": lambda i: sf.prune_global(lns[i], k_ln, gv[i], gi[i], True, gp[i], gws),
-                "restore_global[ln_in, tile pointers]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i], gp[i]),
-                "restore_global[ln_in, zeros+scatter]": lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i]),
+                "prune_global[ln_in, 10%]": (k_ln * (in_sz + 4), lambda i: sf.prune_global(lns[i], k_ln, gv[i], gi[i], True, gp[i], gws)),
+                "restore_global[ln_in, tile pointers]": (n_ln * in_sz, lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i], gp[i])),
+                "restore_global[ln_in, zeros+scatter]": (n_ln * in_sz, lambda i: sf.restore_global(gv[i], gi[i], k_ln, gout[i])),
             }
-            for name, fn in runs.items():
+            for name, (wb, fn) in runs.items():
                 for i in range(len(sets)):
                     fn(i)
                 torch.cuda.synchronize()
@@ -497,9 +516,7 @@ def main() -> int:
                     b.record()
                 torch.cuda.synchronize()
                 ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb, "numel": n_ln, "k": k_ln,
-                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                extras[name] = extra_record(name, ms, nb, wb, counters, numel=n_ln, k=k_ln)
             del gv, gi, gp, gws, gout
             # the caches fused into their producer / consumer (x read once; the dequantised values never stored;
             # softmax and pruning in one pass over the logits)
@@ -509,20 +526,20 @@ def main() -> int:
             nb_s = 2 * rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (in_sz + 2)
             probs = [torch.empty_like(s.scores) for s in sets]
             fused = {
-                "gelu_quant_pack[gelu_in]": (nb_g, lambda i: sf.gelu_quant_pack(
+                "gelu_quant_pack[gelu_in]": (nb_g, nb_g - n_g * in_sz, lambda i: sf.gelu_quant_pack(
                     sets[i].gelu, sf.Q_BLOCK, bits, block, 0, sets[i].deq[0], sets[i].codes[0], sets[i].scales[0])),
-                "gelu_backward_dequant[gelu_in]": (nb_g, lambda i: sf.gelu_backward_dequant(
+                "gelu_backward_dequant[gelu_in]": (nb_g, n_g * in_sz, lambda i: sf.gelu_backward_dequant(
                     sets[i].codes[0], sets[i].scales[0], sf.Q_BLOCK, bits, block, 0, sets[i].gelu, sets[i].deq[0])),
-                "softmax_prune[scores as logits]": (nb_s, lambda i: sf.softmax_prune(
+                "softmax_prune[scores as logits]": (nb_s, nb_s - rows_s * cols_s * in_sz, lambda i: sf.softmax_prune(
                     sets[i].scores, cfg.keep_k, probs[i], sets[i].vals, sets[i].idx)),
                 # consumes the pairs the line above left; the score tensor stands in for the incoming gradient
                 # (only its kept columns are read: k elements per row are the algorithmic bytes, although at
                 # 10 % kept nearly every 128-byte line of it is touched)
                 "softmax_backward_pruned[scores]": (
-                    rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (2 * in_sz + 2),
+                    rows_s * cols_s * in_sz + rows_s * cfg.keep_k * (2 * in_sz + 2), rows_s * cols_s * in_sz,
                     lambda i: sf.softmax_backward_pruned(sets[i].vals, sets[i].idx, None, sets[i].scores, probs[i])),
             }
-            for name, (nb, fn) in fused.items():
+            for name, (nb, wb, fn) in fused.items():
                 for i in range(len(sets)):
                     fn(i)
                 torch.cuda.synchronize()
@@ -533,9 +550,7 @@ def main() -> int:
                     b.record()
                 torch.cuda.synchronize()
                 ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                extras[name] = extra_record(name, ms, nb, wb, counters)
             del probs
             # LayerNorm around its caches: forward with row statistics; the pruned cache (10 % of the standardised input
             # kept without storing it, input gradient of the frozen layer from the kept pairs); the quantised cache fused
@@ -556,20 +571,20 @@ def main() -> int:
             lws = torch.empty(sf.prune_global_workspace(n_l), dtype=torch.uint8, device="cuda")
             nb_lq = 2 * in_sz * n_l + sf.packed_bytes(n_l, bits) + 4 * sf.num_blocks(n_l, block) + 8 * rows_l
             ln_runs = {
-                "layernorm_forward[ln_in]": (2 * in_sz * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
+                "layernorm_forward[ln_in]": (2 * in_sz * n_l + 8 * rows_l, in_sz * n_l + 8 * rows_l, lambda i: sf.layernorm_forward(
                     lnx[i], gam, bet, 1e-5, lny[i], mu[i], rs[i])),
-                "prune_global_standardized[ln_in, 10%]": (in_sz * n_l + 8 * k_l + 12 * rows_l, lambda i:
+                "prune_global_standardized[ln_in, 10%]": (in_sz * n_l + 8 * k_l + 12 * rows_l, 8 * k_l + 4 * rows_l, lambda i:
                     sf.prune_global_standardized(lnx[i], mu[i], rs[i], k_l, pv[i], pi[i], True, None, rp[i], lws)),
-                "layernorm_backward_pruned[ln_in]": (2 * in_sz * n_l + 8 * k_l + 8 * rows_l, lambda i:
+                "layernorm_backward_pruned[ln_in]": (2 * in_sz * n_l + 8 * k_l + 8 * rows_l, in_sz * n_l, lambda i:
                     sf.layernorm_backward_pruned(pv[i], pi[i], rp[i], k_l, rs[i], gam, lnx[i], lny[i])),
                 # the step's own cache (block-scaled codes of the LayerNorm input) written by the LayerNorm that
                 # reads the input anyway, and the input gradient straight from that cache
-                "layernorm_forward_quant_pack[ln_in]": (nb_lq, lambda i: sf.layernorm_forward_quant_pack(
+                "layernorm_forward_quant_pack[ln_in]": (nb_lq, nb_lq - in_sz * n_l, lambda i: sf.layernorm_forward_quant_pack(
                     lnx[i], gam, bet, 1e-5, bits, block, lny[i], mu[i], rs[i], sets[i].codes[1], sets[i].scales[1])),
-                "layernorm_backward_dequant[ln_in]": (nb_lq, lambda i: sf.layernorm_backward_dequant(
+                "layernorm_backward_dequant[ln_in]": (nb_lq, in_sz * n_l, lambda i: sf.layernorm_backward_dequant(
                     sets[i].codes[1], sets[i].scales[1], bits, block, mu[i], rs[i], gam, lnx[i], lny[i])),
             }
-            for name, (nb, fn) in ln_runs.items():
+            for name, (nb, wb, fn) in ln_runs.items():
                 for i in range(len(sets)):
                     fn(i)
                 torch.cuda.synchronize()
@@ -580,9 +595,7 @@ def main() -> int:
                     b.record()
                 torch.cuda.synchronize()
                 ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
-                extras[name] = {"median_ms": round(ms, 5), "bytes_per_launch": nb,
-                                "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                extras[name] = extra_record(name, ms, nb, wb, counters)
             del lny, mu, rs, pv, pi, rp, lws
 
             # Eq. 1 taken while the update is applied (weights read, update read, weights written: one pass instead of
@@ -604,9 +617,8 @@ def main() -> int:
             torch.cuda.synchronize()
             ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
             nb = sum(numel) * (2 * esize(cfg.w_dtype) + 4) + 4 * L
-            extras["apply_update_layer_delta[all weight tensors]"] = {
-                "median_ms": round(ms, 5), "bytes_per_launch": nb, "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
-                "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            extras["apply_update_layer_delta[all weight tensors]"] = extra_record(
+                "apply_update_layer_delta[all weight tensors]", ms, nb, sum(numel) * esize(cfg.w_dtype) + 4 * L, counters)
             del w_tmp, upd, ws_apply, d_apply
 
             # one frozen encoder block of this configuration through the autograd wrappers: activation bytes held between

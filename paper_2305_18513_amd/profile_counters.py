@@ -12,6 +12,14 @@ from the repository root after ``cd /tmp && export TMPDIR=/tmp``, one counter se
     rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/cfgC_write -o r --output-format csv -- \\
         python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy
 
+and, for the operations bench.py times outside the step (its "extras"), two more runs of the default configuration
+with the extras left in:
+
+    rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pc/extras_fetch -o r --output-format csv -- \\
+        python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy
+    rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/extras_write -o r --output-format csv -- \\
+        python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy
+
 The byte counters (KiB per dispatch) are scaled by what the same counter reads for the 1 GiB device copies of
 ``--calibrate-copy`` in the same run.  ``bench.py`` reads the ``DATA`` lines of the summary (HBM traffic of the
 dominant kernel, instructions per row for the bound rule); nothing here is needed to run the library.
@@ -36,6 +44,62 @@ KERNELS = {
     "quant_pack": r"quant_pack_kernel",
     "dequant_unpack": r"dequant_unpack_kernel",
 }
+
+
+# bench.py's extras -> (kernels of one call, the kernel that runs once per call)
+EXTRAS = {
+    "restore_scores": (r"restore_tile_kernel", r"restore_tile_kernel"),
+    "quant_pack[scores, fixed 4.4]": (r"quant_pack_kernel<\w+, 8, false", r"quant_pack_kernel<\w+, 8, false"),
+    "prune_global[ln_in, 10%]": (r"(hist|bracket|count|write)_kernel<\w+, true, false", r"write_kernel<\w+, true, false"),
+    "restore_global[ln_in, tile pointers]": (r"restore_tiles_kernel", r"restore_tiles_kernel"),
+    "restore_global[ln_in, zeros+scatter]": (r"(zero|scatter)_kernel", r"scatter_kernel"),
+    "gelu_quant_pack[gelu_in]": (r"quant_pack_kernel<[^>]*, true>", r"quant_pack_kernel<[^>]*, true>"),
+    "gelu_backward_dequant[gelu_in]": (r"dequant_unpack_kernel<[^>]*, true>", r"dequant_unpack_kernel<[^>]*, true>"),
+    "softmax_prune[scores as logits]": (r"prune_rows_kernel<\w+, \d+, \w+, \w+, true>", r"prune_rows_kernel<\w+, \d+, \w+, \w+, true>"),
+    "softmax_backward_pruned[scores]": (r"softmax_backward_(tile|small)_kernel", r"softmax_backward_(tile|small)_kernel"),
+    "layernorm_forward[ln_in]": (r"layernorm_forward_kernel", r"layernorm_forward_kernel"),
+    "prune_global_standardized[ln_in, 10%]": (r"(hist|bracket|count|write)_kernel<\w+, true, true", r"write_kernel<\w+, true, true"),
+    "layernorm_backward_pruned[ln_in]": (r"layernorm_backward_pruned_kernel", r"layernorm_backward_pruned_kernel"),
+    "layernorm_forward_quant_pack[ln_in]": (r"layernorm_forward_quant_kernel", r"layernorm_forward_quant_kernel"),
+    "layernorm_backward_dequant[ln_in]": (r"layernorm_backward_dequant_kernel", r"layernorm_backward_dequant_kernel"),
+    "apply_update_layer_delta[all weight tensors]": (r"layer_delta_partials_kernel<\w+, \w+, \w+, true>", r"layer_delta_partials_kernel<\w+, \w+, \w+, true>"),
+}
+
+
+def _per_call(rows, counter, pat_all, pat_once):
+    """Sum of the counter over a call's kernels, averaged over the calls of the run."""
+    total, calls = 0.0, 0
+    for r in rows:
+        if r.get("Counter_Name") != counter:
+            continue
+        if re.search(pat_all, r["Kernel_Name"]):
+            total += float(r["Counter_Value"])
+        if re.search(pat_once, r["Kernel_Name"]):
+            calls += 1
+    return (total / calls, calls) if calls else (None, 0)
+
+
+def summarise_extras(root):
+    fetch = _rows(os.path.join(root, "extras_fetch"))
+    write = _rows(os.path.join(root, "extras_write"))
+    if not (fetch and write):
+        return [], []
+    fs, _ = _copy_scale(fetch, "FETCH_SIZE")
+    wsc, _ = _copy_scale(write, "WRITE_SIZE")
+    if not (fs and wsc):
+        return [], []
+    lines = ["operations outside the timed step (bench.py's extras), default configuration: HBM bytes per call"]
+    data = []
+    for name, (pat_all, pat_once) in EXTRAS.items():
+        f, calls = _per_call(fetch, "FETCH_SIZE", pat_all, pat_once)
+        w, _ = _per_call(write, "WRITE_SIZE", pat_all, pat_once)
+        if f is None or w is None:
+            continue
+        fb, wb = f * fs * 1024.0, w * wsc * 1024.0
+        lines.append("  %-46s fetched %.1f MB + written %.1f MB = %.1f MB (mean of %d calls)" % (name, fb / 1e6, wb / 1e6, (fb + wb) / 1e6, calls))
+        data.append("DATA config=-1 kernel=%s fetch_bytes=%.6g write_bytes=%.6g launches=%d" % (name.replace(" ", "_"), fb, wb, calls))
+    lines.append("")
+    return lines, data
 
 
 def _rows(folder):
@@ -116,19 +180,28 @@ def summarise(root):
     return lines, data
 
 
-def trace_summary(folder, bench_json):
+def trace_summary(folder, bench_json, plain_json=None):
     """The kernel-trace statistics of one `rocprofv3 --kernel-trace --stats` run of bench.py, next to the run's own
     JSON line (HIP-event timing inside bench.py), for profiles/bench_config3_bert_large.txt:
 
         rocprofv3 --kernel-trace --stats -d gpurun_out/prof -o bench --output-format csv -- \\
             python3 bench.py --steps 3 --warmup 1 > gpurun_out/prof/bench_stdout.json
-        python3 -m paper_2305_18513_amd.profile_counters --trace gpurun_out/prof gpurun_out/prof/bench_stdout.json
+        python3 bench.py > gpurun_out/bench_plain.json
+        python3 -m paper_2305_18513_amd.profile_counters --trace gpurun_out/prof gpurun_out/prof/bench_stdout.json \\
+            gpurun_out/bench_plain.json
+
+    The second JSON line comes from a run without the profiler (whose per-launch overhead shows in the small
+    configurations and in the multi-launch operations): the other configurations and the extras are quoted from it.
     """
     import json
     stats = glob.glob(os.path.join(folder, "**", "*kernel_stats.csv"), recursive=True)
     traces = glob.glob(os.path.join(folder, "**", "*kernel_trace.csv"), recursive=True)
     with open(bench_json) as fh:
         bench = json.loads([l for l in fh if l.startswith("{")][-1])
+    plain = bench
+    if plain_json:
+        with open(plain_json) as fh:
+            plain = json.loads([l for l in fh if l.startswith("{")][-1])
 
     def short(n):
         n = re.sub(r"\(anonymous namespace\)::", "", n)
@@ -139,7 +212,9 @@ def trace_summary(folder, bench_json):
     print("Commands (from the repository root, after `cd /tmp && export TMPDIR=/tmp`):")
     print("  rocprofv3 --kernel-trace --stats -d gpurun_out/prof -o bench --output-format csv -- \\")
     print("      python3 bench.py --steps 3 --warmup 1 > gpurun_out/prof/bench_stdout.json")
-    print("  python3 -m paper_2305_18513_amd.profile_counters --trace gpurun_out/prof gpurun_out/prof/bench_stdout.json")
+    print("  python3 bench.py > gpurun_out/bench_plain.json")
+    print("  python3 -m paper_2305_18513_amd.profile_counters --trace gpurun_out/prof gpurun_out/prof/bench_stdout.json \\")
+    print("      gpurun_out/bench_plain.json")
     print()
     print("1. Kernel trace statistics, library kernels (all launches of the run: warm-up, survey and timed steps of the")
     print("   default workload, its HIP-graph replays, the extras, the brief runs of the other four configurations)")
@@ -167,7 +242,7 @@ def trace_summary(folder, bench_json):
             print("   min %.1f, max %.1f; bench.py's events around the same launches: %.1f us"
                   % (min(timed), max(timed), 1e3 * bench["kernels"][dom]["avg_ms"]))
     print()
-    print("2. The same run's own JSON line")
+    print("2. The profiled run's own JSON line")
     print("   step: %.3f ms, %.1f GB/s = %.1f %% of 8 TB/s" % (bench["ms_per_step"], bench["value"], 100 * bench["frac_hbm_peak"]))
     for k, v in bench["kernels"].items():
         print("   %-26s calls %4d  avg %.5f ms  %7.1f GB/s  %5.1f %% of 8 TB/s  bound %-6s  %5.1f %% of its streaming probe  [%s]"
@@ -181,28 +256,41 @@ def trace_summary(folder, bench_json):
     if cb and cb.get("value"):
         print("   cpu oracle: %s GB/s on %d threads (box: %s cores), %s s" % (cb["value"], cb["cores"], cb.get("host_cores"), cb.get("seconds")))
     print()
-    print("3. The other configurations of the same run (brief: 1 warm-up, 1 survey, 2 timed steps each)")
-    for c, v in sorted(bench.get("configs", {}).items()):
+    print("3. The run without the profiler: %.3f ms per step, %.1f GB/s = %.1f %% of 8 TB/s; %s %.5f ms = %.1f %% of 8 TB/s,"
+          % (plain["ms_per_step"], plain["value"], 100 * plain["frac_hbm_peak"], dom, plain["roofline"]["avg_ms"],
+             100 * plain["roofline"]["frac"]))
+    print("   bound %s, %.1f %% of its streaming probe.  All five configurations (the others brief: 1 warm-up, 1 survey,"
+          % (plain["roofline"]["bound"], 100 * plain["roofline"].get("frac_of_stream_probe", float("nan"))))
+    print("   2 timed steps each):")
+    for c, v in sorted(plain.get("configs", {}).items()):
         if "kernels" not in v:
             continue
         print("   %s: %.3f ms per step, %.1f GB/s = %.1f %% of 8 TB/s" % (v["workload"], v["ms_per_step"], v["GBps"], 100 * v["frac_hbm_peak"]))
         for k, e in v["kernels"].items():
             print("      %-26s avg %.5f ms  %7.1f GB/s  %5.1f %%  bound %s" % (k, e["avg_ms"], e["GBps"], 100 * e["frac_hbm_peak"], e["bound"]))
     print()
-    print("4. Extras of the same run (outside the timed step; HIP events, median of 12)")
-    for k, v in bench.get("extras", {}).items():
+    print("4. Extras of the run without the profiler (outside the timed step; HIP events, median of 12; bytes moved are")
+    print("   those of profiles/kernel_counters.txt)")
+    for k, v in plain.get("extras", {}).items():
         if isinstance(v, dict) and "median_ms" in v:
-            print("   %-44s %.5f ms  %7.1f GB/s  %5.1f %% of 8 TB/s" % (k, v["median_ms"], v["GBps"], 100 * v["frac_hbm_peak"]))
+            line = "   %-44s %.5f ms  %7.1f GB/s  %5.1f %% of 8 TB/s" % (k, v["median_ms"], v["GBps"], 100 * v["frac_hbm_peak"])
+            if "frac_of_stream_probe" in v:
+                line += "  %5.1f %% of its streaming probe" % (100 * v["frac_of_stream_probe"])
+            if "frac_hbm_peak_on_traffic" in v:
+                line += "  moved %.2fx the algorithmic bytes: %5.1f %% of 8 TB/s on that basis" % (
+                    v["traffic_over_algorithmic"], 100 * v["frac_hbm_peak_on_traffic"])
+            print(line)
     return 0
 
 
 def main(argv):
-    if len(argv) == 4 and argv[1] == "--trace":
-        return trace_summary(argv[2], argv[3])
+    if len(argv) in (4, 5) and argv[1] == "--trace":
+        return trace_summary(argv[2], argv[3], argv[4] if len(argv) == 5 else None)
     if len(argv) != 2:
         sys.stderr.write(__doc__)
         return 2
     lines, data = summarise(argv[1])
+    xlines, xdata = summarise_extras(argv[1])
     print("rocprofv3 counters of the hot-path kernels as bench.py launches them, one MI355X")
     print("=" * 84)
     print()
@@ -214,12 +302,17 @@ def main(argv):
     print("      python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy")
     print("  rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/cfgC_write -o r --output-format csv -- \\")
     print("      python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy")
+    print("and, for the operations outside the timed step, from two runs of the default configuration with its extras:")
+    print("  rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pc/extras_fetch -o r --output-format csv -- \\")
+    print("      python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy")
+    print("  rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/extras_write -o r --output-format csv -- \\")
+    print("      python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy")
     print("Counter values are means over the kernel's launches in the run (first, cold launches included), summed over")
     print("the chip as rocprofv3 reports them; byte counters are scaled by the same counter's reading of a 1 GiB copy.")
     print("bench.py reads the DATA lines (roofline.traffic, the issue side of the bound rule).")
     print()
-    print("\n".join(lines))
-    print("\n".join(data))
+    print("\n".join(lines + xlines))
+    print("\n".join(data + xdata))
     return 0
 
 
