@@ -335,12 +335,12 @@ def sets_for(cfg, requested):
 
 
 def brief_config(ci, counters):
-    """Another configuration, briefly: one warm-up step, the survey step, two timed steps."""
+    """Another configuration, briefly: two warm-up steps, the survey step, five timed steps."""
     cfg = synth.CONFIGS[ci]
     wl = Workload(cfg, sets_for(cfg, 3))
-    wall, survey, timers, dom = wl.measure(2, 1)
-    kernels = kernel_table(wl, survey, timers, dom, 2, counters, with_probe=False)
-    ms = wall * 1e3 / 2
+    wall, survey, timers, dom = wl.measure(5, 2)
+    kernels = kernel_table(wl, survey, timers, dom, 5, counters, with_probe=False)
+    ms = wall * 1e3 / 5
     out = {"workload": wl.describe(), "dtype": "f32" if cfg.act_dtype == torch.float32 else "bf16",
            "quant": "%d-bit block-%d" % (wl.bits, wl.block), "keep_k": cfg.keep_k,
            "prune_mode": "threshold" if cfg.threshold_variant else "topk", "buffer_sets": wl.n_sets,
@@ -358,8 +358,8 @@ def brief_config(ci, counters):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (3 = BERT-large-shaped)")
     ap.add_argument("--sets", type=int, default=3, help="distinct encoder-block buffer sets to rotate over (at least)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

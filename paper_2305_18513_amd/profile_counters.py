@@ -259,9 +259,9 @@ def trace_summary(folder, bench_json, plain_json=None):
     print("3. The run without the profiler: %.3f ms per step, %.1f GB/s = %.1f %% of 8 TB/s; %s %.5f ms = %.1f %% of 8 TB/s,"
           % (plain["ms_per_step"], plain["value"], 100 * plain["frac_hbm_peak"], dom, plain["roofline"]["avg_ms"],
              100 * plain["roofline"]["frac"]))
-    print("   bound %s, %.1f %% of its streaming probe.  All five configurations (the others brief: 1 warm-up, 1 survey,"
+    print("   bound %s, %.1f %% of its streaming probe.  All five configurations (the others brief: 2 warm-ups, 1 survey,"
           % (plain["roofline"]["bound"], 100 * plain["roofline"].get("frac_of_stream_probe", float("nan"))))
-    print("   2 timed steps each):")
+    print("   5 timed steps each):")
     for c, v in sorted(plain.get("configs", {}).items()):
         if "kernels" not in v:
             continue
