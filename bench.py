@@ -686,6 +686,16 @@ def main() -> int:
                 "bound_rule": "launch: bytes / 8 TB/s < 4 us; issue: max(VALU, SALU) wave instructions per row "
                               "(profiles/kernel_counters.txt) x rows x 4 cycles / (1024 SIMDs x 2.4 GHz) >= half the "
                               "measured time; hbm: otherwise"}
+    if cnt.get("rows") and (cnt.get("valu_per_row") or cnt.get("salu_per_row")):
+        # the other roofline of this kernel: wave instructions issued against what the chip can issue (each compute
+        # unit starts one vector and one scalar wave instruction a cycle: 256 x 2.4 GHz = 614.4 G/s per pipe)
+        per_row = max(cnt.get("valu_per_row", 0.0), cnt.get("salu_per_row", 0.0))
+        rate = per_row * cnt["rows"] / (kd["avg_ms"] * 1e-3) / 1e9
+        peak = SIMDS * CLOCK_HZ / ISSUE_CYCLES / 1e9
+        roofline["issue"] = {"valu_per_row": round(cnt.get("valu_per_row", 0.0), 1),
+                             "salu_per_row": round(cnt.get("salu_per_row", 0.0), 1), "rows": int(cnt["rows"]),
+                             "achieved": round(rate, 1), "peak": round(peak, 1), "unit": "G wave instructions/s (busier pipe)",
+                             "frac": round(rate / peak, 4)}
     if "stream_probe" in kd:
         # a streaming kernel of the same read : write mix and size, timed the same way on this machine
         roofline["stream_probe"] = kd["stream_probe"]
