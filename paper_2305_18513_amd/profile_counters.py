@@ -1,23 +1,23 @@
 """Turns the rocprofv3 counter runs of ``bench.py`` into the tracked summary ``profiles/kernel_counters.txt``.
 
-    python3 -m paper_2305_18513_amd.profile_counters gpurun_out/pc > profiles/kernel_counters.txt
+    python3 -m paper_2305_18513_amd.profile_counters OUT/pc > profiles/kernel_counters.txt
 
-``gpurun_out/pc`` holds, for every profiled configuration C, the output folders of three runs (each started
+(``OUT`` is any scratch folder.)  ``OUT/pc`` holds, for every profiled configuration C, the output folders of three runs (each started
 from the repository root after ``cd /tmp && export TMPDIR=/tmp``, one counter set per run):
 
-    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU -d gpurun_out/pc/cfgC_insts -o r --output-format csv -- \\
+    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU -d OUT/pc/cfgC_insts -o r --output-format csv -- \\
         python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs
-    rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pc/cfgC_fetch -o r --output-format csv -- \\
+    rocprofv3 --pmc FETCH_SIZE -d OUT/pc/cfgC_fetch -o r --output-format csv -- \\
         python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy
-    rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/cfgC_write -o r --output-format csv -- \\
+    rocprofv3 --pmc WRITE_SIZE -d OUT/pc/cfgC_write -o r --output-format csv -- \\
         python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy
 
 and, for the operations bench.py times outside the step (its "extras"), two more runs of the default configuration
 with the extras left in:
 
-    rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pc/extras_fetch -o r --output-format csv -- \\
+    rocprofv3 --pmc FETCH_SIZE -d OUT/pc/extras_fetch -o r --output-format csv -- \\
         python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy
-    rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/extras_write -o r --output-format csv -- \\
+    rocprofv3 --pmc WRITE_SIZE -d OUT/pc/extras_write -o r --output-format csv -- \\
         python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy
 
 The byte counters (KiB per dispatch) are scaled by what the same counter reads for the 1 GiB device copies of
@@ -184,11 +184,11 @@ def trace_summary(folder, bench_json, plain_json=None):
     """The kernel-trace statistics of one `rocprofv3 --kernel-trace --stats` run of bench.py, next to the run's own
     JSON line (HIP-event timing inside bench.py), for profiles/bench_config3_bert_large.txt:
 
-        rocprofv3 --kernel-trace --stats -d gpurun_out/prof -o bench --output-format csv -- \\
-            python3 bench.py --steps 3 --warmup 1 > gpurun_out/prof/bench_stdout.json
-        python3 bench.py > gpurun_out/bench_plain.json
-        python3 -m paper_2305_18513_amd.profile_counters --trace gpurun_out/prof gpurun_out/prof/bench_stdout.json \\
-            gpurun_out/bench_plain.json
+        rocprofv3 --kernel-trace --stats -d OUT/prof -o bench --output-format csv -- \\
+            python3 bench.py --steps 3 --warmup 1 > OUT/prof/bench_stdout.json
+        python3 bench.py > OUT/bench_plain.json
+        python3 -m paper_2305_18513_amd.profile_counters --trace OUT/prof OUT/prof/bench_stdout.json \\
+            OUT/bench_plain.json
 
     The second JSON line comes from a run without the profiler (whose per-launch overhead shows in the small
     configurations and in the multi-launch operations): the other configurations and the extras are quoted from it.
@@ -210,11 +210,11 @@ def trace_summary(folder, bench_json, plain_json=None):
     print("=" * 84)
     print()
     print("Commands (from the repository root, after `cd /tmp && export TMPDIR=/tmp`):")
-    print("  rocprofv3 --kernel-trace --stats -d gpurun_out/prof -o bench --output-format csv -- \\")
-    print("      python3 bench.py --steps 3 --warmup 1 > gpurun_out/prof/bench_stdout.json")
-    print("  python3 bench.py > gpurun_out/bench_plain.json")
-    print("  python3 -m paper_2305_18513_amd.profile_counters --trace gpurun_out/prof gpurun_out/prof/bench_stdout.json \\")
-    print("      gpurun_out/bench_plain.json")
+    print("  rocprofv3 --kernel-trace --stats -d %s -o bench --output-format csv -- \\" % folder)
+    print("      python3 bench.py --steps 3 --warmup 1 > %s" % bench_json)
+    print("  python3 bench.py > %s" % (plain_json or "(not given)"))
+    print("  python3 -m paper_2305_18513_amd.profile_counters --trace %s %s \\" % (folder, bench_json))
+    print("      %s" % (plain_json or ""))
     print()
     print("1. Kernel trace statistics, library kernels (all launches of the run: warm-up, survey and timed steps of the")
     print("   default workload, its HIP-graph replays, the extras, the brief runs of the other four configurations)")
@@ -294,18 +294,19 @@ def main(argv):
     print("rocprofv3 counters of the hot-path kernels as bench.py launches them, one MI355X")
     print("=" * 84)
     print()
-    print("Written by `python3 -m paper_2305_18513_amd.profile_counters gpurun_out/pc` from three counter runs per")
+    out = argv[1].rstrip("/")
+    print("Written by `python3 -m paper_2305_18513_amd.profile_counters %s` from three counter runs per" % out)
     print("configuration C (from the repository root, after `cd /tmp && export TMPDIR=/tmp`):")
-    print("  rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU -d gpurun_out/pc/cfgC_insts -o r --output-format csv -- \\")
+    print("  rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU -d %s/cfgC_insts -o r --output-format csv -- \\" % out)
     print("      python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs")
-    print("  rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pc/cfgC_fetch -o r --output-format csv -- \\")
+    print("  rocprofv3 --pmc FETCH_SIZE -d %s/cfgC_fetch -o r --output-format csv -- \\" % out)
     print("      python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy")
-    print("  rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/cfgC_write -o r --output-format csv -- \\")
+    print("  rocprofv3 --pmc WRITE_SIZE -d %s/cfgC_write -o r --output-format csv -- \\" % out)
     print("      python3 bench.py --config C --steps 1 --warmup 0 --no-cpu-baseline --no-extras --no-other-configs --calibrate-copy")
     print("and, for the operations outside the timed step, from two runs of the default configuration with its extras:")
-    print("  rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pc/extras_fetch -o r --output-format csv -- \\")
+    print("  rocprofv3 --pmc FETCH_SIZE -d %s/extras_fetch -o r --output-format csv -- \\" % out)
     print("      python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy")
-    print("  rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pc/extras_write -o r --output-format csv -- \\")
+    print("  rocprofv3 --pmc WRITE_SIZE -d %s/extras_write -o r --output-format csv -- \\" % out)
     print("      python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-other-configs --calibrate-copy")
     print("Counter values are means over the kernel's launches in the run (first, cold launches included), summed over")
     print("the chip as rocprofv3 reports them; byte counters are scaled by the same counter's reading of a 1 GiB copy.")
