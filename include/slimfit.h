@@ -315,7 +315,7 @@ int32_t slimfit_restore_scores(const void *vals, const uint16_t *idx, const int3
  *     is decided on the logits: they order the row exactly as the probabilities
  *     do and are not subject to rounding (equal logits: lower column first);
  *     vals are the row's p_j, emitted in ascending column order.  Arithmetic is
- *     fp32 (hardware exp2, fixed-order wave sum, one IEEE division per row):
+ *     fp32 (hardware exp2, a sum in a fixed order, one IEEE division per row):
  *     p_j within p_j * (2e-6 + 2e-7 * (max l - l_j)) of the exact value (a
  *     subnormal p_j may be flushed to zero), bf16 results within one further
  *     bf16 rounding.

@@ -31,6 +31,8 @@ constexpr int kShortPruneMaxKF32 = 9;                   // fp32 rows
 bool prune_short_eligible(const void *p, int32_t dt, int64_t rows, int cols, int k);
 void launch_prune_short(const void *p, int32_t dt, int64_t rows, int cols, int k, int mode, float tau, void *vals,
                         uint16_t *idx, int32_t *counts, hipStream_t st);
+void launch_softmax_prune_short(const void *logits, int32_t dt, int64_t rows, int cols, int k, void *probs, void *vals,
+                                uint16_t *idx, hipStream_t st);
 
 inline bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline bool dtype_ok(int32_t dt) { return dt == SLIMFIT_F32 || dt == SLIMFIT_BF16; }

@@ -137,6 +137,9 @@ __device__ __forceinline__ float wave_sum_f32(float v)
 #ifndef SLIMFIT_PRUNE_SHORT
 #define SLIMFIT_PRUNE_SHORT 1          // rows of <= 256 columns keeping <= 16 entries take the short-row kernel
 #endif
+#ifndef SLIMFIT_SOFTMAX_SHORT
+#define SLIMFIT_SOFTMAX_SHORT 1        // the fused softmax takes the short-row kernel under the same conditions
+#endif
 #ifndef SLIMFIT_PRUNE_NT
 #define SLIMFIT_PRUNE_NT 1             // row loads are streamed once
 #endif
@@ -1083,6 +1086,10 @@ void launch_prune(const void *p, int64_t rows, int cols, int k, int mode, float 
     constexpr int32_t dt = sizeof(T) == 4 ? SLIMFIT_F32 : SLIMFIT_BF16;
     if (!SOFTMAX && SLIMFIT_PRUNE_SHORT && prune_short_eligible(p, dt, rows, cols, k)) {
         launch_prune_short(p, dt, rows, cols, k, mode, tau, vals, idx, counts, st);
+        return;
+    }
+    if (SOFTMAX && SLIMFIT_SOFTMAX_SHORT && prune_short_eligible(p, dt, rows, cols, k) && aligned_to(probs, 16)) {
+        launch_softmax_prune_short(p, dt, rows, cols, k, probs, vals, idx, st);      // (the dense rows leave in 16-byte stores)
         return;
     }
     const int slots = (cols + kWave - 1) / kWave;

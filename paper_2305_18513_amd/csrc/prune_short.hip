@@ -213,9 +213,15 @@ struct ShortRows {
     // the positive entries correctly and puts everything else (zeros of either sign, negative values in reversed
     // order) below them: enough whenever every kept entry is positive.  The plain pass notices when that fails for
     // one of the wave's rows and returns false before it has written anything; the caller then runs the signed pass.
-    template <bool NEG>
+    // between(): called once, after the kept columns are staged and before the kept values are fetched from the
+    // staged rows (FROM_ROWS: always from there); the fused softmax rewrites the rows in between.
+    struct Nothing {
+        __device__ void operator()() const {}
+    };
+    template <bool NEG, bool FROM_ROWS = false, typename Between = Nothing>
     static __device__ bool run(const ShortArgs &a, const T *rows_lds, uint32_t *oc, int lane, int n_here, int64_t row0,
-                               T *__restrict__ vals, uint16_t *__restrict__ idx, int32_t *__restrict__ counts)
+                               T *__restrict__ vals, uint16_t *__restrict__ idx, int32_t *__restrict__ counts,
+                               Between between = Between())
     {
         const int cols = a.cols, k = a.k;
         const int r = lane / G, q = lane % G;
@@ -386,8 +392,9 @@ struct ShortRows {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        between();
         const int n_out = n_here * k;
-        constexpr bool REREAD = !BF || NEG;                 // values come from the staged rows again
+        constexpr bool REREAD = !BF || NEG || FROM_ROWS;    // values come from the staged rows again
         T *ov = vals + row0 * (int64_t)k;
         uint16_t *oi = idx + row0 * (int64_t)k;
         uint32_t w[N_OUT];
@@ -482,6 +489,147 @@ __global__ __launch_bounds__(kWave) void prune_rows_short_kernel(const T *__rest
         S::template run<true>(a, rows_lds, oc, lane, n_here, row0, vals, idx, counts);
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Row softmax and Alg. 5 in one pass over short rows of logits: the kept set is decided on the logits (which order
+// a row exactly as its probabilities do), the dense probabilities are written once, and the kept values are the
+// numbers the dense row holds.  The rows are staged and selected as above; before the kept values are fetched each
+// lane turns its part of its row into probabilities in place (row maximum and sum of exponentials by exchanges
+// between the row's G lanes; hardware exp2; four running sums a lane, so that no sum is longer than a quarter of
+// the lane's part; one IEEE division a row), and the wave's rows leave for `probs` as they came, as one contiguous
+// piece.
+template <typename T, int G, int K, int NV>
+__global__ __launch_bounds__(kWave) void softmax_prune_short_kernel(const T *__restrict__ p, ShortArgs a,
+                                                                    T *__restrict__ probs, T *__restrict__ vals,
+                                                                    uint16_t *__restrict__ idx)
+{
+    using S = ShortRows<T, G, K, NV>;
+    extern __shared__ uint4 short_lds[];
+    constexpr bool BF = sizeof(T) == 2;
+    constexpr int R = S::R;
+    constexpr int PER16 = 16 / (int)sizeof(T);
+    const int lane = threadIdx.x;
+    const int cols = a.cols, k = a.k;
+    char *slab = reinterpret_cast<char *>(short_lds);
+    const int slab_bytes = (R * cols * (int)sizeof(T) + 15) & ~15;
+    uint32_t *oc = reinterpret_cast<uint32_t *>(slab + slab_bytes);        // R * k output slots
+    u32x4 *slab_v = reinterpret_cast<u32x4 *>(slab);
+
+    const int64_t row0 = (int64_t)blockIdx.x * R;
+    const int n_here = (int)min((int64_t)R, a.rows - row0);        // >= 1 by the launch size
+    const int n_elem = n_here * cols;
+    const int n_vec = n_elem / PER16;
+    const u32x4 *src_v = reinterpret_cast<const u32x4 *>(p + row0 * (int64_t)cols);
+    if (n_vec > 0) {
+        // lanes past the end of a short last piece re-read its last vector (and store it again where it belongs)
+        u32x4 v[NV];
+#pragma unroll
+        for (int u = 0; u < NV; ++u) v[u] = load_global<SLIMFIT_SHORT_NT != 0>(src_v + min(u * kWave + lane, n_vec - 1));
+#pragma unroll
+        for (int u = 0; u < NV; ++u) slab_v[min(u * kWave + lane, n_vec - 1)] = v[u];
+    }
+    {
+        const int ei = n_vec * PER16 + lane;           // fewer than PER16 entries are left over (short last piece only)
+        if (ei < n_elem) reinterpret_cast<T *>(slab)[ei] = p[row0 * (int64_t)cols + ei];
+    }
+    for (int t = lane; t < R * k; t += kWave) oc[t] = kNoPair;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    auto to_probabilities = [&]() {
+        const int r = lane / G, q = lane % G;
+        const int E = (cols + G - 1) / G;
+        const int len = min(max(cols - q * E, 0), E);
+        const int e_all = max(cols - (G - 1) * E, 0);
+        T *seg = reinterpret_cast<T *>(slab) + r * cols + q * E;
+        auto value = [](int bits) { return __builtin_bit_cast(float, BF ? (uint32_t)bits << 16 : (uint32_t)bits); };
+        constexpr float kLog2e = 1.44269504088896340736f;
+        float mx = -__builtin_inff();
+        S::template for_each_entry<false>(seg, E, len, e_all, [&](int, int bits, bool ok) {
+            const float x = value(bits);
+            mx = ok ? fmaxf(mx, x) : mx;
+        });
+        mx = fmaxf(mx, dpp_f32<kDppXor1>(mx));
+        if constexpr (G == 4) mx = fmaxf(mx, dpp_f32<kDppXor2>(mx));
+        // (a lane of a row past the tensor's end, or one without entries, holds -inf here: its results are not used)
+        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+        S::template for_each_entry<false>(seg, E, len, e_all, [&](int e, int bits, bool ok) {
+            const float t = __builtin_amdgcn_exp2f((value(bits) - mx) * kLog2e);
+            const float s = s0 + (ok ? t : 0.0f);           // the four sums take turns
+            s0 = s1; s1 = s2; s2 = s3; s3 = s;
+            if constexpr (!BF) {
+                if (ok) seg[e] = t;                         // fp32 rows keep the exponential in place of the logit
+            }
+        });
+        float sum = (s0 + s1) + (s2 + s3);
+        sum += dpp_f32<kDppXor1>(sum);
+        if constexpr (G == 4) sum += dpp_f32<kDppXor2>(sum);
+        const float inv = 1.0f / sum;                       // IEEE division
+        if constexpr (!BF) {                                // (the lane reads back what it wrote itself: LDS keeps a wave's order)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        S::template for_each_entry<false>(seg, E, len, e_all, [&](int e, int bits, bool ok) {
+            const float pj = (BF ? __builtin_amdgcn_exp2f((value(bits) - mx) * kLog2e) : value(bits)) * inv;
+            if (ok) {
+                if constexpr (BF) seg[e] = (T)bf16_narrow(pj);
+                else seg[e] = pj;
+            }
+        });
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // the dense rows leave as they came: one contiguous piece, 16 bytes a lane
+        u32x4 *dst_v = reinterpret_cast<u32x4 *>(probs + row0 * (int64_t)cols);
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int v = u * kWave + lane;
+            if (v < n_vec) store_global<true>(dst_v + v, slab_v[v]);
+        }
+        const int ei = n_vec * PER16 + lane;
+        if (ei < n_elem) probs[row0 * (int64_t)cols + ei] = reinterpret_cast<const T *>(slab)[ei];
+    };
+
+    const T *rows_lds = reinterpret_cast<const T *>(slab);
+    if (!S::template run<false, true>(a, rows_lds, oc, lane, n_here, row0, vals, idx, nullptr, to_probabilities))
+        S::template run<true, true>(a, rows_lds, oc, lane, n_here, row0, vals, idx, nullptr, to_probabilities);
+}
+
+template <typename T, int G, int K, int NV>
+void launch_softmax_short(const T *p, const ShortArgs &a, T *probs, T *vals, uint16_t *idx, hipStream_t st)
+{
+    constexpr int R = kWave / G;
+    const int64_t blocks = (a.rows + R - 1) / R;
+    const size_t lds = (size_t)((R * a.cols * (int)sizeof(T) + 15) & ~15) + (size_t)R * (size_t)a.k * 4u;
+    softmax_prune_short_kernel<T, G, K, NV><<<(unsigned)blocks, kWave, lds, st>>>(p, a, probs, vals, idx);
+}
+
+template <typename T, int G, int K>
+void launch_softmax_short_nv(const T *p, const ShortArgs &a, T *probs, T *vals, uint16_t *idx, hipStream_t st)
+{
+    constexpr int R = kWave / G;
+    constexpr int S = R * (int)sizeof(T) / 64;
+    const int nv = (a.cols * S * 4 + kWave - 1) / kWave;
+    if (nv <= 4 * S) launch_softmax_short<T, G, K, 4 * S>(p, a, probs, vals, idx, st);
+    else if (nv <= 8 * S) launch_softmax_short<T, G, K, 8 * S>(p, a, probs, vals, idx, st);
+    else if (nv <= 12 * S + 1) launch_softmax_short<T, G, K, 12 * S + 1>(p, a, probs, vals, idx, st);
+    else launch_softmax_short<T, G, K, 16 * S>(p, a, probs, vals, idx, st);
+}
+
+template <typename T, int G>
+void launch_softmax_short_k(const T *p, const ShortArgs &a, T *probs, T *vals, uint16_t *idx, hipStream_t st)
+{
+    if (a.k <= 2) launch_softmax_short_nv<T, G, 2>(p, a, probs, vals, idx, st);
+    else if (a.k <= 4) launch_softmax_short_nv<T, G, 4>(p, a, probs, vals, idx, st);
+    else if (a.k <= 6) launch_softmax_short_nv<T, G, 6>(p, a, probs, vals, idx, st);
+    else if (a.k <= 9) launch_softmax_short_nv<T, G, 9>(p, a, probs, vals, idx, st);
+    else if constexpr (sizeof(T) == 2) {
+        if (a.k <= 12) launch_softmax_short_nv<T, G, 12>(p, a, probs, vals, idx, st);
+        else launch_softmax_short_nv<T, G, 16>(p, a, probs, vals, idx, st);
+    }
+}
+
 template <typename T, int G, int K, int NV>
 void launch_short(const T *p, const ShortArgs &a, T *vals, uint16_t *idx, int32_t *counts, hipStream_t st)
 {
@@ -529,6 +677,24 @@ bool prune_short_eligible(const void *p, int32_t dt, int64_t rows, int cols, int
     const int k_max = dt == SLIMFIT_BF16 ? kShortPruneMaxK : kShortPruneMaxKF32;
     // (the rows are staged with 16-byte loads)
     return cols <= kShortPruneMaxCols && k <= k_max && aligned_to(p, 16) && rows <= (int64_t)0x7FFFFFFF * 16;
+}
+
+void launch_softmax_prune_short(const void *logits, int32_t dt, int64_t rows, int cols, int k, void *probs, void *vals,
+                                uint16_t *idx, hipStream_t st)
+{
+    ShortArgs a;
+    a.rows = rows;
+    a.cols = cols;
+    a.k = k;
+    a.mode = SLIMFIT_PRUNE_TOPK;
+    a.tau = 0.0f;
+    a.div_magic = 65536u / (uint32_t)k + 1u;
+    if (dt == SLIMFIT_F32)
+        launch_softmax_short_k<float, 4>(static_cast<const float *>(logits), a, static_cast<float *>(probs),
+                                         static_cast<float *>(vals), idx, st);
+    else
+        launch_softmax_short_k<uint16_t, 2>(static_cast<const uint16_t *>(logits), a, static_cast<uint16_t *>(probs),
+                                            static_cast<uint16_t *>(vals), idx, st);
 }
 
 void launch_prune_short(const void *p, int32_t dt, int64_t rows, int cols, int k, int mode, float tau, void *vals,

@@ -74,6 +74,34 @@ def test_random_rows_ties_and_ranges(rows, cols, k, dtype):
     _run_both(l.to(dtype), k)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("rows,cols,k", [(1, 8, 1), (15, 197, 9), (16, 197, 9), (17, 197, 9), (33, 250, 9), (64, 256, 2),
+                                         (31, 100, 6), (1037, 197, 9), (129, 3, 2), (70, 65, 4)])
+def test_short_rows_several_rows_a_wavefront(rows, cols, k, dtype):
+    """Rows of at most 256 columns that keep few entries take the kernel that gives a wavefront 16 or 32 rows at
+    once: ragged row counts, logits of either sign, ties, and fp32 logits that only their lowest bits tell apart."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(rows * 7 + cols * 3 + k)
+    l = torch.randn(rows, cols, generator=g, device="cuda") * 3
+    if rows > 8:
+        l[1] = -l[1].abs() - 2.0                                           # every logit negative
+        l[2] = torch.randint(-1, 2, (cols,), generator=g, device="cuda").float()      # ties across the cut, zeros
+        l[3] = 0.0
+        low = torch.randint(0, 256, (cols,), generator=g, device="cuda", dtype=torch.int32)
+        l[4] = (torch.full((cols,), 0x3F800000, dtype=torch.int32, device="cuda") + low).view(torch.float32)   # 1 + j 2^-23
+        l[5] = -l[4]
+        l[6] = l[6] + 300.0
+    _run_both(l.to(dtype), k)
+
+
+@pytest.mark.parametrize("cols,k", [(197, 12), (128, 16), (250, 13)])
+def test_short_bf16_rows_keep_up_to_sixteen(cols, k):
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(cols + k)
+    l = (torch.randn(200, cols, generator=g, device="cuda") * 0.5).to(torch.bfloat16)        # many tied logits
+    _run_both(l, k)
+
+
 def test_argument_errors():
     require_gpu()
     l = torch.randn(8, 2049, device="cuda")
