@@ -646,12 +646,11 @@ template <typename T, int G, int K>
 void launch_short_nv(const T *p, const ShortArgs &a, T *vals, uint16_t *idx, int32_t *counts, hipStream_t st)
 {
     constexpr int R = kWave / G;
-    constexpr int S = R * (int)sizeof(T) / 64;          // a piece is S * 64 * cols bytes
-    const int nv = (a.cols * S * 4 + kWave - 1) / kWave;                // rounds of 64 vectors
-    if (nv <= 4 * S) launch_short<T, G, K, 4 * S>(p, a, vals, idx, counts, st);
-    else if (nv <= 8 * S) launch_short<T, G, K, 8 * S>(p, a, vals, idx, counts, st);
-    else if (nv <= 12 * S + 1) launch_short<T, G, K, 12 * S + 1>(p, a, vals, idx, counts, st);     // 197 columns
-    else launch_short<T, G, K, 16 * S>(p, a, vals, idx, counts, st);
+    const int nv = (R * a.cols * (int)sizeof(T) / 16 + kWave - 1) / kWave;      // rounds of 64 vectors a piece takes
+    if (nv <= 4) launch_short<T, G, K, 4>(p, a, vals, idx, counts, st);
+    else if (nv <= 8) launch_short<T, G, K, 8>(p, a, vals, idx, counts, st);
+    else if (nv <= 13) launch_short<T, G, K, 13>(p, a, vals, idx, counts, st);   // 197 columns
+    else launch_short<T, G, K, 16>(p, a, vals, idx, counts, st);
 }
 
 template <typename T, int G>
@@ -713,7 +712,10 @@ void launch_prune_short(const void *p, int32_t dt, int64_t rows, int cols, int k
     if (dt == SLIMFIT_F32)
         launch_short_k<float, SLIMFIT_SHORT_G_F32>(static_cast<const float *>(p), a, static_cast<float *>(vals), idx, counts, st);
     else
-        launch_short_k<uint16_t, 2>(static_cast<const uint16_t *>(p), a, static_cast<uint16_t *>(vals), idx, counts, st);
+#ifndef SLIMFIT_SHORT_G_BF16
+#define SLIMFIT_SHORT_G_BF16 2
+#endif
+        launch_short_k<uint16_t, SLIMFIT_SHORT_G_BF16>(static_cast<const uint16_t *>(p), a, static_cast<uint16_t *>(vals), idx, counts, st);
 }
 
 }  // namespace slimfit
